@@ -1,0 +1,151 @@
+/*
+ * sgmv.h -- C ABI of libsgmv: Segmented Gather Matrix-Vector multiplication
+ * (SGMV) for AMD MI355X (gfx950).
+ *
+ * SGMV is the batched LoRA add-on of Punica (arxiv 2310.18547, section
+ * "Segmented Gather Matrix-Vector Multiplication").  The token rows of a batch
+ * are grouped so that rows using the same LoRA adapter are consecutive; the
+ * index sequence s_0 = 0 <= s_1 <= ... <= s_n = number of rows delimits n
+ * segments, segment i owning rows s_i .. s_{i+1}-1 (zero based).  Rows of
+ * segment i receive x * A_i * B_i on top of the backbone projection already
+ * stored in y, evaluated as two steps ("v := 0; v += x A; y += v B", the
+ * sentence after the section's displayed equation):
+ *
+ *     shrink :  v[rows of i] += x[rows of i] * A_i            (h_in  -> r)
+ *     expand :  y[rows of i] += scale * v[rows of i] * B_i    (r -> h_out)
+ *
+ * with A_i in R^{h_in x r}, B_i in R^{r x h_out} (Background, "Low-Rank
+ * Adaptation").  "Gather" = every segment names its own weights through an
+ * array of device pointers.
+ *
+ * General conventions
+ *   - Every data pointer (x, y, v, A_ptrs, B_ptrs, seg_starts, workspace, and
+ *     whatever A_ptrs[i] / B_ptrs[i] point to) is DEVICE memory owned by the
+ *     caller.  The sgmv_problem struct itself is HOST memory, read during the
+ *     call only.  The library allocates nothing, frees nothing and keeps no
+ *     state between calls.
+ *   - x is [n_tokens][h_in], y is [n_tokens][h_out], row-major, 16-bit floats
+ *     of type `dtype` (IEEE binary16 or bfloat16), 16-byte aligned.
+ *   - A_ptrs[i] points to segment i's shrink weights stacked over layers,
+ *     [num_layers][h_in][r] row-major; B_ptrs[i] to [num_layers][r][h_out].
+ *     The kernels add layer_idx * h_in * r (resp. layer_idx * r * h_out)
+ *     elements, so one pointer array and one seg_starts serve all layers of a
+ *     model invocation.  Each base must be 16-byte aligned.  Two segments may
+ *     carry the same pointer.  A NULL entry means "no adapter": the segment's
+ *     rows are left untouched.
+ *   - seg_starts has n_segs + 1 int32 entries, seg_starts[0] = 0,
+ *     non-decreasing, seg_starts[n_segs] = n_tokens.  Empty segments are
+ *     allowed.  Its *contents* are not checked on the device path; use
+ *     sgmv_validate_segments() on a host copy if they are not trusted.
+ *   - v (shrink output / expand input) is fp32 [n_tokens][r], 16-byte aligned.
+ *   - All products and sums are taken in fp32; y is rounded once, to nearest
+ *     even, when it is stored.  Results are deterministic run to run (no
+ *     floating-point atomics).
+ *   - Supported shapes: r in {8, 16, 32, 64}; h_in and h_out positive
+ *     multiples of 8.  Anything else returns SGMV_ERR_UNSUPPORTED; there is no
+ *     fallback path.
+ *   - Calls are asynchronous: kernels are enqueued on `stream` (a hipStream_t
+ *     passed as void*; NULL = the default stream) and the call returns at
+ *     once.  The return value reports what the host can detect (argument
+ *     errors, a failed launch).  n_segs == 0 or n_tokens == 0 returns SGMV_OK
+ *     and enqueues nothing.
+ *   - x and y must not alias.  Two calls that share a workspace must be
+ *     ordered (same stream, or otherwise synchronised).
+ */
+#ifndef SGMV_H_
+#define SGMV_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { SGMV_F16 = 0, SGMV_BF16 = 1 } sgmv_dtype;
+
+typedef enum {
+  SGMV_OK = 0,
+  SGMV_ERR_NULL = 1,         /* a required pointer is NULL                         */
+  SGMV_ERR_SHAPE = 2,        /* negative / zero sizes that make no sense           */
+  SGMV_ERR_UNSUPPORTED = 3,  /* dtype, r, h_in or h_out outside the supported set  */
+  SGMV_ERR_ALIGN = 4,        /* x, y, v or workspace not 16-byte aligned           */
+  SGMV_ERR_WORKSPACE = 5,    /* workspace missing or smaller than required         */
+  SGMV_ERR_RANGE = 6,        /* layer_idx outside [0, num_layers)                  */
+  SGMV_ERR_LAUNCH = 7        /* the HIP runtime rejected a kernel launch           */
+} sgmv_status;
+
+/* Kernel family selection.  AUTO picks from max_seg_len; the others force one
+ * family for every segment (all families compute the same result). */
+typedef enum {
+  SGMV_PATH_AUTO = 0,
+  SGMV_PATH_VECTOR = 1,      /* bandwidth path: vector ALU, for short segments     */
+  SGMV_PATH_MATRIX = 2       /* MFMA path: for long (prefill-like) segments        */
+} sgmv_path;
+
+/* Problem descriptor: plain data, host memory, read during the call only. */
+typedef struct sgmv_problem {
+  int32_t dtype;             /* sgmv_dtype of x, y, A, B                            */
+  int32_t h_in;              /* input features of shrink                            */
+  int32_t h_out;             /* output features of expand                           */
+  int32_t r;                 /* LoRA rank                                           */
+  int32_t num_layers;        /* layers stacked behind every A_ptrs[i] / B_ptrs[i]   */
+  int32_t n_tokens;          /* rows of x / y / v, = seg_starts[n_segs]             */
+  int32_t max_seg_len;       /* longest segment, a hint for launch shape and path;  */
+                             /* 0 = unknown.  A wrong hint costs speed, never       */
+                             /* correctness.                                        */
+  int32_t path;              /* sgmv_path, normally SGMV_PATH_AUTO                  */
+  int32_t ksplit;            /* split-K factor of shrink; 0 = choose automatically  */
+  int32_t expand_threads;    /* workgroup size of the vector expand kernel          */
+                             /* (64, 128 or 256); 0 = choose automatically          */
+  void*   workspace;         /* device scratch, 256-byte aligned, at least          */
+  size_t  workspace_bytes;   /*   sgmv_workspace_bytes(n_tokens, r) bytes           */
+} sgmv_problem;
+
+/* Text for a status code (static storage; never NULL). */
+const char* sgmv_status_string(int status);
+
+/* Bytes of device scratch that sgmv_shrink and sgmv_add_lora need for a batch
+ * of n_tokens rows at rank r (split-K partial sums of the shrink step, see the
+ * "Split-K" remark in the paper's kernel-schedule paragraph).  Pure host
+ * function.  Returns 0 for n_tokens <= 0. */
+size_t sgmv_workspace_bytes(int32_t n_tokens, int32_t r);
+
+/* Host-side check of a HOST copy of the segment index sequence against the
+ * segment definition paragraph: n_segs >= 0, seg_starts[0] == 0,
+ * non-decreasing, seg_starts[n_segs] == n_tokens.  Returns SGMV_OK,
+ * SGMV_ERR_NULL or SGMV_ERR_SHAPE. */
+int sgmv_validate_segments(const int32_t* host_seg_starts, int32_t n_segs, int32_t n_tokens);
+
+/* SGMV-shrink, "v += x A" per segment (first operator of the LoRA module in
+ * the paper's kernel-schedule paragraph).
+ *   v      device fp32 [n_tokens][r], read and written (accumulated into)
+ *   x      device 16-bit [n_tokens][h_in], read
+ *   A_ptrs device array of n_segs device pointers
+ * Uses p->workspace.  h_out of the descriptor is ignored. */
+int sgmv_shrink(const sgmv_problem* p, float* v, const void* x,
+                const void* const* A_ptrs, const int32_t* seg_starts,
+                int32_t n_segs, int32_t layer_idx, void* stream);
+
+/* SGMV-expand, "y += scale * v B" per segment (second operator of the LoRA
+ * module).
+ *   y      device 16-bit [n_tokens][h_out], read and written
+ *   v      device fp32 [n_tokens][r], read
+ *   B_ptrs device array of n_segs device pointers
+ * Needs no workspace.  h_in of the descriptor is ignored. */
+int sgmv_expand(const sgmv_problem* p, void* y, const float* v,
+                const void* const* B_ptrs, const int32_t* seg_starts,
+                int32_t n_segs, int32_t layer_idx, float scale, void* stream);
+
+/* The whole LoRA add-on, y += scale * (x A_i) B_i per segment, i.e. v := 0,
+ * shrink, expand in one call; v lives in the workspace in fp32 and is never
+ * rounded.  A segment is skipped when either of its pointers is NULL. */
+int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x,
+                  const void* const* A_ptrs, const void* const* B_ptrs,
+                  const int32_t* seg_starts, int32_t n_segs, int32_t layer_idx,
+                  float scale, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SGMV_H_ */

@@ -1,0 +1,20 @@
+"""libsgmv for MI355X: Python binding of the C ABI (argument marshalling only).
+
+Every step of the operator runs in the HIP kernels of ``libsgmv.so``; there is
+no Python or CPU implementation behind these names.  The binding is loaded on
+first use of any of its names and raises ``ImportError`` if the library has not
+been built (``python -m paper_2310_18547_amd.build``).
+"""
+_BINDING_NAMES = (
+    "F16", "BF16", "PATH_AUTO", "PATH_VECTOR", "PATH_MATRIX", "SgmvError", "SgmvProblem", "lib",
+    "library_path", "make_problem", "sgmv_add_lora", "sgmv_expand", "sgmv_shrink",
+    "sgmv_status_string", "sgmv_validate_segments", "sgmv_workspace_bytes",
+)
+__all__ = list(_BINDING_NAMES)
+
+
+def __getattr__(name):
+    if name in _BINDING_NAMES:
+        from . import binding
+        return getattr(binding, name)
+    raise AttributeError(f"module {__name__!r} has no attribute {name!r}")

@@ -1,0 +1,138 @@
+"""ctypes binding of include/sgmv.h.
+
+The functions have the C names and the C argument order.  Pointer arguments
+accept a ``torch`` tensor (its ``data_ptr()`` is taken), an ``int`` address or
+``None``; nothing is copied, converted or computed here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsgmv.so")
+
+F16, BF16 = 0, 1
+PATH_AUTO, PATH_VECTOR, PATH_MATRIX = 0, 1, 2
+
+
+class SgmvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({sgmv_status_string(status)})")
+
+
+class SgmvProblem(ctypes.Structure):
+    """Mirror of ``struct sgmv_problem``."""
+    _fields_ = [
+        ("dtype", ctypes.c_int32),
+        ("h_in", ctypes.c_int32),
+        ("h_out", ctypes.c_int32),
+        ("r", ctypes.c_int32),
+        ("num_layers", ctypes.c_int32),
+        ("n_tokens", ctypes.c_int32),
+        ("max_seg_len", ctypes.c_int32),
+        ("path", ctypes.c_int32),
+        ("ksplit", ctypes.c_int32),
+        ("expand_threads", ctypes.c_int32),
+        ("workspace", ctypes.c_void_p),
+        ("workspace_bytes", ctypes.c_size_t),
+    ]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def _load():
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2310_18547_amd.build` "
+            "(there is no fallback implementation)")
+    L = ctypes.CDLL(_LIB_PATH)
+    c = ctypes
+    P = c.POINTER(SgmvProblem)
+    L.sgmv_status_string.argtypes = [c.c_int]
+    L.sgmv_status_string.restype = c.c_char_p
+    L.sgmv_workspace_bytes.argtypes = [c.c_int32, c.c_int32]
+    L.sgmv_workspace_bytes.restype = c.c_size_t
+    L.sgmv_validate_segments.argtypes = [c.c_void_p, c.c_int32, c.c_int32]
+    L.sgmv_validate_segments.restype = c.c_int
+    L.sgmv_shrink.argtypes = [P, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32,
+                              c.c_int32, c.c_void_p]
+    L.sgmv_shrink.restype = c.c_int
+    L.sgmv_expand.argtypes = [P, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32,
+                              c.c_int32, c.c_float, c.c_void_p]
+    L.sgmv_expand.restype = c.c_int
+    L.sgmv_add_lora.argtypes = [P, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+                                c.c_int32, c.c_int32, c.c_float, c.c_void_p]
+    L.sgmv_add_lora.restype = c.c_int
+    return L
+
+
+lib = _load()
+
+
+def _addr(a) -> Optional[int]:
+    if a is None:
+        return None
+    if isinstance(a, int):
+        return a
+    if hasattr(a, "data_ptr"):
+        return a.data_ptr()
+    if hasattr(a, "ctypes"):          # host numpy array (sgmv_validate_segments only)
+        return a.ctypes.data
+    raise TypeError(f"cannot take the address of {type(a)!r}")
+
+
+def _stream(s) -> Optional[int]:
+    if s is None or isinstance(s, int):
+        return s
+    return s.cuda_stream              # a torch.cuda.Stream
+
+
+def make_problem(dtype: int, h_in: int, h_out: int, r: int, num_layers: int, n_tokens: int,
+                 workspace=None, workspace_bytes: int = 0, max_seg_len: int = 0,
+                 path: int = PATH_AUTO, ksplit: int = 0, expand_threads: int = 0) -> SgmvProblem:
+    return SgmvProblem(dtype, h_in, h_out, r, num_layers, n_tokens, max_seg_len, path, ksplit,
+                       expand_threads, _addr(workspace), workspace_bytes)
+
+
+def sgmv_status_string(status: int) -> str:
+    return lib.sgmv_status_string(int(status)).decode()
+
+
+def sgmv_workspace_bytes(n_tokens: int, r: int) -> int:
+    return int(lib.sgmv_workspace_bytes(n_tokens, r))
+
+
+def sgmv_validate_segments(host_seg_starts, n_segs: int, n_tokens: int) -> int:
+    return lib.sgmv_validate_segments(_addr(host_seg_starts), n_segs, n_tokens)
+
+
+def sgmv_shrink(p: SgmvProblem, v, x, A_ptrs, seg_starts, n_segs: int, layer_idx: int,
+                stream=None, check: bool = True) -> int:
+    rc = lib.sgmv_shrink(ctypes.byref(p), _addr(v), _addr(x), _addr(A_ptrs), _addr(seg_starts),
+                         n_segs, layer_idx, _stream(stream))
+    if check and rc != 0:
+        raise SgmvError(rc, "sgmv_shrink")
+    return rc
+
+
+def sgmv_expand(p: SgmvProblem, y, v, B_ptrs, seg_starts, n_segs: int, layer_idx: int,
+                scale: float, stream=None, check: bool = True) -> int:
+    rc = lib.sgmv_expand(ctypes.byref(p), _addr(y), _addr(v), _addr(B_ptrs), _addr(seg_starts),
+                         n_segs, layer_idx, scale, _stream(stream))
+    if check and rc != 0:
+        raise SgmvError(rc, "sgmv_expand")
+    return rc
+
+
+def sgmv_add_lora(p: SgmvProblem, y, x, A_ptrs, B_ptrs, seg_starts, n_segs: int, layer_idx: int,
+                  scale: float, stream=None, check: bool = True) -> int:
+    rc = lib.sgmv_add_lora(ctypes.byref(p), _addr(y), _addr(x), _addr(A_ptrs), _addr(B_ptrs),
+                           _addr(seg_starts), n_segs, layer_idx, scale, _stream(stream))
+    if check and rc != 0:
+        raise SgmvError(rc, "sgmv_add_lora")
+    return rc

@@ -1,0 +1,214 @@
+// C ABI of libsgmv: argument checks, launch-shape choice, kernel dispatch.
+// Everything that computes runs in the kernels; this file only validates and
+// enqueues.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/sgmv.h"
+#include "launch.h"
+
+namespace {
+
+using namespace sgmv;
+
+constexpr int kMinSplitCap = 16;       // the workspace always allows this many slices
+constexpr int kTargetWorkgroups = 512; // about two workgroups per compute unit
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// Most split-K slices the workspace is sized for at a given batch.
+int split_cap(int n_tokens) {
+  int c = ceil_div(16384, n_tokens > 0 ? n_tokens : 1);
+  if (c > kMaxKSplit) c = kMaxKSplit;
+  if (c < kMinSplitCap) c = kMinSplitCap;
+  return c;
+}
+
+int check_common(const sgmv_problem* p, const int32_t* seg_starts, int32_t n_segs,
+                 int32_t layer_idx, bool need_in, bool need_out) {
+  if (p == nullptr) return SGMV_ERR_NULL;
+  if (p->dtype != SGMV_F16 && p->dtype != SGMV_BF16) return SGMV_ERR_UNSUPPORTED;
+  if (n_segs < 0 || p->n_tokens < 0 || p->num_layers <= 0 || p->max_seg_len < 0)
+    return SGMV_ERR_SHAPE;
+  if (p->r <= 0 || (need_in && p->h_in <= 0) || (need_out && p->h_out <= 0)) return SGMV_ERR_SHAPE;
+  if (p->r != 8 && p->r != 16 && p->r != 32 && p->r != 64) return SGMV_ERR_UNSUPPORTED;
+  if ((need_in && (p->h_in % 8) != 0) || (need_out && (p->h_out % 8) != 0))
+    return SGMV_ERR_UNSUPPORTED;
+  if (p->path != SGMV_PATH_AUTO && p->path != SGMV_PATH_VECTOR && p->path != SGMV_PATH_MATRIX)
+    return SGMV_ERR_UNSUPPORTED;
+  if (p->ksplit < 0 || p->ksplit > kMaxKSplit) return SGMV_ERR_UNSUPPORTED;
+  if (p->expand_threads != 0 && p->expand_threads != 64 && p->expand_threads != 128 &&
+      p->expand_threads != 256)
+    return SGMV_ERR_UNSUPPORTED;
+  if (layer_idx < 0 || layer_idx >= p->num_layers) return SGMV_ERR_RANGE;
+  if (n_segs > 0 && p->n_tokens > 0 && seg_starts == nullptr) return SGMV_ERR_NULL;
+  return SGMV_OK;
+}
+
+int check_workspace(const sgmv_problem* p) {
+  if (p->workspace == nullptr) return SGMV_ERR_WORKSPACE;
+  if (!aligned(p->workspace, 256)) return SGMV_ERR_ALIGN;
+  if (p->workspace_bytes < sgmv_workspace_bytes(p->n_tokens, p->r)) return SGMV_ERR_WORKSPACE;
+  return SGMV_OK;
+}
+
+// Split-K shape: ksplit slices of kslice elements, kslice a multiple of 8 and at
+// most kMaxKSlice, no slice empty.  Returns false when h_in is too wide for the
+// workspace's slice count.
+bool choose_split(const sgmv_problem* p, int n_segs, int* ksplit, int* kslice) {
+  const int cap = split_cap(p->n_tokens);
+  const int need = ceil_div(p->h_in, kMaxKSlice);
+  if (need > cap) return false;
+  int s = p->ksplit > 0 ? p->ksplit : ceil_div(kTargetWorkgroups, n_segs);
+  const int most = p->h_in / 64 > 0 ? p->h_in / 64 : 1;  // keep slices >= 64 elements
+  if (s > most) s = most;
+  if (s > cap) s = cap;
+  if (s < need) s = need;
+  int len = ceil_div(ceil_div(p->h_in, s), 8) * 8;
+  *kslice = len;
+  *ksplit = ceil_div(p->h_in, len);
+  return true;
+}
+
+int choose_expand_threads(const sgmv_problem* p, int n_segs) {
+  if (p->expand_threads) return p->expand_threads;
+  const int sizes[3] = {256, 128, 64};
+  for (int i = 0; i < 3; ++i)
+    if ((long long)n_segs * ceil_div(p->h_out, sizes[i] * 8) >= kTargetWorkgroups / 2 ||
+        i == 2)
+      return sizes[i];
+  return 64;
+}
+
+ShrinkArgs make_shrink(const sgmv_problem* p, const void* x, const void* const* A_ptrs,
+                       const int32_t* seg_starts, int n_segs, int layer_idx) {
+  ShrinkArgs a;
+  a.bf16 = p->dtype == SGMV_BF16;
+  a.r = p->r;
+  a.h_in = p->h_in;
+  a.n_tokens = p->n_tokens;
+  a.n_segs = n_segs;
+  a.ksplit = a.kslice = 0;
+  a.max_seg_len = p->max_seg_len;
+  a.layer_off = (long long)layer_idx * p->h_in * p->r;
+  a.x = x;
+  a.A_ptrs = A_ptrs;
+  a.seg_starts = seg_starts;
+  a.partials = static_cast<float*>(p->workspace);
+  return a;
+}
+
+ExpandArgs make_expand(const sgmv_problem* p, void* y, const float* v_parts, int nparts,
+                       const void* const* A_ptrs, const void* const* B_ptrs,
+                       const int32_t* seg_starts, int n_segs, int layer_idx, float scale) {
+  ExpandArgs a;
+  a.bf16 = p->dtype == SGMV_BF16;
+  a.r = p->r;
+  a.h_out = p->h_out;
+  a.n_tokens = p->n_tokens;
+  a.n_segs = n_segs;
+  a.threads = choose_expand_threads(p, n_segs);
+  a.max_seg_len = p->max_seg_len;
+  a.layer_off = (long long)layer_idx * p->r * p->h_out;
+  a.y = y;
+  a.v_parts = v_parts;
+  a.nparts = nparts;
+  a.A_ptrs = A_ptrs;
+  a.B_ptrs = B_ptrs;
+  a.seg_starts = seg_starts;
+  a.scale = scale;
+  return a;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* sgmv_status_string(int status) {
+  switch (status) {
+    case SGMV_OK: return "ok";
+    case SGMV_ERR_NULL: return "a required pointer is NULL";
+    case SGMV_ERR_SHAPE: return "invalid size";
+    case SGMV_ERR_UNSUPPORTED: return "unsupported dtype, rank, width or option";
+    case SGMV_ERR_ALIGN: return "pointer not sufficiently aligned";
+    case SGMV_ERR_WORKSPACE: return "workspace missing or too small";
+    case SGMV_ERR_RANGE: return "layer_idx out of range";
+    case SGMV_ERR_LAUNCH: return "kernel launch failed";
+  }
+  return "unknown status";
+}
+
+size_t sgmv_workspace_bytes(int32_t n_tokens, int32_t r) {
+  if (n_tokens <= 0 || r <= 0) return 0;
+  return (size_t)split_cap(n_tokens) * (size_t)n_tokens * (size_t)r * sizeof(float);
+}
+
+int sgmv_validate_segments(const int32_t* host_seg_starts, int32_t n_segs, int32_t n_tokens) {
+  if (n_segs < 0 || n_tokens < 0) return SGMV_ERR_SHAPE;
+  if (host_seg_starts == nullptr) return SGMV_ERR_NULL;
+  if (host_seg_starts[0] != 0) return SGMV_ERR_SHAPE;
+  for (int32_t i = 0; i < n_segs; ++i)
+    if (host_seg_starts[i + 1] < host_seg_starts[i]) return SGMV_ERR_SHAPE;
+  if (host_seg_starts[n_segs] != n_tokens) return SGMV_ERR_SHAPE;
+  return SGMV_OK;
+}
+
+int sgmv_shrink(const sgmv_problem* p, float* v, const void* x, const void* const* A_ptrs,
+                const int32_t* seg_starts, int32_t n_segs, int32_t layer_idx, void* stream) {
+  int rc = check_common(p, seg_starts, n_segs, layer_idx, true, false);
+  if (rc != SGMV_OK) return rc;
+  if (n_segs == 0 || p->n_tokens == 0) return SGMV_OK;
+  if (v == nullptr || x == nullptr || A_ptrs == nullptr) return SGMV_ERR_NULL;
+  if (!aligned(v, 16) || !aligned(x, 16)) return SGMV_ERR_ALIGN;
+  rc = check_workspace(p);
+  if (rc != SGMV_OK) return rc;
+  if (p->path == SGMV_PATH_MATRIX) return SGMV_ERR_UNSUPPORTED;
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  ShrinkArgs a = make_shrink(p, x, A_ptrs, seg_starts, n_segs, layer_idx);
+  if (!choose_split(p, n_segs, &a.ksplit, &a.kslice)) return SGMV_ERR_UNSUPPORTED;
+  if (launch_shrink_vector(a, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+  if (launch_shrink_reduce(v, a, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+  return SGMV_OK;
+}
+
+int sgmv_expand(const sgmv_problem* p, void* y, const float* v, const void* const* B_ptrs,
+                const int32_t* seg_starts, int32_t n_segs, int32_t layer_idx, float scale,
+                void* stream) {
+  int rc = check_common(p, seg_starts, n_segs, layer_idx, false, true);
+  if (rc != SGMV_OK) return rc;
+  if (n_segs == 0 || p->n_tokens == 0) return SGMV_OK;
+  if (y == nullptr || v == nullptr || B_ptrs == nullptr) return SGMV_ERR_NULL;
+  if (!aligned(v, 16) || !aligned(y, 16)) return SGMV_ERR_ALIGN;
+  if (p->path == SGMV_PATH_MATRIX) return SGMV_ERR_UNSUPPORTED;
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  ExpandArgs a = make_expand(p, y, v, 1, nullptr, B_ptrs, seg_starts, n_segs, layer_idx, scale);
+  if (launch_expand_vector(a, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+  return SGMV_OK;
+}
+
+int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x, const void* const* A_ptrs,
+                  const void* const* B_ptrs, const int32_t* seg_starts, int32_t n_segs,
+                  int32_t layer_idx, float scale, void* stream) {
+  int rc = check_common(p, seg_starts, n_segs, layer_idx, true, true);
+  if (rc != SGMV_OK) return rc;
+  if (n_segs == 0 || p->n_tokens == 0) return SGMV_OK;
+  if (y == nullptr || x == nullptr || A_ptrs == nullptr || B_ptrs == nullptr) return SGMV_ERR_NULL;
+  if (!aligned(y, 16) || !aligned(x, 16)) return SGMV_ERR_ALIGN;
+  rc = check_workspace(p);
+  if (rc != SGMV_OK) return rc;
+  if (p->path == SGMV_PATH_MATRIX) return SGMV_ERR_UNSUPPORTED;
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  ShrinkArgs s = make_shrink(p, x, A_ptrs, seg_starts, n_segs, layer_idx);
+  if (!choose_split(p, n_segs, &s.ksplit, &s.kslice)) return SGMV_ERR_UNSUPPORTED;
+  if (launch_shrink_vector(s, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+  ExpandArgs e = make_expand(p, y, s.partials, s.ksplit, A_ptrs, B_ptrs, seg_starts, n_segs,
+                             layer_idx, scale);
+  if (launch_expand_vector(e, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+  return SGMV_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,81 @@
+// Device-side helpers shared by the SGMV kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sgmv {
+
+struct F16 {};
+struct BF16 {};
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+// Two packed 16-bit values -> two fp32 values (element 0 is the low half).
+template <class DT>
+__device__ __forceinline__ void unpack2(uint32_t u, float& lo, float& hi);
+
+template <>
+__device__ __forceinline__ void unpack2<F16>(uint32_t u, float& lo, float& hi) {
+  half2_t h = __builtin_bit_cast(half2_t, u);
+  lo = (float)h.x;
+  hi = (float)h.y;
+}
+template <>
+__device__ __forceinline__ void unpack2<BF16>(uint32_t u, float& lo, float& hi) {
+  lo = __uint_as_float(u << 16);
+  hi = __uint_as_float(u & 0xFFFF0000u);
+}
+
+template <class DT>
+__device__ __forceinline__ float decode1(uint16_t b);
+template <>
+__device__ __forceinline__ float decode1<F16>(uint16_t b) {
+  return (float)__builtin_bit_cast(_Float16, b);
+}
+template <>
+__device__ __forceinline__ float decode1<BF16>(uint16_t b) {
+  return __uint_as_float((uint32_t)b << 16);
+}
+
+// fp32 -> 16 bit, round to nearest even.
+template <class DT>
+__device__ __forceinline__ uint32_t encode1(float f);
+template <>
+__device__ __forceinline__ uint32_t encode1<F16>(float f) {
+  return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);
+}
+template <>
+__device__ __forceinline__ uint32_t encode1<BF16>(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;  // keep NaN a NaN
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+template <class DT>
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+  return encode1<DT>(lo) | (encode1<DT>(hi) << 16);
+}
+
+// Eight packed 16-bit values (one 128-bit load) -> eight fp32 values.
+template <class DT>
+__device__ __forceinline__ void unpack8(const uint4& q, float (&f)[8]) {
+  unpack2<DT>(q.x, f[0], f[1]);
+  unpack2<DT>(q.y, f[2], f[3]);
+  unpack2<DT>(q.z, f[4], f[5]);
+  unpack2<DT>(q.w, f[6], f[7]);
+}
+
+__device__ __forceinline__ uint4 load128(const void* p) {
+  return *reinterpret_cast<const uint4*>(p);
+}
+// Streaming variant for data that is read exactly once (adapter weights).
+__device__ __forceinline__ uint4 load128_stream(const void* p) {
+  const uint32_t* q = reinterpret_cast<const uint32_t*>(p);
+  typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+  u4 v = __builtin_nontemporal_load(reinterpret_cast<const u4*>(q));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store128(void* p, const uint4& v) {
+  *reinterpret_cast<uint4*>(p) = v;
+}
+
+}  // namespace sgmv

@@ -1,0 +1,44 @@
+// Host-side launch descriptors shared by the C ABI and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sgmv {
+
+// Longest k-slice one shrink workgroup stages in LDS (elements of one x row).
+constexpr int kMaxKSlice = 2048;
+// Upper bound of the split-K factor.
+constexpr int kMaxKSplit = 64;
+
+struct ShrinkArgs {
+  bool bf16;
+  int r, h_in, n_tokens, n_segs;
+  int ksplit, kslice;        // ksplit slices of kslice elements cover h_in, none empty
+  int max_seg_len;           // hint, 0 = unknown
+  long long layer_off;       // elements to add to every A pointer
+  const void* x;
+  const void* const* A_ptrs;
+  const int32_t* seg_starts;
+  float* partials;           // [ksplit][n_tokens][r]
+};
+
+struct ExpandArgs {
+  bool bf16;
+  int r, h_out, n_tokens, n_segs;
+  int threads;               // vector path: workgroup size
+  int max_seg_len;           // hint, 0 = unknown
+  long long layer_off;       // elements to add to every B pointer
+  void* y;
+  const float* v_parts;      // [nparts][n_tokens][r]
+  int nparts;
+  const void* const* A_ptrs; // may be nullptr
+  const void* const* B_ptrs;
+  const int32_t* seg_starts;
+  float scale;
+};
+
+hipError_t launch_shrink_vector(const ShrinkArgs& a, hipStream_t st);
+hipError_t launch_shrink_reduce(float* v, const ShrinkArgs& a, hipStream_t st);
+hipError_t launch_expand_vector(const ExpandArgs& a, hipStream_t st);
+
+}  // namespace sgmv

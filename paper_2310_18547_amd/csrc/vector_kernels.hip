@@ -1,0 +1,354 @@
+// Bandwidth path of SGMV for short segments (decode-shaped batches), gfx950.
+//
+// When every request brings its own adapter the per-segment product is a
+// matrix-vector product and the operator is bound by streaming the adapter
+// weights from HBM (last paragraph of the paper's SGMV section: "totally
+// IO-bound", no matrix units).  These kernels therefore use the vector ALUs
+// only and are organised around keeping as many 128-bit weight loads in flight
+// as possible:
+//
+//   shrink  one workgroup per (segment, k-slice): split-K over h_in (the paper's
+//           kernel-schedule paragraph uses Split-K for the thin output too).
+//           Every lane issues all of its weight loads before it consumes any,
+//           accumulates eight rank columns in fp32, then the lanes are summed
+//           with a transposing butterfly and the waves through LDS.  Each
+//           slice writes its partial sums to the workspace; nothing is
+//           accumulated with atomics, so results are deterministic.  The
+//           consumer (expand, or the small reduce kernel) adds the slices in
+//           a fixed order -- this replaces the grid synchronisation and
+//           cross-block reduction of the paper's schedule.
+//   expand  one workgroup per (segment, column block): the weight is split
+//           along the output features (same as the paper's expand schedule).
+//           The r-wide v rows are summed from the split-K partials into LDS
+//           while the B_i loads are already in flight; y is read, updated in
+//           fp32 and rounded once.
+//
+// The segment lookup (row range and weight pointers) is resolved once per
+// workgroup from wave-uniform values.
+#include "device_common.h"
+#include "launch.h"
+
+namespace sgmv {
+
+// Sum eight per-lane accumulators over all lanes that hold the same rank
+// columns.  Lane l of a wave works on column group (l % LPR); lanes that differ
+// in the bits above log2(LPR) hold partial sums of the same eight columns.
+// Three exchange steps halve the number of live values per lane (8 -> 4 -> 2
+// -> 1) while doubling the span each value covers; plain butterflies finish.
+// On return every lane holds the complete sum of column
+//   (l % LPR) * 8 + e_out.
+template <int LPR>
+__device__ __forceinline__ float reduce_lanes8(const float (&a)[8], int lane, int& e_out) {
+  constexpr int M1 = LPR, M2 = LPR * 2, M3 = LPR * 4;
+  float b[4], c[2], d;
+  bool up = (lane & M1) != 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float send = up ? a[i] : a[i + 4];
+    float keep = up ? a[i + 4] : a[i];
+    b[i] = keep + __shfl_xor(send, M1, 64);
+  }
+  up = (lane & M2) != 0;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    float send = up ? b[i] : b[i + 2];
+    float keep = up ? b[i + 2] : b[i];
+    c[i] = keep + __shfl_xor(send, M2, 64);
+  }
+  up = (lane & M3) != 0;
+  {
+    float send = up ? c[0] : c[1];
+    float keep = up ? c[1] : c[0];
+    d = keep + __shfl_xor(send, M3, 64);
+  }
+#pragma unroll
+  for (int m = M3 * 2; m < 64; m <<= 1) d += __shfl_xor(d, m, 64);
+  e_out = ((lane & M1) ? 4 : 0) | ((lane & M2) ? 2 : 0) | ((lane & M3) ? 1 : 0);
+  return d;
+}
+
+// ---------------------------------------------------------------- shrink
+//
+// grid = (n_segs, ksplit).  Slice s covers k in [s*kslice, min(h_in, (s+1)*kslice)).
+// The slice of A_i is one contiguous run of kslice*R elements; 128-bit chunk q
+// of it holds row k = q / LPR, columns (q % LPR)*8 .. +7, LPR = R/8.
+// partials is [ksplit][n_tokens][R] fp32.
+template <class DT, int R, int NT, int U, int RB>
+__global__ __launch_bounds__(NT) void shrink_vector_kernel(
+    const uint16_t* __restrict__ x, const uint16_t* const* __restrict__ A_ptrs,
+    const int32_t* __restrict__ seg_starts, float* __restrict__ partials, int h_in, int kslice,
+    int n_tokens, long long layer_off) {
+  constexpr int LPR = R / 8;
+  constexpr int NW = NT / 64;
+  static_assert(NT % 64 == 0 && NT % LPR == 0, "bad workgroup size");
+  static_assert(NT >= RB * R, "write-out needs one thread per (row, column)");
+  __shared__ __align__(16) uint16_t xs[RB][kMaxKSlice];
+  __shared__ float red[NW][RB][R];
+
+  const int seg = blockIdx.x, s = blockIdx.y, tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
+  if (lo >= hi) return;
+  const uint16_t* A = A_ptrs[seg];
+  if (A == nullptr) return;
+  const int k0 = s * kslice;
+  const int klen = min(h_in, k0 + kslice) - k0;
+  if (klen <= 0) return;
+  A += layer_off + (long long)k0 * R;
+  const int nchunks = klen * LPR;
+  const int cpr = klen >> 3;  // 128-bit chunks per x row slice
+
+  for (int row0 = lo; row0 < hi; row0 += RB) {
+    const int nrows = min(RB, hi - row0);
+    float acc[RB][8];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[rb][e] = 0.f;
+
+    if (row0 != lo) __syncthreads();  // xs / red are reused
+
+    for (int base = 0; base < nchunks; base += NT * U) {
+      uint4 a[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int q = base + u * NT + tid;
+        a[u] = (q < nchunks) ? load128_stream(A + (long long)q * 8) : make_uint4(0, 0, 0, 0);
+      }
+      if (base == 0) {
+        // stage this row block's slice of x while the weight loads are in flight
+        for (int idx = tid; idx < nrows * cpr; idx += NT) {
+          const int rr = idx / cpr, c = idx - rr * cpr;
+          store128(&xs[rr][c * 8], load128(x + (long long)(row0 + rr) * h_in + k0 + c * 8));
+        }
+        __syncthreads();
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int q = base + u * NT + tid;
+        if (q < nchunks) {
+          const int kk = q / LPR;
+          float af[8];
+          unpack8<DT>(a[u], af);
+#pragma unroll
+          for (int rb = 0; rb < RB; ++rb) {
+            if (rb < nrows) {
+              const float xv = decode1<DT>(xs[rb][kk]);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) acc[rb][e] = fmaf(xv, af[e], acc[rb][e]);
+            }
+          }
+        }
+      }
+    }
+
+    // lanes -> one value per column, waves -> LDS
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      if (rb < nrows) {
+        int e;
+        const float d = reduce_lanes8<LPR>(acc[rb], lane, e);
+        if (lane < R) red[wave][rb][(lane % LPR) * 8 + e] = d;
+      }
+    }
+    __syncthreads();
+    if (tid < nrows * R) {
+      const int rb = tid / R, j = tid - rb * R;
+      float sum = red[0][rb][j];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) sum += red[w][rb][j];
+      partials[((long long)s * n_tokens + row0 + rb) * R + j] = sum;
+    }
+  }
+}
+
+// v[row][j] += sum over slices of partials[s][row][j], slices in ascending order.
+// grid = n_segs; rows of segments without an adapter are left alone.
+template <int R>
+__global__ __launch_bounds__(256) void shrink_reduce_kernel(
+    float* __restrict__ v, const float* __restrict__ partials,
+    const uint16_t* const* __restrict__ A_ptrs, const int32_t* __restrict__ seg_starts, int ksplit,
+    int n_tokens) {
+  const int seg = blockIdx.x;
+  const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
+  if (lo >= hi || A_ptrs[seg] == nullptr) return;
+  const long long first = (long long)lo * R, count = (long long)(hi - lo) * R;
+  for (long long i = threadIdx.x; i < count; i += blockDim.x) {
+    float sum = 0.f;
+    for (int s = 0; s < ksplit; ++s) sum += partials[(long long)s * n_tokens * R + first + i];
+    v[first + i] += sum;
+  }
+}
+
+// ---------------------------------------------------------------- expand
+//
+// grid = (n_segs, ceil(h_out / (NT*8))).  A lane owns eight consecutive output
+// columns.  v_parts is [nparts][n_tokens][R] fp32; the rows' v is the sum of the
+// parts in ascending order (nparts = 1 for a caller-supplied v).
+// A_ptrs may be nullptr (stand-alone expand); when given, a segment whose A
+// pointer is NULL is skipped like one whose B pointer is NULL.
+template <class DT, int R, int NT, int RB>
+__global__ __launch_bounds__(NT) void expand_vector_kernel(
+    uint16_t* __restrict__ y, const float* __restrict__ v_parts, int nparts,
+    const uint16_t* const* __restrict__ A_ptrs, const uint16_t* const* __restrict__ B_ptrs,
+    const int32_t* __restrict__ seg_starts, int h_out, int n_tokens, long long layer_off,
+    float scale) {
+  constexpr int JC = R < 16 ? R : 16;  // weight rows held in registers at a time
+  __shared__ float vs[RB][R];
+
+  const int seg = blockIdx.x, tid = threadIdx.x;
+  const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
+  if (lo >= hi) return;
+  const uint16_t* B = B_ptrs[seg];
+  if (B == nullptr) return;
+  if (A_ptrs != nullptr && A_ptrs[seg] == nullptr) return;
+  const int c0 = (blockIdx.y * NT + tid) * 8;
+  const bool active = c0 < h_out;
+  B += layer_off + c0;
+
+  for (int row0 = lo; row0 < hi; row0 += RB) {
+    const int nrows = min(RB, hi - row0);
+
+    // first weight rows: issue before waiting for v
+    uint4 b[JC];
+#pragma unroll
+    for (int j = 0; j < JC; ++j)
+      b[j] = active ? load128_stream(B + (long long)j * h_out) : make_uint4(0, 0, 0, 0);
+    uint4 yq[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+      if (active && rb < nrows) yq[rb] = load128(y + (long long)(row0 + rb) * h_out + c0);
+
+    if (row0 != lo) __syncthreads();  // vs is reused
+    for (int idx = tid; idx < nrows * R; idx += NT) {
+      const int rr = idx / R, j = idx - rr * R;
+      const float* src = v_parts + (long long)(row0 + rr) * R + j;
+      float sum = src[0];
+      for (int s = 1; s < nparts; ++s) sum += src[(long long)s * n_tokens * R];
+      vs[rr][j] = sum;
+    }
+    __syncthreads();
+
+    float acc[RB][8];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[rb][e] = 0.f;
+
+#pragma unroll
+    for (int jc = 0; jc < R; jc += JC) {
+      if (jc != 0) {
+#pragma unroll
+        for (int j = 0; j < JC; ++j)
+          b[j] = active ? load128_stream(B + (long long)(jc + j) * h_out) : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int j = 0; j < JC; ++j) {
+        float bf[8];
+        unpack8<DT>(b[j], bf);
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+          if (rb < nrows) {
+            const float vj = vs[rb][jc + j];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[rb][e] = fmaf(vj, bf[e], acc[rb][e]);
+          }
+        }
+      }
+    }
+
+    if (active) {
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        if (rb < nrows) {
+          float yf[8];
+          unpack8<DT>(yq[rb], yf);
+          uint4 out;
+          out.x = pack2<DT>(yf[0] + scale * acc[rb][0], yf[1] + scale * acc[rb][1]);
+          out.y = pack2<DT>(yf[2] + scale * acc[rb][2], yf[3] + scale * acc[rb][3]);
+          out.z = pack2<DT>(yf[4] + scale * acc[rb][4], yf[5] + scale * acc[rb][5]);
+          out.w = pack2<DT>(yf[6] + scale * acc[rb][6], yf[7] + scale * acc[rb][7]);
+          store128(y + (long long)(row0 + rb) * h_out + c0, out);
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------- launchers
+
+template <class DT, int R>
+static hipError_t launch_shrink_t(const ShrinkArgs& a, hipStream_t st) {
+  constexpr int NT = 256, U = 8, RB = 4;
+  dim3 grid((unsigned)a.n_segs, (unsigned)a.ksplit);
+  hipLaunchKernelGGL((shrink_vector_kernel<DT, R, NT, U, RB>), grid, dim3(NT), 0, st,
+                     (const uint16_t*)a.x, (const uint16_t* const*)a.A_ptrs, a.seg_starts,
+                     a.partials, a.h_in, a.kslice, a.n_tokens, a.layer_off);
+  return hipGetLastError();
+}
+
+template <class DT>
+static hipError_t launch_shrink_r(const ShrinkArgs& a, hipStream_t st) {
+  switch (a.r) {
+    case 8: return launch_shrink_t<DT, 8>(a, st);
+    case 16: return launch_shrink_t<DT, 16>(a, st);
+    case 32: return launch_shrink_t<DT, 32>(a, st);
+    case 64: return launch_shrink_t<DT, 64>(a, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_shrink_vector(const ShrinkArgs& a, hipStream_t st) {
+  return a.bf16 ? launch_shrink_r<BF16>(a, st) : launch_shrink_r<F16>(a, st);
+}
+
+hipError_t launch_shrink_reduce(float* v, const ShrinkArgs& a, hipStream_t st) {
+  dim3 grid((unsigned)a.n_segs);
+  const uint16_t* const* ap = (const uint16_t* const*)a.A_ptrs;
+  switch (a.r) {
+    case 8: hipLaunchKernelGGL(shrink_reduce_kernel<8>, grid, dim3(256), 0, st, v, a.partials, ap, a.seg_starts, a.ksplit, a.n_tokens); break;
+    case 16: hipLaunchKernelGGL(shrink_reduce_kernel<16>, grid, dim3(256), 0, st, v, a.partials, ap, a.seg_starts, a.ksplit, a.n_tokens); break;
+    case 32: hipLaunchKernelGGL(shrink_reduce_kernel<32>, grid, dim3(256), 0, st, v, a.partials, ap, a.seg_starts, a.ksplit, a.n_tokens); break;
+    case 64: hipLaunchKernelGGL(shrink_reduce_kernel<64>, grid, dim3(256), 0, st, v, a.partials, ap, a.seg_starts, a.ksplit, a.n_tokens); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+template <class DT, int R, int NT>
+static hipError_t launch_expand_t(const ExpandArgs& a, hipStream_t st) {
+  constexpr int RB = 4;
+  dim3 grid((unsigned)a.n_segs, (unsigned)((a.h_out + NT * 8 - 1) / (NT * 8)));
+  hipLaunchKernelGGL((expand_vector_kernel<DT, R, NT, RB>), grid, dim3(NT), 0, st,
+                     (uint16_t*)a.y, a.v_parts, a.nparts, (const uint16_t* const*)a.A_ptrs,
+                     (const uint16_t* const*)a.B_ptrs, a.seg_starts, a.h_out, a.n_tokens,
+                     a.layer_off, a.scale);
+  return hipGetLastError();
+}
+
+template <class DT, int R>
+static hipError_t launch_expand_nt(const ExpandArgs& a, hipStream_t st) {
+  switch (a.threads) {
+    case 64: return launch_expand_t<DT, R, 64>(a, st);
+    case 128: return launch_expand_t<DT, R, 128>(a, st);
+    case 256: return launch_expand_t<DT, R, 256>(a, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+template <class DT>
+static hipError_t launch_expand_r(const ExpandArgs& a, hipStream_t st) {
+  switch (a.r) {
+    case 8: return launch_expand_nt<DT, 8>(a, st);
+    case 16: return launch_expand_nt<DT, 16>(a, st);
+    case 32: return launch_expand_nt<DT, 32>(a, st);
+    case 64: return launch_expand_nt<DT, 64>(a, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_expand_vector(const ExpandArgs& a, hipStream_t st) {
+  return a.bf16 ? launch_expand_r<BF16>(a, st) : launch_expand_r<F16>(a, st);
+}
+
+}  // namespace sgmv

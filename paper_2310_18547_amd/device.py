@@ -1,0 +1,75 @@
+"""Device-side plumbing: put a host workload into HBM and call the C ABI on it.
+
+PyTorch is used for device allocations, copies and streams only; no tensor
+arithmetic of the operator happens here.
+"""
+from __future__ import annotations
+
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+_DT = {"f16": B.F16, "bf16": B.BF16}
+
+
+def _to_dev(a: np.ndarray, device) -> torch.Tensor:
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    return torch.from_numpy(np.ascontiguousarray(a)).to(device)
+
+
+class DeviceWorkload:
+    """A ``sgmv_workloads.Workload`` resident on one GPU.
+
+    ``n_sets`` independent copies of x / y are kept so that a timed loop can
+    rotate over them (together with the layers) and defeat the on-die caches.
+    """
+
+    def __init__(self, w, device="cuda:0", n_sets: int = 1, max_seg_len_hint: bool = True,
+                 path: int = B.PATH_AUTO, ksplit: int = 0, expand_threads: int = 0):
+        self.w = w
+        self.device = torch.device(device)
+        self.A: List[torch.Tensor] = [_to_dev(a, self.device) for a in w.A]
+        self.B: List[torch.Tensor] = [_to_dev(b, self.device) for b in w.B]
+        a_ptrs = [0 if a < 0 else self.A[a].data_ptr() for a in w.seg_adapter]
+        b_ptrs = [0 if a < 0 else self.B[a].data_ptr() for a in w.seg_adapter]
+        self.A_ptrs = torch.tensor(a_ptrs, dtype=torch.int64, device=self.device)
+        self.B_ptrs = torch.tensor(b_ptrs, dtype=torch.int64, device=self.device)
+        self.seg_starts = _to_dev(w.seg_starts.astype(np.int32), self.device)
+        self.x = [_to_dev(w.x, self.device) for _ in range(n_sets)]
+        self.y0 = _to_dev(w.y0, self.device)
+        self.y = [self.y0.clone() for _ in range(n_sets)]
+        self.ws_bytes = max(B.sgmv_workspace_bytes(w.n_tokens, w.r), 256)
+        self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.device)
+        self.problem = B.make_problem(
+            _DT[w.dtype], w.h_in, w.h_out, w.r, w.num_layers, w.n_tokens,
+            workspace=self.workspace, workspace_bytes=self.ws_bytes,
+            max_seg_len=w.max_seg_len if max_seg_len_hint else 0, path=path, ksplit=ksplit,
+            expand_threads=expand_threads)
+
+    # -- the three entry points, on set `k` ---------------------------------
+    def add_lora(self, layer_idx: int = 0, k: int = 0, stream=None, scale: Optional[float] = None):
+        return B.sgmv_add_lora(self.problem, self.y[k], self.x[k], self.A_ptrs, self.B_ptrs,
+                               self.seg_starts, self.w.n_segs, layer_idx,
+                               self.w.scale if scale is None else scale, stream)
+
+    def shrink(self, v: torch.Tensor, layer_idx: int = 0, k: int = 0, stream=None):
+        return B.sgmv_shrink(self.problem, v, self.x[k], self.A_ptrs, self.seg_starts,
+                             self.w.n_segs, layer_idx, stream)
+
+    def expand(self, v: torch.Tensor, layer_idx: int = 0, k: int = 0, stream=None,
+               scale: Optional[float] = None):
+        return B.sgmv_expand(self.problem, self.y[k], v, self.B_ptrs, self.seg_starts,
+                             self.w.n_segs, layer_idx, self.w.scale if scale is None else scale,
+                             stream)
+
+    def reset_y(self, k: Optional[int] = None):
+        for i in (range(len(self.y)) if k is None else [k]):
+            self.y[i].copy_(self.y0)
+
+    def y_bits(self, k: int = 0) -> np.ndarray:
+        torch.cuda.synchronize(self.device)
+        return self.y[k].cpu().numpy().view(np.uint16)

@@ -10,6 +10,11 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # load what is built; build only if nothing is there
+    lib = os.path.join(ROOT, "paper_2310_18547_amd", "libsgmv.so")
+    if not os.path.exists(lib):
+        from paper_2310_18547_amd.build import build
+        build(verbose=False)
 
 
 def _gpu_present() -> bool:

@@ -1,0 +1,245 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by
+element, on the same seeded inputs.
+
+Bar: |gpu - oracle| <= 2e-3 + 2e-2 |oracle| for floating point (16-bit inputs,
+fp32 accumulation); bit-exact for everything that encodes segment routing.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import sgmv_workloads as wl
+from helpers import decode64, tolerance
+
+pytestmark = pytest.mark.gpu
+
+DTYPES = ["f16", "bf16"]
+
+
+def _dev(w, **kw):
+    from paper_2310_18547_amd.device import DeviceWorkload
+    return DeviceWorkload(w, "cuda:0", **kw)
+
+
+def assert_parity(got_bits, ref_bits, dtype, what=""):
+    got, ref = decode64(got_bits, dtype), decode64(ref_bits, dtype)
+    assert got.shape == ref.shape
+    bad = ~(np.abs(got - ref) <= tolerance(ref))
+    if bad.any():
+        idx = np.argwhere(bad)[0]
+        raise AssertionError(f"{what}: {bad.sum()} of {bad.size} outside tolerance; first at "
+                             f"{tuple(idx)}: gpu={got[tuple(idx)]} oracle={ref[tuple(idx)]}")
+
+
+def run_add_lora(w, layer_idx=0, **kw):
+    d = _dev(w, **kw)
+    d.add_lora(layer_idx)
+    return d.y_bits()
+
+
+def run_two_step(w, layer_idx=0, **kw):
+    d = _dev(w, **kw)
+    v = torch.zeros(w.n_tokens, w.r, dtype=torch.float32, device="cuda:0")
+    d.shrink(v, layer_idx)
+    d.expand(v, layer_idx)
+    return d.y_bits(), v.cpu().numpy()
+
+
+# ---------------------------------------------------------------- config 1
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_tiny_add_lora(dtype):
+    w = wl.tiny(seed=0, dtype=dtype)
+    assert_parity(run_add_lora(w), oracle.run_workload(w), dtype, "tiny add_lora")
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_tiny_shrink_then_expand(dtype):
+    w = wl.tiny(seed=0, dtype=dtype)
+    y, v = run_two_step(w)
+    v_ref = oracle.run_workload(w, op="shrink")
+    assert np.all(np.abs(v - v_ref) <= 2e-3 + 2e-2 * np.abs(v_ref))
+    assert_parity(y, oracle.run_workload(w), dtype, "tiny two-step")
+
+
+def test_shrink_accumulates_into_v():
+    w = wl.tiny(seed=0)
+    d = _dev(w)
+    v = torch.full((w.n_tokens, w.r), 1.5, dtype=torch.float32, device="cuda:0")
+    d.shrink(v)
+    ref = oracle.run_workload(w, op="shrink", v=np.full((w.n_tokens, w.r), 1.5, np.float32))
+    assert np.all(np.abs(v.cpu().numpy() - ref) <= 2e-3 + 2e-2 * np.abs(ref))
+
+
+# ------------------------------------------------------- bit-exact routing
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("hint", [True, False])
+def test_fingerprint_routing_bit_exact(dtype, hint):
+    lens = [1, 0, 3, 2, 0, 0, 5, 1, 9, 4, 1, 1, 17]
+    L = 3
+    w = wl.fingerprint(lens, 256, 192, 16, dtype, num_layers=L)
+    for layer in range(L):
+        ref = oracle.run_workload(w, layer_idx=layer)
+        got = run_add_lora(w, layer, max_seg_len_hint=hint)
+        assert np.array_equal(got, ref), f"layer {layer}"
+        y2, _ = run_two_step(w, layer, max_seg_len_hint=hint)
+        assert np.array_equal(y2, ref)
+
+
+@pytest.mark.parametrize("r", [8, 16, 32, 64])
+def test_fingerprint_all_ranks(r):
+    lens = [2, 1, 1, 6, 0, 3]
+    w = wl.fingerprint(lens, 128, 136, r, "bf16", num_layers=2)
+    ref = oracle.run_workload(w, layer_idx=1)
+    assert np.array_equal(run_add_lora(w, 1), ref)
+
+
+def test_null_adapter_and_empty_segments():
+    w = wl.custom([2, 0, 3, 1, 4], 512, 264, 16, "f16", seed=21)
+    w.seg_adapter = np.asarray([0, 1, -1, 3, 4], np.int64)
+    ref = oracle.run_workload(w)
+    got = run_add_lora(w)
+    assert np.array_equal(got[2:5], w.y0[2:5])          # untouched rows stay bit-identical
+    assert_parity(got, ref, "f16", "null adapter")
+    y2, v = run_two_step(w)
+    assert np.array_equal(y2[2:5], w.y0[2:5]) and np.all(v[2:5] == 0)
+
+
+def test_zero_scale_is_identity_on_bits():
+    w = wl.custom([3, 2], 256, 256, 16, "bf16", seed=22)
+    w.scale = 0.0
+    assert np.array_equal(run_add_lora(w), w.y0)
+
+
+def test_deterministic_run_to_run():
+    w = wl.decode_distinct(batch=16, h_in=1024, r=16, num_layers=1, seed=23)
+    a = run_add_lora(w)
+    for _ in range(3):
+        assert np.array_equal(run_add_lora(w), a)
+
+
+# ---------------------------------------------------------------- config 2
+@pytest.mark.parametrize("batch", [1, 8, 16, 32, 64])
+def test_decode_distinct_llama7b(batch):
+    w = wl.decode_distinct(batch=batch, h_in=4096, r=16, dtype="f16", num_layers=3, seed=batch)
+    for layer in (0, 2):
+        assert_parity(run_add_lora(w, layer), oracle.run_workload(w, layer_idx=layer, n_threads=8),
+                      "f16", f"distinct B={batch} layer {layer}")
+
+
+def test_decode_distinct_full_size_32_layers():
+    # the bench's metric configuration, all 32 layers behind every pointer
+    w = wl.decode_distinct(batch=64, h_in=4096, r=16, dtype="f16", num_layers=32, seed=0)
+    d = _dev(w)
+    for layer in (0, 17, 31):
+        d.reset_y()
+        d.add_lora(layer)
+        assert_parity(d.y_bits(), oracle.run_workload(w, layer_idx=layer, n_threads=8), "f16",
+                      f"metric config layer {layer}")
+
+
+# ---------------------------------------------------------------- config 3
+@pytest.mark.parametrize("kind", ["uniform", "skewed", "identical", "uniform_paper", "skewed_paper"])
+def test_popularity_mixes(kind):
+    w = wl.popularity(kind, batch=64, h_in=4096, r=16, dtype="f16", num_layers=2, seed=5)
+    ref = oracle.run_workload(w, layer_idx=1, n_threads=8)
+    assert_parity(run_add_lora(w, 1), ref, "f16", kind)
+    assert_parity(run_add_lora(w, 1, max_seg_len_hint=False), ref, "f16", kind + " (no hint)")
+
+
+# ---------------------------------------------------------------- config 4
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("h", [4096, 5120])
+@pytest.mark.parametrize("r", [8, 16, 32, 64])
+def test_rank_width_sweep(dtype, h, r):
+    for batch in (1, 16, 64):
+        w = wl.decode_distinct(batch=batch, h_in=h, r=r, dtype=dtype, num_layers=1, seed=r + batch)
+        assert_parity(run_add_lora(w), oracle.run_workload(w, n_threads=8), dtype,
+                      f"sweep h={h} r={r} B={batch} {dtype}")
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("r", [8, 16, 64])
+def test_mlp_shapes_one_sided(dtype, r):
+    # shrink 13824 -> r on its own
+    w = wl.decode_distinct(batch=16, h_in=13824, h_out=8, r=r, dtype=dtype, num_layers=1, seed=r)
+    d = _dev(w)
+    v = torch.zeros(16, r, dtype=torch.float32, device="cuda:0")
+    d.shrink(v)
+    ref = oracle.run_workload(w, op="shrink", n_threads=8)
+    assert np.all(np.abs(v.cpu().numpy() - ref) <= 2e-3 + 2e-2 * np.abs(ref))
+    # expand r -> 13824 on its own
+    w = wl.decode_distinct(batch=16, h_in=8, h_out=13824, r=r, dtype=dtype, num_layers=1, seed=r)
+    vin = np.random.Generator(np.random.PCG64(r)).standard_normal((16, r)).astype(np.float32)
+    d = _dev(w)
+    d.expand(torch.from_numpy(vin).to("cuda:0"))
+    assert_parity(d.y_bits(), oracle.run_workload(w, op="expand", v=vin, n_threads=8), dtype,
+                  f"mlp expand r={r}")
+
+
+# ---------------------------------------------------------------- config 5
+def _row_sample(w, per_seg=6, seed=0):
+    """Sub-problem holding a few rows of every segment (first, last, random)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    rows, lens = [], []
+    for i in range(w.n_segs):
+        lo, hi = int(w.seg_starts[i]), int(w.seg_starts[i + 1])
+        pick = {lo, hi - 1} | set(rng.integers(lo, hi, per_seg).tolist())
+        pick = sorted(pick)
+        rows += pick
+        lens.append(len(pick))
+    sub = wl.custom(lens, w.h_in, w.h_out, w.r, w.dtype, seed=0, seg_adapter=w.seg_adapter)
+    sub.A, sub.B = w.A, w.B
+    sub.x, sub.y0 = w.x[rows].copy(), w.y0[rows].copy()
+    sub.scale, sub.num_layers = w.scale, w.num_layers
+    return rows, sub
+
+
+@pytest.mark.parametrize("r", [16, 64])
+def test_prefill_long_segments_reduced_width(r):
+    # whole output against the oracle at a width the oracle finishes in seconds
+    w = wl.prefill(h_in=1024, h_out=1536, r=r, dtype="bf16", seed=1)
+    assert_parity(run_add_lora(w), oracle.run_workload(w, n_threads=8), "bf16", f"prefill r={r}")
+
+
+@pytest.mark.parametrize("h_out", [8192, 28672])
+@pytest.mark.parametrize("r", [16, 64])
+def test_prefill_full_size_sampled_rows(h_out, r):
+    w = wl.prefill(h_in=8192, h_out=h_out, r=r, dtype="bf16", seed=2)
+    got = run_add_lora(w)
+    rows, sub = _row_sample(w)
+    ref = oracle.run_workload(sub, n_threads=8)
+    assert_parity(got[rows], ref, "bf16", f"prefill 8192x{h_out} r={r}")
+    # rows are only ever modified through the add-on: every row must have moved
+    assert np.all(np.any(got != w.y0, axis=1))
+
+
+# ------------------------------------------------------------- tunables
+@pytest.mark.parametrize("ksplit", [1, 2, 3, 7, 16, 64])
+def test_every_split_k_factor(ksplit):
+    w = wl.custom([1, 2, 5, 1], 2048, 512, 16, "f16", seed=31)
+    assert_parity(run_add_lora(w, ksplit=ksplit), oracle.run_workload(w), "f16", f"ksplit {ksplit}")
+
+
+@pytest.mark.parametrize("threads", [64, 128, 256])
+def test_every_expand_workgroup_size(threads):
+    w = wl.custom([1, 2, 5, 1], 512, 2056, 32, "bf16", seed=32)
+    assert_parity(run_add_lora(w, expand_threads=threads), oracle.run_workload(w), "bf16",
+                  f"threads {threads}")
+
+
+def test_guard_rows_are_not_written():
+    # y and the workspace sit inside larger buffers filled with a canary
+    from paper_2310_18547_amd import binding as B
+    w = wl.custom([3, 1, 4], 520, 264, 8, "f16", seed=33)
+    d = _dev(w)
+    T, H = w.n_tokens, w.h_out
+    big = torch.full(((T + 4) * H,), 0x5A5A, dtype=torch.int16, device="cuda:0")
+    ybuf = big[2 * H:(T + 2) * H].view(T, H)
+    ybuf.copy_(d.y0)
+    B.sgmv_add_lora(d.problem, ybuf, d.x[0], d.A_ptrs, d.B_ptrs, d.seg_starts, w.n_segs, 0, 1.0)
+    torch.cuda.synchronize()
+    host = big.cpu().numpy()
+    assert np.all(host[:2 * H] == 0x5A5A) and np.all(host[(T + 2) * H:] == 0x5A5A)
+    assert_parity(host[2 * H:(T + 2) * H].reshape(T, H).view(np.uint16), oracle.run_workload(w),
+                  "f16", "guarded y")
