@@ -23,7 +23,8 @@
  *     whatever A_ptrs[i] / B_ptrs[i] point to) is DEVICE memory owned by the
  *     caller.  The sgmv_problem struct itself is HOST memory, read during the
  *     call only.  The library allocates nothing, frees nothing and keeps no
- *     state between calls.
+ *     state of its own between calls (the single-launch path keeps its
+ *     arrival counters in the caller's workspace, see sgmv_workspace_init).
  *   - x is [n_tokens][h_in], y is [n_tokens][h_out], row-major, 16-bit floats
  *     of type `dtype` (IEEE binary16 or bfloat16), 16-byte aligned.
  *   - A_ptrs[i] points to segment i's shrink weights stacked over layers,
@@ -72,15 +73,19 @@ typedef enum {
   SGMV_ERR_ALIGN = 4,        /* x, y, v or workspace not 16-byte aligned           */
   SGMV_ERR_WORKSPACE = 5,    /* workspace missing or smaller than required         */
   SGMV_ERR_RANGE = 6,        /* layer_idx outside [0, num_layers)                  */
-  SGMV_ERR_LAUNCH = 7        /* the HIP runtime rejected a kernel launch           */
+  SGMV_ERR_LAUNCH = 7,       /* the HIP runtime rejected a kernel launch           */
+  SGMV_ERR_TIMEOUT = 8       /* a workgroup gave up waiting (sgmv_workspace_check) */
 } sgmv_status;
 
 /* Kernel family selection.  AUTO picks from max_seg_len; the others force one
  * family for every segment (all families compute the same result). */
 typedef enum {
   SGMV_PATH_AUTO = 0,
-  SGMV_PATH_VECTOR = 1,      /* bandwidth path: vector ALU, for short segments     */
-  SGMV_PATH_MATRIX = 2       /* MFMA path: for long (prefill-like) segments        */
+  SGMV_PATH_VECTOR = 1,      /* bandwidth path: vector ALU, one launch per step    */
+  SGMV_PATH_MATRIX = 2,      /* MFMA path: for long (prefill-like) segments        */
+  SGMV_PATH_FUSED = 3        /* sgmv_add_lora only: shrink and expand in a single  */
+                             /* launch; needs workspace_ready and 0 < max_seg_len  */
+                             /* <= 16, else SGMV_ERR_UNSUPPORTED                   */
 } sgmv_path;
 
 /* Problem descriptor: plain data, host memory, read during the call only. */
@@ -98,6 +103,10 @@ typedef struct sgmv_problem {
   int32_t ksplit;            /* split-K factor of shrink; 0 = choose automatically  */
   int32_t expand_threads;    /* workgroup size of the vector expand kernel          */
                              /* (64, 128 or 256); 0 = choose automatically          */
+  int32_t workspace_ready;   /* nonzero: sgmv_workspace_init() has been run on this */
+                             /* workspace (and no call on it was ever aborted);     */
+                             /* enables the single-launch path                      */
+  int32_t reserved;          /* must be 0                                           */
   void*   workspace;         /* device scratch, 256-byte aligned, at least          */
   size_t  workspace_bytes;   /*   sgmv_workspace_bytes(n_tokens, r) bytes           */
 } sgmv_problem;
@@ -110,6 +119,22 @@ const char* sgmv_status_string(int status);
  * "Split-K" remark in the paper's kernel-schedule paragraph).  Pure host
  * function.  Returns 0 for n_tokens <= 0. */
 size_t sgmv_workspace_bytes(int32_t n_tokens, int32_t r);
+
+/* Prepare a workspace for the single-launch path of sgmv_add_lora: zero-fills
+ * it with a small kernel on `stream` (so the call may be recorded into a HIP
+ * graph).  The single-launch path keeps per-segment arrival counters in the
+ * workspace and leaves them at zero after every call; run this once after
+ * allocating the workspace, and again if a call using it was ever aborted.
+ * `workspace` is device memory, 256-byte aligned. */
+int sgmv_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+
+/* Synchronous health check of a workspace used by the single-launch path:
+ * waits for `stream`, reads the workspace's error word and returns
+ * SGMV_ERR_TIMEOUT if any workgroup ever gave up its (bounded) wait for a
+ * neighbour's partial sums -- results of that call are then invalid and the
+ * workspace must be re-initialised.  Returns SGMV_OK otherwise.  Not meant for
+ * the hot path. */
+int sgmv_workspace_check(const void* workspace, int32_t n_tokens, int32_t r, void* stream);
 
 /* Host-side check of a HOST copy of the segment index sequence against the
  * segment definition paragraph: n_segs >= 0, seg_starts[0] == 0,
@@ -139,7 +164,9 @@ int sgmv_expand(const sgmv_problem* p, void* y, const float* v,
 
 /* The whole LoRA add-on, y += scale * (x A_i) B_i per segment, i.e. v := 0,
  * shrink, expand in one call; v lives in the workspace in fp32 and is never
- * rounded.  A segment is skipped when either of its pointers is NULL. */
+ * rounded.  A segment is skipped when either of its pointers is NULL.
+ * With workspace_ready set and 0 < max_seg_len <= 16 both steps run in a
+ * single kernel launch; otherwise one launch per step is used. */
 int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x,
                   const void* const* A_ptrs, const void* const* B_ptrs,
                   const int32_t* seg_starts, int32_t n_segs, int32_t layer_idx,

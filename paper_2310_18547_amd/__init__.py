@@ -6,9 +6,10 @@ first use of any of its names and raises ``ImportError`` if the library has not
 been built (``python -m paper_2310_18547_amd.build``).
 """
 _BINDING_NAMES = (
-    "F16", "BF16", "PATH_AUTO", "PATH_VECTOR", "PATH_MATRIX", "SgmvError", "SgmvProblem", "lib",
+    "F16", "BF16", "PATH_AUTO", "PATH_VECTOR", "PATH_MATRIX", "PATH_FUSED", "SgmvError", "SgmvProblem", "lib",
     "library_path", "make_problem", "sgmv_add_lora", "sgmv_expand", "sgmv_shrink",
-    "sgmv_status_string", "sgmv_validate_segments", "sgmv_workspace_bytes",
+    "sgmv_status_string", "sgmv_validate_segments", "sgmv_workspace_bytes", "sgmv_workspace_init",
+    "sgmv_workspace_check",
 )
 __all__ = list(_BINDING_NAMES)
 

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libsgmv.so")
 
 F16, BF16 = 0, 1
-PATH_AUTO, PATH_VECTOR, PATH_MATRIX = 0, 1, 2
+PATH_AUTO, PATH_VECTOR, PATH_MATRIX, PATH_FUSED = 0, 1, 2, 3
 
 
 class SgmvError(RuntimeError):
@@ -36,6 +36,8 @@ class SgmvProblem(ctypes.Structure):
         ("path", ctypes.c_int32),
         ("ksplit", ctypes.c_int32),
         ("expand_threads", ctypes.c_int32),
+        ("workspace_ready", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
         ("workspace", ctypes.c_void_p),
         ("workspace_bytes", ctypes.c_size_t),
     ]
@@ -57,6 +59,10 @@ def _load():
     L.sgmv_status_string.restype = c.c_char_p
     L.sgmv_workspace_bytes.argtypes = [c.c_int32, c.c_int32]
     L.sgmv_workspace_bytes.restype = c.c_size_t
+    L.sgmv_workspace_init.argtypes = [c.c_void_p, c.c_size_t, c.c_void_p]
+    L.sgmv_workspace_init.restype = c.c_int
+    L.sgmv_workspace_check.argtypes = [c.c_void_p, c.c_int32, c.c_int32, c.c_void_p]
+    L.sgmv_workspace_check.restype = c.c_int
     L.sgmv_validate_segments.argtypes = [c.c_void_p, c.c_int32, c.c_int32]
     L.sgmv_validate_segments.restype = c.c_int
     L.sgmv_shrink.argtypes = [P, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32,
@@ -94,9 +100,10 @@ def _stream(s) -> Optional[int]:
 
 def make_problem(dtype: int, h_in: int, h_out: int, r: int, num_layers: int, n_tokens: int,
                  workspace=None, workspace_bytes: int = 0, max_seg_len: int = 0,
-                 path: int = PATH_AUTO, ksplit: int = 0, expand_threads: int = 0) -> SgmvProblem:
+                 path: int = PATH_AUTO, ksplit: int = 0, expand_threads: int = 0,
+                 workspace_ready: int = 0) -> SgmvProblem:
     return SgmvProblem(dtype, h_in, h_out, r, num_layers, n_tokens, max_seg_len, path, ksplit,
-                       expand_threads, _addr(workspace), workspace_bytes)
+                       expand_threads, workspace_ready, 0, _addr(workspace), workspace_bytes)
 
 
 def sgmv_status_string(status: int) -> str:
@@ -105,6 +112,17 @@ def sgmv_status_string(status: int) -> str:
 
 def sgmv_workspace_bytes(n_tokens: int, r: int) -> int:
     return int(lib.sgmv_workspace_bytes(n_tokens, r))
+
+
+def sgmv_workspace_init(workspace, workspace_bytes: int, stream=None, check: bool = True) -> int:
+    rc = lib.sgmv_workspace_init(_addr(workspace), workspace_bytes, _stream(stream))
+    if check and rc != 0:
+        raise SgmvError(rc, "sgmv_workspace_init")
+    return rc
+
+
+def sgmv_workspace_check(workspace, n_tokens: int, r: int, stream=None) -> int:
+    return lib.sgmv_workspace_check(_addr(workspace), n_tokens, r, _stream(stream))
 
 
 def sgmv_validate_segments(host_seg_starts, n_segs: int, n_tokens: int) -> int:

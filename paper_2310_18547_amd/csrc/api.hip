@@ -13,6 +13,13 @@ using namespace sgmv;
 
 constexpr int kMinSplitCap = 16;       // the workspace always allows this many slices
 constexpr int kTargetWorkgroups = 512; // about two workgroups per compute unit
+constexpr int kFusedMaxSegLen = 16;    // longest segment the single-launch path is used for
+constexpr int kFusedWorkgroups = 256;  // one workgroup per compute unit
+constexpr int kFusedMaxWorkgroups = 1024;
+constexpr int kFusedSpinLimit = 1 << 18;
+constexpr size_t kCounterSlack = 64;   // words after the two counter arrays (error word first)
+
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
@@ -35,8 +42,8 @@ int check_common(const sgmv_problem* p, const int32_t* seg_starts, int32_t n_seg
   if (p->r != 8 && p->r != 16 && p->r != 32 && p->r != 64) return SGMV_ERR_UNSUPPORTED;
   if ((need_in && (p->h_in % 8) != 0) || (need_out && (p->h_out % 8) != 0))
     return SGMV_ERR_UNSUPPORTED;
-  if (p->path != SGMV_PATH_AUTO && p->path != SGMV_PATH_VECTOR && p->path != SGMV_PATH_MATRIX)
-    return SGMV_ERR_UNSUPPORTED;
+  if (p->path < SGMV_PATH_AUTO || p->path > SGMV_PATH_FUSED) return SGMV_ERR_UNSUPPORTED;
+  if (p->reserved != 0) return SGMV_ERR_UNSUPPORTED;
   if (p->ksplit < 0 || p->ksplit > kMaxKSplit) return SGMV_ERR_UNSUPPORTED;
   if (p->expand_threads != 0 && p->expand_threads != 64 && p->expand_threads != 128 &&
       p->expand_threads != 256)
@@ -71,6 +78,37 @@ bool choose_split(const sgmv_problem* p, int n_segs, int* ksplit, int* kslice) {
   return true;
 }
 
+size_t partial_bytes(int n_tokens, int r) {
+  return round_up((size_t)split_cap(n_tokens) * (size_t)n_tokens * (size_t)r * sizeof(float), 256);
+}
+
+// Launch shape of the single-launch path; false when it does not apply.
+bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f) {
+  if (!p->workspace_ready) return false;
+  if (p->max_seg_len <= 0 || p->max_seg_len > kFusedMaxSegLen) return false;
+  if (n_segs > kFusedMaxWorkgroups) return false;
+  const int cap = split_cap(p->n_tokens);
+  const int need = ceil_div(p->h_in, kMaxKSlice);
+  if (need > cap) return false;
+  int s = p->ksplit > 0 ? p->ksplit : (kFusedWorkgroups + n_segs / 2) / n_segs;
+  const int wide = p->h_in > p->h_out ? p->h_in : p->h_out;
+  if (s > wide / 64) s = wide / 64;
+  if (s > cap) s = cap;
+  if (s > kFusedMaxWorkgroups / n_segs) s = kFusedMaxWorkgroups / n_segs;
+  if (s < need) s = need;
+  if (s < 1) s = 1;
+  if ((long long)s * n_segs > kFusedMaxWorkgroups) return false;
+  f->S = s;
+  f->kslice = ceil_div(ceil_div(p->h_in, s), 8) * 8;
+  f->cslice = ceil_div(ceil_div(p->h_out, s), 8) * 8;
+  const int chunks = f->cslice / 8;
+  int g = 1;
+  while (g * 2 <= 8 && 256 / (g * 2) >= chunks) g *= 2;
+  while (p->r / g > 16) g *= 2;
+  f->G = g;
+  return true;
+}
+
 int choose_expand_threads(const sgmv_problem* p, int n_segs) {
   if (p->expand_threads) return p->expand_threads;
   const int sizes[3] = {256, 128, 64};
@@ -97,6 +135,11 @@ ShrinkArgs make_shrink(const sgmv_problem* p, const void* x, const void* const* 
   a.seg_starts = seg_starts;
   a.partials = static_cast<float*>(p->workspace);
   return a;
+}
+
+unsigned* counter_base(const void* workspace, int n_tokens, int r) {
+  return reinterpret_cast<unsigned*>(static_cast<char*>(const_cast<void*>(workspace)) +
+                                     partial_bytes(n_tokens, r));
 }
 
 ExpandArgs make_expand(const sgmv_problem* p, void* y, const float* v_parts, int nparts,
@@ -135,13 +178,35 @@ const char* sgmv_status_string(int status) {
     case SGMV_ERR_WORKSPACE: return "workspace missing or too small";
     case SGMV_ERR_RANGE: return "layer_idx out of range";
     case SGMV_ERR_LAUNCH: return "kernel launch failed";
+    case SGMV_ERR_TIMEOUT: return "a workgroup gave up waiting for partial sums";
   }
   return "unknown status";
 }
 
 size_t sgmv_workspace_bytes(int32_t n_tokens, int32_t r) {
   if (n_tokens <= 0 || r <= 0) return 0;
-  return (size_t)split_cap(n_tokens) * (size_t)n_tokens * (size_t)r * sizeof(float);
+  return partial_bytes(n_tokens, r) +
+         round_up((2 * (size_t)n_tokens + kCounterSlack) * sizeof(unsigned), 256);
+}
+
+int sgmv_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+  if (workspace == nullptr) return SGMV_ERR_NULL;
+  if (!aligned(workspace, 256)) return SGMV_ERR_ALIGN;
+  if (launch_fill_zero(workspace, workspace_bytes, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return SGMV_ERR_LAUNCH;
+  return SGMV_OK;
+}
+
+int sgmv_workspace_check(const void* workspace, int32_t n_tokens, int32_t r, void* stream) {
+  if (workspace == nullptr) return SGMV_ERR_NULL;
+  if (n_tokens <= 0 || r <= 0) return SGMV_ERR_SHAPE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  unsigned word = 0;
+  const unsigned* src = counter_base(workspace, n_tokens, r) + 2 * (size_t)n_tokens;
+  if (hipMemcpyAsync(&word, src, sizeof word, hipMemcpyDeviceToHost, st) != hipSuccess)
+    return SGMV_ERR_LAUNCH;
+  if (hipStreamSynchronize(st) != hipSuccess) return SGMV_ERR_LAUNCH;
+  return word == 0 ? SGMV_OK : SGMV_ERR_TIMEOUT;
 }
 
 int sgmv_validate_segments(const int32_t* host_seg_starts, int32_t n_segs, int32_t n_tokens) {
@@ -202,6 +267,31 @@ int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x, const void* con
   if (p->path == SGMV_PATH_MATRIX) return SGMV_ERR_UNSUPPORTED;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) {
+    FusedArgs f;
+    if (choose_fused(p, n_segs, &f)) {
+      f.bf16 = p->dtype == SGMV_BF16;
+      f.r = p->r;
+      f.h_in = p->h_in;
+      f.h_out = p->h_out;
+      f.n_tokens = p->n_tokens;
+      f.n_segs = n_segs;
+      f.spin_limit = kFusedSpinLimit;
+      f.offA = (long long)layer_idx * p->h_in * p->r;
+      f.offB = (long long)layer_idx * p->r * p->h_out;
+      f.y = y;
+      f.x = x;
+      f.A_ptrs = A_ptrs;
+      f.B_ptrs = B_ptrs;
+      f.seg_starts = seg_starts;
+      f.partials = static_cast<float*>(p->workspace);
+      f.counters = counter_base(p->workspace, p->n_tokens, p->r);
+      f.scale = scale;
+      if (launch_add_lora_fused(f, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+      return SGMV_OK;
+    }
+    if (p->path == SGMV_PATH_FUSED) return SGMV_ERR_UNSUPPORTED;
+  }
   ShrinkArgs s = make_shrink(p, x, A_ptrs, seg_starts, n_segs, layer_idx);
   if (!choose_split(p, n_segs, &s.ksplit, &s.kslice)) return SGMV_ERR_UNSUPPORTED;
   if (launch_shrink_vector(s, st) != hipSuccess) return SGMV_ERR_LAUNCH;

@@ -37,6 +37,26 @@ struct ExpandArgs {
   float scale;
 };
 
+struct FusedArgs {
+  bool bf16;
+  int r, h_in, h_out, n_tokens, n_segs;
+  int S;                     // workgroups per segment = k-slices = column slices
+  int kslice, cslice;        // elements per k-slice / columns per column slice
+  int G;                     // lane groups of the expand phase (1, 2, 4 or 8)
+  int spin_limit;            // polls before a waiting workgroup gives up
+  long long offA, offB;      // layer offsets in elements
+  float scale;
+  void* y;
+  const void* x;
+  const void* const* A_ptrs;
+  const void* const* B_ptrs;
+  const int32_t* seg_starts;
+  float* partials;           // [S][n_tokens][r]
+  unsigned* counters;        // arrive[n_tokens], done[n_tokens], error word
+};
+
+hipError_t launch_add_lora_fused(const FusedArgs& a, hipStream_t st);
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
 hipError_t launch_shrink_vector(const ShrinkArgs& a, hipStream_t st);
 hipError_t launch_shrink_reduce(float* v, const ShrinkArgs& a, hipStream_t st);
 hipError_t launch_expand_vector(const ExpandArgs& a, hipStream_t st);

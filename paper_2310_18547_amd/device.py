@@ -29,7 +29,8 @@ class DeviceWorkload:
     """
 
     def __init__(self, w, device="cuda:0", n_sets: int = 1, max_seg_len_hint: bool = True,
-                 path: int = B.PATH_AUTO, ksplit: int = 0, expand_threads: int = 0):
+                 path: int = B.PATH_AUTO, ksplit: int = 0, expand_threads: int = 0,
+                 init_workspace: bool = True):
         self.w = w
         self.device = torch.device(device)
         self.A: List[torch.Tensor] = [_to_dev(a, self.device) for a in w.A]
@@ -43,12 +44,16 @@ class DeviceWorkload:
         self.y0 = _to_dev(w.y0, self.device)
         self.y = [self.y0.clone() for _ in range(n_sets)]
         self.ws_bytes = max(B.sgmv_workspace_bytes(w.n_tokens, w.r), 256)
-        self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.device)
+        # deliberately not zero-filled by torch: sgmv_workspace_init does that
+        self.workspace = torch.full((self.ws_bytes,), 0xA5, dtype=torch.uint8, device=self.device)
+        if init_workspace:
+            B.sgmv_workspace_init(self.workspace, self.ws_bytes)
+            torch.cuda.synchronize(self.device)   # later calls may use other streams
         self.problem = B.make_problem(
             _DT[w.dtype], w.h_in, w.h_out, w.r, w.num_layers, w.n_tokens,
             workspace=self.workspace, workspace_bytes=self.ws_bytes,
             max_seg_len=w.max_seg_len if max_seg_len_hint else 0, path=path, ksplit=ksplit,
-            expand_threads=expand_threads)
+            expand_threads=expand_threads, workspace_ready=1 if init_workspace else 0)
 
     # -- the three entry points, on set `k` ---------------------------------
     def add_lora(self, layer_idx: int = 0, k: int = 0, stream=None, scale: Optional[float] = None):
@@ -65,6 +70,10 @@ class DeviceWorkload:
         return B.sgmv_expand(self.problem, self.y[k], v, self.B_ptrs, self.seg_starts,
                              self.w.n_segs, layer_idx, self.w.scale if scale is None else scale,
                              stream)
+
+    def check(self, stream=None) -> int:
+        """Synchronous health check of the workspace (0 = fine)."""
+        return B.sgmv_workspace_check(self.workspace, self.w.n_tokens, self.w.r, stream)
 
     def reset_y(self, k: Optional[int] = None):
         for i in (range(len(self.y)) if k is None else [k]):

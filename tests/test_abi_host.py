@@ -29,13 +29,13 @@ def test_header_symbols_are_exported():
 
 def test_struct_layout_matches_header():
     # 10 int32 fields, pointer, size_t
-    assert ctypes.sizeof(sg.SgmvProblem) == 10 * 4 + 8 + 8
-    assert sg.SgmvProblem.workspace.offset == 40
+    assert ctypes.sizeof(sg.SgmvProblem) == 12 * 4 + 8 + 8
+    assert sg.SgmvProblem.workspace.offset == 48
 
 
 def test_status_strings():
-    seen = {sg.sgmv_status_string(i) for i in range(8)}
-    assert len(seen) == 8 and "unknown status" not in seen
+    seen = {sg.sgmv_status_string(i) for i in range(9)}
+    assert len(seen) == 9 and "unknown status" not in seen
     assert sg.sgmv_status_string(99) == "unknown status"
 
 
@@ -45,9 +45,9 @@ def test_workspace_bytes():
     for T in (1, 7, 64, 1000, 4608, 100000):
         for r in (8, 16, 32, 64):
             b = sg.sgmv_workspace_bytes(T, r)
-            assert b >= 16 * T * r * 4          # room for at least 16 split-K slices
-            assert b <= 64 * T * r * 4
-    assert sg.sgmv_workspace_bytes(64, 16) == 64 * 64 * 16 * 4
+            assert b >= 16 * T * r * 4 + 2 * T * 4   # >= 16 split-K slices + two counter arrays
+            assert b <= 64 * T * r * 4 + 2 * T * 4 + 1024 and b % 256 == 0
+    assert sg.sgmv_workspace_bytes(64, 16) == 64 * 64 * 16 * 4 + 768
 
 
 def test_validate_segments():
@@ -98,6 +98,13 @@ def test_argument_errors_are_reported_without_a_device():
     assert _add(_prob(workspace=FAKE + 16)) == 4
     assert _add(_prob(workspace_bytes=16)) == 5
     assert _add(_prob(path=9)) == 3
+    assert _add(_prob(path=sg.PATH_FUSED)) == 3            # workspace not declared ready
+    assert _add(_prob(path=sg.PATH_FUSED, workspace_ready=1, max_seg_len=0)) == 3
+    assert _add(_prob(path=sg.PATH_FUSED, workspace_ready=1, max_seg_len=17)) == 3
+    assert sg.sgmv_workspace_init(None, 1024, check=False) == 1
+    assert sg.sgmv_workspace_init(FAKE + 8, 1024, check=False) == 4
+    assert sg.sgmv_workspace_check(None, 8, 16) == 1
+    assert sg.sgmv_workspace_check(FAKE, 0, 16) == 2
     assert _add(_prob(ksplit=1000)) == 3
     assert _add(_prob(expand_threads=100)) == 3
     # nothing to do: OK without any launch

@@ -243,3 +243,100 @@ def test_guard_rows_are_not_written():
     assert np.all(host[:2 * H] == 0x5A5A) and np.all(host[(T + 2) * H:] == 0x5A5A)
     assert_parity(host[2 * H:(T + 2) * H].reshape(T, H).view(np.uint16), oracle.run_workload(w),
                   "f16", "guarded y")
+
+
+# ------------------------------------------------- single-launch (fused) path
+def _fused(w, **kw):
+    from paper_2310_18547_amd import binding as B
+    return _dev(w, path=B.PATH_FUSED, **kw)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("r", [8, 16, 32, 64])
+def test_fused_matches_oracle_and_two_launch_path(dtype, r):
+    from paper_2310_18547_amd import binding as B
+    w = wl.custom([1, 3, 2, 16, 1, 7, 0, 4], 2048, 1544, r, dtype, seed=40 + r, num_layers=2)
+    ref = oracle.run_workload(w, layer_idx=1)
+    d = _fused(w)
+    d.add_lora(1)
+    got = d.y_bits()
+    assert d.check() == 0
+    assert_parity(got, ref, dtype, f"fused r={r}")
+    assert_parity(run_add_lora(w, 1, path=B.PATH_VECTOR), ref, dtype, f"two-launch r={r}")
+
+
+@pytest.mark.parametrize("ksplit", [1, 2, 3, 5, 8, 16])
+def test_fused_every_slice_count(ksplit):
+    w = wl.custom([1, 2, 5, 1, 1, 1], 2048, 1024, 16, "f16", seed=45)
+    d = _fused(w, ksplit=ksplit)
+    d.add_lora()
+    assert_parity(d.y_bits(), oracle.run_workload(w), "f16", f"fused S={ksplit}")
+    assert d.check() == 0
+
+
+def test_fused_counters_reset_between_calls():
+    # many back-to-back calls on one workspace: each must see fresh counters
+    w = wl.decode_distinct(batch=64, h_in=4096, r=16, dtype="f16", num_layers=4, seed=46)
+    d = _fused(w, n_sets=2)
+    refs = [oracle.run_workload(w, layer_idx=l, n_threads=8) for l in range(4)]
+    for rep in range(5):
+        for layer in range(4):
+            d.reset_y(rep % 2)
+            d.add_lora(layer, rep % 2)
+            assert_parity(d.y_bits(rep % 2), refs[layer], "f16", f"rep {rep} layer {layer}")
+    assert d.check() == 0
+    # bit-identical from call to call
+    d.reset_y(0); d.add_lora(2, 0); a = d.y_bits(0)
+    d.reset_y(0); d.add_lora(2, 0)
+    assert np.array_equal(d.y_bits(0), a)
+
+
+def test_fused_graph_replay():
+    # the bench's launch configuration: calls recorded into a HIP graph and replayed
+    w = wl.decode_distinct(batch=64, h_in=4096, r=16, dtype="f16", num_layers=8, seed=47)
+    d = _fused(w, n_sets=8)
+    stream = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        d.add_lora(0, 0, stream=stream.cuda_stream)
+        stream.synchronize()
+        d.reset_y()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=stream):
+            for i in range(8):
+                d.add_lora(i, i, stream=stream.cuda_stream)
+        for rep in range(3):
+            d.reset_y()
+            torch.cuda.synchronize()
+            g.replay()
+            stream.synchronize()
+            for i in (0, 3, 7):
+                assert_parity(d.y_bits(i), oracle.run_workload(w, layer_idx=i, n_threads=8), "f16",
+                              f"graph replay {rep} set {i}")
+    assert d.check(stream.cuda_stream) == 0
+
+
+def test_fused_fingerprint_bit_exact():
+    lens = [1, 0, 3, 2, 0, 0, 5, 1, 9, 4, 1, 1, 16]
+    w = wl.fingerprint(lens, 256, 192, 16, "bf16", num_layers=3)
+    for layer in range(3):
+        d = _fused(w)
+        d.add_lora(layer)
+        assert np.array_equal(d.y_bits(), oracle.run_workload(w, layer_idx=layer))
+
+
+def test_fused_null_adapter():
+    w = wl.custom([2, 0, 3, 1, 4], 512, 264, 16, "f16", seed=48)
+    w.seg_adapter = np.asarray([0, 1, -1, 3, 4], np.int64)
+    d = _fused(w)
+    d.add_lora()
+    d.add_lora()          # skipped segments must not leave counters behind
+    got = d.y_bits()
+    assert np.array_equal(got[2:5], w.y0[2:5]) and d.check() == 0
+
+
+def test_auto_uses_two_launches_without_ready_workspace():
+    w = wl.tiny()
+    d = _dev(w, init_workspace=False)
+    d.add_lora()
+    assert_parity(d.y_bits(), oracle.run_workload(w), "f16", "workspace not initialised")
