@@ -23,8 +23,8 @@
  *     whatever A_ptrs[i] / B_ptrs[i] point to) is DEVICE memory owned by the
  *     caller.  The sgmv_problem struct itself is HOST memory, read during the
  *     call only.  The library allocates nothing, frees nothing and keeps no
- *     state of its own between calls (the single-launch path keeps its
- *     arrival counters in the caller's workspace, see sgmv_workspace_init).
+ *     state of its own between calls (the single-launch path keeps an
+ *     epoch word in the caller's workspace, see sgmv_workspace_init).
  *   - x is [n_tokens][h_in], y is [n_tokens][h_out], row-major, 16-bit floats
  *     of type `dtype` (IEEE binary16 or bfloat16), 16-byte aligned.
  *   - A_ptrs[i] points to segment i's shrink weights stacked over layers,
@@ -120,12 +120,14 @@ const char* sgmv_status_string(int status);
  * function.  Returns 0 for n_tokens <= 0. */
 size_t sgmv_workspace_bytes(int32_t n_tokens, int32_t r);
 
-/* Prepare a workspace for the single-launch path of sgmv_add_lora: zero-fills
- * it with a small kernel on `stream` (so the call may be recorded into a HIP
- * graph).  The single-launch path keeps per-segment arrival counters in the
- * workspace and leaves them at zero after every call; run this once after
- * allocating the workspace, and again if a call using it was ever aborted.
- * `workspace` is device memory, 256-byte aligned. */
+/* Prepare a workspace for the single-launch path of sgmv_add_lora: clears it
+ * and sets its epoch word with a small kernel on `stream` (so the call may be
+ * recorded into a HIP graph).  The single-launch path exchanges partial sums
+ * between workgroups through the workspace and tells one call's words from
+ * the previous call's by an epoch that every such call advances; run this once
+ * after allocating the workspace, and again if a call using it was ever
+ * aborted.  `workspace` is device memory, 256-byte aligned, of at least 1024
+ * bytes. */
 int sgmv_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 
 /* Synchronous health check of a workspace used by the single-launch path:
@@ -134,7 +136,7 @@ int sgmv_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
  * neighbour's partial sums -- results of that call are then invalid and the
  * workspace must be re-initialised.  Returns SGMV_OK otherwise.  Not meant for
  * the hot path. */
-int sgmv_workspace_check(const void* workspace, int32_t n_tokens, int32_t r, void* stream);
+int sgmv_workspace_check(const void* workspace, void* stream);
 
 /* Host-side check of a HOST copy of the segment index sequence against the
  * segment definition paragraph: n_segs >= 0, seg_starts[0] == 0,

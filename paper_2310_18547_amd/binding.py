@@ -61,7 +61,7 @@ def _load():
     L.sgmv_workspace_bytes.restype = c.c_size_t
     L.sgmv_workspace_init.argtypes = [c.c_void_p, c.c_size_t, c.c_void_p]
     L.sgmv_workspace_init.restype = c.c_int
-    L.sgmv_workspace_check.argtypes = [c.c_void_p, c.c_int32, c.c_int32, c.c_void_p]
+    L.sgmv_workspace_check.argtypes = [c.c_void_p, c.c_void_p]
     L.sgmv_workspace_check.restype = c.c_int
     L.sgmv_validate_segments.argtypes = [c.c_void_p, c.c_int32, c.c_int32]
     L.sgmv_validate_segments.restype = c.c_int
@@ -121,8 +121,8 @@ def sgmv_workspace_init(workspace, workspace_bytes: int, stream=None, check: boo
     return rc
 
 
-def sgmv_workspace_check(workspace, n_tokens: int, r: int, stream=None) -> int:
-    return lib.sgmv_workspace_check(_addr(workspace), n_tokens, r, _stream(stream))
+def sgmv_workspace_check(workspace, stream=None) -> int:
+    return lib.sgmv_workspace_check(_addr(workspace), _stream(stream))
 
 
 def sgmv_validate_segments(host_seg_starts, n_segs: int, n_tokens: int) -> int:

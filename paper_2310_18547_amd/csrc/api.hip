@@ -17,7 +17,6 @@ constexpr int kFusedMaxSegLen = 16;    // longest segment the single-launch path
 constexpr int kFusedWorkgroups = 256;  // one workgroup per compute unit
 constexpr int kFusedMaxWorkgroups = 1024;
 constexpr int kFusedSpinLimit = 1 << 18;
-constexpr size_t kCounterSlack = 64;   // words after the two counter arrays (error word first)
 
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -82,6 +81,16 @@ size_t partial_bytes(int n_tokens, int r) {
   return round_up((size_t)split_cap(n_tokens) * (size_t)n_tokens * (size_t)r * sizeof(float), 256);
 }
 
+// Workspace layout: [header: epoch, error word][split-K partials of the
+// one-launch-per-step kernels][exchange words of the single-launch kernel].
+float* partials_base(void* workspace) {
+  return reinterpret_cast<float*>(static_cast<char*>(workspace) + kWorkspaceHeader);
+}
+unsigned long long* exchange_base(void* workspace, int n_tokens, int r) {
+  return reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + kWorkspaceHeader +
+                                               partial_bytes(n_tokens, r));
+}
+
 // Launch shape of the single-launch path; false when it does not apply.
 bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f) {
   if (!p->workspace_ready) return false;
@@ -106,6 +115,7 @@ bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f) {
   while (g * 2 <= 8 && 256 / (g * 2) >= chunks) g *= 2;
   while (p->r / g > 16) g *= 2;
   f->G = g;
+  f->rows_per_pass = p->max_seg_len == 1 ? 1 : 4;
   return true;
 }
 
@@ -133,13 +143,8 @@ ShrinkArgs make_shrink(const sgmv_problem* p, const void* x, const void* const* 
   a.x = x;
   a.A_ptrs = A_ptrs;
   a.seg_starts = seg_starts;
-  a.partials = static_cast<float*>(p->workspace);
+  a.partials = partials_base(p->workspace);
   return a;
-}
-
-unsigned* counter_base(const void* workspace, int n_tokens, int r) {
-  return reinterpret_cast<unsigned*>(static_cast<char*>(const_cast<void*>(workspace)) +
-                                     partial_bytes(n_tokens, r));
 }
 
 ExpandArgs make_expand(const sgmv_problem* p, void* y, const float* v_parts, int nparts,
@@ -185,24 +190,24 @@ const char* sgmv_status_string(int status) {
 
 size_t sgmv_workspace_bytes(int32_t n_tokens, int32_t r) {
   if (n_tokens <= 0 || r <= 0) return 0;
-  return partial_bytes(n_tokens, r) +
-         round_up((2 * (size_t)n_tokens + kCounterSlack) * sizeof(unsigned), 256);
+  return kWorkspaceHeader + 3 * partial_bytes(n_tokens, r);  // fp32 partials + 64-bit exchange words
 }
 
 int sgmv_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
   if (workspace == nullptr) return SGMV_ERR_NULL;
   if (!aligned(workspace, 256)) return SGMV_ERR_ALIGN;
-  if (launch_fill_zero(workspace, workspace_bytes, static_cast<hipStream_t>(stream)) != hipSuccess)
+  if (workspace_bytes < kWorkspaceHeader) return SGMV_ERR_WORKSPACE;
+  if (launch_workspace_init(workspace, workspace_bytes, 0, static_cast<hipStream_t>(stream)) !=
+      hipSuccess)
     return SGMV_ERR_LAUNCH;
   return SGMV_OK;
 }
 
-int sgmv_workspace_check(const void* workspace, int32_t n_tokens, int32_t r, void* stream) {
+int sgmv_workspace_check(const void* workspace, void* stream) {
   if (workspace == nullptr) return SGMV_ERR_NULL;
-  if (n_tokens <= 0 || r <= 0) return SGMV_ERR_SHAPE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   unsigned word = 0;
-  const unsigned* src = counter_base(workspace, n_tokens, r) + 2 * (size_t)n_tokens;
+  const unsigned* src = static_cast<const unsigned*>(workspace) + 2 * kEpochCounters;  // after the epoch counters
   if (hipMemcpyAsync(&word, src, sizeof word, hipMemcpyDeviceToHost, st) != hipSuccess)
     return SGMV_ERR_LAUNCH;
   if (hipStreamSynchronize(st) != hipSuccess) return SGMV_ERR_LAUNCH;
@@ -284,8 +289,8 @@ int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x, const void* con
       f.A_ptrs = A_ptrs;
       f.B_ptrs = B_ptrs;
       f.seg_starts = seg_starts;
-      f.partials = static_cast<float*>(p->workspace);
-      f.counters = counter_base(p->workspace, p->n_tokens, p->r);
+      f.exch = exchange_base(p->workspace, p->n_tokens, p->r);
+      f.header = static_cast<unsigned long long*>(p->workspace);
       f.scale = scale;
       if (launch_add_lora_fused(f, st) != hipSuccess) return SGMV_ERR_LAUNCH;
       return SGMV_OK;

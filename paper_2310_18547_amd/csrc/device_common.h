@@ -79,3 +79,31 @@ __device__ __forceinline__ void store128(void* p, const uint4& v) {
 }
 
 }  // namespace sgmv
+
+// ---------------------------------------------------------------------------
+// Buffer addressing.  A buffer resource carries a wave-uniform base and a byte
+// length; the hardware range-checks every lane, returns zero for loads beyond
+// the length and drops such stores.  Lanes are predicated by giving them the
+// offset kOutOfRange, so guarded 128-bit accesses need no branches and the
+// compiler can issue all of a lane's loads back to back.
+namespace sgmv {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+constexpr uint32_t kOutOfRange = 0x80000000u;
+constexpr int kBufferWord3 = 0x00020000;  // raw buffer, 32-bit data format
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_buffer(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, kBufferWord3);
+}
+template <int AUX = 0>
+__device__ __forceinline__ uint4 buffer_load128(__amdgpu_buffer_rsrc_t rsrc, uint32_t byte_off) {
+  u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)byte_off, 0, AUX);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void buffer_store128(__amdgpu_buffer_rsrc_t rsrc, uint32_t byte_off,
+                                                const uint4& q) {
+  u32x4 v = {q.x, q.y, q.z, q.w};
+  __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, (int)byte_off, 0, 0);
+}
+
+}  // namespace sgmv

@@ -5,27 +5,57 @@
 // by a cross-block reduction of the Split-K partial sums.  On MI355X a kernel
 // boundary costs about as much as streaming the whole batch's adapter weights
 // (the operator moves ~18 MB; an empty launch is ~1.5 us), so here both steps
-// run in ONE launch and the only cross-workgroup hand-off is per segment:
+// run in ONE launch and the only cross-workgroup hand-off is per segment.
 //
-//   * S workgroups serve one segment.  Workgroup s first does the shrink of
-//     k-slice s for all rows of the segment, then the expand of column-slice s.
-//   * All weight loads of both phases (its A slice and its B slice) are issued
-//     at the very start, A first, so the B slice streams in while the shrink
-//     is computed and the partial sums are exchanged.
-//   * Partial sums go to the workspace; a per-segment arrival counter
-//     (release / acquire at agent scope, the L2s of the eight XCDs are not
-//     coherent with each other) tells the S consumers when all slices are
-//     there.  Every consumer adds the slices in the same ascending order, so
-//     the result is deterministic.  The last consumer to read resets the
-//     segment's counters for the next call.
-//   * Producers never wait before publishing, the S workgroups of a segment
-//     have consecutive ids, and workgroups are dispatched in id order, so a
-//     waiting workgroup only ever waits for workgroups that are already
-//     resident or next in line.  The wait is bounded all the same: after
-//     spin_limit polls a workgroup raises the workspace's error word and
-//     leaves, so no wave can stay in the kernel for ever.
+// Work split.  S workgroups serve one segment.  Workgroup s does the shrink of
+// k-slice s for all rows of the segment, then the expand of column-slice s.
+// A workgroup has five waves:
+//   * four STREAM waves issue every weight load of both phases at the very
+//     start (x, then the A slice, then the B slice, then y) through buffer
+//     resources, whose hardware range check does the predication, so the loads
+//     sit back to back with no branches between them.  They multiply, reduce
+//     their lanes with a transposing butterfly and leave per-wave sums in LDS;
+//     later they pick the complete v rows up from LDS and finish the expand.
+//     The barriers between the phases order LDS only, so a stream wave never
+//     drains its outstanding B / y loads while the partial sums are exchanged.
+//   * one EXCHANGE wave, which has no bulk loads in flight (vector memory
+//     returns in order, so a wave that polls must not queue behind its own
+//     streaming loads), publishes the workgroup's partial sums and collects
+//     those of the other S-1 workgroups.
+//
+// Hand-off.  The L2s of the eight XCDs are not coherent with each other, so
+// the exchanged words are written and read with agent-scope accesses that
+// bypass them.  A partial sum travels as one 64-bit word {value, tag}; the tag
+// is the call's generation number, so a consumer simply polls the S words it
+// needs until their tags match -- there is no separate flag, no ordering
+// between separate stores to get wrong, and nothing to reset afterwards.  The
+// generation comes from a 64-bit epoch word in the workspace: every workgroup
+// of a launch adds to it on exit so that each launch advances it by exactly
+// kEpochStep in total; while a launch is running the epoch therefore stays
+// inside one window of kEpochStep values and epoch / kEpochStep is the same
+// for every workgroup of the launch, whenever it reads it.  Calls that share a
+// workspace must be stream-ordered.
+//
+// Every consumer adds the S slices in the same ascending order, so results are
+// deterministic.  Producers never wait before publishing, the S workgroups of
+// a segment have consecutive ids and workgroups are dispatched in id order, so
+// a polling workgroup only waits for workgroups that are resident or next in
+// line.  The wait is bounded all the same: after spin_limit polls a workgroup
+// raises the workspace's error word and carries on, so no wave can stay in the
+// kernel for ever.
+#include <type_traits>
+
 #include "device_common.h"
 #include "launch.h"
+
+// Optional timeline probe for kernel tuning: a tuning build defines this macro to
+// record a timestamp per (workgroup, point) in registers and to write them out when a
+// wave leaves; it is empty in the library.
+#ifndef SGMV_TRACE_POINT
+#define SGMV_TRACE_DECL
+#define SGMV_TRACE_POINT(point)
+#define SGMV_TRACE_FLUSH(cond, first, last)
+#endif
 
 namespace sgmv {
 
@@ -59,27 +89,69 @@ __device__ __forceinline__ float fused_reduce_lanes8(const float (&a)[8], int la
   return d;
 }
 
-// grid = n_segs * S workgroups of 256 threads; workgroup w serves segment w / S
-// with slice index w % S.
-//   partials  [S][n_tokens][R] fp32
-//   counters  arrive[n_tokens], done[n_tokens] (indexed by the segment's first
-//             row), then one error word; all zero between calls
-// G = lane groups of the expand phase: group g multiplies weight rows
-// g*R/G .. (g+1)*R/G-1; the groups are summed through LDS.
+// Workgroup barrier that orders LDS traffic only: outstanding global loads stay
+// outstanding.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+__device__ __forceinline__ uint32_t generation_tag(unsigned long long epoch) {
+  return (uint32_t)((epoch / kEpochStep) % 0xFFFFFFFFull) + 1u;  // never 0
+}
+
+// Each workgroup adds to the epoch exactly once, on its way out; the first
+// workgroup adds the remainder so that the launch's total is kEpochStep.  The
+// epoch is the sum of kEpochCounters words and a workgroup adds to the word
+// its id selects, which spreads the atomics over many addresses.
+__device__ __forceinline__ void leave_launch(unsigned long long* epoch, int n_workgroups) {
+  const unsigned id = blockIdx.y * gridDim.x + blockIdx.x;
+  const unsigned long long inc =
+      id == 0 ? (unsigned long long)kEpochStep - (n_workgroups - 1) : 1ull;
+  __hip_atomic_fetch_add(epoch + (id % kEpochCounters), inc, __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Read the epoch with one wave: lane l reads counter l, the lanes are summed.
+// The counters only grow, and this workgroup has not added its share yet, so
+// whatever mixture of old and new counter values the lanes see, the sum lies
+// in the running launch's window.
+__device__ __forceinline__ unsigned long long read_epoch(const unsigned long long* epoch, int lane) {
+  static_assert(kEpochCounters == 64, "one counter per lane");
+  unsigned long long v = __hip_atomic_load(epoch + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) {
+    const unsigned lo = __shfl_xor((unsigned)v, m, 64);
+    const unsigned hi = __shfl_xor((unsigned)(v >> 32), m, 64);
+    v += ((unsigned long long)hi << 32) | lo;
+  }
+  return v;
+}
+
+// grid = (S, n_segs) workgroups of 320 threads: blockIdx.y is the segment,
+// blockIdx.x its slice index (so the S workgroups of a segment are neighbours
+// in dispatch order and no division is needed to find them).
+//   exch   [S][n_tokens][R] 64-bit words {fp32 value (high), tag (low)}
+//   header kEpochCounters 64-bit counters whose sum is the epoch, then the error flag
+// G  = lane groups of the expand phase: group g multiplies weight rows
+//      g*R/G .. (g+1)*R/G-1; the groups are summed through LDS.
+// RB = rows handled per pass over the weights (1 when every segment is one row).
 template <class DT, int R, int G, int RB>
-__global__ __launch_bounds__(256) void add_lora_fused_kernel(
-    uint16_t* __restrict__ y, const uint16_t* __restrict__ x,
-    const uint16_t* const* __restrict__ A_ptrs, const uint16_t* const* __restrict__ B_ptrs,
-    const int32_t* __restrict__ seg_starts, float* partials, unsigned* counters, int h_in,
-    int h_out, int S, int kslice, int cslice, int n_tokens, long long offA, long long offB,
+__global__ __launch_bounds__(320) void add_lora_fused_kernel(
+    // the first sixteen dwords are preloaded into SGPRs at wave launch: keep what the
+    // first dependent loads need at the front
+    const int32_t* __restrict__ seg_starts, const uint16_t* const* __restrict__ A_ptrs,
+    const uint16_t* const* __restrict__ B_ptrs, const uint16_t* __restrict__ x,
+    uint16_t* __restrict__ y, int kslice, int cslice, int h_in, int h_out, int n_tokens, int S,
+    long long offA, long long offB, unsigned long long* exch, unsigned long long* header,
     float scale, int spin_limit) {
-  constexpr int NT = 256, NW = 4, U = 8;
+  constexpr int NT = 256, NW = 4, U = 8;  // stream threads / waves, A loads per lane and batch
   constexpr int LPR = R / 8;
   constexpr int CPW = NT / G;  // 8-column chunks per pass
   constexpr int JL = R / G;    // weight rows per lane in the expand phase
-  constexpr int XU = RB * kMaxKSlice / 8 / NT;
   static_assert(JL >= 1 && JL <= 16, "bad lane-group count");
-  static_assert(NT >= RB * R, "one thread per (row, column) of a row block");
+  static_assert(kMaxKSlice / 8 == NT, "one 128-bit x chunk per lane and row");
 
   __shared__ __align__(16) uint16_t xs[RB][kMaxKSlice];
   __shared__ float red[NW][RB][R];
@@ -87,194 +159,219 @@ __global__ __launch_bounds__(256) void add_lora_fused_kernel(
   __shared__ __align__(16) float ex[(G > 1 ? (G - 1) : 1) * RB * CPW * 8];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int seg = blockIdx.x / S, s = blockIdx.x - seg * S;
+  SGMV_TRACE_DECL
+  SGMV_TRACE_POINT(0);
+  const int seg = blockIdx.y, s = blockIdx.x;
   const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
-  if (lo >= hi) return;
   const uint16_t* A = A_ptrs[seg];
   const uint16_t* B = B_ptrs[seg];
-  if (A == nullptr || B == nullptr) return;  // same decision in all S workgroups
-
-  // ---- shrink geometry
+  if (lo >= hi || A == nullptr || B == nullptr) {  // same decision in all S workgroups
+    if (tid == 0) leave_launch(header, S * (int)gridDim.y);
+    return;
+  }
+  SGMV_TRACE_POINT(8);
   const int k0 = s * kslice;
   const int klen = max(0, min(h_in, k0 + kslice) - k0);
-  const int nchunks = klen * LPR;
-  const int cpr = klen >> 3;
-  A += offA + (long long)k0 * R;
-  // ---- expand geometry
-  const int col_lo = s * cslice;
-  const int col_hi = min(h_out, col_lo + cslice);
-  const int cg = tid / CPW, cc = tid - cg * CPW;  // lane group, chunk within pass
-  B += offB + (long long)(cg * JL) * h_out;
+  const int nchunks = klen * LPR;  // 128-bit chunks in this workgroup's slice of A_i
+  const int col_lo = min(h_out, s * cslice);
+  const int ncols = max(0, min(h_out, col_lo + cslice) - col_lo);
+  const int npass = (ncols + CPW * 8 - 1) / (CPW * 8);  // 0 when the column slice is empty
 
-  // ---- issue everything that does not depend on another workgroup: A, x, B, y
-  uint4 a[U];
+  if (wave == NW) {
+    // ============================================================ exchange wave
+    const uint32_t tag = generation_tag(read_epoch(header, lane));
+    const long long stride = (long long)n_tokens * R;
+    // ---- shrink phase: publish this workgroup's partial sums
+    for (int row0 = lo; row0 < hi; row0 += RB) {
+      const int nrows = min(RB, hi - row0);
+      if (row0 != lo) lds_barrier();  // (a) xs / red free
+      lds_barrier();                  // (b) xs filled
+      lds_barrier();                  // (c) red filled
+      for (int idx = lane; idx < nrows * R; idx += 64) {
+        const int rb = idx / R, j = idx - rb * R;
+        float sum = red[0][rb][j];
 #pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const int q = u * NT + tid;
-    a[u] = (q < nchunks) ? load128_stream(A + (long long)q * 8) : make_uint4(0, 0, 0, 0);
-  }
-  uint4 xr[XU];
-  {
-    const int nrows = min(RB, hi - lo);
-#pragma unroll
-    for (int i = 0; i < XU; ++i) {
-      const int idx = i * NT + tid;
-      if (idx < nrows * cpr) {
-        const int rr = idx / cpr, c = idx - rr * cpr;
-        xr[i] = load128(x + (long long)(lo + rr) * h_in + k0 + c * 8);
+        for (int w = 1; w < NW; ++w) sum += red[w][rb][j];
+        const unsigned long long word = ((unsigned long long)__float_as_uint(sum) << 32) | tag;
+        __hip_atomic_store(exch + (long long)s * stride + (long long)(row0 + rb) * R + j, word,
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
+    SGMV_TRACE_POINT(4);
+    // ---- expand phase: collect all S slices of every row, in ascending order
+    bool timed_out = false;
+    for (int row0 = lo; row0 < hi; row0 += RB) {
+      const int nrows = min(RB, hi - row0);
+      if (row0 != lo) lds_barrier();  // (d) vs / ex free
+      for (int idx = lane; idx < nrows * R; idx += 64) {
+        const int rb = idx / R, j = idx - rb * R;
+        const unsigned long long* src = exch + (long long)(row0 + rb) * R + j;
+        float sum = 0.f;
+        for (int s0 = 0; s0 < S; s0 += 8) {
+          unsigned long long wv[8];
+          int polls = 0;
+          bool ready;
+          do {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+              wv[i] = __hip_atomic_load(src + min(s0 + i, S - 1) * stride, __ATOMIC_RELAXED,
+                                        __HIP_MEMORY_SCOPE_AGENT);
+            ready = true;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) ready = ready && ((uint32_t)wv[i] == tag);
+            if (!ready && ++polls > spin_limit) {
+              timed_out = true;
+              break;
+            }
+          } while (!ready);
+#pragma unroll
+          for (int i = 0; i < 8; ++i)
+            sum += (s0 + i < S) ? __uint_as_float((uint32_t)(wv[i] >> 32)) : 0.f;
+        }
+        vs[rb][j] = sum;
+      }
+      SGMV_TRACE_POINT(5);
+      lds_barrier();  // (e) vs filled
+      if (G > 1) {
+        for (int pass = 0; pass < npass; ++pass) {
+          if (pass != 0) lds_barrier();  // (f) ex free
+          lds_barrier();                 // (g) ex filled
+        }
+      }
+    }
+    if (timed_out) __hip_atomic_store((unsigned*)(header + kEpochCounters), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (lane == 0) leave_launch(header, S * (int)gridDim.y);
+    SGMV_TRACE_POINT(7);
+    SGMV_TRACE_FLUSH(lane == 0, 4, 7);
+    return;
   }
+
+  // ================================================================ stream waves
+  const int cpr = klen >> 3;  // 128-bit chunks in one x row slice
+  const __amdgpu_buffer_rsrc_t rA = make_buffer(A + offA + (long long)k0 * R, (uint32_t)nchunks * 16u);
+  const int cg = tid / CPW, cc = tid - cg * CPW;  // lane group, chunk within pass
+  const __amdgpu_buffer_rsrc_t rB = make_buffer(
+      B + offB + col_lo, ncols > 0 ? (uint32_t)((long long)(R - 1) * h_out + ncols) * 2u : 0u);
+  const uint32_t b_row0 = (uint32_t)(cg * JL) * (uint32_t)h_out * 2u;
+  const uint32_t row_bytes_out = (uint32_t)h_out * 2u;
+
+  // ---- issue everything that does not depend on another workgroup: x, A, B, y
+  const int nrows_first = min(RB, hi - lo);
+  uint4 xr[RB];
+  {
+    const __amdgpu_buffer_rsrc_t rX = make_buffer(
+        x + (long long)lo * h_in + k0, (uint32_t)((long long)(nrows_first - 1) * h_in + klen) * 2u);
+#pragma unroll
+    for (int rr = 0; rr < RB; ++rr)
+      xr[rr] = buffer_load128(rX, (tid < cpr && rr < nrows_first) ? (uint32_t)(rr * h_in + tid * 8) * 2u : kOutOfRange);
+  }
+  uint4 a[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) a[u] = buffer_load128(rA, (uint32_t)(u * NT + tid) * 16u);
+  __builtin_amdgcn_sched_barrier(0);  // keep x and A ahead of B and y in the memory pipe
   uint4 b[JL];
   {
-    const int c0 = col_lo + cc * 8;
+    const bool active = cc * 8 < ncols;
 #pragma unroll
     for (int j = 0; j < JL; ++j)
-      b[j] = (c0 < col_hi) ? load128_stream(B + (long long)j * h_out + c0) : make_uint4(0, 0, 0, 0);
+      b[j] = buffer_load128(rB, active ? b_row0 + (uint32_t)j * row_bytes_out + (uint32_t)cc * 16u : kOutOfRange);
   }
   uint4 yq[RB];
   {
-    const int c0 = col_lo + cc * 8;
-    const int nrows = min(RB, hi - lo);
+    const __amdgpu_buffer_rsrc_t rY = make_buffer(
+        y + (long long)lo * h_out + col_lo,
+        ncols > 0 ? (uint32_t)((long long)(nrows_first - 1) * h_out + ncols) * 2u : 0u);
+    const bool active = cg == 0 && cc * 8 < ncols;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
-      if (cg == 0 && c0 < col_hi && rb < nrows) yq[rb] = load128(y + (long long)(lo + rb) * h_out + c0);
+      yq[rb] = buffer_load128(rY, (active && rb < nrows_first) ? (uint32_t)rb * row_bytes_out + (uint32_t)cc * 16u : kOutOfRange);
   }
+  __builtin_amdgcn_sched_barrier(0);
+  SGMV_TRACE_POINT(1);
 
-  // ================================================================ shrink
-  for (int row0 = lo; row0 < hi; row0 += RB) {
+  // One row block of the shrink phase.  `first` selects the copy that uses the
+  // loads issued above; it is a separate, straight-line copy so that the waits
+  // in it count exactly the loads that are still needed.
+  auto shrink_block = [&](int row0, auto first_tag) {
+    constexpr bool first = decltype(first_tag)::value;
     const int nrows = min(RB, hi - row0);
     float acc[RB][8];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[rb][e] = 0.f;
-
-    if (row0 != lo) {
-      __syncthreads();  // xs / red are reused
+    if (!first) {
+      lds_barrier();  // (a) xs / red free
+      const __amdgpu_buffer_rsrc_t rX = make_buffer(
+          x + (long long)row0 * h_in + k0, (uint32_t)((long long)(nrows - 1) * h_in + klen) * 2u);
 #pragma unroll
-      for (int i = 0; i < XU; ++i) {
-        const int idx = i * NT + tid;
-        if (idx < nrows * cpr) {
-          const int rr = idx / cpr, c = idx - rr * cpr;
-          xr[i] = load128(x + (long long)(row0 + rr) * h_in + k0 + c * 8);
-        }
-      }
+      for (int rr = 0; rr < RB; ++rr)
+        xr[rr] = buffer_load128(rX, (tid < cpr && rr < nrows) ? (uint32_t)(rr * h_in + tid * 8) * 2u : kOutOfRange);
     }
+    // rows and chunks that do not exist arrive as zeros, so xs is always fully defined
 #pragma unroll
-    for (int i = 0; i < XU; ++i) {
-      const int idx = i * NT + tid;
-      if (idx < nrows * cpr) {
-        const int rr = idx / cpr, c = idx - rr * cpr;
-        store128(&xs[rr][c * 8], xr[i]);
-      }
-    }
-    __syncthreads();
+    for (int rr = 0; rr < RB; ++rr) store128(&xs[rr][tid * 8], xr[rr]);
+    lds_barrier();  // (b) xs filled
+    SGMV_TRACE_POINT(2);
 
     for (int base = 0; base < nchunks; base += NT * U) {
-      if (base != 0 || row0 != lo) {
+      if (!first || base != 0) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const int q = base + u * NT + tid;
-          a[u] = (q < nchunks) ? load128_stream(A + (long long)q * 8) : make_uint4(0, 0, 0, 0);
-        }
+        for (int u = 0; u < U; ++u) a[u] = buffer_load128(rA, (uint32_t)(base + u * NT + tid) * 16u);
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int q = base + u * NT + tid;
-        if (q < nchunks) {
-          const int kk = q / LPR;
-          float af[8];
-          unpack8<DT>(a[u], af);
+        const int kk = (q / LPR) & (kMaxKSlice - 1);
+        float af[8];
+        unpack8<DT>(a[u], af);
 #pragma unroll
-          for (int rb = 0; rb < RB; ++rb) {
-            if (rb < nrows) {
-              const float xv = decode1<DT>(xs[rb][kk]);
+        for (int rb = 0; rb < RB; ++rb) {
+          if (RB == 1 || rb < nrows) {
+            const float xraw = decode1<DT>(xs[rb][kk]);
+            const float xv = (q < nchunks) ? xraw : 0.f;
 #pragma unroll
-              for (int e = 0; e < 8; ++e) acc[rb][e] = fmaf(xv, af[e], acc[rb][e]);
-            }
+            for (int e = 0; e < 8; ++e) acc[rb][e] = fmaf(xv, af[e], acc[rb][e]);
           }
         }
       }
     }
-
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      if (rb < nrows) {
+      if (RB == 1 || rb < nrows) {
         int e;
         const float d = fused_reduce_lanes8<LPR>(acc[rb], lane, e);
         if (lane < R) red[wave][rb][(lane % LPR) * 8 + e] = d;
       }
     }
-    __syncthreads();
-    if (tid < nrows * R) {
-      const int rb = tid / R, j = tid - rb * R;
-      float sum = red[0][rb][j];
-#pragma unroll
-      for (int w = 1; w < NW; ++w) sum += red[w][rb][j];
-      partials[((long long)s * n_tokens + row0 + rb) * R + j] = sum;
-    }
-  }
+    SGMV_TRACE_POINT(3);
+    lds_barrier();  // (c) red filled
+  };
 
-  // ================================================================ hand-off
-  unsigned* arrive = counters + lo;
-  unsigned* done = counters + n_tokens + lo;
-  unsigned* error_word = counters + 2 * (long long)n_tokens;
-  __syncthreads();  // every partial of this workgroup has been stored
-  if (tid == 0) {
-    __hip_atomic_fetch_add(arrive, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-    int polls = 0;
-    while (__hip_atomic_load(arrive, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < (unsigned)S) {
-      if (++polls > spin_limit) {
-        __hip_atomic_store(error_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        break;
-      }
-      __builtin_amdgcn_s_sleep(1);
-    }
-  }
-  __syncthreads();  // the acquire above now covers the whole workgroup
+  shrink_block(lo, std::true_type{});
+  for (int row0 = lo + RB; row0 < hi; row0 += RB) shrink_block(row0, std::false_type{});
 
-  // ================================================================ expand
-  const int npass = (col_hi - col_lo + CPW * 8 - 1) / (CPW * 8);  // <= 0 when the slice is empty
-  for (int row0 = lo; row0 < hi; row0 += RB) {
+  // One row block of the expand phase.
+  auto expand_block = [&](int row0, auto first_tag) {
+    constexpr bool first = decltype(first_tag)::value;
     const int nrows = min(RB, hi - row0);
-    if (row0 != lo) __syncthreads();  // vs is reused
-    if (tid < nrows * R) {
-      const int rb = tid / R, j = tid - rb * R;
-      const float* src = partials + (long long)(row0 + rb) * R + j;
-      const long long stride = (long long)n_tokens * R;
-      float sum = 0.f;
-      for (int s0 = 0; s0 < S; s0 += 8) {
-        float t[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) t[i] = (s0 + i < S) ? src[(s0 + i) * stride] : 0.f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) sum += t[i];
-      }
-      vs[rb][j] = sum;
-    }
-    __syncthreads();
-    if (row0 + RB >= hi && tid == 0) {
-      // this workgroup has read everything it needs from the segment's partials
-      const unsigned before = __hip_atomic_fetch_add(done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (before == (unsigned)S - 1u) {
-        __hip_atomic_store(arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-    }
-
+    if (!first) lds_barrier();  // (d) vs / ex free
+    const __amdgpu_buffer_rsrc_t rY = make_buffer(
+        y + (long long)row0 * h_out + col_lo,
+        ncols > 0 ? (uint32_t)((long long)(nrows - 1) * h_out + ncols) * 2u : 0u);
+    lds_barrier();  // (e) vs filled
     for (int pass = 0; pass < npass; ++pass) {
-      const int c0 = col_lo + (pass * CPW + cc) * 8;
-      const bool active = c0 < col_hi;
-      if (pass != 0 || row0 != lo) {
+      const int c = pass * CPW + cc;  // 8-column chunk within the slice
+      const bool active = c * 8 < ncols;
+      if (!first || pass != 0) {
         if (npass > 1) {
 #pragma unroll
           for (int j = 0; j < JL; ++j)
-            b[j] = active ? load128_stream(B + (long long)j * h_out + c0) : make_uint4(0, 0, 0, 0);
+            b[j] = buffer_load128(rB, active ? b_row0 + (uint32_t)j * row_bytes_out + (uint32_t)c * 16u : kOutOfRange);
         }
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
-          if (cg == 0 && active && rb < nrows) yq[rb] = load128(y + (long long)(row0 + rb) * h_out + c0);
+          yq[rb] = buffer_load128(rY, (cg == 0 && active && rb < nrows) ? (uint32_t)rb * row_bytes_out + (uint32_t)c * 16u : kOutOfRange);
       }
       float acc[RB][8];
 #pragma unroll
@@ -287,7 +384,7 @@ __global__ __launch_bounds__(256) void add_lora_fused_kernel(
         unpack8<DT>(b[j], bf);
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
-          if (rb < nrows) {
+          if (RB == 1 || rb < nrows) {
             const float vj = vs[rb][cg * JL + j];
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[rb][e] = fmaf(vj, bf[e], acc[rb][e]);
@@ -295,24 +392,24 @@ __global__ __launch_bounds__(256) void add_lora_fused_kernel(
         }
       }
       if (G > 1) {
-        if (pass != 0) __syncthreads();  // ex is reused
+        if (pass != 0) lds_barrier();  // (f) ex free
         if (cg > 0) {
 #pragma unroll
           for (int rb = 0; rb < RB; ++rb) {
-            if (rb < nrows) {
+            if (RB == 1 || rb < nrows) {
               float* dst = &ex[(((cg - 1) * RB + rb) * CPW + cc) * 8];
               *reinterpret_cast<float4*>(dst) = make_float4(acc[rb][0], acc[rb][1], acc[rb][2], acc[rb][3]);
               *reinterpret_cast<float4*>(dst + 4) = make_float4(acc[rb][4], acc[rb][5], acc[rb][6], acc[rb][7]);
             }
           }
         }
-        __syncthreads();
+        lds_barrier();  // (g) ex filled
         if (cg == 0) {
 #pragma unroll
           for (int g = 1; g < G; ++g) {
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-              if (rb < nrows) {
+              if (RB == 1 || rb < nrows) {
                 const float* srcp = &ex[(((g - 1) * RB + rb) * CPW + cc) * 8];
                 const float4 p0 = *reinterpret_cast<const float4*>(srcp);
                 const float4 p1 = *reinterpret_cast<const float4*>(srcp + 4);
@@ -323,60 +420,71 @@ __global__ __launch_bounds__(256) void add_lora_fused_kernel(
           }
         }
       }
-      if (cg == 0 && active) {
+      if (cg == 0) {
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
-          if (rb < nrows) {
-            float yf[8];
-            unpack8<DT>(yq[rb], yf);
-            uint4 out;
-            out.x = pack2<DT>(yf[0] + scale * acc[rb][0], yf[1] + scale * acc[rb][1]);
-            out.y = pack2<DT>(yf[2] + scale * acc[rb][2], yf[3] + scale * acc[rb][3]);
-            out.z = pack2<DT>(yf[4] + scale * acc[rb][4], yf[5] + scale * acc[rb][5]);
-            out.w = pack2<DT>(yf[6] + scale * acc[rb][6], yf[7] + scale * acc[rb][7]);
-            store128(y + (long long)(row0 + rb) * h_out + c0, out);
-          }
+          float yf[8];
+          unpack8<DT>(yq[rb], yf);
+          uint4 out;
+          out.x = pack2<DT>(yf[0] + scale * acc[rb][0], yf[1] + scale * acc[rb][1]);
+          out.y = pack2<DT>(yf[2] + scale * acc[rb][2], yf[3] + scale * acc[rb][3]);
+          out.z = pack2<DT>(yf[4] + scale * acc[rb][4], yf[5] + scale * acc[rb][5]);
+          out.w = pack2<DT>(yf[6] + scale * acc[rb][6], yf[7] + scale * acc[rb][7]);
+          buffer_store128(rY, (active && rb < nrows) ? (uint32_t)rb * row_bytes_out + (uint32_t)c * 16u : kOutOfRange, out);
         }
       }
     }
-  }
+  };
+
+  expand_block(lo, std::true_type{});
+  for (int row0 = lo + RB; row0 < hi; row0 += RB) expand_block(row0, std::false_type{});
+  SGMV_TRACE_POINT(6);
+  SGMV_TRACE_FLUSH(tid == 0, 0, 3);
+  SGMV_TRACE_FLUSH(tid == 0, 6, 6);
+  SGMV_TRACE_FLUSH(tid == 0, 8, 9);
 }
 
-// Fill kernel used to zero the workspace (a kernel rather than a memset so the
-// call can be recorded into a HIP graph).
-__global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t* p, size_t n) {
+// Workspace initialisation: zero everything, then start the epoch one full
+// step above zero so that the zeroed exchange words (tag 0) never match.
+__global__ __launch_bounds__(256) void workspace_init_kernel(uint32_t* p, size_t n_words,
+                                                             size_t header_word) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (; i < n; i += stride) p[i] = 0u;
+  for (; i < n_words; i += stride) p[i] = (i == header_word) ? (uint32_t)kEpochStep : 0u;
 }
 
-hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
+hipError_t launch_workspace_init(void* p, size_t bytes, size_t header_offset, hipStream_t st) {
   const size_t n = bytes / 4;
   if (n == 0) return hipSuccess;
   unsigned blocks = (unsigned)((n + 255) / 256);
   if (blocks > 1024) blocks = 1024;
-  hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, st, (uint32_t*)p, n);
+  hipLaunchKernelGGL(workspace_init_kernel, dim3(blocks), dim3(256), 0, st, (uint32_t*)p, n,
+                     header_offset / 4);
+  return hipGetLastError();
+}
+
+template <class DT, int R, int G, int RB>
+static hipError_t launch_fused_t(const FusedArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL((add_lora_fused_kernel<DT, R, G, RB>), dim3((unsigned)a.S, (unsigned)a.n_segs),
+                     dim3(320), 0, st, a.seg_starts, (const uint16_t* const*)a.A_ptrs,
+                     (const uint16_t* const*)a.B_ptrs, (const uint16_t*)a.x, (uint16_t*)a.y,
+                     a.kslice, a.cslice, a.h_in, a.h_out, a.n_tokens, a.S, a.offA, a.offB, a.exch,
+                     a.header, a.scale, a.spin_limit);
   return hipGetLastError();
 }
 
 template <class DT, int R, int G>
-static hipError_t launch_fused_t(const FusedArgs& a, hipStream_t st) {
-  constexpr int RB = 4;
-  hipLaunchKernelGGL((add_lora_fused_kernel<DT, R, G, RB>), dim3((unsigned)(a.n_segs * a.S)),
-                     dim3(256), 0, st, (uint16_t*)a.y, (const uint16_t*)a.x,
-                     (const uint16_t* const*)a.A_ptrs, (const uint16_t* const*)a.B_ptrs,
-                     a.seg_starts, a.partials, a.counters, a.h_in, a.h_out, a.S, a.kslice,
-                     a.cslice, a.n_tokens, a.offA, a.offB, a.scale, a.spin_limit);
-  return hipGetLastError();
+static hipError_t launch_fused_rb(const FusedArgs& a, hipStream_t st) {
+  return a.rows_per_pass == 1 ? launch_fused_t<DT, R, G, 1>(a, st) : launch_fused_t<DT, R, G, 4>(a, st);
 }
 
 template <class DT, int R>
 static hipError_t launch_fused_g(const FusedArgs& a, hipStream_t st) {
   switch (a.G) {
-    case 1: if constexpr (R <= 16) return launch_fused_t<DT, R, 1>(a, st); break;
-    case 2: if constexpr (R <= 32) return launch_fused_t<DT, R, 2>(a, st); break;
-    case 4: return launch_fused_t<DT, R, 4>(a, st);
-    case 8: return launch_fused_t<DT, R, 8>(a, st);
+    case 1: if constexpr (R <= 16) return launch_fused_rb<DT, R, 1>(a, st); break;
+    case 2: if constexpr (R <= 32) return launch_fused_rb<DT, R, 2>(a, st); break;
+    case 4: return launch_fused_rb<DT, R, 4>(a, st);
+    case 8: return launch_fused_rb<DT, R, 8>(a, st);
   }
   return hipErrorInvalidValue;
 }

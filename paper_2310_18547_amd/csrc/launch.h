@@ -7,6 +7,16 @@ namespace sgmv {
 
 // Longest k-slice one shrink workgroup stages in LDS (elements of one x row).
 constexpr int kMaxKSlice = 2048;
+// Every single-launch call advances the workspace's epoch word by exactly this
+// much; it also bounds the grid of that kernel.
+constexpr unsigned long long kEpochStep = 1ull << 16;
+// The epoch is kept as the sum of this many 64-bit counters so that the
+// workgroups of a launch do not all add to one address (same-address atomics
+// serialise at the memory side, ~10 ns each).
+constexpr int kEpochCounters = 64;
+// Bytes reserved at the start of a workspace: the epoch counters, then the
+// error word.
+constexpr size_t kWorkspaceHeader = 1024;
 // Upper bound of the split-K factor.
 constexpr int kMaxKSplit = 64;
 
@@ -43,6 +53,7 @@ struct FusedArgs {
   int S;                     // workgroups per segment = k-slices = column slices
   int kslice, cslice;        // elements per k-slice / columns per column slice
   int G;                     // lane groups of the expand phase (1, 2, 4 or 8)
+  int rows_per_pass;         // 1 when every segment is a single row, else 4
   int spin_limit;            // polls before a waiting workgroup gives up
   long long offA, offB;      // layer offsets in elements
   float scale;
@@ -51,12 +62,12 @@ struct FusedArgs {
   const void* const* A_ptrs;
   const void* const* B_ptrs;
   const int32_t* seg_starts;
-  float* partials;           // [S][n_tokens][r]
-  unsigned* counters;        // arrive[n_tokens], done[n_tokens], error word
+  unsigned long long* exch;  // [S][n_tokens][r] words {value, generation tag}
+  unsigned long long* header;// kEpochCounters epoch counters, then the error word
 };
 
 hipError_t launch_add_lora_fused(const FusedArgs& a, hipStream_t st);
-hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
+hipError_t launch_workspace_init(void* p, size_t bytes, size_t header_offset, hipStream_t st);
 hipError_t launch_shrink_vector(const ShrinkArgs& a, hipStream_t st);
 hipError_t launch_shrink_reduce(float* v, const ShrinkArgs& a, hipStream_t st);
 hipError_t launch_expand_vector(const ExpandArgs& a, hipStream_t st);

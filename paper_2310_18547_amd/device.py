@@ -73,7 +73,7 @@ class DeviceWorkload:
 
     def check(self, stream=None) -> int:
         """Synchronous health check of the workspace (0 = fine)."""
-        return B.sgmv_workspace_check(self.workspace, self.w.n_tokens, self.w.r, stream)
+        return B.sgmv_workspace_check(self.workspace, stream)
 
     def reset_y(self, k: Optional[int] = None):
         for i in (range(len(self.y)) if k is None else [k]):

@@ -45,9 +45,9 @@ def test_workspace_bytes():
     for T in (1, 7, 64, 1000, 4608, 100000):
         for r in (8, 16, 32, 64):
             b = sg.sgmv_workspace_bytes(T, r)
-            assert b >= 16 * T * r * 4 + 2 * T * 4   # >= 16 split-K slices + two counter arrays
-            assert b <= 64 * T * r * 4 + 2 * T * 4 + 1024 and b % 256 == 0
-    assert sg.sgmv_workspace_bytes(64, 16) == 64 * 64 * 16 * 4 + 768
+            assert b >= 1024 + 3 * 16 * T * r * 4     # header, >= 16 split-K slices, exchange words
+            assert b <= 1024 + 3 * (64 * T * r * 4 + 256) and b % 256 == 0
+    assert sg.sgmv_workspace_bytes(64, 16) == 1024 + 3 * 64 * 64 * 16 * 4
 
 
 def test_validate_segments():
@@ -103,8 +103,8 @@ def test_argument_errors_are_reported_without_a_device():
     assert _add(_prob(path=sg.PATH_FUSED, workspace_ready=1, max_seg_len=17)) == 3
     assert sg.sgmv_workspace_init(None, 1024, check=False) == 1
     assert sg.sgmv_workspace_init(FAKE + 8, 1024, check=False) == 4
-    assert sg.sgmv_workspace_check(None, 8, 16) == 1
-    assert sg.sgmv_workspace_check(FAKE, 0, 16) == 2
+    assert sg.sgmv_workspace_check(None) == 1
+    assert sg.sgmv_workspace_init(FAKE, 16, check=False) == 5
     assert _add(_prob(ksplit=1000)) == 3
     assert _add(_prob(expand_threads=100)) == 3
     # nothing to do: OK without any launch
