@@ -91,6 +91,12 @@ def main():
     ap.add_argument("--expand-threads", type=int, default=0)
     ap.add_argument("--path", type=int, default=0)
     ap.add_argument("--blocks", type=int, default=5, help="timed repetitions; the median is reported")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 64 MiB read + 64 MiB write elementwise kernel, as the "
+                         "known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="HBM bytes per launch measured with rocprofv3 --pmc (reported as "
+                         "roofline.traffic)")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -113,6 +119,12 @@ def main():
 
     def step(i):
         d.add_lora(i % L, i % S, stream=sh)
+
+    if args.calibrate_copy:
+        src = torch.ones(16 << 20, dtype=torch.int32, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.add(src, 1, out=dst)            # reads 64 MiB, writes 64 MiB
+        torch.cuda.synchronize()
 
     K, W = args.steps, args.warmup
     with torch.cuda.stream(stream):
@@ -171,8 +183,12 @@ def main():
                    "algorithmic_bytes_per_step": bytes_step,
                    "flops_per_step": acc.flops("add_lora", T, w.h_in, w.h_out, w.r)},
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": gbs / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "sgmv_add_lora (all kernels of one step)",
+                     "frac": gbs / HBM_PEAK_GBS, "traffic": args.traffic_bytes,
+                     "kernel": "add_lora_fused_kernel (one launch per step)"
+                               if (w.max_seg_len <= 16 and args.path in (0, 3))
+                               else "all kernels of one sgmv_add_lora step",
+                     "launches_per_step": 1 if (w.max_seg_len <= 16 and args.path in (0, 3)) else 2,
+                     "algorithmic_bytes_per_launch": bytes_step,
                      "avg_launch_us": us},
         "paper_a100_us": PAPER_A100_US.get(args.workload),
         "block_ms": times,
