@@ -17,6 +17,8 @@ constexpr int kFusedMaxSegLen = 16;    // longest segment the single-launch path
 constexpr int kFusedWorkgroups = 256;  // one workgroup per compute unit
 constexpr int kFusedMaxWorkgroups = 1024;
 constexpr int kFusedSpinLimit = 1 << 18;
+constexpr int kMatrixMinSegLen = 32;   // AUTO uses the MFMA kernels from this segment length on
+constexpr int kMatrixWorkgroups = 320; // workgroups the MFMA shrink aims for
 
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -75,6 +77,30 @@ bool choose_split(const sgmv_problem* p, int n_segs, int* ksplit, int* kslice) {
   *kslice = len;
   *ksplit = ceil_div(p->h_in, len);
   return true;
+}
+
+// Whether a call goes to the MFMA kernels: forced, or segments long enough that
+// 16-row tiles are mostly full (from the hint, else from the mean length).
+bool use_matrix(const sgmv_problem* p, int n_segs) {
+  if (p->path == SGMV_PATH_MATRIX) return true;
+  if (p->path != SGMV_PATH_AUTO) return false;
+  const int len = p->max_seg_len > 0 ? p->max_seg_len : p->n_tokens / (n_segs > 0 ? n_segs : 1);
+  return len >= kMatrixMinSegLen;
+}
+
+// Split-K shape of the MFMA shrink: row blocks of 64 rows times ksplit slices should
+// give every compute unit a workgroup; slices are multiples of the MFMA depth (32).
+void choose_split_matrix(const sgmv_problem* p, int n_segs, int* ksplit, int* kslice) {
+  const int cap = split_cap(p->n_tokens);
+  const int blocks = p->n_tokens / 64 + (n_segs + 1) / 2;
+  int s = p->ksplit > 0 ? p->ksplit : ceil_div(kMatrixWorkgroups, blocks > 0 ? blocks : 1);
+  const int most = p->h_in / 256 > 0 ? p->h_in / 256 : 1;  // keep slices >= one LDS chunk
+  if (s > most) s = most;
+  if (s > cap) s = cap;
+  if (s < 1) s = 1;
+  const int len = ceil_div(ceil_div(p->h_in, s), 32) * 32;
+  *kslice = len;
+  *ksplit = ceil_div(p->h_in, len);
 }
 
 size_t partial_bytes(int n_tokens, int r) {
@@ -233,12 +259,17 @@ int sgmv_shrink(const sgmv_problem* p, float* v, const void* x, const void* cons
   if (!aligned(v, 16) || !aligned(x, 16)) return SGMV_ERR_ALIGN;
   rc = check_workspace(p);
   if (rc != SGMV_OK) return rc;
-  if (p->path == SGMV_PATH_MATRIX) return SGMV_ERR_UNSUPPORTED;
+  if (p->path == SGMV_PATH_FUSED) return SGMV_ERR_UNSUPPORTED;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   ShrinkArgs a = make_shrink(p, x, A_ptrs, seg_starts, n_segs, layer_idx);
-  if (!choose_split(p, n_segs, &a.ksplit, &a.kslice)) return SGMV_ERR_UNSUPPORTED;
-  if (launch_shrink_vector(a, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+  if (use_matrix(p, n_segs)) {
+    choose_split_matrix(p, n_segs, &a.ksplit, &a.kslice);
+    if (launch_shrink_matrix(a, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+  } else {
+    if (!choose_split(p, n_segs, &a.ksplit, &a.kslice)) return SGMV_ERR_UNSUPPORTED;
+    if (launch_shrink_vector(a, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+  }
   if (launch_shrink_reduce(v, a, st) != hipSuccess) return SGMV_ERR_LAUNCH;
   return SGMV_OK;
 }
@@ -251,11 +282,15 @@ int sgmv_expand(const sgmv_problem* p, void* y, const float* v, const void* cons
   if (n_segs == 0 || p->n_tokens == 0) return SGMV_OK;
   if (y == nullptr || v == nullptr || B_ptrs == nullptr) return SGMV_ERR_NULL;
   if (!aligned(v, 16) || !aligned(y, 16)) return SGMV_ERR_ALIGN;
-  if (p->path == SGMV_PATH_MATRIX) return SGMV_ERR_UNSUPPORTED;
+  if (p->path == SGMV_PATH_FUSED) return SGMV_ERR_UNSUPPORTED;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   ExpandArgs a = make_expand(p, y, v, 1, nullptr, B_ptrs, seg_starts, n_segs, layer_idx, scale);
-  if (launch_expand_vector(a, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+  if (use_matrix(p, n_segs)) {
+    if (launch_expand_matrix(a, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+  } else {
+    if (launch_expand_vector(a, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+  }
   return SGMV_OK;
 }
 
@@ -269,7 +304,6 @@ int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x, const void* con
   if (!aligned(y, 16) || !aligned(x, 16)) return SGMV_ERR_ALIGN;
   rc = check_workspace(p);
   if (rc != SGMV_OK) return rc;
-  if (p->path == SGMV_PATH_MATRIX) return SGMV_ERR_UNSUPPORTED;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) {
@@ -298,6 +332,14 @@ int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x, const void* con
     if (p->path == SGMV_PATH_FUSED) return SGMV_ERR_UNSUPPORTED;
   }
   ShrinkArgs s = make_shrink(p, x, A_ptrs, seg_starts, n_segs, layer_idx);
+  if (use_matrix(p, n_segs)) {
+    choose_split_matrix(p, n_segs, &s.ksplit, &s.kslice);
+    if (launch_shrink_matrix(s, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+    ExpandArgs e = make_expand(p, y, s.partials, s.ksplit, A_ptrs, B_ptrs, seg_starts, n_segs,
+                               layer_idx, scale);
+    if (launch_expand_matrix(e, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+    return SGMV_OK;
+  }
   if (!choose_split(p, n_segs, &s.ksplit, &s.kslice)) return SGMV_ERR_UNSUPPORTED;
   if (launch_shrink_vector(s, st) != hipSuccess) return SGMV_ERR_LAUNCH;
   ExpandArgs e = make_expand(p, y, s.partials, s.ksplit, A_ptrs, B_ptrs, seg_starts, n_segs,

@@ -71,5 +71,7 @@ hipError_t launch_workspace_init(void* p, size_t bytes, size_t header_offset, hi
 hipError_t launch_shrink_vector(const ShrinkArgs& a, hipStream_t st);
 hipError_t launch_shrink_reduce(float* v, const ShrinkArgs& a, hipStream_t st);
 hipError_t launch_expand_vector(const ExpandArgs& a, hipStream_t st);
+hipError_t launch_shrink_matrix(const ShrinkArgs& a, hipStream_t st);
+hipError_t launch_expand_matrix(const ExpandArgs& a, hipStream_t st);
 
 }  // namespace sgmv

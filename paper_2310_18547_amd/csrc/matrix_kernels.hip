@@ -1,0 +1,396 @@
+// MFMA path of SGMV for long (prefill-shaped) segments, gfx950.
+//
+// When a segment holds hundreds of rows, the per-segment product really is a
+// dense contraction (the paper groups requests "to increase operational
+// intensity and use Tensor Cores"), and at ranks up to 64 the vector ALUs can no
+// longer keep up with HBM: the shrink needs r FLOP per byte of x and the expand
+// r/2 FLOP per byte of y.  Both kernels are still bound by HBM (x is read once,
+// y is read and written once); the matrix cores only have to be fast enough not
+// to matter, so the code is organised around streaming x and y, not around
+// MFMA utilisation.
+//
+// Both kernels use v_mfma_f32_16x16x32_{f16,bf16}.  Its operands want eight
+// consecutive k per lane: lane l of a wave holds row (l % 16), k = 8 (l / 16) ..
+// +7 of the first operand and column (l % 16), same k, of the second; it
+// receives D[4 (l / 16) + i][l % 16], i = 0..3.  x and v are k-contiguous in
+// memory, the weights A_i [h_in][r] and B_i [r][h_out] are not, so weight tiles
+// are transposed once per workgroup through LDS (pairs of k packed into a dword
+// on the way in, so the LDS writes are conflict-free dword writes) and are then
+// reused for every row tile of the workgroup.
+//
+//   shrink  workgroup = (segment, block of 64 rows, k-slice); wave w owns rows
+//           16w..16w+15 of the block.  The k-slice is walked in chunks of 256:
+//           the chunk of A_i is staged transposed in LDS while the wave's x
+//           loads (eight 128-bit loads per lane) are in flight.  Split-K
+//           partial sums go to the workspace exactly like the vector path's.
+//   expand  workgroup = (segment, strip of 256 columns, block of rows); wave w
+//           owns 64 columns.  The strip of B_i is staged once and kept in
+//           registers as MFMA operands.  The product is taken transposed
+//           (D = B_i^T v^T) with the columns of four 16-wide tiles interleaved,
+//           so that a lane ends up with 16 consecutive columns of one row and
+//           y is read and written with 128-bit accesses.  v stays fp32 in the
+//           workspace; it enters the matrix cores as a high and a low 16-bit
+//           part (two MFMAs), which keeps ~16 significant bits.
+#include <type_traits>
+
+#include "device_common.h"
+#include "launch.h"
+
+namespace sgmv {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <class DT>
+__device__ __forceinline__ f32x4 mfma16x16x32(const uint4& a, const uint4& b, f32x4 c);
+template <>
+__device__ __forceinline__ f32x4 mfma16x16x32<F16>(const uint4& a, const uint4& b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a),
+                                                __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+template <>
+__device__ __forceinline__ f32x4 mfma16x16x32<BF16>(const uint4& a, const uint4& b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+constexpr int kShrinkRows = 64;    // rows per shrink workgroup (four 16-row tiles)
+constexpr int kShrinkChunk = 256;  // k per LDS stage
+constexpr int kExpandCols = 256;   // columns per expand workgroup (64 per wave)
+constexpr int kExpandRows = 256;   // rows per expand workgroup pass
+
+// ---------------------------------------------------------------- shrink
+//
+// grid = (ksplit, row blocks, n_segs); the row-block dimension is walked with a
+// stride, so any grid size is correct.  partials is [ksplit][n_tokens][R] fp32.
+template <class DT, int R>
+__global__ __launch_bounds__(256) void shrink_matrix_kernel(
+    const uint16_t* __restrict__ x, const uint16_t* const* __restrict__ A_ptrs,
+    const int32_t* __restrict__ seg_starts, float* __restrict__ partials, int h_in, int kslice,
+    int n_tokens, long long layer_off) {
+  constexpr int NT = 256;
+  constexpr int NTILE = (R + 15) / 16;  // 16-column tiles of v
+  constexpr int RPAD = NTILE * 16;
+  constexpr int KC = kShrinkChunk;
+  constexpr int KCP = KC + 8;           // LDS pitch in elements: 16 bytes x odd
+  constexpr int CG = R / 8;             // 8-column groups of A_i
+  constexpr int KSTEPS = KC / 32;
+  __shared__ __align__(16) uint32_t at[RPAD * KCP / 2];  // A_i chunk, transposed: [n][k]
+
+  const int seg = blockIdx.z, s = blockIdx.x, tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
+  if (lo >= hi) return;
+  const uint16_t* A = A_ptrs[seg];
+  if (A == nullptr) return;
+  const int k0 = s * kslice;
+  const int klen = min(h_in, k0 + kslice) - k0;
+  if (klen <= 0) return;
+  const __amdgpu_buffer_rsrc_t rA =
+      make_buffer(A + layer_off + (long long)k0 * R, (uint32_t)klen * R * 2u);
+
+  if (R < RPAD) {  // rows of the transposed tile that no column of A_i fills
+    for (int i = tid; i < RPAD * KCP / 2; i += NT) at[i] = 0u;
+    __syncthreads();
+  }
+
+  const int m = lane & 15, g = lane >> 4;
+  for (int rb = blockIdx.y; rb * kShrinkRows < hi - lo; rb += gridDim.y) {
+    const int row0 = lo + rb * kShrinkRows + wave * 16;  // this wave's tile
+    const int rows_here = max(0, min(16, hi - row0));
+    // rows beyond the segment read as zeros
+    const __amdgpu_buffer_rsrc_t rX = make_buffer(
+        x + (long long)row0 * h_in + k0,
+        rows_here > 0 ? (uint32_t)((long long)(rows_here - 1) * h_in + klen) * 2u : 0u);
+    f32x4 acc[NTILE];
+#pragma unroll
+    for (int t = 0; t < NTILE; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int kc = 0; kc < klen; kc += KC) {
+      // this wave's x operands for the whole chunk: row m, k = kc + 32 ks + 8 g .. +7
+      uint4 xa[KSTEPS];
+#pragma unroll
+      for (int ks = 0; ks < KSTEPS; ++ks) {
+        const int k = kc + ks * 32 + g * 8;
+        xa[ks] = buffer_load128(rX, (m < rows_here && k < klen) ? (uint32_t)(m * h_in + k) * 2u : kOutOfRange);
+      }
+      // stage A_i[kc .. kc+KC) transposed; a thread takes a pair of k and eight columns
+      __syncthreads();  // previous chunk's readers are done
+#pragma unroll
+      for (int it = 0; it < (CG * (KC / 2) + NT - 1) / NT; ++it) {
+        const int item = it * NT + tid;
+        const int kp = item % (KC / 2), cg = item / (KC / 2);
+        if (cg < CG) {
+          const int k = kc + 2 * kp;
+          const uint4 r0 = buffer_load128(rA, (uint32_t)(k * R + cg * 8) * 2u);        // zeros past the slice
+          const uint4 r1 = buffer_load128(rA, (uint32_t)((k + 1) * R + cg * 8) * 2u);
+          const uint32_t a0[4] = {r0.x, r0.y, r0.z, r0.w}, a1[4] = {r1.x, r1.y, r1.z, r1.w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            at[((cg * 8 + 2 * i) * KCP) / 2 + kp] = (a0[i] & 0xFFFFu) | (a1[i] << 16);
+            at[((cg * 8 + 2 * i + 1) * KCP) / 2 + kp] = (a0[i] >> 16) | (a1[i] & 0xFFFF0000u);
+          }
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int ks = 0; ks < KSTEPS; ++ks) {
+        if (kc + ks * 32 < klen) {
+#pragma unroll
+          for (int t = 0; t < NTILE; ++t) {
+            const uint4 bt = *reinterpret_cast<const uint4*>(&at[((t * 16 + m) * KCP + ks * 32 + g * 8) / 2]);
+            acc[t] = mfma16x16x32<DT>(xa[ks], bt, acc[t]);
+          }
+        }
+      }
+    }
+    // D[row 4g+i][column m] of every tile
+#pragma unroll
+    for (int t = 0; t < NTILE; ++t) {
+      const int n = t * 16 + m;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = row0 + 4 * g + i;
+        if (n < R && row < hi) partials[((long long)s * n_tokens + row) * R + n] = acc[t][i];
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------- expand
+
+// Split an fp32 value into two 16-bit parts whose sum carries ~16-22 significant bits.
+template <class DT>
+__device__ __forceinline__ void split16(float v, uint32_t& hi, uint32_t& lo) {
+  hi = encode1<DT>(v);
+  lo = encode1<DT>(v - decode1<DT>((uint16_t)hi));
+}
+
+// grid = (column strips, row blocks, n_segs); the row-block dimension is walked
+// with a stride.  v_parts is [nparts][n_tokens][R] fp32, summed in ascending order.
+template <class DT, int R>
+__global__ __launch_bounds__(256) void expand_matrix_kernel(
+    uint16_t* __restrict__ y, const float* __restrict__ v_parts, int nparts,
+    const uint16_t* const* __restrict__ A_ptrs, const uint16_t* const* __restrict__ B_ptrs,
+    const int32_t* __restrict__ seg_starts, int h_out, int n_tokens, long long layer_off,
+    float scale) {
+  constexpr int NT = 256;
+  constexpr int KPAD = R < 32 ? 32 : R;  // k padded to the MFMA depth
+  constexpr int KSTEPS = KPAD / 32;
+  constexpr int KP = KPAD + 8;           // LDS pitch in elements: 16 bytes x odd
+  constexpr int NC = kExpandCols;
+  constexpr int KPAIRS = R / 2;
+  __shared__ __align__(16) uint32_t bt[NC * KP / 2];  // B_i strip, transposed: [column][k]
+
+  const int seg = blockIdx.z, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
+  if (lo >= hi) return;
+  const uint16_t* B = B_ptrs[seg];
+  if (B == nullptr) return;
+  if (A_ptrs != nullptr && A_ptrs[seg] == nullptr) return;
+  const int c0 = blockIdx.x * NC;
+  const int ncols = min(NC, h_out - c0);
+  const __amdgpu_buffer_rsrc_t rB = make_buffer(
+      B + layer_off + c0, (uint32_t)((long long)(R - 1) * h_out + ncols) * 2u);
+
+  // ---- stage the strip transposed: a thread takes a pair of k and eight columns
+  if (R < KPAD) {
+    for (int i = tid; i < NC * KP / 2; i += NT) bt[i] = 0u;
+    __syncthreads();
+  }
+  for (int item = tid; item < KPAIRS * (NC / 8); item += NT) {
+    const int kp = item % KPAIRS, cg = item / KPAIRS;
+    const bool in = cg * 8 < ncols;
+    const uint4 r0 = buffer_load128(rB, in ? (uint32_t)((2 * kp) * h_out + cg * 8) * 2u : kOutOfRange);
+    const uint4 r1 = buffer_load128(rB, in ? (uint32_t)((2 * kp + 1) * h_out + cg * 8) * 2u : kOutOfRange);
+    const uint32_t a0[4] = {r0.x, r0.y, r0.z, r0.w}, a1[4] = {r1.x, r1.y, r1.z, r1.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      bt[((cg * 8 + 2 * i) * KP) / 2 + kp] = (a0[i] & 0xFFFFu) | (a1[i] << 16);
+      bt[((cg * 8 + 2 * i + 1) * KP) / 2 + kp] = (a0[i] >> 16) | (a1[i] & 0xFFFF0000u);
+    }
+  }
+  __syncthreads();
+
+  // ---- operands: tile t, slot (lane % 16) = 4 q + i  <->  column 16 q + 4 t + i of the wave's 64
+  const int slot = lane & 15, g = lane >> 4;
+  uint4 bop[KSTEPS][4];
+#pragma unroll
+  for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int col = wave * 64 + (slot >> 2) * 16 + t * 4 + (slot & 3);
+      bop[ks][t] = *reinterpret_cast<const uint4*>(&bt[(col * KP + ks * 32 + g * 8) / 2]);
+    }
+
+  // this lane's output: row (lane % 16) of the tile, columns cw .. cw+15
+  const int m = lane & 15;
+  const int cw = c0 + wave * 64 + g * 16;
+  const long long pstride = (long long)n_tokens * R;
+  const int nblocks = (hi - lo + kExpandRows - 1) / kExpandRows;
+  for (int rb = blockIdx.y; rb < nblocks; rb += gridDim.y) {
+    const int rbeg = lo + rb * kExpandRows, rend = min(hi, rbeg + kExpandRows);
+    const __amdgpu_buffer_rsrc_t rY = make_buffer(
+        y + (long long)rbeg * h_out, (uint32_t)((long long)(rend - rbeg) * h_out) * 2u);
+    for (int row0 = rbeg; row0 < rend; row0 += 16) {
+      const int row = row0 + m;
+      const bool row_ok = row < rend;
+      const uint32_t yoff = (uint32_t)((row - rbeg) * h_out + cw) * 2u;
+      const uint4 y0 = buffer_load128(rY, (row_ok && cw < h_out) ? yoff : kOutOfRange);
+      const uint4 y1 = buffer_load128(rY, (row_ok && cw + 8 < h_out) ? yoff + 16u : kOutOfRange);
+
+      // v operand: row m, k = 32 ks + 8 g .. +7, summed over the split-K parts
+      float vf[KSTEPS][8];
+      const float* vrow = v_parts + (long long)min(row, rend - 1) * R;
+#pragma unroll
+      for (int ks = 0; ks < KSTEPS; ++ks) {
+        const int k = ks * 32 + g * 8;
+        if (k < R) {
+          float4 p0 = *reinterpret_cast<const float4*>(vrow + k);
+          float4 p1 = *reinterpret_cast<const float4*>(vrow + k + 4);
+          for (int p = 1; p < nparts; ++p) {
+            const float4 q0 = *reinterpret_cast<const float4*>(vrow + p * pstride + k);
+            const float4 q1 = *reinterpret_cast<const float4*>(vrow + p * pstride + k + 4);
+            p0.x += q0.x; p0.y += q0.y; p0.z += q0.z; p0.w += q0.w;
+            p1.x += q1.x; p1.y += q1.y; p1.z += q1.z; p1.w += q1.w;
+          }
+          vf[ks][0] = p0.x; vf[ks][1] = p0.y; vf[ks][2] = p0.z; vf[ks][3] = p0.w;
+          vf[ks][4] = p1.x; vf[ks][5] = p1.y; vf[ks][6] = p1.z; vf[ks][7] = p1.w;
+        } else {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) vf[ks][i] = 0.f;
+        }
+      }
+      // binary16 has a narrow range: bring the tile's largest |v| below 2^15 with an
+      // exact power-of-two factor that is undone on the fp32 result
+      float undo = 1.f;
+      if (std::is_same<DT, F16>::value) {
+        float amax = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+          for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(vf[ks][i]));
+#pragma unroll
+        for (int msk = 1; msk < 64; msk <<= 1) amax = fmaxf(amax, __shfl_xor(amax, msk, 64));
+        if (amax >= 16384.f && amax < 3.0e38f) {
+          const int e = ((__float_as_uint(amax) >> 23) & 0xFF) - 127 - 13;  // amax * 2^-e < 2^14
+          const float down = __uint_as_float((uint32_t)(127 - e) << 23);
+          undo = __uint_as_float((uint32_t)(127 + e) << 23);
+#pragma unroll
+          for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) vf[ks][i] *= down;
+        }
+      }
+      // as a high and a low 16-bit part
+      uint4 vh[KSTEPS], vl[KSTEPS];
+#pragma unroll
+      for (int ks = 0; ks < KSTEPS; ++ks) {
+        uint32_t h[8], l[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) split16<DT>(vf[ks][i], h[i], l[i]);
+        vh[ks] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+        vl[ks] = make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16));
+      }
+
+      f32x4 acc[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+          acc[t] = mfma16x16x32<DT>(bop[ks][t], vl[ks], acc[t]);
+          acc[t] = mfma16x16x32<DT>(bop[ks][t], vh[ks], acc[t]);
+        }
+      }
+      // acc[t][i] is column cw + 4 t + i of row m
+      float yf[16];
+      {
+        float a8[8];
+        unpack8<DT>(y0, a8);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) yf[i] = a8[i];
+        unpack8<DT>(y1, a8);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) yf[8 + i] = a8[i];
+      }
+      float o[16];
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[t * 4 + i] = yf[t * 4 + i] + scale * (undo * acc[t][i]);
+      uint4 out0, out1;
+      out0.x = pack2<DT>(o[0], o[1]);   out0.y = pack2<DT>(o[2], o[3]);
+      out0.z = pack2<DT>(o[4], o[5]);   out0.w = pack2<DT>(o[6], o[7]);
+      out1.x = pack2<DT>(o[8], o[9]);   out1.y = pack2<DT>(o[10], o[11]);
+      out1.z = pack2<DT>(o[12], o[13]); out1.w = pack2<DT>(o[14], o[15]);
+      buffer_store128(rY, (row_ok && cw < h_out) ? yoff : kOutOfRange, out0);
+      buffer_store128(rY, (row_ok && cw + 8 < h_out) ? yoff + 16u : kOutOfRange, out1);
+    }
+  }
+}
+
+// ---------------------------------------------------------------- launchers
+
+static unsigned row_blocks(int max_seg_len, int n_tokens, int rows_per_block) {
+  const int longest = max_seg_len > 0 ? max_seg_len : n_tokens;
+  int b = (longest + rows_per_block - 1) / rows_per_block;
+  if (b < 1) b = 1;
+  if (b > 1024) b = 1024;  // the kernels stride over row blocks
+  return (unsigned)b;
+}
+
+template <class DT, int R>
+static hipError_t launch_shrink_matrix_t(const ShrinkArgs& a, hipStream_t st) {
+  dim3 grid((unsigned)a.ksplit, row_blocks(a.max_seg_len, a.n_tokens, kShrinkRows), (unsigned)a.n_segs);
+  hipLaunchKernelGGL((shrink_matrix_kernel<DT, R>), grid, dim3(256), 0, st, (const uint16_t*)a.x,
+                     (const uint16_t* const*)a.A_ptrs, a.seg_starts, a.partials, a.h_in, a.kslice,
+                     a.n_tokens, a.layer_off);
+  return hipGetLastError();
+}
+
+template <class DT>
+static hipError_t launch_shrink_matrix_r(const ShrinkArgs& a, hipStream_t st) {
+  switch (a.r) {
+    case 8: return launch_shrink_matrix_t<DT, 8>(a, st);
+    case 16: return launch_shrink_matrix_t<DT, 16>(a, st);
+    case 32: return launch_shrink_matrix_t<DT, 32>(a, st);
+    case 64: return launch_shrink_matrix_t<DT, 64>(a, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_shrink_matrix(const ShrinkArgs& a, hipStream_t st) {
+  if (a.n_segs > 65535) return hipErrorInvalidValue;
+  return a.bf16 ? launch_shrink_matrix_r<BF16>(a, st) : launch_shrink_matrix_r<F16>(a, st);
+}
+
+template <class DT, int R>
+static hipError_t launch_expand_matrix_t(const ExpandArgs& a, hipStream_t st) {
+  dim3 grid((unsigned)((a.h_out + kExpandCols - 1) / kExpandCols),
+            row_blocks(a.max_seg_len, a.n_tokens, kExpandRows), (unsigned)a.n_segs);
+  hipLaunchKernelGGL((expand_matrix_kernel<DT, R>), grid, dim3(256), 0, st, (uint16_t*)a.y,
+                     a.v_parts, a.nparts, (const uint16_t* const*)a.A_ptrs,
+                     (const uint16_t* const*)a.B_ptrs, a.seg_starts, a.h_out, a.n_tokens,
+                     a.layer_off, a.scale);
+  return hipGetLastError();
+}
+
+template <class DT>
+static hipError_t launch_expand_matrix_r(const ExpandArgs& a, hipStream_t st) {
+  switch (a.r) {
+    case 8: return launch_expand_matrix_t<DT, 8>(a, st);
+    case 16: return launch_expand_matrix_t<DT, 16>(a, st);
+    case 32: return launch_expand_matrix_t<DT, 32>(a, st);
+    case 64: return launch_expand_matrix_t<DT, 64>(a, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_expand_matrix(const ExpandArgs& a, hipStream_t st) {
+  if (a.n_segs > 65535) return hipErrorInvalidValue;
+  return a.bf16 ? launch_expand_matrix_r<BF16>(a, st) : launch_expand_matrix_r<F16>(a, st);
+}
+
+}  // namespace sgmv

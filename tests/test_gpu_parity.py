@@ -340,3 +340,79 @@ def test_auto_uses_two_launches_without_ready_workspace():
     d = _dev(w, init_workspace=False)
     d.add_lora()
     assert_parity(d.y_bits(), oracle.run_workload(w), "f16", "workspace not initialised")
+
+
+# ------------------------------------------------------- MFMA (matrix) path
+def _matrix(w, **kw):
+    from paper_2310_18547_amd import binding as B
+    return _dev(w, path=B.PATH_MATRIX, **kw)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("r", [8, 16, 32, 64])
+def test_matrix_path_ragged_segments(dtype, r):
+    # tile-boundary lengths (15, 16, 17, 64, 65), an empty segment, widths that are not
+    # multiples of the 256-column strip or the 256-deep k chunk
+    w = wl.custom([17, 1, 64, 0, 15, 65, 16, 130], 1032, 776, r, dtype, seed=60 + r, num_layers=2,
+                  scale=0.5)
+    ref = oracle.run_workload(w, layer_idx=1, n_threads=8)
+    d = _matrix(w)
+    d.add_lora(1)
+    assert_parity(d.y_bits(), ref, dtype, f"matrix add_lora r={r}")
+    # the two steps on their own
+    d2 = _matrix(w)
+    v = torch.zeros(w.n_tokens, r, dtype=torch.float32, device="cuda:0")
+    d2.shrink(v, 1)
+    v_ref = oracle.run_workload(w, op="shrink", layer_idx=1, n_threads=8)
+    assert np.all(np.abs(v.cpu().numpy() - v_ref) <= 2e-3 + 2e-2 * np.abs(v_ref))
+    d2.expand(v, 1)
+    assert_parity(d2.y_bits(), ref, dtype, f"matrix two-step r={r}")
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_matrix_path_fingerprint_bit_exact(dtype):
+    lens = [40, 0, 3, 129, 16, 1, 70]
+    w = wl.fingerprint(lens, 512, 328, 16, dtype, num_layers=3)
+    for layer in range(3):
+        d = _matrix(w)
+        d.add_lora(layer)
+        assert np.array_equal(d.y_bits(), oracle.run_workload(w, layer_idx=layer))
+
+
+@pytest.mark.parametrize("ksplit", [1, 2, 3, 8])
+def test_matrix_path_every_split(ksplit):
+    w = wl.custom([100, 33], 2048 + 64, 512, 32, "bf16", seed=70)
+    d = _matrix(w, ksplit=ksplit)
+    d.add_lora()
+    assert_parity(d.y_bits(), oracle.run_workload(w, n_threads=8), "bf16", f"matrix ksplit={ksplit}")
+
+
+def test_matrix_path_null_adapter_and_tiny():
+    w = wl.custom([20, 30, 10], 256, 264, 16, "f16", seed=71)
+    w.seg_adapter = np.asarray([0, -1, 2], np.int64)
+    d = _matrix(w)
+    d.add_lora()
+    got = d.y_bits()
+    assert np.array_equal(got[20:50], w.y0[20:50])
+    assert_parity(got, oracle.run_workload(w), "f16", "matrix null adapter")
+    t = wl.tiny()
+    assert_parity(run_add_lora(t, path=3 - 1), oracle.run_workload(t), "f16", "matrix tiny")
+
+
+def test_matrix_path_f16_large_v_keeps_range():
+    # |v| far beyond the binary16 range must not overflow inside the matrix cores
+    w = wl.custom([48], 256, 256, 16, "f16", seed=72)
+    w.x = wl.encode(np.full(w.x.shape, 2048.0, np.float32), "f16")
+    w.A = [wl.encode(np.full(a.shape, 1.0, np.float32), "f16") for a in w.A]      # v = 2048*256 = 524288
+    w.B = [wl.encode(np.full(b.shape, 2.0 ** -16, np.float32), "f16") for b in w.B]
+    d = _matrix(w)
+    d.add_lora()
+    got = decode64(d.y_bits(), "f16")
+    ref = decode64(oracle.run_workload(w), "f16")
+    assert np.all(np.isfinite(got)) and np.all(np.abs(got - ref) <= tolerance(ref))
+
+
+def test_matrix_path_deterministic():
+    w = wl.custom([200, 77], 1024, 512, 64, "bf16", seed=73)
+    a = run_add_lora(w, path=2)
+    assert np.array_equal(run_add_lora(w, path=2), a)
