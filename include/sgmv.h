@@ -159,7 +159,9 @@ int sgmv_shrink(const sgmv_problem* p, float* v, const void* x,
  *   y      device 16-bit [n_tokens][h_out], read and written
  *   v      device fp32 [n_tokens][r], read
  *   B_ptrs device array of n_segs device pointers
- * Needs no workspace.  h_in of the descriptor is ignored. */
+ * The vector kernels need no workspace; the MFMA kernels (SGMV_PATH_MATRIX, or
+ * SGMV_PATH_AUTO with long segments and a workspace present) keep v's 16-bit
+ * operand pairs in p->workspace.  h_in of the descriptor is ignored. */
 int sgmv_expand(const sgmv_problem* p, void* y, const float* v,
                 const void* const* B_ptrs, const int32_t* seg_starts,
                 int32_t n_segs, int32_t layer_idx, float scale, void* stream);

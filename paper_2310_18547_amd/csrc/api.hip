@@ -117,6 +117,18 @@ unsigned long long* exchange_base(void* workspace, int n_tokens, int r) {
                                                partial_bytes(n_tokens, r));
 }
 
+// Operands of the MFMA expand: v as high and low 16-bit parts, one range factor per row.
+size_t operand_bytes(int n_tokens, int r) {
+  return 2 * round_up((size_t)n_tokens * r * 2, 256) + round_up((size_t)n_tokens * 4, 256);
+}
+void set_operands(ExpandArgs* a, void* workspace, int n_tokens, int r) {
+  char* base = static_cast<char*>(workspace) + kWorkspaceHeader + 3 * partial_bytes(n_tokens, r);
+  const size_t half = round_up((size_t)n_tokens * r * 2, 256);
+  a->vh = reinterpret_cast<uint16_t*>(base);
+  a->vl = reinterpret_cast<uint16_t*>(base + half);
+  a->undo = reinterpret_cast<float*>(base + 2 * half);
+}
+
 // Launch shape of the single-launch path; false when it does not apply.
 bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f) {
   if (!p->workspace_ready) return false;
@@ -192,6 +204,8 @@ ExpandArgs make_expand(const sgmv_problem* p, void* y, const float* v_parts, int
   a.B_ptrs = B_ptrs;
   a.seg_starts = seg_starts;
   a.scale = scale;
+  a.vh = a.vl = nullptr;
+  a.undo = nullptr;
   return a;
 }
 
@@ -216,7 +230,8 @@ const char* sgmv_status_string(int status) {
 
 size_t sgmv_workspace_bytes(int32_t n_tokens, int32_t r) {
   if (n_tokens <= 0 || r <= 0) return 0;
-  return kWorkspaceHeader + 3 * partial_bytes(n_tokens, r);  // fp32 partials + 64-bit exchange words
+  // header, fp32 split-K partials, 64-bit exchange words, 16-bit operand pairs of v
+  return kWorkspaceHeader + 3 * partial_bytes(n_tokens, r) + operand_bytes(n_tokens, r);
 }
 
 int sgmv_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
@@ -286,7 +301,11 @@ int sgmv_expand(const sgmv_problem* p, void* y, const float* v, const void* cons
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   ExpandArgs a = make_expand(p, y, v, 1, nullptr, B_ptrs, seg_starts, n_segs, layer_idx, scale);
-  if (use_matrix(p, n_segs)) {
+  // the MFMA kernels keep v's 16-bit operand pairs in the workspace
+  const bool have_ws = check_workspace(p) == SGMV_OK;
+  if (p->path == SGMV_PATH_MATRIX && !have_ws) return check_workspace(p);
+  if (have_ws && use_matrix(p, n_segs)) {
+    set_operands(&a, p->workspace, p->n_tokens, p->r);
     if (launch_expand_matrix(a, st) != hipSuccess) return SGMV_ERR_LAUNCH;
   } else {
     if (launch_expand_vector(a, st) != hipSuccess) return SGMV_ERR_LAUNCH;
@@ -337,6 +356,7 @@ int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x, const void* con
     if (launch_shrink_matrix(s, st) != hipSuccess) return SGMV_ERR_LAUNCH;
     ExpandArgs e = make_expand(p, y, s.partials, s.ksplit, A_ptrs, B_ptrs, seg_starts, n_segs,
                                layer_idx, scale);
+    set_operands(&e, p->workspace, p->n_tokens, p->r);
     if (launch_expand_matrix(e, st) != hipSuccess) return SGMV_ERR_LAUNCH;
     return SGMV_OK;
   }

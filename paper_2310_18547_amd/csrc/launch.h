@@ -45,6 +45,10 @@ struct ExpandArgs {
   const void* const* B_ptrs;
   const int32_t* seg_starts;
   float scale;
+  // MFMA path only: 16-bit operand pairs of v and the per-row range factor (workspace)
+  uint16_t* vh;
+  uint16_t* vl;
+  float* undo;
 };
 
 struct FusedArgs {

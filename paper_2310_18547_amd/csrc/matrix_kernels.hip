@@ -107,25 +107,41 @@ __global__ __launch_bounds__(256) void shrink_matrix_kernel(
 #pragma unroll
     for (int t = 0; t < NTILE; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    for (int kc = 0; kc < klen; kc += KC) {
-      // this wave's x operands for the whole chunk: row m, k = kc + 32 ks + 8 g .. +7
-      uint4 xa[KSTEPS];
+    // Software pipeline over the k chunks: while the matrix cores work on chunk c
+    // (x operands in registers, A_i chunk transposed in LDS), the loads of chunk
+    // c+1 -- this wave's x operands and this thread's share of A_i -- are in flight.
+    constexpr int ITEMS = (CG * (KC / 2) + NT - 1) / NT;  // (k pair, 8 columns) items per thread
+    uint4 xn[KSTEPS], an0[ITEMS], an1[ITEMS];
+    auto issue = [&](int kc) {
 #pragma unroll
       for (int ks = 0; ks < KSTEPS; ++ks) {
-        const int k = kc + ks * 32 + g * 8;
-        xa[ks] = buffer_load128(rX, (m < rows_here && k < klen) ? (uint32_t)(m * h_in + k) * 2u : kOutOfRange);
+        const int k = kc + ks * 32 + g * 8;  // row m, k .. k+7
+        xn[ks] = buffer_load128(rX, (m < rows_here && k < klen) ? (uint32_t)(m * h_in + k) * 2u : kOutOfRange);
       }
-      // stage A_i[kc .. kc+KC) transposed; a thread takes a pair of k and eight columns
-      __syncthreads();  // previous chunk's readers are done
 #pragma unroll
-      for (int it = 0; it < (CG * (KC / 2) + NT - 1) / NT; ++it) {
+      for (int it = 0; it < ITEMS; ++it) {
+        const int item = it * NT + tid;
+        const int kp = item % (KC / 2), cg = item / (KC / 2);
+        const int k = kc + 2 * kp;
+        const bool in = cg < CG;               // rows past the slice read as zeros
+        an0[it] = buffer_load128(rA, in ? (uint32_t)(k * R + cg * 8) * 2u : kOutOfRange);
+        an1[it] = buffer_load128(rA, in ? (uint32_t)((k + 1) * R + cg * 8) * 2u : kOutOfRange);
+      }
+    };
+    issue(0);
+    for (int kc = 0; kc < klen; kc += KC) {
+      uint4 xa[KSTEPS];
+#pragma unroll
+      for (int ks = 0; ks < KSTEPS; ++ks) xa[ks] = xn[ks];
+      __syncthreads();  // previous chunk's readers are done
+      // a thread's item: a pair of k and eight columns, written transposed
+#pragma unroll
+      for (int it = 0; it < ITEMS; ++it) {
         const int item = it * NT + tid;
         const int kp = item % (KC / 2), cg = item / (KC / 2);
         if (cg < CG) {
-          const int k = kc + 2 * kp;
-          const uint4 r0 = buffer_load128(rA, (uint32_t)(k * R + cg * 8) * 2u);        // zeros past the slice
-          const uint4 r1 = buffer_load128(rA, (uint32_t)((k + 1) * R + cg * 8) * 2u);
-          const uint32_t a0[4] = {r0.x, r0.y, r0.z, r0.w}, a1[4] = {r1.x, r1.y, r1.z, r1.w};
+          const uint32_t a0[4] = {an0[it].x, an0[it].y, an0[it].z, an0[it].w};
+          const uint32_t a1[4] = {an1[it].x, an1[it].y, an1[it].z, an1[it].w};
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             at[((cg * 8 + 2 * i) * KCP) / 2 + kp] = (a0[i] & 0xFFFFu) | (a1[i] << 16);
@@ -134,6 +150,7 @@ __global__ __launch_bounds__(256) void shrink_matrix_kernel(
         }
       }
       __syncthreads();
+      if (kc + KC < klen) issue(kc + KC);
 #pragma unroll
       for (int ks = 0; ks < KSTEPS; ++ks) {
         if (kc + ks * 32 < klen) {
@@ -167,14 +184,77 @@ __device__ __forceinline__ void split16(float v, uint32_t& hi, uint32_t& lo) {
   lo = encode1<DT>(v - decode1<DT>((uint16_t)hi));
 }
 
+// v[row][k] = sum over the split-K parts (ascending), written out as the two
+// 16-bit operands the expand kernel feeds to the matrix cores:
+//   vh, vl  [n_tokens][R] 16-bit, undo [n_tokens] fp32.
+// binary16 has a narrow range, so for F16 a row whose largest |v| reaches 2^14 is
+// scaled down by an exact power of two; `undo` is the factor that restores the
+// fp32 result (1 otherwise).  One thread handles eight consecutive k of a row.
+template <class DT, int R>
+__global__ __launch_bounds__(256) void finalize_v_kernel(
+    const float* __restrict__ v_parts, int nparts, uint16_t* __restrict__ vh,
+    uint16_t* __restrict__ vl, float* __restrict__ undo, int n_tokens) {
+  constexpr int GPR = R / 8;  // threads per row
+  const long long item = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long total = (long long)n_tokens * GPR;
+  const bool live = item < total;
+  const long long e0 = (live ? item : total - 1) * 8;  // first element (row * R + k)
+  const long long pstride = (long long)n_tokens * R;
+  float f[8];
+  {
+    float4 p0 = make_float4(0.f, 0.f, 0.f, 0.f), p1 = p0;
+    for (int pb = 0; pb < nparts; pb += 4) {  // four parts' loads in flight together, added in order
+      float4 q0[4], q1[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int p = min(pb + i, nparts - 1);
+        q0[i] = *reinterpret_cast<const float4*>(v_parts + p * pstride + e0);
+        q1[i] = *reinterpret_cast<const float4*>(v_parts + p * pstride + e0 + 4);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (pb + i < nparts) {
+          p0.x += q0[i].x; p0.y += q0[i].y; p0.z += q0[i].z; p0.w += q0[i].w;
+          p1.x += q1[i].x; p1.y += q1[i].y; p1.z += q1[i].z; p1.w += q1[i].w;
+        }
+      }
+    }
+    f[0] = p0.x; f[1] = p0.y; f[2] = p0.z; f[3] = p0.w;
+    f[4] = p1.x; f[5] = p1.y; f[6] = p1.z; f[7] = p1.w;
+  }
+  float un = 1.f;
+  if (std::is_same<DT, F16>::value) {
+    float amax = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(f[i]));
+#pragma unroll
+    for (int msk = 1; msk < GPR; msk <<= 1) amax = fmaxf(amax, __shfl_xor(amax, msk, 64));  // the row's threads
+    if (amax >= 16384.f && amax < 3.0e38f) {
+      const int e = ((__float_as_uint(amax) >> 23) & 0xFF) - 127 - 13;  // amax * 2^-e < 2^14
+      const float down = __uint_as_float((uint32_t)(127 - e) << 23);
+      un = __uint_as_float((uint32_t)(127 + e) << 23);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) f[i] *= down;
+    }
+  }
+  uint32_t h[8], l[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) split16<DT>(f[i], h[i], l[i]);
+  if (live) {
+    store128(vh + e0, make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)));
+    store128(vl + e0, make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)));
+    if (item % GPR == 0) undo[item / GPR] = un;
+  }
+}
+
 // grid = (column strips, row blocks, n_segs); the row-block dimension is walked
-// with a stride.  v_parts is [nparts][n_tokens][R] fp32, summed in ascending order.
+// with a stride.  vh / vl / undo come from finalize_v_kernel.
 template <class DT, int R>
 __global__ __launch_bounds__(256) void expand_matrix_kernel(
-    uint16_t* __restrict__ y, const float* __restrict__ v_parts, int nparts,
-    const uint16_t* const* __restrict__ A_ptrs, const uint16_t* const* __restrict__ B_ptrs,
-    const int32_t* __restrict__ seg_starts, int h_out, int n_tokens, long long layer_off,
-    float scale) {
+    uint16_t* __restrict__ y, const uint16_t* __restrict__ vh, const uint16_t* __restrict__ vl,
+    const float* __restrict__ undo, const uint16_t* const* __restrict__ A_ptrs,
+    const uint16_t* const* __restrict__ B_ptrs, const int32_t* __restrict__ seg_starts, int h_out,
+    int n_tokens, long long layer_off, float scale) {
   constexpr int NT = 256;
   constexpr int KPAD = R < 32 ? 32 : R;  // k padded to the MFMA depth
   constexpr int KSTEPS = KPAD / 32;
@@ -189,6 +269,8 @@ __global__ __launch_bounds__(256) void expand_matrix_kernel(
   const uint16_t* B = B_ptrs[seg];
   if (B == nullptr) return;
   if (A_ptrs != nullptr && A_ptrs[seg] == nullptr) return;
+  const int nblocks = (hi - lo + kExpandRows - 1) / kExpandRows;
+  if ((int)blockIdx.y >= nblocks) return;
   const int c0 = blockIdx.x * NC;
   const int ncols = min(NC, h_out - c0);
   const __amdgpu_buffer_rsrc_t rB = make_buffer(
@@ -199,16 +281,33 @@ __global__ __launch_bounds__(256) void expand_matrix_kernel(
     for (int i = tid; i < NC * KP / 2; i += NT) bt[i] = 0u;
     __syncthreads();
   }
-  for (int item = tid; item < KPAIRS * (NC / 8); item += NT) {
-    const int kp = item % KPAIRS, cg = item / KPAIRS;
-    const bool in = cg * 8 < ncols;
-    const uint4 r0 = buffer_load128(rB, in ? (uint32_t)((2 * kp) * h_out + cg * 8) * 2u : kOutOfRange);
-    const uint4 r1 = buffer_load128(rB, in ? (uint32_t)((2 * kp + 1) * h_out + cg * 8) * 2u : kOutOfRange);
-    const uint32_t a0[4] = {r0.x, r0.y, r0.z, r0.w}, a1[4] = {r1.x, r1.y, r1.z, r1.w};
+  {
+    constexpr int TOTAL = KPAIRS * (NC / 8);  // (k pair, 8 columns) items
+    constexpr int BATCH = 4;                  // items per thread with their loads in flight together
+    for (int base = 0; base < TOTAL; base += NT * BATCH) {
+      uint4 r0[BATCH], r1[BATCH];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      bt[((cg * 8 + 2 * i) * KP) / 2 + kp] = (a0[i] & 0xFFFFu) | (a1[i] << 16);
-      bt[((cg * 8 + 2 * i + 1) * KP) / 2 + kp] = (a0[i] >> 16) | (a1[i] & 0xFFFF0000u);
+      for (int b = 0; b < BATCH; ++b) {
+        const int item = base + b * NT + tid;
+        const int kp = item % KPAIRS, cg = item / KPAIRS;
+        const bool in = item < TOTAL && cg * 8 < ncols;
+        r0[b] = buffer_load128(rB, in ? (uint32_t)((2 * kp) * h_out + cg * 8) * 2u : kOutOfRange);
+        r1[b] = buffer_load128(rB, in ? (uint32_t)((2 * kp + 1) * h_out + cg * 8) * 2u : kOutOfRange);
+      }
+#pragma unroll
+      for (int b = 0; b < BATCH; ++b) {
+        const int item = base + b * NT + tid;
+        const int kp = item % KPAIRS, cg = item / KPAIRS;
+        if (item < TOTAL) {
+          const uint32_t a0[4] = {r0[b].x, r0[b].y, r0[b].z, r0[b].w};
+          const uint32_t a1[4] = {r1[b].x, r1[b].y, r1[b].z, r1[b].w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            bt[((cg * 8 + 2 * i) * KP) / 2 + kp] = (a0[i] & 0xFFFFu) | (a1[i] << 16);
+            bt[((cg * 8 + 2 * i + 1) * KP) / 2 + kp] = (a0[i] >> 16) | (a1[i] & 0xFFFF0000u);
+          }
+        }
+      }
     }
   }
   __syncthreads();
@@ -227,106 +326,84 @@ __global__ __launch_bounds__(256) void expand_matrix_kernel(
   // this lane's output: row (lane % 16) of the tile, columns cw .. cw+15
   const int m = lane & 15;
   const int cw = c0 + wave * 64 + g * 16;
-  const long long pstride = (long long)n_tokens * R;
-  const int nblocks = (hi - lo + kExpandRows - 1) / kExpandRows;
+  const bool c_ok0 = cw < h_out, c_ok1 = cw + 8 < h_out;
+
+  struct Tile {  // everything one row tile reads from memory
+    uint4 y0, y1, h[KSTEPS], l[KSTEPS];
+    float un;
+  };
   for (int rb = blockIdx.y; rb < nblocks; rb += gridDim.y) {
     const int rbeg = lo + rb * kExpandRows, rend = min(hi, rbeg + kExpandRows);
-    const __amdgpu_buffer_rsrc_t rY = make_buffer(
-        y + (long long)rbeg * h_out, (uint32_t)((long long)(rend - rbeg) * h_out) * 2u);
-    for (int row0 = rbeg; row0 < rend; row0 += 16) {
-      const int row = row0 + m;
-      const bool row_ok = row < rend;
-      const uint32_t yoff = (uint32_t)((row - rbeg) * h_out + cw) * 2u;
-      const uint4 y0 = buffer_load128(rY, (row_ok && cw < h_out) ? yoff : kOutOfRange);
-      const uint4 y1 = buffer_load128(rY, (row_ok && cw + 8 < h_out) ? yoff + 16u : kOutOfRange);
+    const int nrows = rend - rbeg;
+    const __amdgpu_buffer_rsrc_t rY = make_buffer(y + (long long)rbeg * h_out, (uint32_t)((long long)nrows * h_out) * 2u);
+    const __amdgpu_buffer_rsrc_t rH = make_buffer(vh + (long long)rbeg * R, (uint32_t)(nrows * R) * 2u);
+    const __amdgpu_buffer_rsrc_t rL = make_buffer(vl + (long long)rbeg * R, (uint32_t)(nrows * R) * 2u);
 
-      // v operand: row m, k = 32 ks + 8 g .. +7, summed over the split-K parts
-      float vf[KSTEPS][8];
-      const float* vrow = v_parts + (long long)min(row, rend - 1) * R;
+    auto fetch = [&](int r0, Tile& T) {  // rows r0 .. r0+15 relative to rbeg
+      const int row = r0 + m;
+      const bool ok = row < nrows;
+      const uint32_t yoff = (uint32_t)(row * h_out + cw) * 2u;
+      T.y0 = buffer_load128(rY, (ok && c_ok0) ? yoff : kOutOfRange);
+      T.y1 = buffer_load128(rY, (ok && c_ok1) ? yoff + 16u : kOutOfRange);
 #pragma unroll
       for (int ks = 0; ks < KSTEPS; ++ks) {
         const int k = ks * 32 + g * 8;
-        if (k < R) {
-          float4 p0 = *reinterpret_cast<const float4*>(vrow + k);
-          float4 p1 = *reinterpret_cast<const float4*>(vrow + k + 4);
-          for (int p = 1; p < nparts; ++p) {
-            const float4 q0 = *reinterpret_cast<const float4*>(vrow + p * pstride + k);
-            const float4 q1 = *reinterpret_cast<const float4*>(vrow + p * pstride + k + 4);
-            p0.x += q0.x; p0.y += q0.y; p0.z += q0.z; p0.w += q0.w;
-            p1.x += q1.x; p1.y += q1.y; p1.z += q1.z; p1.w += q1.w;
-          }
-          vf[ks][0] = p0.x; vf[ks][1] = p0.y; vf[ks][2] = p0.z; vf[ks][3] = p0.w;
-          vf[ks][4] = p1.x; vf[ks][5] = p1.y; vf[ks][6] = p1.z; vf[ks][7] = p1.w;
-        } else {
-#pragma unroll
-          for (int i = 0; i < 8; ++i) vf[ks][i] = 0.f;
-        }
+        const uint32_t voff = (ok && k < R) ? (uint32_t)(row * R + k) * 2u : kOutOfRange;
+        T.h[ks] = buffer_load128(rH, voff);
+        T.l[ks] = buffer_load128(rL, voff);
       }
-      // binary16 has a narrow range: bring the tile's largest |v| below 2^15 with an
-      // exact power-of-two factor that is undone on the fp32 result
-      float undo = 1.f;
-      if (std::is_same<DT, F16>::value) {
-        float amax = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks)
-#pragma unroll
-          for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(vf[ks][i]));
-#pragma unroll
-        for (int msk = 1; msk < 64; msk <<= 1) amax = fmaxf(amax, __shfl_xor(amax, msk, 64));
-        if (amax >= 16384.f && amax < 3.0e38f) {
-          const int e = ((__float_as_uint(amax) >> 23) & 0xFF) - 127 - 13;  // amax * 2^-e < 2^14
-          const float down = __uint_as_float((uint32_t)(127 - e) << 23);
-          undo = __uint_as_float((uint32_t)(127 + e) << 23);
-#pragma unroll
-          for (int ks = 0; ks < KSTEPS; ++ks)
-#pragma unroll
-            for (int i = 0; i < 8; ++i) vf[ks][i] *= down;
-        }
-      }
-      // as a high and a low 16-bit part
-      uint4 vh[KSTEPS], vl[KSTEPS];
-#pragma unroll
-      for (int ks = 0; ks < KSTEPS; ++ks) {
-        uint32_t h[8], l[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) split16<DT>(vf[ks][i], h[i], l[i]);
-        vh[ks] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-        vl[ks] = make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16));
-      }
-
+      T.un = std::is_same<DT, F16>::value ? undo[rbeg + min(row, nrows - 1)] : 1.f;
+    };
+    auto finish = [&](int r0, const Tile& T) {
       f32x4 acc[4];
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
-          acc[t] = mfma16x16x32<DT>(bop[ks][t], vl[ks], acc[t]);
-          acc[t] = mfma16x16x32<DT>(bop[ks][t], vh[ks], acc[t]);
+          acc[t] = mfma16x16x32<DT>(bop[ks][t], T.l[ks], acc[t]);
+          acc[t] = mfma16x16x32<DT>(bop[ks][t], T.h[ks], acc[t]);
         }
       }
       // acc[t][i] is column cw + 4 t + i of row m
       float yf[16];
       {
         float a8[8];
-        unpack8<DT>(y0, a8);
+        unpack8<DT>(T.y0, a8);
 #pragma unroll
         for (int i = 0; i < 8; ++i) yf[i] = a8[i];
-        unpack8<DT>(y1, a8);
+        unpack8<DT>(T.y1, a8);
 #pragma unroll
         for (int i = 0; i < 8; ++i) yf[8 + i] = a8[i];
       }
+      const float sc = scale * T.un;
       float o[16];
 #pragma unroll
       for (int t = 0; t < 4; ++t)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) o[t * 4 + i] = yf[t * 4 + i] + scale * (undo * acc[t][i]);
+        for (int i = 0; i < 4; ++i) o[t * 4 + i] = yf[t * 4 + i] + sc * acc[t][i];
       uint4 out0, out1;
       out0.x = pack2<DT>(o[0], o[1]);   out0.y = pack2<DT>(o[2], o[3]);
       out0.z = pack2<DT>(o[4], o[5]);   out0.w = pack2<DT>(o[6], o[7]);
       out1.x = pack2<DT>(o[8], o[9]);   out1.y = pack2<DT>(o[10], o[11]);
       out1.z = pack2<DT>(o[12], o[13]); out1.w = pack2<DT>(o[14], o[15]);
-      buffer_store128(rY, (row_ok && cw < h_out) ? yoff : kOutOfRange, out0);
-      buffer_store128(rY, (row_ok && cw + 8 < h_out) ? yoff + 16u : kOutOfRange, out1);
+      const int row = r0 + m;
+      const bool ok = row < nrows;
+      const uint32_t yoff = (uint32_t)(row * h_out + cw) * 2u;
+      buffer_store128(rY, (ok && c_ok0) ? yoff : kOutOfRange, out0);
+      buffer_store128(rY, (ok && c_ok1) ? yoff + 16u : kOutOfRange, out1);
+    };
+
+    // two row tiles in flight: the next tile's loads are issued before this one is finished
+    Tile cur, nxt;
+    fetch(0, cur);
+    for (int r0 = 0; r0 < nrows; r0 += 32) {
+      if (r0 + 16 < nrows) fetch(r0 + 16, nxt);
+      finish(r0, cur);
+      if (r0 + 16 < nrows) {
+        if (r0 + 32 < nrows) fetch(r0 + 32, cur);
+        finish(r0 + 16, nxt);
+      }
     }
   }
 }
@@ -370,8 +447,14 @@ template <class DT, int R>
 static hipError_t launch_expand_matrix_t(const ExpandArgs& a, hipStream_t st) {
   dim3 grid((unsigned)((a.h_out + kExpandCols - 1) / kExpandCols),
             row_blocks(a.max_seg_len, a.n_tokens, kExpandRows), (unsigned)a.n_segs);
-  hipLaunchKernelGGL((expand_matrix_kernel<DT, R>), grid, dim3(256), 0, st, (uint16_t*)a.y,
-                     a.v_parts, a.nparts, (const uint16_t* const*)a.A_ptrs,
+  // v -> 16-bit operand pairs, then the expand proper
+  const long long items = (long long)a.n_tokens * (R / 8);
+  hipLaunchKernelGGL((finalize_v_kernel<DT, R>), dim3((unsigned)((items + 255) / 256)), dim3(256), 0,
+                     st, a.v_parts, a.nparts, a.vh, a.vl, a.undo, a.n_tokens);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  hipLaunchKernelGGL((expand_matrix_kernel<DT, R>), grid, dim3(256), 0, st, (uint16_t*)a.y, a.vh,
+                     a.vl, a.undo, (const uint16_t* const*)a.A_ptrs,
                      (const uint16_t* const*)a.B_ptrs, a.seg_starts, a.h_out, a.n_tokens,
                      a.layer_off, a.scale);
   return hipGetLastError();

@@ -45,9 +45,9 @@ def test_workspace_bytes():
     for T in (1, 7, 64, 1000, 4608, 100000):
         for r in (8, 16, 32, 64):
             b = sg.sgmv_workspace_bytes(T, r)
-            assert b >= 1024 + 3 * 16 * T * r * 4     # header, >= 16 split-K slices, exchange words
-            assert b <= 1024 + 3 * (64 * T * r * 4 + 256) and b % 256 == 0
-    assert sg.sgmv_workspace_bytes(64, 16) == 1024 + 3 * 64 * 64 * 16 * 4
+            assert b >= 1024 + 3 * 16 * T * r * 4 + T * r * 4 + T * 4   # header, >= 16 slices, exchange, operands
+            assert b <= 1024 + 3 * (64 * T * r * 4 + 256) + T * r * 4 + T * 4 + 768 and b % 256 == 0
+    assert sg.sgmv_workspace_bytes(64, 16) == 1024 + 3 * 64 * 64 * 16 * 4 + 2 * 2048 + 256
 
 
 def test_validate_segments():
