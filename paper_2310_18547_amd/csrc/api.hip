@@ -18,7 +18,7 @@ constexpr int kFusedWorkgroups = 256;  // one workgroup per compute unit
 constexpr int kFusedMaxWorkgroups = 1024;
 constexpr int kFusedSpinLimit = 1 << 18;
 constexpr int kMatrixMinSegLen = 32;   // AUTO uses the MFMA kernels from this segment length on
-constexpr int kMatrixWorkgroups = 320; // workgroups the MFMA shrink aims for
+constexpr int kMatrixWorkgroups = 448; // workgroups the MFMA shrink aims for
 
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

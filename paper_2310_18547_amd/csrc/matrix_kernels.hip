@@ -58,7 +58,7 @@ __device__ __forceinline__ f32x4 mfma16x16x32<BF16>(const uint4& a, const uint4&
 constexpr int kShrinkRows = 64;    // rows per shrink workgroup (four 16-row tiles)
 constexpr int kShrinkChunk = 256;  // k per LDS stage
 constexpr int kExpandCols = 256;   // columns per expand workgroup (64 per wave)
-constexpr int kExpandRows = 256;   // rows per expand workgroup pass
+constexpr int kExpandRows = 128;   // rows per expand workgroup pass
 
 // ---------------------------------------------------------------- shrink
 //
@@ -73,10 +73,15 @@ __global__ __launch_bounds__(256) void shrink_matrix_kernel(
   constexpr int NTILE = (R + 15) / 16;  // 16-column tiles of v
   constexpr int RPAD = NTILE * 16;
   constexpr int KC = kShrinkChunk;
-  constexpr int KCP = KC + 8;           // LDS pitch in elements: 16 bytes x odd
   constexpr int CG = R / 8;             // 8-column groups of A_i
   constexpr int KSTEPS = KC / 32;
-  __shared__ __align__(16) uint32_t at[RPAD * KCP / 2];  // A_i chunk, transposed: [n][k]
+  // A_i chunk, transposed, as 16-byte slots {8 consecutive k of one column}:
+  // at[k / 8][slot], RPAD + 1 slots per k block (the odd pitch spreads the banks).
+  // Column n = 8 cg + c sits in slot c * CG + cg, so that the lanes of a staging
+  // load (consecutive cg) write consecutive slots and the sixteen lanes of an
+  // operand read (consecutive slots) hit distinct banks.
+  constexpr int BLK = RPAD + 1;
+  __shared__ __align__(16) uint32_t at[(KC / 8) * BLK * 4];
 
   const int seg = blockIdx.z, s = blockIdx.x, tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -91,7 +96,7 @@ __global__ __launch_bounds__(256) void shrink_matrix_kernel(
       make_buffer(A + layer_off + (long long)k0 * R, (uint32_t)klen * R * 2u);
 
   if (R < RPAD) {  // rows of the transposed tile that no column of A_i fills
-    for (int i = tid; i < RPAD * KCP / 2; i += NT) at[i] = 0u;
+    for (int i = tid; i < (KC / 8) * BLK * 4; i += NT) at[i] = 0u;
     __syncthreads();
   }
 
@@ -120,10 +125,10 @@ __global__ __launch_bounds__(256) void shrink_matrix_kernel(
       }
 #pragma unroll
       for (int it = 0; it < ITEMS; ++it) {
-        const int item = it * NT + tid;
-        const int kp = item % (KC / 2), cg = item / (KC / 2);
+        const int item = it * NT + tid;       // consecutive lanes: consecutive 16 bytes of a row
+        const int cg = item % CG, kp = item / CG;
         const int k = kc + 2 * kp;
-        const bool in = cg < CG;               // rows past the slice read as zeros
+        const bool in = kp < KC / 2;           // rows past the slice read as zeros
         an0[it] = buffer_load128(rA, in ? (uint32_t)(k * R + cg * 8) * 2u : kOutOfRange);
         an1[it] = buffer_load128(rA, in ? (uint32_t)((k + 1) * R + cg * 8) * 2u : kOutOfRange);
       }
@@ -138,14 +143,15 @@ __global__ __launch_bounds__(256) void shrink_matrix_kernel(
 #pragma unroll
       for (int it = 0; it < ITEMS; ++it) {
         const int item = it * NT + tid;
-        const int kp = item % (KC / 2), cg = item / (KC / 2);
-        if (cg < CG) {
+        const int cg = item % CG, kp = item / CG;
+        if (kp < KC / 2) {
           const uint32_t a0[4] = {an0[it].x, an0[it].y, an0[it].z, an0[it].w};
           const uint32_t a1[4] = {an1[it].x, an1[it].y, an1[it].z, an1[it].w};
+          uint32_t* blk = &at[(kp >> 2) * BLK * 4 + (kp & 3)];  // k block, dword of the k pair
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            at[((cg * 8 + 2 * i) * KCP) / 2 + kp] = (a0[i] & 0xFFFFu) | (a1[i] << 16);
-            at[((cg * 8 + 2 * i + 1) * KCP) / 2 + kp] = (a0[i] >> 16) | (a1[i] & 0xFFFF0000u);
+          for (int i = 0; i < 4; ++i) {  // columns 8 cg + 2 i and + 2 i + 1
+            blk[((2 * i) * CG + cg) * 4] = (a0[i] & 0xFFFFu) | (a1[i] << 16);
+            blk[((2 * i + 1) * CG + cg) * 4] = (a0[i] >> 16) | (a1[i] & 0xFFFF0000u);
           }
         }
       }
@@ -156,20 +162,21 @@ __global__ __launch_bounds__(256) void shrink_matrix_kernel(
         if (kc + ks * 32 < klen) {
 #pragma unroll
           for (int t = 0; t < NTILE; ++t) {
-            const uint4 bt = *reinterpret_cast<const uint4*>(&at[((t * 16 + m) * KCP + ks * 32 + g * 8) / 2]);
+            const uint4 bt = *reinterpret_cast<const uint4*>(&at[((ks * 4 + g) * BLK + t * 16 + m) * 4]);
             acc[t] = mfma16x16x32<DT>(xa[ks], bt, acc[t]);
           }
         }
       }
     }
-    // D[row 4g+i][column m] of every tile
+    // D[row 4g+i][slot m] of every tile; slot p holds column 8 (p % CG) + p / CG
 #pragma unroll
     for (int t = 0; t < NTILE; ++t) {
-      const int n = t * 16 + m;
+      const int p = t * 16 + m;
+      const int n = (p % CG) * 8 + p / CG;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int row = row0 + 4 * g + i;
-        if (n < R && row < hi) partials[((long long)s * n_tokens + row) * R + n] = acc[t][i];
+        if (p < R && row < hi) partials[((long long)s * n_tokens + row) * R + n] = acc[t][i];
       }
     }
   }
@@ -258,10 +265,13 @@ __global__ __launch_bounds__(256) void expand_matrix_kernel(
   constexpr int NT = 256;
   constexpr int KPAD = R < 32 ? 32 : R;  // k padded to the MFMA depth
   constexpr int KSTEPS = KPAD / 32;
-  constexpr int KP = KPAD + 8;           // LDS pitch in elements: 16 bytes x odd
   constexpr int NC = kExpandCols;
   constexpr int KPAIRS = R / 2;
-  __shared__ __align__(16) uint32_t bt[NC * KP / 2];  // B_i strip, transposed: [column][k]
+  // B_i strip, transposed, as 16-byte slots {8 consecutive k of one column}:
+  // bt[k / 8][slot], NC + 1 slots per k block; column 8 cg + c of the strip sits in
+  // slot c * (NC / 8) + cg, so the lanes of a staging load write consecutive slots.
+  constexpr int BLK = NC + 1;
+  __shared__ __align__(16) uint32_t bt[(KPAD / 8) * BLK * 4];
 
   const int seg = blockIdx.z, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
@@ -278,7 +288,7 @@ __global__ __launch_bounds__(256) void expand_matrix_kernel(
 
   // ---- stage the strip transposed: a thread takes a pair of k and eight columns
   if (R < KPAD) {
-    for (int i = tid; i < NC * KP / 2; i += NT) bt[i] = 0u;
+    for (int i = tid; i < (KPAD / 8) * BLK * 4; i += NT) bt[i] = 0u;
     __syncthreads();
   }
   {
@@ -288,8 +298,8 @@ __global__ __launch_bounds__(256) void expand_matrix_kernel(
       uint4 r0[BATCH], r1[BATCH];
 #pragma unroll
       for (int b = 0; b < BATCH; ++b) {
-        const int item = base + b * NT + tid;
-        const int kp = item % KPAIRS, cg = item / KPAIRS;
+        const int item = base + b * NT + tid;  // consecutive lanes: consecutive 16 bytes of a row
+        const int cg = item % (NC / 8), kp = item / (NC / 8);
         const bool in = item < TOTAL && cg * 8 < ncols;
         r0[b] = buffer_load128(rB, in ? (uint32_t)((2 * kp) * h_out + cg * 8) * 2u : kOutOfRange);
         r1[b] = buffer_load128(rB, in ? (uint32_t)((2 * kp + 1) * h_out + cg * 8) * 2u : kOutOfRange);
@@ -297,14 +307,15 @@ __global__ __launch_bounds__(256) void expand_matrix_kernel(
 #pragma unroll
       for (int b = 0; b < BATCH; ++b) {
         const int item = base + b * NT + tid;
-        const int kp = item % KPAIRS, cg = item / KPAIRS;
+        const int cg = item % (NC / 8), kp = item / (NC / 8);
         if (item < TOTAL) {
           const uint32_t a0[4] = {r0[b].x, r0[b].y, r0[b].z, r0[b].w};
           const uint32_t a1[4] = {r1[b].x, r1[b].y, r1[b].z, r1[b].w};
+          uint32_t* blk = &bt[(kp >> 2) * BLK * 4 + (kp & 3)];  // k block, dword of the k pair
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            bt[((cg * 8 + 2 * i) * KP) / 2 + kp] = (a0[i] & 0xFFFFu) | (a1[i] << 16);
-            bt[((cg * 8 + 2 * i + 1) * KP) / 2 + kp] = (a0[i] >> 16) | (a1[i] & 0xFFFF0000u);
+          for (int i = 0; i < 4; ++i) {  // columns 8 cg + 2 i and + 2 i + 1
+            blk[((2 * i) * (NC / 8) + cg) * 4] = (a0[i] & 0xFFFFu) | (a1[i] << 16);
+            blk[((2 * i + 1) * (NC / 8) + cg) * 4] = (a0[i] >> 16) | (a1[i] & 0xFFFF0000u);
           }
         }
       }
@@ -312,21 +323,24 @@ __global__ __launch_bounds__(256) void expand_matrix_kernel(
   }
   __syncthreads();
 
-  // ---- operands: tile t, slot (lane % 16) = 4 q + i  <->  column 16 q + 4 t + i of the wave's 64
+  // ---- operands: tile t, slot (lane % 16) = 4 q + i  <->  column 32 (t / 2) + 8 q + 4 (t % 2) + i
+  // of the wave's 64, so that lane group q ends up with columns 8 q .. 8 q + 7 (tiles 0, 1)
+  // and 32 + 8 q .. + 7 (tiles 2, 3): each 128-bit access of the wave is a dense 64-byte run per row
   const int slot = lane & 15, g = lane >> 4;
   uint4 bop[KSTEPS][4];
 #pragma unroll
   for (int ks = 0; ks < KSTEPS; ++ks)
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      const int col = wave * 64 + (slot >> 2) * 16 + t * 4 + (slot & 3);
-      bop[ks][t] = *reinterpret_cast<const uint4*>(&bt[(col * KP + ks * 32 + g * 8) / 2]);
+      const int col = wave * 64 + (t >> 1) * 32 + (slot >> 2) * 8 + (t & 1) * 4 + (slot & 3);
+      const int pos = (col & 7) * (NC / 8) + (col >> 3);
+      bop[ks][t] = *reinterpret_cast<const uint4*>(&bt[((ks * 4 + g) * BLK + pos) * 4]);
     }
 
-  // this lane's output: row (lane % 16) of the tile, columns cw .. cw+15
+  // this lane's output: row (lane % 16) of the tile, columns cw .. cw+7 and cw+32 .. cw+39
   const int m = lane & 15;
-  const int cw = c0 + wave * 64 + g * 16;
-  const bool c_ok0 = cw < h_out, c_ok1 = cw + 8 < h_out;
+  const int cw = c0 + wave * 64 + g * 8;
+  const bool c_ok0 = cw < h_out, c_ok1 = cw + 32 < h_out;
 
   struct Tile {  // everything one row tile reads from memory
     uint4 y0, y1, h[KSTEPS], l[KSTEPS];
@@ -344,7 +358,7 @@ __global__ __launch_bounds__(256) void expand_matrix_kernel(
       const bool ok = row < nrows;
       const uint32_t yoff = (uint32_t)(row * h_out + cw) * 2u;
       T.y0 = buffer_load128(rY, (ok && c_ok0) ? yoff : kOutOfRange);
-      T.y1 = buffer_load128(rY, (ok && c_ok1) ? yoff + 16u : kOutOfRange);
+      T.y1 = buffer_load128(rY, (ok && c_ok1) ? yoff + 64u : kOutOfRange);
 #pragma unroll
       for (int ks = 0; ks < KSTEPS; ++ks) {
         const int k = ks * 32 + g * 8;
@@ -365,7 +379,7 @@ __global__ __launch_bounds__(256) void expand_matrix_kernel(
           acc[t] = mfma16x16x32<DT>(bop[ks][t], T.h[ks], acc[t]);
         }
       }
-      // acc[t][i] is column cw + 4 t + i of row m
+      // acc[t][i] is column cw + 32 (t / 2) + 4 (t % 2) + i of row m, i.e. element 4 t + i of {y0, y1}
       float yf[16];
       {
         float a8[8];
@@ -391,7 +405,7 @@ __global__ __launch_bounds__(256) void expand_matrix_kernel(
       const bool ok = row < nrows;
       const uint32_t yoff = (uint32_t)(row * h_out + cw) * 2u;
       buffer_store128(rY, (ok && c_ok0) ? yoff : kOutOfRange, out0);
-      buffer_store128(rY, (ok && c_ok1) ? yoff + 16u : kOutOfRange, out1);
+      buffer_store128(rY, (ok && c_ok1) ? yoff + 64u : kOutOfRange, out1);
     };
 
     // two row tiles in flight: the next tile's loads are issued before this one is finished
