@@ -13,11 +13,13 @@ using namespace sgmv;
 
 constexpr int kMinSplitCap = 16;       // the workspace always allows this many slices
 constexpr int kTargetWorkgroups = 512; // about two workgroups per compute unit
-constexpr int kFusedMaxSegLen = 16;    // longest segment the single-launch path is used for
+constexpr int kFusedMaxSegLen = 16;    // longest segment the single-launch vector kernel takes
+constexpr int kTileMaxSegLen = 64;     // longest segment the single-launch MFMA kernel is used for
+constexpr int kFusedSlices = 8;        // most slices per segment the single-launch kernels pick
 constexpr int kFusedWorkgroups = 256;  // one workgroup per compute unit
 constexpr int kFusedMaxWorkgroups = 1024;
 constexpr int kFusedSpinLimit = 1 << 18;
-constexpr int kMatrixMinSegLen = 32;   // AUTO uses the MFMA kernels from this segment length on
+constexpr int kMatrixMinSegLen = 17;   // AUTO uses the MFMA kernels from this segment length on
 constexpr int kMatrixWorkgroups = 448; // workgroups the MFMA shrink aims for
 
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -137,7 +139,10 @@ bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f) {
   const int cap = split_cap(p->n_tokens);
   const int need = ceil_div(p->h_in, kMaxKSlice);
   if (need > cap) return false;
-  int s = p->ksplit > 0 ? p->ksplit : (kFusedWorkgroups + n_segs / 2) / n_segs;
+  // every workgroup of a launch must be resident at once (one per compute unit): a
+  // workgroup that waits for a slice of a workgroup not yet started only idles
+  int s = p->ksplit > 0 ? p->ksplit : kFusedWorkgroups / n_segs;
+  if (p->ksplit == 0 && s > kFusedSlices) s = kFusedSlices;
   const int wide = p->h_in > p->h_out ? p->h_in : p->h_out;
   if (s > wide / 64) s = wide / 64;
   if (s > cap) s = cap;
@@ -154,6 +159,33 @@ bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f) {
   while (p->r / g > 16) g *= 2;
   f->G = g;
   f->rows_per_pass = p->max_seg_len == 1 ? 1 : 4;
+  return true;
+}
+
+// Launch shape of the single-launch MFMA kernel; false when it does not apply.
+bool choose_tile(const sgmv_problem* p, int n_segs, TileArgs* t) {
+  if (!p->workspace_ready) return false;
+  if (p->max_seg_len <= 0 || p->max_seg_len > kTileMaxSegLen) return false;
+  if (n_segs > kFusedMaxWorkgroups) return false;
+  const int cap = split_cap(p->n_tokens);
+  int z = ceil_div(p->max_seg_len, 16);
+  if ((long long)n_segs * z > kFusedWorkgroups) z = kFusedWorkgroups / n_segs > 0 ? kFusedWorkgroups / n_segs : 1;
+  int s = p->ksplit > 0 ? p->ksplit : kFusedWorkgroups / (n_segs * z);
+  if (p->ksplit == 0 && s > kFusedSlices) s = kFusedSlices;
+  const int narrow = p->h_in < p->h_out ? p->h_in : p->h_out;
+  if (s > narrow / 64) s = narrow / 64;  // no slice thinner than 64
+  if (s > cap) s = cap;
+  if (s < 1) s = 1;
+  // more slices make the LDS-resident weight slices smaller
+  for (;; ++s) {
+    t->kslice = ceil_div(ceil_div(p->h_in, s), 32) * 32;
+    t->cslice = ceil_div(ceil_div(p->h_out, s), 64) * 64;
+    t->lds_bytes = tile_lds_bytes(p->r, t->kslice, t->cslice);
+    if (t->lds_bytes <= kTileMaxLds) break;
+    if (p->ksplit > 0 || s + 1 > cap || (long long)(s + 1) * n_segs * z > kFusedWorkgroups) return false;
+  }
+  t->S = s;
+  t->Z = z;
   return true;
 }
 
@@ -325,6 +357,30 @@ int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x, const void* con
   if (rc != SGMV_OK) return rc;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if ((p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->max_seg_len != 1) {
+    TileArgs t;
+    if (choose_tile(p, n_segs, &t)) {
+      t.bf16 = p->dtype == SGMV_BF16;
+      t.r = p->r;
+      t.h_in = p->h_in;
+      t.h_out = p->h_out;
+      t.n_tokens = p->n_tokens;
+      t.n_segs = n_segs;
+      t.spin_limit = kFusedSpinLimit;
+      t.offA = (long long)layer_idx * p->h_in * p->r;
+      t.offB = (long long)layer_idx * p->r * p->h_out;
+      t.y = y;
+      t.x = x;
+      t.A_ptrs = A_ptrs;
+      t.B_ptrs = B_ptrs;
+      t.seg_starts = seg_starts;
+      t.exch = exchange_base(p->workspace, p->n_tokens, p->r);
+      t.header = static_cast<unsigned long long*>(p->workspace);
+      t.scale = scale;
+      if (launch_add_lora_tile(t, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+      return SGMV_OK;
+    }
+  }
   if (p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) {
     FusedArgs f;
     if (choose_fused(p, n_segs, &f)) {

@@ -46,6 +46,7 @@
 #include <type_traits>
 
 #include "device_common.h"
+#include "exchange.h"
 #include "launch.h"
 
 // Optional timeline probe for kernel tuning: a tuning build defines this macro to
@@ -87,46 +88,6 @@ __device__ __forceinline__ float fused_reduce_lanes8(const float (&a)[8], int la
   for (int m = M3 * 2; m < 64; m <<= 1) d += __shfl_xor(d, m, 64);
   e_out = ((lane & M1) ? 4 : 0) | ((lane & M2) ? 2 : 0) | ((lane & M3) ? 1 : 0);
   return d;
-}
-
-// Workgroup barrier that orders LDS traffic only: outstanding global loads stay
-// outstanding.
-__device__ __forceinline__ void lds_barrier() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-  __builtin_amdgcn_s_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
-__device__ __forceinline__ uint32_t generation_tag(unsigned long long epoch) {
-  return (uint32_t)((epoch / kEpochStep) % 0xFFFFFFFFull) + 1u;  // never 0
-}
-
-// Each workgroup adds to the epoch exactly once, on its way out; the first
-// workgroup adds the remainder so that the launch's total is kEpochStep.  The
-// epoch is the sum of kEpochCounters words and a workgroup adds to the word
-// its id selects, which spreads the atomics over many addresses.
-__device__ __forceinline__ void leave_launch(unsigned long long* epoch, int n_workgroups) {
-  const unsigned id = blockIdx.y * gridDim.x + blockIdx.x;
-  const unsigned long long inc =
-      id == 0 ? (unsigned long long)kEpochStep - (n_workgroups - 1) : 1ull;
-  __hip_atomic_fetch_add(epoch + (id % kEpochCounters), inc, __ATOMIC_RELAXED,
-                         __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// Read the epoch with one wave: lane l reads counter l, the lanes are summed.
-// The counters only grow, and this workgroup has not added its share yet, so
-// whatever mixture of old and new counter values the lanes see, the sum lies
-// in the running launch's window.
-__device__ __forceinline__ unsigned long long read_epoch(const unsigned long long* epoch, int lane) {
-  static_assert(kEpochCounters == 64, "one counter per lane");
-  unsigned long long v = __hip_atomic_load(epoch + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-  for (int m = 1; m < 64; m <<= 1) {
-    const unsigned lo = __shfl_xor((unsigned)v, m, 64);
-    const unsigned hi = __shfl_xor((unsigned)(v >> 32), m, 64);
-    v += ((unsigned long long)hi << 32) | lo;
-  }
-  return v;
 }
 
 // grid = (S, n_segs) workgroups of 320 threads: blockIdx.y is the segment,

@@ -70,6 +70,29 @@ struct FusedArgs {
   unsigned long long* header;// kEpochCounters epoch counters, then the error word
 };
 
+// Single-launch kernel for segments of a few rows (sixteen-row MFMA tiles).
+constexpr size_t kTileMaxLds = 160 * 1024;  // LDS of one compute unit
+struct TileArgs {
+  bool bf16;
+  int r, h_in, h_out, n_tokens, n_segs;
+  int S;                     // workgroups per segment and row block = k-slices = column slices
+  int Z;                     // grid depth: row blocks of a segment are dealt round-robin over it
+  int kslice, cslice;        // multiples of 32 / 64
+  int spin_limit;
+  size_t lds_bytes;          // tile_lds_bytes(r, kslice, cslice)
+  long long offA, offB;
+  float scale;
+  void* y;
+  const void* x;
+  const void* const* A_ptrs;
+  const void* const* B_ptrs;
+  const int32_t* seg_starts;
+  unsigned long long* exch;
+  unsigned long long* header;
+};
+
+size_t tile_lds_bytes(int r, int kslice, int cslice);
+hipError_t launch_add_lora_tile(const TileArgs& a, hipStream_t st);
 hipError_t launch_add_lora_fused(const FusedArgs& a, hipStream_t st);
 hipError_t launch_workspace_init(void* p, size_t bytes, size_t header_offset, hipStream_t st);
 hipError_t launch_shrink_vector(const ShrinkArgs& a, hipStream_t st);

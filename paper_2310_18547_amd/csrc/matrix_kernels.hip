@@ -35,25 +35,9 @@
 
 #include "device_common.h"
 #include "launch.h"
+#include "mfma.h"
 
 namespace sgmv {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-template <class DT>
-__device__ __forceinline__ f32x4 mfma16x16x32(const uint4& a, const uint4& b, f32x4 c);
-template <>
-__device__ __forceinline__ f32x4 mfma16x16x32<F16>(const uint4& a, const uint4& b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a),
-                                                __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-}
-template <>
-__device__ __forceinline__ f32x4 mfma16x16x32<BF16>(const uint4& a, const uint4& b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
-                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-}
 
 constexpr int kShrinkRows = 64;    // rows per shrink workgroup (four 16-row tiles)
 constexpr int kShrinkChunk = 256;  // k per LDS stage
@@ -183,13 +167,6 @@ __global__ __launch_bounds__(256) void shrink_matrix_kernel(
 }
 
 // ---------------------------------------------------------------- expand
-
-// Split an fp32 value into two 16-bit parts whose sum carries ~16-22 significant bits.
-template <class DT>
-__device__ __forceinline__ void split16(float v, uint32_t& hi, uint32_t& lo) {
-  hi = encode1<DT>(v);
-  lo = encode1<DT>(v - decode1<DT>((uint16_t)hi));
-}
 
 // v[row][k] = sum over the split-K parts (ascending), written out as the two
 // 16-bit operands the expand kernel feeds to the matrix cores:

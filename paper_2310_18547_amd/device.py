@@ -30,7 +30,7 @@ class DeviceWorkload:
 
     def __init__(self, w, device="cuda:0", n_sets: int = 1, max_seg_len_hint: bool = True,
                  path: int = B.PATH_AUTO, ksplit: int = 0, expand_threads: int = 0,
-                 init_workspace: bool = True):
+                 init_workspace: bool = True, max_seg_len: Optional[int] = None):
         self.w = w
         self.device = torch.device(device)
         self.A: List[torch.Tensor] = [_to_dev(a, self.device) for a in w.A]
@@ -52,7 +52,8 @@ class DeviceWorkload:
         self.problem = B.make_problem(
             _DT[w.dtype], w.h_in, w.h_out, w.r, w.num_layers, w.n_tokens,
             workspace=self.workspace, workspace_bytes=self.ws_bytes,
-            max_seg_len=w.max_seg_len if max_seg_len_hint else 0, path=path, ksplit=ksplit,
+            max_seg_len=(max_seg_len if max_seg_len is not None else
+                         w.max_seg_len if max_seg_len_hint else 0), path=path, ksplit=ksplit,
             expand_threads=expand_threads, workspace_ready=1 if init_workspace else 0)
 
     # -- the three entry points, on set `k` ---------------------------------

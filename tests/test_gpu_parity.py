@@ -342,6 +342,105 @@ def test_auto_uses_two_launches_without_ready_workspace():
     assert_parity(d.y_bits(), oracle.run_workload(w), "f16", "workspace not initialised")
 
 
+# ---------------------------------- single-launch MFMA (tile) kernel, segments of a few rows
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("r", [8, 16, 32, 64])
+def test_tile_matches_oracle(dtype, r):
+    w = wl.custom([1, 3, 2, 16, 1, 7, 0, 4, 33, 17], 2048, 1544, r, dtype, seed=60 + r, num_layers=2)
+    ref = oracle.run_workload(w, layer_idx=1)
+    d = _fused(w)
+    d.add_lora(1)
+    got = d.y_bits()
+    assert d.check() == 0
+    assert_parity(got, ref, dtype, f"tile r={r}")
+
+
+@pytest.mark.parametrize("ksplit", [1, 2, 3, 5, 8, 16])
+def test_tile_every_slice_count(ksplit):
+    w = wl.custom([1, 2, 5, 1, 20, 1], 1000, 1096, 16, "f16", seed=65)
+    d = _fused(w, ksplit=ksplit)
+    d.add_lora()
+    assert_parity(d.y_bits(), oracle.run_workload(w), "f16", f"tile S={ksplit}")
+    assert d.check() == 0
+
+
+@pytest.mark.parametrize("hint", [2, 16, 64])
+def test_tile_wrong_length_hint_is_still_correct(hint):
+    # the hint only shapes the grid: longer segments are covered by striding over row blocks
+    w = wl.custom([40, 1, 3, 70, 2], 512, 768, 16, "bf16", seed=66)
+    d = _fused(w, max_seg_len=hint)
+    d.add_lora()
+    assert_parity(d.y_bits(), oracle.run_workload(w), "bf16", f"tile hint={hint}")
+    assert d.check() == 0
+
+
+def test_tile_on_single_row_segments():
+    w = wl.decode_distinct(batch=24, h_in=4096, r=16, dtype="f16", num_layers=2, seed=67)
+    d = _fused(w, max_seg_len=2)
+    d.add_lora(1)
+    assert_parity(d.y_bits(), oracle.run_workload(w, layer_idx=1, n_threads=8), "f16", "tile, one row each")
+
+
+def test_tile_fingerprint_bit_exact():
+    lens = [1, 0, 3, 2, 0, 0, 5, 1, 9, 4, 1, 1, 16, 18, 35]
+    for dtype, r in (("bf16", 16), ("f16", 8), ("f16", 64)):
+        w = wl.fingerprint(lens, 256, 192, r, dtype, num_layers=3)
+        for layer in range(3):
+            d = _fused(w)
+            d.add_lora(layer)
+            assert np.array_equal(d.y_bits(), oracle.run_workload(w, layer_idx=layer)), (dtype, r, layer)
+
+
+def test_tile_null_adapter_and_repeated_calls():
+    w = wl.custom([2, 0, 3, 1, 4, 19], 512, 264, 16, "f16", seed=68)
+    w.seg_adapter = np.asarray([0, 1, -1, 3, 4, 5], np.int64)
+    d = _fused(w)
+    d.add_lora()
+    got = d.y_bits()
+    assert np.array_equal(got[2:5], w.y0[2:5]) and d.check() == 0
+    assert_parity(got, oracle.run_workload(w), "f16", "tile null adapter")
+    # bit-identical from call to call, counters left clean by skipped segments
+    for _ in range(3):
+        d.reset_y(); d.add_lora()
+        assert np.array_equal(d.y_bits(), got)
+    assert d.check() == 0
+
+
+def test_tile_f16_large_v_keeps_range():
+    # |v| far beyond binary16's range: the 16-bit operand pairs are scaled per row
+    w = wl.custom([5, 2, 18], 512, 512, 16, "f16", seed=69)
+    w.x = wl.encode(np.full(w.x.shape, 60.0, np.float32), "f16")
+    for a in w.A:
+        a[...] = wl.encode(np.full(a.shape, 30.0, np.float32), "f16")
+    for b in w.B:
+        b[...] = wl.encode(np.full(b.shape, 1.0 / 65536.0, np.float32), "f16")
+    d = _fused(w)
+    d.add_lora()
+    assert_parity(d.y_bits(), oracle.run_workload(w), "f16", "tile large v")
+
+
+def test_tile_graph_replay_mixed_segments():
+    w = wl.popularity("skewed", batch=64, h_in=4096, r=16, dtype="f16", num_layers=4, seed=70)
+    d = _fused(w, n_sets=4)
+    stream = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        d.add_lora(0, 0, stream=stream.cuda_stream)
+        stream.synchronize()
+        with torch.cuda.graph(g, stream=stream):
+            for i in range(4):
+                d.add_lora(i, i, stream=stream.cuda_stream)
+        for rep in range(3):
+            d.reset_y()
+            torch.cuda.synchronize()
+            g.replay()
+            stream.synchronize()
+            for i in (0, 3):
+                assert_parity(d.y_bits(i), oracle.run_workload(w, layer_idx=i, n_threads=8), "f16",
+                              f"tile graph replay {rep} set {i}")
+    assert d.check(stream.cuda_stream) == 0
+
+
 # ------------------------------------------------------- MFMA (matrix) path
 def _matrix(w, **kw):
     from paper_2310_18547_amd import binding as B
