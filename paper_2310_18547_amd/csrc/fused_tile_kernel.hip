@@ -145,17 +145,18 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
       const int nel = min(16, hi - row0) * R;
       float* vd = vs + (it & 1) * TILE;
       const unsigned long long* src0 = exch + (long long)row0 * R;
-      for (int e0 = 0; e0 < nel; e0 += 64 * EB) {
-        float sum[EB];
+      auto collect = [&](int e0, auto eb_tag) {
+        constexpr int EN = decltype(eb_tag)::value;
+        float sum[EN];
 #pragma unroll
-        for (int e = 0; e < EB; ++e) sum[e] = 0.f;
+        for (int e = 0; e < EN; ++e) sum[e] = 0.f;
         for (int s0 = 0; s0 < S; s0 += 8) {
-          unsigned long long wv[EB][8];
+          unsigned long long wv[EN][8];
           int polls = 0;
           bool ready;
           do {
 #pragma unroll
-            for (int e = 0; e < EB; ++e) {
+            for (int e = 0; e < EN; ++e) {
               const unsigned long long* src = src0 + min(e0 + e * 64 + lane, nel - 1);
 #pragma unroll
               for (int i = 0; i < 8; ++i)
@@ -164,7 +165,7 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
             }
             ready = true;
 #pragma unroll
-            for (int e = 0; e < EB; ++e)
+            for (int e = 0; e < EN; ++e)
 #pragma unroll
               for (int i = 0; i < 8; ++i) ready = ready && ((uint32_t)wv[e][i] == tag);
             if (!ready && ++polls > spin_limit) {
@@ -173,14 +174,14 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
             }
           } while (!ready);
 #pragma unroll
-          for (int e = 0; e < EB; ++e)
+          for (int e = 0; e < EN; ++e)
 #pragma unroll
             for (int i = 0; i < 8; ++i)
               sum[e] += (s0 + i < S) ? __uint_as_float((uint32_t)(wv[e][i] >> 32)) : 0.f;
         }
         // a row of v sits in R consecutive lanes of one element batch
 #pragma unroll
-        for (int e = 0; e < EB; ++e) {
+        for (int e = 0; e < EN; ++e) {
           const int idx = e0 + e * 64 + lane;
           const bool live = idx < nel;
           float f = live ? sum[e] : 0.f;
@@ -198,6 +199,12 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
           }
           if (live) vd[idx] = f;
         }
+      };
+      // short segments (at most 64 partial sums per slice) poll one element per lane
+      if (nel <= 64) {
+        collect(0, std::integral_constant<int, 1>{});
+      } else {
+        for (int e0 = 0; e0 < nel; e0 += 64 * EB) collect(e0, std::integral_constant<int, EB>{});
       }
       SGMV_TRACE_POINT(5);
       lds_barrier();  // (E) vs[it & 1] filled
@@ -216,7 +223,6 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
   const int ngroups = (ncols + 63) >> 6;  // 64-column groups in this column slice
   const int total_a = (kslice >> 1) * CG; // (k pair, chunk) staging items of the A slice
   const int total_b = (R / 2) * ncg;      // (j pair, 8-column group) staging items of the B slice
-  const float inv_ncg = 1.0f / (float)ncg;
   const uint32_t row_bytes_in = (uint32_t)h_in * 2u, row_bytes_out = (uint32_t)h_out * 2u;
 
   const __amdgpu_buffer_rsrc_t rA = make_buffer(A + offA + (long long)k0 * R, (uint32_t)klen * R * 2u);
@@ -231,26 +237,39 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
     return make_buffer(y + (long long)row0 * h_out + col_lo,
                        ncols > 0 ? (uint32_t)((long long)(nrows - 1) * h_out + ncols) * 2u : 0u);
   };
-  // k-step `step` of the slice: row m, k = 32 step + 8 g .. +7
+  // Offsets are kept to an add, a compare and a select per load, with no branches,
+  // so that the loads below issue back to back.
+  // x, k-step `step` of the slice: row m, k = 32 step + 8 g .. +7 (lanes of rows past
+  // the block and k past the slice read zeros)
+  const uint32_t x_lane = (uint32_t)m * row_bytes_in + (uint32_t)g * 16u;
   auto x_offset = [&](int step, int nrows) {
-    const int k = step * 32 + g * 8;
-    return (m < nrows && k < klen) ? (uint32_t)m * row_bytes_in + (uint32_t)k * 2u : kOutOfRange;
+    const int k_end = m < nrows ? klen : 0;
+    return (step * 32 + g * 8 < k_end) ? x_lane + (uint32_t)step * 64u : kOutOfRange;
   };
-  // 64-column group `grp` of the slice: row m, columns 64 grp + 8 g .. +7 (half 0) and + 32 (half 1)
+  // y, 64-column group `grp` of the slice: row m, columns 64 grp + 8 g .. +7 (half 0), + 32 (half 1)
+  const uint32_t y_lane = (uint32_t)m * row_bytes_out + (uint32_t)g * 16u;
   auto y_offset = [&](int grp, int half, int nrows) {
-    const int c = grp * 64 + g * 8 + half * 32;
-    return (m < nrows && c < ncols) ? (uint32_t)m * row_bytes_out + (uint32_t)c * 2u : kOutOfRange;
+    const int c_end = m < nrows ? ncols : 0;
+    return (grp * 64 + g * 8 + half * 32 < c_end) ? y_lane + (uint32_t)(grp * 128 + half * 64) : kOutOfRange;
   };
-  auto a_item = [&](int item, uint32_t& o0, uint32_t& o1) {
-    const int cg = item % CG, kp = item / CG;
-    const bool in = item < total_a;
-    o0 = in ? (uint32_t)((2 * kp) * R + cg * 8) * 2u : kOutOfRange;
-    o1 = in ? (uint32_t)((2 * kp + 1) * R + cg * 8) * 2u : kOutOfRange;
+  // A staging item (k pair kp, chunk cg) = kp * CG + cg: rows 2 kp and 2 kp + 1 of the
+  // slice, columns 8 cg .. +7.  Items past the slice fall outside the buffer by themselves.
+  auto a_offset = [&](int item) { return (uint32_t)(2 * item - (tid % CG)) * 16u; };
+  // B staging item (j pair kp, 8-column group cg) = kp * ncg + cg: rows 2 kp, 2 kp + 1 of
+  // B_i, columns 8 cg .. +7 of the slice.  Item -> (kp, cg) is a division by ncg, done once
+  // per lane; consecutive items of a lane are NT apart and follow by increments.  Pairs past
+  // the rank fall outside the buffer by themselves; column groups past a short last slice
+  // read columns that are never stored.
+  int b_step_kp, b_step_cg, b_kp, b_cg;
+  auto b_next = [&]() {
+    b_kp += b_step_kp;
+    b_cg += b_step_cg;
+    if (b_cg >= ncg) {
+      b_cg -= ncg;
+      ++b_kp;
+    }
   };
-  auto b_item = [&](int item, int& kp, int& cg) {
-    kp = (int)(((float)item + 0.5f) * inv_ncg);  // item / ncg, exact for these sizes
-    cg = item - kp * ncg;
-  };
+  auto b_offset = [&]() { return (uint32_t)(2 * b_kp) * row_bytes_out + (uint32_t)b_cg * 16u; };
 
   // ---- issue everything that depends on no other workgroup: x, A, then B, y
   const int row_first = lo + (int)blockIdx.z * 16;
@@ -264,20 +283,27 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
   uint4 a0[AB], a1[AB];
 #pragma unroll
   for (int b = 0; b < AB; ++b) {
-    uint32_t o0, o1;
-    a_item(b * NT + tid, o0, o1);
-    a0[b] = buffer_load128(rA, o0);
-    a1[b] = buffer_load128(rA, o1);
+    const uint32_t o = a_offset(b * NT + tid);
+    a0[b] = buffer_load128(rA, o);
+    a1[b] = buffer_load128(rA, o + (uint32_t)R * 2u);
   }
   __builtin_amdgcn_sched_barrier(0);  // keep x and A ahead of B and y in the memory pipe
+  const float inv_ncg = 1.0f / (float)ncg;
+  // (the division sits here, behind the x and A loads, so that it does not delay them)
+  b_step_kp = (int)(((float)NT + 0.5f) * inv_ncg);  // NT / ncg, wave-uniform
+  b_step_cg = NT - b_step_kp * ncg;
+  b_kp = (int)(((float)tid + 0.5f) * inv_ncg);      // tid / ncg, exact for these sizes
+  b_cg = tid - b_kp * ncg;
   uint4 b0[BB], b1[BB];
+  int bkp[BB], bcg[BB];
 #pragma unroll
   for (int b = 0; b < BB; ++b) {
-    int kp, cg;
-    b_item(b * NT + tid, kp, cg);
-    const bool in = b * NT + tid < total_b && cg * 8 < ncols;
-    b0[b] = buffer_load128(rB, in ? (uint32_t)(2 * kp) * row_bytes_out + (uint32_t)cg * 16u : kOutOfRange);
-    b1[b] = buffer_load128(rB, in ? (uint32_t)(2 * kp + 1) * row_bytes_out + (uint32_t)cg * 16u : kOutOfRange);
+    const uint32_t o = b_offset();
+    bkp[b] = b_kp;
+    bcg[b] = b_cg;
+    b0[b] = buffer_load128(rB, o);
+    b1[b] = buffer_load128(rB, o + row_bytes_out);
+    b_next();
   }
   uint4 yq[YB][2];
   {
@@ -308,10 +334,9 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
     if (base != 0) {
 #pragma unroll
       for (int b = 0; b < AB; ++b) {
-        uint32_t o0, o1;
-        a_item(base + b * NT + tid, o0, o1);
-        a0[b] = buffer_load128(rA, o0);
-        a1[b] = buffer_load128(rA, o1);
+        const uint32_t o = a_offset(base + b * NT + tid);
+        a0[b] = buffer_load128(rA, o);
+        a1[b] = buffer_load128(rA, o + (uint32_t)R * 2u);
       }
     }
 #pragma unroll
@@ -384,19 +409,18 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
     if (base != 0) {
 #pragma unroll
       for (int b = 0; b < BB; ++b) {
-        int kp, cg;
-        b_item(base + b * NT + tid, kp, cg);
-        const bool in = base + b * NT + tid < total_b && cg * 8 < ncols;
-        b0[b] = buffer_load128(rB, in ? (uint32_t)(2 * kp) * row_bytes_out + (uint32_t)cg * 16u : kOutOfRange);
-        b1[b] = buffer_load128(rB, in ? (uint32_t)(2 * kp + 1) * row_bytes_out + (uint32_t)cg * 16u : kOutOfRange);
+        const uint32_t o = b_offset();
+        bkp[b] = b_kp;
+        bcg[b] = b_cg;
+        b0[b] = buffer_load128(rB, o);
+        b1[b] = buffer_load128(rB, o + row_bytes_out);
+        b_next();
       }
     }
 #pragma unroll
     for (int b = 0; b < BB; ++b) {
-      const int item = base + b * NT + tid;
-      int kp, cg;
-      b_item(item, kp, cg);
-      if (item < total_b) {
+      const int kp = bkp[b], cg = bcg[b];
+      if (kp < R / 2) {
         const uint32_t w0[4] = {b0[b].x, b0[b].y, b0[b].z, b0[b].w};
         const uint32_t w1[4] = {b1[b].x, b1[b].y, b1[b].z, b1[b].w};
         uint32_t* blk = &bt[(kp >> 2) * BBLK * 4 + (kp & 3)];  // j block, dword of the j pair
