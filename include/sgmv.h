@@ -85,7 +85,8 @@ typedef enum {
   SGMV_PATH_MATRIX = 2,      /* MFMA path: for long (prefill-like) segments        */
   SGMV_PATH_FUSED = 3        /* sgmv_add_lora only: shrink and expand in a single  */
                              /* launch; needs workspace_ready and 0 < max_seg_len  */
-                             /* <= 16, else SGMV_ERR_UNSUPPORTED                   */
+                             /* <= 64 (and, beyond one row per segment, weight     */
+                             /* slices that fit the LDS), else SGMV_ERR_UNSUPPORTED*/
 } sgmv_path;
 
 /* Problem descriptor: plain data, host memory, read during the call only. */
@@ -169,12 +170,35 @@ int sgmv_expand(const sgmv_problem* p, void* y, const float* v,
 /* The whole LoRA add-on, y += scale * (x A_i) B_i per segment, i.e. v := 0,
  * shrink, expand in one call; v lives in the workspace in fp32 and is never
  * rounded.  A segment is skipped when either of its pointers is NULL.
- * With workspace_ready set and 0 < max_seg_len <= 16 both steps run in a
- * single kernel launch; otherwise one launch per step is used. */
+ * With workspace_ready set and 0 < max_seg_len <= 64 both steps run in a
+ * single kernel launch (vector ALUs for one row per segment, matrix cores on
+ * sixteen-row tiles otherwise); longer segments, or no hint, take one launch
+ * per step. */
 int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x,
                   const void* const* A_ptrs, const void* const* B_ptrs,
                   const int32_t* seg_starts, int32_t n_segs, int32_t layer_idx,
                   float scale, void* stream);
+
+/* Several LoRA add-ons of ONE shape in a single call: n_proj (at most 8)
+ * independent add-ons y_i += scale * (x_i A^(i)_seg) B^(i)_seg that share the
+ * descriptor (dtype, h_in, h_out, r, num_layers), the segment indices and
+ * layer_idx -- the projections of a transformer layer that read the same
+ * activations (query / key / value, or gate / up).  The paper applies LoRA to
+ * every dense projection of a layer and notes that the segment indices stay
+ * the same for all of these add-ons within one model invocation.
+ *   ys, xs          HOST arrays of n_proj device pointers ([n_tokens][h_out] and
+ *                   [n_tokens][h_in]); the y_i must be distinct, the x_i may be
+ *                   the same buffer
+ *   A_ptrs, B_ptrs  HOST arrays of n_proj device pointers, each to a device
+ *                   array of n_segs weight pointers as in sgmv_add_lora
+ * With workspace_ready set and max_seg_len == 1 (every request its own
+ * adapter) all add-ons run in ONE kernel launch; otherwise the call is the
+ * same as n_proj calls of sgmv_add_lora in order.  The result of every add-on
+ * is bit-identical to a separate sgmv_add_lora call. */
+int sgmv_add_lora_multi(const sgmv_problem* p, int32_t n_proj, void* const* ys,
+                        const void* const* xs, const void* const* const* A_ptrs,
+                        const void* const* const* B_ptrs, const int32_t* seg_starts,
+                        int32_t n_segs, int32_t layer_idx, float scale, void* stream);
 
 #ifdef __cplusplus
 }

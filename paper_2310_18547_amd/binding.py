@@ -74,6 +74,9 @@ def _load():
     L.sgmv_add_lora.argtypes = [P, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
                                 c.c_int32, c.c_int32, c.c_float, c.c_void_p]
     L.sgmv_add_lora.restype = c.c_int
+    L.sgmv_add_lora_multi.argtypes = [P, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+                                      c.c_void_p, c.c_int32, c.c_int32, c.c_float, c.c_void_p]
+    L.sgmv_add_lora_multi.restype = c.c_int
     return L
 
 
@@ -153,4 +156,18 @@ def sgmv_add_lora(p: SgmvProblem, y, x, A_ptrs, B_ptrs, seg_starts, n_segs: int,
                            _addr(seg_starts), n_segs, layer_idx, scale, _stream(stream))
     if check and rc != 0:
         raise SgmvError(rc, "sgmv_add_lora")
+    return rc
+
+
+def sgmv_add_lora_multi(p: SgmvProblem, ys, xs, A_ptrs, B_ptrs, seg_starts, n_segs: int,
+                        layer_idx: int, scale: float, stream=None, check: bool = True) -> int:
+    """``ys, xs, A_ptrs, B_ptrs`` are sequences of equal length (one entry per add-on)."""
+    n = len(ys)
+    arr = ctypes.c_void_p * n
+    rc = lib.sgmv_add_lora_multi(
+        ctypes.byref(p), n, arr(*[_addr(a) for a in ys]), arr(*[_addr(a) for a in xs]),
+        arr(*[_addr(a) for a in A_ptrs]), arr(*[_addr(a) for a in B_ptrs]), _addr(seg_starts),
+        n_segs, layer_idx, scale, _stream(stream))
+    if check and rc != 0:
+        raise SgmvError(rc, "sgmv_add_lora_multi")
     return rc

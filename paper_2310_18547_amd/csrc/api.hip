@@ -13,7 +13,6 @@ using namespace sgmv;
 
 constexpr int kMinSplitCap = 16;       // the workspace always allows this many slices
 constexpr int kTargetWorkgroups = 512; // about two workgroups per compute unit
-constexpr int kFusedMaxSegLen = 16;    // longest segment the single-launch vector kernel takes
 constexpr int kTileMaxSegLen = 64;     // longest segment the single-launch MFMA kernel is used for
 constexpr int kFusedSlices = 8;        // most slices per segment the single-launch kernels pick
 constexpr int kFusedWorkgroups = 256;  // one workgroup per compute unit
@@ -134,7 +133,7 @@ void set_operands(ExpandArgs* a, void* workspace, int n_tokens, int r) {
 // Launch shape of the single-launch path; false when it does not apply.
 bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f) {
   if (!p->workspace_ready) return false;
-  if (p->max_seg_len <= 0 || p->max_seg_len > kFusedMaxSegLen) return false;
+  if (p->max_seg_len != 1) return false;  // one row per segment; longer ones go to the tile kernel
   if (n_segs > kFusedMaxWorkgroups) return false;
   const int cap = split_cap(p->n_tokens);
   const int need = ceil_div(p->h_in, kMaxKSlice);
@@ -158,7 +157,7 @@ bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f) {
   while (g * 2 <= 8 && 256 / (g * 2) >= chunks) g *= 2;
   while (p->r / g > 16) g *= 2;
   f->G = g;
-  f->rows_per_pass = p->max_seg_len == 1 ? 1 : 4;
+  f->rows_per_pass = 1;
   return true;
 }
 
@@ -187,6 +186,27 @@ bool choose_tile(const sgmv_problem* p, int n_segs, TileArgs* t) {
   t->S = s;
   t->Z = z;
   return true;
+}
+
+void fill_fused(FusedArgs* f, const sgmv_problem* p, const int32_t* seg_starts, int n_segs,
+                int layer_idx, float scale) {
+  f->bf16 = p->dtype == SGMV_BF16;
+  f->r = p->r;
+  f->h_in = p->h_in;
+  f->h_out = p->h_out;
+  f->n_tokens = p->n_tokens;
+  f->n_segs = n_segs;
+  f->spin_limit = kFusedSpinLimit;
+  f->offA = (long long)layer_idx * p->h_in * p->r;
+  f->offB = (long long)layer_idx * p->r * p->h_out;
+  f->seg_starts = seg_starts;
+  f->exch = exchange_base(p->workspace, p->n_tokens, p->r);
+  f->header = static_cast<unsigned long long*>(p->workspace);
+  f->scale = scale;
+  f->n_proj = 0;
+  f->y = nullptr;
+  f->x = nullptr;
+  f->A_ptrs = f->B_ptrs = nullptr;
 }
 
 int choose_expand_threads(const sgmv_problem* p, int n_segs) {
@@ -384,23 +404,11 @@ int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x, const void* con
   if (p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) {
     FusedArgs f;
     if (choose_fused(p, n_segs, &f)) {
-      f.bf16 = p->dtype == SGMV_BF16;
-      f.r = p->r;
-      f.h_in = p->h_in;
-      f.h_out = p->h_out;
-      f.n_tokens = p->n_tokens;
-      f.n_segs = n_segs;
-      f.spin_limit = kFusedSpinLimit;
-      f.offA = (long long)layer_idx * p->h_in * p->r;
-      f.offB = (long long)layer_idx * p->r * p->h_out;
+      fill_fused(&f, p, seg_starts, n_segs, layer_idx, scale);
       f.y = y;
       f.x = x;
       f.A_ptrs = A_ptrs;
       f.B_ptrs = B_ptrs;
-      f.seg_starts = seg_starts;
-      f.exch = exchange_base(p->workspace, p->n_tokens, p->r);
-      f.header = static_cast<unsigned long long*>(p->workspace);
-      f.scale = scale;
       if (launch_add_lora_fused(f, st) != hipSuccess) return SGMV_ERR_LAUNCH;
       return SGMV_OK;
     }
@@ -421,6 +429,54 @@ int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x, const void* con
   ExpandArgs e = make_expand(p, y, s.partials, s.ksplit, A_ptrs, B_ptrs, seg_starts, n_segs,
                              layer_idx, scale);
   if (launch_expand_vector(e, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+  return SGMV_OK;
+}
+
+int sgmv_add_lora_multi(const sgmv_problem* p, int32_t n_proj, void* const* ys,
+                        const void* const* xs, const void* const* const* A_ptrs,
+                        const void* const* const* B_ptrs, const int32_t* seg_starts, int32_t n_segs,
+                        int32_t layer_idx, float scale, void* stream) {
+  int rc = check_common(p, seg_starts, n_segs, layer_idx, true, true);
+  if (rc != SGMV_OK) return rc;
+  if (n_proj < 0 || n_proj > kMaxProjections) return SGMV_ERR_SHAPE;
+  if (n_proj == 0 || n_segs == 0 || p->n_tokens == 0) return SGMV_OK;
+  if (ys == nullptr || xs == nullptr || A_ptrs == nullptr || B_ptrs == nullptr) return SGMV_ERR_NULL;
+  for (int i = 0; i < n_proj; ++i) {
+    if (ys[i] == nullptr || xs[i] == nullptr || A_ptrs[i] == nullptr || B_ptrs[i] == nullptr)
+      return SGMV_ERR_NULL;
+    if (!aligned(ys[i], 16) || !aligned(xs[i], 16)) return SGMV_ERR_ALIGN;
+    for (int j = 0; j < i; ++j)
+      if (ys[i] == ys[j]) return SGMV_ERR_SHAPE;  // two add-ons into one y would race
+  }
+  rc = check_workspace(p);
+  if (rc != SGMV_OK) return rc;
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if ((p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->max_seg_len == 1 && n_proj > 1) {
+    FusedArgs f;
+    // every projection exchanges through its own S slices of the workspace
+    if (choose_fused(p, n_segs, &f) && f.S * n_proj <= split_cap(p->n_tokens) &&
+        (long long)f.S * n_segs * n_proj <= kEpochStep / 2) {
+      fill_fused(&f, p, seg_starts, n_segs, layer_idx, scale);
+      f.n_proj = n_proj;
+      for (int i = 0; i < n_proj; ++i) {
+        f.table.x[i] = xs[i];
+        f.table.y[i] = ys[i];
+        f.table.A_ptrs[i] = A_ptrs[i];
+        f.table.B_ptrs[i] = B_ptrs[i];
+      }
+      for (int i = n_proj; i < kMaxProjections; ++i)
+        f.table.x[i] = f.table.y[i] = nullptr, f.table.A_ptrs[i] = f.table.B_ptrs[i] = nullptr;
+      if (launch_add_lora_fused(f, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+      return SGMV_OK;
+    }
+  }
+  // any other shape: one add-on after the other
+  for (int i = 0; i < n_proj; ++i) {
+    rc = sgmv_add_lora(p, ys[i], xs[i], A_ptrs[i], B_ptrs[i], seg_starts, n_segs, layer_idx, scale,
+                       stream);
+    if (rc != SGMV_OK) return rc;
+  }
   return SGMV_OK;
 }
 

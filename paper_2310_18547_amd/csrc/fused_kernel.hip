@@ -90,7 +90,7 @@ __device__ __forceinline__ float fused_reduce_lanes8(const float (&a)[8], int la
   return d;
 }
 
-// grid = (S, n_segs) workgroups of 320 threads: blockIdx.y is the segment,
+// Body of the kernels below.  grid = (S, n_segs[, projections]) workgroups of 320 threads: blockIdx.y is the segment,
 // blockIdx.x its slice index (so the S workgroups of a segment are neighbours
 // in dispatch order and no division is needed to find them).
 //   exch   [S][n_tokens][R] 64-bit words {fp32 value (high), tag (low)}
@@ -99,9 +99,7 @@ __device__ __forceinline__ float fused_reduce_lanes8(const float (&a)[8], int la
 //      g*R/G .. (g+1)*R/G-1; the groups are summed through LDS.
 // RB = rows handled per pass over the weights (1 when every segment is one row).
 template <class DT, int R, int G, int RB>
-__global__ __launch_bounds__(320) void add_lora_fused_kernel(
-    // the first sixteen dwords are preloaded into SGPRs at wave launch: keep what the
-    // first dependent loads need at the front
+__device__ __forceinline__ void add_lora_fused_body(
     const int32_t* __restrict__ seg_starts, const uint16_t* const* __restrict__ A_ptrs,
     const uint16_t* const* __restrict__ B_ptrs, const uint16_t* __restrict__ x,
     uint16_t* __restrict__ y, int kslice, int cslice, int h_in, int h_out, int n_tokens, int S,
@@ -127,7 +125,7 @@ __global__ __launch_bounds__(320) void add_lora_fused_kernel(
   const uint16_t* A = A_ptrs[seg];
   const uint16_t* B = B_ptrs[seg];
   if (lo >= hi || A == nullptr || B == nullptr) {  // same decision in all S workgroups
-    if (tid == 0) leave_launch(header, S * (int)gridDim.y);
+    if (tid == 0) leave_launch(header, (int)(gridDim.x * gridDim.y * gridDim.z));
     return;
   }
   SGMV_TRACE_POINT(8);
@@ -201,7 +199,7 @@ __global__ __launch_bounds__(320) void add_lora_fused_kernel(
       }
     }
     if (timed_out) __hip_atomic_store((unsigned*)(header + kEpochCounters), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (lane == 0) leave_launch(header, S * (int)gridDim.y);
+    if (lane == 0) leave_launch(header, (int)(gridDim.x * gridDim.y * gridDim.z));
     SGMV_TRACE_POINT(7);
     SGMV_TRACE_FLUSH(lane == 0, 4, 7);
     return;
@@ -405,6 +403,39 @@ __global__ __launch_bounds__(320) void add_lora_fused_kernel(
   SGMV_TRACE_FLUSH(tid == 0, 8, 9);
 }
 
+// One add-on per launch.
+template <class DT, int R, int G, int RB>
+__global__ __launch_bounds__(320) void add_lora_fused_kernel(
+    // the first sixteen dwords are preloaded into SGPRs at wave launch: keep what the
+    // first dependent loads need at the front
+    const int32_t* __restrict__ seg_starts, const uint16_t* const* __restrict__ A_ptrs,
+    const uint16_t* const* __restrict__ B_ptrs, const uint16_t* __restrict__ x,
+    uint16_t* __restrict__ y, int kslice, int cslice, int h_in, int h_out, int n_tokens, int S,
+    long long offA, long long offB, unsigned long long* exch, unsigned long long* header,
+    float scale, int spin_limit) {
+  add_lora_fused_body<DT, R, G, RB>(seg_starts, A_ptrs, B_ptrs, x, y, kslice, cslice, h_in, h_out,
+                                    n_tokens, S, offA, offB, exch, header, scale, spin_limit);
+}
+
+// Several independent add-ons of one shape per launch (the projections of a
+// transformer layer that read the same activations: q / k / v, or gate / up): the
+// segment indices are shared, as the paper notes they are for all LoRA add-ons of a
+// model invocation; blockIdx.z selects the projection's x, y and pointer arrays.
+// Each projection exchanges through its own stretch of the workspace.
+template <class DT, int R, int G>
+__global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
+    const int32_t* __restrict__ seg_starts, int kslice, int cslice, int h_in, int h_out, int n_tokens,
+    int S, long long offA, long long offB, unsigned long long* exch, unsigned long long* header,
+    float scale, int spin_limit, FusedTable tab) {
+  const int z = blockIdx.z;
+  add_lora_fused_body<DT, R, G, 1>(
+      seg_starts, reinterpret_cast<const uint16_t* const*>(tab.A_ptrs[z]),
+      reinterpret_cast<const uint16_t* const*>(tab.B_ptrs[z]),
+      reinterpret_cast<const uint16_t*>(tab.x[z]), reinterpret_cast<uint16_t*>(tab.y[z]), kslice, cslice,
+      h_in, h_out, n_tokens, S, offA, offB, exch + (long long)z * S * n_tokens * R, header, scale,
+      spin_limit);
+}
+
 // Workspace initialisation: zero everything, then start the epoch one full
 // step above zero so that the zeroed exchange words (tag 0) never match.
 __global__ __launch_bounds__(256) void workspace_init_kernel(uint32_t* p, size_t n_words,
@@ -435,8 +466,18 @@ static hipError_t launch_fused_t(const FusedArgs& a, hipStream_t st) {
 }
 
 template <class DT, int R, int G>
+static hipError_t launch_fused_multi_t(const FusedArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL((add_lora_fused_multi_kernel<DT, R, G>),
+                     dim3((unsigned)a.S, (unsigned)a.n_segs, (unsigned)a.n_proj), dim3(320), 0, st,
+                     a.seg_starts, a.kslice, a.cslice, a.h_in, a.h_out, a.n_tokens, a.S, a.offA, a.offB,
+                     a.exch, a.header, a.scale, a.spin_limit, a.table);
+  return hipGetLastError();
+}
+
+template <class DT, int R, int G>
 static hipError_t launch_fused_rb(const FusedArgs& a, hipStream_t st) {
-  return a.rows_per_pass == 1 ? launch_fused_t<DT, R, G, 1>(a, st) : launch_fused_t<DT, R, G, 4>(a, st);
+  if (a.n_proj > 0) return launch_fused_multi_t<DT, R, G>(a, st);
+  return launch_fused_t<DT, R, G, 1>(a, st);
 }
 
 template <class DT, int R>

@@ -51,6 +51,16 @@ struct ExpandArgs {
   float* undo;
 };
 
+// Most add-ons one multi-projection launch takes.
+constexpr int kMaxProjections = 8;
+// Per-projection pointers of a multi-projection launch (passed by value as a kernel argument).
+struct FusedTable {
+  const void* x[kMaxProjections];
+  void* y[kMaxProjections];
+  const void* A_ptrs[kMaxProjections];
+  const void* B_ptrs[kMaxProjections];
+};
+
 struct FusedArgs {
   bool bf16;
   int r, h_in, h_out, n_tokens, n_segs;
@@ -68,6 +78,8 @@ struct FusedArgs {
   const int32_t* seg_starts;
   unsigned long long* exch;  // [S][n_tokens][r] words {value, generation tag}
   unsigned long long* header;// kEpochCounters epoch counters, then the error word
+  int n_proj;                // 0: one add-on (x, y, A_ptrs, B_ptrs above); else `table` holds n_proj of them
+  FusedTable table;
 };
 
 // Single-launch kernel for segments of a few rows (sixteen-row MFMA tiles).

@@ -100,7 +100,7 @@ def test_argument_errors_are_reported_without_a_device():
     assert _add(_prob(path=9)) == 3
     assert _add(_prob(path=sg.PATH_FUSED)) == 3            # workspace not declared ready
     assert _add(_prob(path=sg.PATH_FUSED, workspace_ready=1, max_seg_len=0)) == 3
-    assert _add(_prob(path=sg.PATH_FUSED, workspace_ready=1, max_seg_len=17)) == 3
+    assert _add(_prob(path=sg.PATH_FUSED, workspace_ready=1, max_seg_len=65)) == 3
     assert sg.sgmv_workspace_init(None, 1024, check=False) == 1
     assert sg.sgmv_workspace_init(FAKE + 8, 1024, check=False) == 4
     assert sg.sgmv_workspace_check(None) == 1

@@ -441,6 +441,72 @@ def test_tile_graph_replay_mixed_segments():
     assert d.check(stream.cuda_stream) == 0
 
 
+# ------------------------------------------- several add-ons of one shape in one launch
+def _multi_setup(P, batch, h_in, h_out, r, dtype, layers, share_x):
+    ws = [wl.decode_distinct(batch=batch, h_in=h_in, h_out=h_out, r=r, dtype=dtype, num_layers=layers,
+                             seed=80 + i) for i in range(P)]
+    if share_x:
+        for w in ws[1:]:
+            w.x = ws[0].x
+    return ws, [_dev(w) for w in ws]
+
+
+@pytest.mark.parametrize("P,batch,share_x", [(3, 64, True), (2, 16, False), (8, 5, True), (1, 7, True)])
+def test_add_lora_multi_matches_single_calls_and_oracle(P, batch, share_x):
+    from paper_2310_18547_amd import binding as B
+    ws, ds = _multi_setup(P, batch, 4096, 4096, 16, "f16", 2, share_x)
+    d0 = ds[0]
+    xs = [d0.x[0] if share_x else d.x[0] for d in ds]
+    B.sgmv_add_lora_multi(d0.problem, [d.y[0] for d in ds], xs, [d.A_ptrs for d in ds],
+                          [d.B_ptrs for d in ds], d0.seg_starts, ws[0].n_segs, 1, ws[0].scale)
+    got = [d.y_bits() for d in ds]
+    assert d0.check() == 0
+    for i, (w, d) in enumerate(zip(ws, ds)):
+        assert_parity(got[i], oracle.run_workload(w, layer_idx=1, n_threads=8), "f16", f"multi proj {i}")
+        d.reset_y()
+        d.add_lora(1)
+        assert np.array_equal(d.y_bits(), got[i]), f"projection {i} differs from a single call"
+
+
+@pytest.mark.parametrize("dtype,r,h_in,h_out", [("bf16", 64, 2048, 1544), ("f16", 8, 1000, 4096)])
+def test_add_lora_multi_shapes(dtype, r, h_in, h_out):
+    from paper_2310_18547_amd import binding as B
+    ws, ds = _multi_setup(3, 12, h_in, h_out, r, dtype, 1, False)
+    d0 = ds[0]
+    for rep in range(2):        # twice: the exchange words of the first call must not satisfy the second
+        for d in ds:
+            d.reset_y()
+        B.sgmv_add_lora_multi(d0.problem, [d.y[0] for d in ds], [d.x[0] for d in ds],
+                              [d.A_ptrs for d in ds], [d.B_ptrs for d in ds], d0.seg_starts,
+                              ws[0].n_segs, 0, ws[0].scale)
+        for i, (w, d) in enumerate(zip(ws, ds)):
+            assert_parity(d.y_bits(), oracle.run_workload(w), dtype, f"multi {dtype} r={r} proj {i} rep {rep}")
+    assert d0.check() == 0
+
+
+def test_add_lora_multi_falls_back_for_mixed_segments():
+    from paper_2310_18547_amd import binding as B
+    ws = [wl.custom([3, 1, 20, 2], 512, 768, 16, "f16", seed=90 + i) for i in range(2)]
+    ds = [_dev(w) for w in ws]
+    d0 = ds[0]
+    B.sgmv_add_lora_multi(d0.problem, [d.y[0] for d in ds], [d.x[0] for d in ds],
+                          [d.A_ptrs for d in ds], [d.B_ptrs for d in ds], d0.seg_starts,
+                          ws[0].n_segs, 0, 1.0)
+    for w, d in zip(ws, ds):
+        assert_parity(d.y_bits(), oracle.run_workload(w), "f16", "multi, mixed segments")
+
+
+def test_add_lora_multi_rejects_bad_arguments():
+    from paper_2310_18547_amd import binding as B
+    ws, ds = _multi_setup(2, 4, 256, 256, 16, "f16", 1, False)
+    d0 = ds[0]
+    args = ([d.x[0] for d in ds], [d.A_ptrs for d in ds], [d.B_ptrs for d in ds], d0.seg_starts, 4, 0, 1.0)
+    assert B.sgmv_add_lora_multi(d0.problem, [d0.y[0], d0.y[0]], *args, check=False) == 2   # same y twice
+    assert B.sgmv_add_lora_multi(d0.problem, [d0.y[0], None], *args, check=False) == 1
+    nine = [d0.y[0]] * 9
+    assert B.sgmv_add_lora_multi(d0.problem, nine, nine, nine, nine, d0.seg_starts, 4, 0, 1.0, check=False) == 2
+
+
 # ------------------------------------------------------- MFMA (matrix) path
 def _matrix(w, **kw):
     from paper_2310_18547_amd import binding as B
