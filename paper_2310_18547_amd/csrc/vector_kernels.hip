@@ -163,7 +163,8 @@ __global__ __launch_bounds__(NT) void shrink_vector_kernel(
 }
 
 // v[row][j] += sum over slices of partials[s][row][j], slices in ascending order.
-// grid = n_segs; rows of segments without an adapter are left alone.
+// grid = (n_segs, chunks): the chunk dimension strides over the segment's elements,
+// four per thread; rows of segments without an adapter are left alone.
 template <int R>
 __global__ __launch_bounds__(256) void shrink_reduce_kernel(
     float* __restrict__ v, const float* __restrict__ partials,
@@ -172,11 +173,27 @@ __global__ __launch_bounds__(256) void shrink_reduce_kernel(
   const int seg = blockIdx.x;
   const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
   if (lo >= hi || A_ptrs[seg] == nullptr) return;
-  const long long first = (long long)lo * R, count = (long long)(hi - lo) * R;
-  for (long long i = threadIdx.x; i < count; i += blockDim.x) {
-    float sum = 0.f;
-    for (int s = 0; s < ksplit; ++s) sum += partials[(long long)s * n_tokens * R + first + i];
-    v[first + i] += sum;
+  const long long first = (long long)lo * R, count = (long long)(hi - lo) * R;  // multiples of 4
+  const long long pstride = (long long)n_tokens * R;
+  for (long long i = ((long long)blockIdx.y * blockDim.x + threadIdx.x) * 4; i < count;
+       i += (long long)gridDim.y * blockDim.x * 4) {
+    float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s0 = 0; s0 < ksplit; s0 += 4) {  // four slices' loads in flight together, added in order
+      float4 q[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        q[j] = *reinterpret_cast<const float4*>(partials + (long long)min(s0 + j, ksplit - 1) * pstride + first + i);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (s0 + j < ksplit) {
+          sum.x += q[j].x; sum.y += q[j].y; sum.z += q[j].z; sum.w += q[j].w;
+        }
+      }
+    }
+    float4* dst = reinterpret_cast<float4*>(v + first + i);
+    float4 cur = *dst;
+    cur.x += sum.x; cur.y += sum.y; cur.z += sum.z; cur.w += sum.w;
+    *dst = cur;
   }
 }
 
@@ -303,7 +320,11 @@ hipError_t launch_shrink_vector(const ShrinkArgs& a, hipStream_t st) {
 }
 
 hipError_t launch_shrink_reduce(float* v, const ShrinkArgs& a, hipStream_t st) {
-  dim3 grid((unsigned)a.n_segs);
+  const long long longest = (long long)(a.max_seg_len > 0 ? a.max_seg_len : a.n_tokens) * a.r;
+  long long chunks = (longest + 1023) / 1024;  // 256 threads x 4 elements
+  if (chunks > 64) chunks = 64;
+  if (chunks < 1) chunks = 1;
+  dim3 grid((unsigned)a.n_segs, (unsigned)chunks);
   const uint16_t* const* ap = (const uint16_t* const*)a.A_ptrs;
   switch (a.r) {
     case 8: hipLaunchKernelGGL(shrink_reduce_kernel<8>, grid, dim3(256), 0, st, v, a.partials, ap, a.seg_starts, a.ksplit, a.n_tokens); break;
