@@ -552,6 +552,18 @@ def test_matrix_path_every_split(ksplit):
     assert_parity(d.y_bits(), oracle.run_workload(w, n_threads=8), "bf16", f"matrix ksplit={ksplit}")
 
 
+def test_matrix_path_one_deep_slice_at_high_rank():
+    # a single k-slice of 4104 x 64 weights: many LDS stages per workgroup
+    w = wl.custom([40, 7, 129], 4096 + 8, 256, 64, "f16", seed=74)
+    d = _matrix(w, ksplit=1)
+    d.add_lora()
+    assert_parity(d.y_bits(), oracle.run_workload(w, n_threads=8), "f16", "matrix, one deep slice")
+    v = torch.zeros(w.n_tokens, 64, dtype=torch.float32, device="cuda:0")
+    _matrix(w, ksplit=2).shrink(v)
+    v_ref = oracle.run_workload(w, op="shrink", n_threads=8)
+    assert np.all(np.abs(v.cpu().numpy() - v_ref) <= 2e-3 + 2e-2 * np.abs(v_ref))
+
+
 def test_matrix_path_null_adapter_and_tiny():
     w = wl.custom([20, 30, 10], 256, 264, 16, "f16", seed=71)
     w.seg_adapter = np.asarray([0, -1, 2], np.int64)
