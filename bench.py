@@ -30,6 +30,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a
+# 64 MiB + 64 MiB copy kernel), from the summaries under profiles/; reported as roofline.traffic
+MEASURED_TRAFFIC = {"distinct_b64": 18738076.0}
+
 # the paper's own latencies for this operator (one A100 80 GB, fp16, r = 16), context only
 PAPER_A100_US = {"distinct_b64": [116.0, 75.0], "distinct_b1": [37.0, 42.0]}
 
@@ -94,6 +98,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 64 MiB read + 64 MiB write elementwise kernel, as the "
                          "known-size reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--projections", type=int, default=1,
+                    help="add-ons of the same shape per step through sgmv_add_lora_multi (q/k/v = 3); "
+                         "1 = the headline metric, one sgmv_add_lora call per step")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch measured with rocprofv3 --pmc (reported as "
                          "roofline.traffic)")
@@ -116,9 +123,22 @@ def main():
     L, S = w.num_layers, args.sets
     stream = torch.cuda.Stream(device="cuda:0")          # default priority
     sh = stream.cuda_stream
+    P = args.projections
+    if P > 1:
+        # P add-ons with their own adapters and outputs, sharing x and the segment indices
+        from paper_2310_18547_amd import binding as B
+        others = [DeviceWorkload(make_workload(args.workload, args.seed + 1 + i), "cuda:0",
+                                 n_sets=args.sets) for i in range(P - 1)]
+        ds = [d] + others
 
-    def step(i):
-        d.add_lora(i % L, i % S, stream=sh)
+        def step(i):
+            k = i % S
+            B.sgmv_add_lora_multi(d.problem, [q.y[k] for q in ds], [d.x[k]] * P,
+                                  [q.A_ptrs for q in ds], [q.B_ptrs for q in ds], d.seg_starts,
+                                  w.n_segs, i % L, w.scale, sh)
+    else:
+        def step(i):
+            d.add_lora(i % L, i % S, stream=sh)
 
     if args.calibrate_copy:
         src = torch.ones(16 << 20, dtype=torch.int32, device="cuda:0")
@@ -160,7 +180,18 @@ def main():
     us = ms_per_step * 1e3
 
     T, n = w.n_tokens, w.n_distinct
-    bytes_step = acc.algorithmic_bytes("add_lora", T, n, w.h_in, w.h_out, w.r)
+    bytes_step = P * acc.algorithmic_bytes("add_lora", T, n, w.h_in, w.h_out, w.r)
+    single = w.max_seg_len == 1 and args.path in (0, 3)
+    tiled = 1 < w.max_seg_len <= 64 and args.path in (0, 3)
+    if single:
+        kernel, launches = ("add_lora_fused_multi_kernel" if P > 1 else "add_lora_fused_kernel"), 1
+    elif tiled:
+        kernel, launches = "add_lora_tile_kernel", P
+    else:
+        kernel, launches = "shrink / finalize_v / expand kernels of one sgmv_add_lora step", 3 * P
+    traffic = args.traffic_bytes
+    if traffic is None and P == 1 and args.path == 0 and args.ksplit == 0:
+        traffic = MEASURED_TRAFFIC.get(args.workload)
     gbs = bytes_step / (ms_per_step * 1e-3) / 1e9
 
     out = {
@@ -180,16 +211,14 @@ def main():
                    "tokens": T, "segments": w.n_segs, "distinct_adapters": n,
                    "layers_cycled": L, "xy_sets": S, "mode": args.mode,
                    "steps_per_s": 1e3 / ms_per_step,
+                   "projections_per_step": P,
                    "algorithmic_bytes_per_step": bytes_step,
-                   "flops_per_step": acc.flops("add_lora", T, w.h_in, w.h_out, w.r)},
+                   "flops_per_step": P * acc.flops("add_lora", T, w.h_in, w.h_out, w.r)},
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": gbs / HBM_PEAK_GBS, "traffic": args.traffic_bytes,
-                     "kernel": "add_lora_fused_kernel (one launch per step)"
-                               if (w.max_seg_len <= 16 and args.path in (0, 3))
-                               else "all kernels of one sgmv_add_lora step",
-                     "launches_per_step": 1 if (w.max_seg_len <= 16 and args.path in (0, 3)) else 2,
-                     "algorithmic_bytes_per_launch": bytes_step,
-                     "avg_launch_us": us},
+                     "frac": gbs / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": kernel, "launches_per_step": launches,
+                     "algorithmic_bytes_per_step": bytes_step,
+                     "avg_step_us": us},
         "paper_a100_us": PAPER_A100_US.get(args.workload),
         "block_ms": times,
     }
