@@ -17,6 +17,7 @@ constexpr int kTileMaxSegLen = 64;     // longest segment the single-launch MFMA
 constexpr int kFusedSlices = 8;        // most slices per segment the single-launch kernels pick
 constexpr int kFusedWorkgroups = 256;  // one workgroup per compute unit
 constexpr int kFusedMaxWorkgroups = 1024;
+constexpr int kMultiWorkgroups = 512;  // workgroups of a multi-projection launch that run side by side (two per compute unit)
 constexpr int kFusedSpinLimit = 1 << 18;
 constexpr int kMatrixMinSegLen = 17;   // AUTO uses the MFMA kernels from this segment length on
 constexpr int kMatrixWorkgroups = 448; // workgroups the MFMA shrink aims for
@@ -209,6 +210,7 @@ void fill_fused(FusedArgs* f, const sgmv_problem* p, const int32_t* seg_starts, 
   f->header = static_cast<unsigned long long*>(p->workspace);
   f->scale = scale;
   f->n_proj = 0;
+  f->Z = 1;
   f->y = nullptr;
   f->x = nullptr;
   f->A_ptrs = f->B_ptrs = nullptr;
@@ -460,19 +462,28 @@ int sgmv_add_lora_multi(const sgmv_problem* p, int32_t n_proj, void* const* ys,
   if ((p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->max_seg_len == 1 && n_proj > 1) {
     FusedArgs f;
     // every projection exchanges through its own S slices of the workspace
-    if (choose_fused(p, n_segs, &f) && f.S * n_proj <= split_cap(p->n_tokens) &&
-        (long long)f.S * n_segs * n_proj <= kEpochStep / 2) {
+    bool ok = choose_fused(p, n_segs, &f) && f.S * n_proj <= split_cap(p->n_tokens);
+    if (ok) {
       fill_fused(&f, p, seg_starts, n_segs, layer_idx, scale);
+      ok = (long long)f.S * n_segs * n_proj <= kMultiWorkgroups || fused_multi_fits(f);
+    }
+    if (ok) {
       f.n_proj = n_proj;
-      for (int i = 0; i < n_proj; ++i) {
-        f.table.x[i] = xs[i];
-        f.table.y[i] = ys[i];
-        f.table.A_ptrs[i] = A_ptrs[i];
-        f.table.B_ptrs[i] = B_ptrs[i];
+      for (int i = 0; i < kMaxProjections; ++i) {
+        f.table.x[i] = i < n_proj ? xs[i] : nullptr;
+        f.table.y[i] = i < n_proj ? ys[i] : nullptr;
+        f.table.A_ptrs[i] = i < n_proj ? A_ptrs[i] : nullptr;
+        f.table.B_ptrs[i] = i < n_proj ? B_ptrs[i] : nullptr;
       }
-      for (int i = n_proj; i < kMaxProjections; ++i)
-        f.table.x[i] = f.table.y[i] = nullptr, f.table.A_ptrs[i] = f.table.B_ptrs[i] = nullptr;
-      if (launch_add_lora_fused(f, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+      // side by side while every workgroup of the launch is resident (two fit a compute
+      // unit); beyond that one workgroup per (slice, segment) walks the projections in
+      // turn, the next one's loads in flight
+      if ((long long)f.S * n_segs * n_proj <= kMultiWorkgroups) {
+        if (launch_add_lora_fused(f, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+        return SGMV_OK;
+      }
+      f.Z = 1;
+      if (launch_add_lora_fused_multi(f, st) != hipSuccess) return SGMV_ERR_LAUNCH;
       return SGMV_OK;
     }
   }

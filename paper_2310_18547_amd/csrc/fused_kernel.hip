@@ -417,13 +417,12 @@ __global__ __launch_bounds__(320) void add_lora_fused_kernel(
                                     n_tokens, S, offA, offB, exch, header, scale, spin_limit);
 }
 
-// Several independent add-ons of one shape per launch (the projections of a
-// transformer layer that read the same activations: q / k / v, or gate / up): the
-// segment indices are shared, as the paper notes they are for all LoRA add-ons of a
-// model invocation; blockIdx.z selects the projection's x, y and pointer arrays.
-// Each projection exchanges through its own stretch of the workspace.
+// Several independent add-ons of one shape per launch, side by side: blockIdx.z selects
+// the projection's x, y and pointer arrays; each projection exchanges through its own
+// stretch of the workspace.  Used while all workgroups of the launch are resident together
+// (small batches); larger launches take the pipelined kernel in fused_multi_kernel.hip.
 template <class DT, int R, int G>
-__global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
+__global__ __launch_bounds__(320) void add_lora_fused_side_kernel(
     const int32_t* __restrict__ seg_starts, int kslice, int cslice, int h_in, int h_out, int n_tokens,
     int S, long long offA, long long offB, unsigned long long* exch, unsigned long long* header,
     float scale, int spin_limit, FusedTable tab) {
@@ -466,8 +465,8 @@ static hipError_t launch_fused_t(const FusedArgs& a, hipStream_t st) {
 }
 
 template <class DT, int R, int G>
-static hipError_t launch_fused_multi_t(const FusedArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL((add_lora_fused_multi_kernel<DT, R, G>),
+static hipError_t launch_fused_side_t(const FusedArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL((add_lora_fused_side_kernel<DT, R, G>),
                      dim3((unsigned)a.S, (unsigned)a.n_segs, (unsigned)a.n_proj), dim3(320), 0, st,
                      a.seg_starts, a.kslice, a.cslice, a.h_in, a.h_out, a.n_tokens, a.S, a.offA, a.offB,
                      a.exch, a.header, a.scale, a.spin_limit, a.table);
@@ -476,7 +475,7 @@ static hipError_t launch_fused_multi_t(const FusedArgs& a, hipStream_t st) {
 
 template <class DT, int R, int G>
 static hipError_t launch_fused_rb(const FusedArgs& a, hipStream_t st) {
-  if (a.n_proj > 0) return launch_fused_multi_t<DT, R, G>(a, st);
+  if (a.n_proj > 0) return launch_fused_side_t<DT, R, G>(a, st);
   return launch_fused_t<DT, R, G, 1>(a, st);
 }
 

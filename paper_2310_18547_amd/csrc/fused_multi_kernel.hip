@@ -1,0 +1,411 @@
+// Several single-row LoRA add-ons of one shape in ONE launch, gfx950.
+//
+// A transformer layer applies LoRA to every dense projection, and the paper
+// notes that the segment indices stay the same for all of these add-ons of a
+// model invocation.  The projections that read the same activations (query /
+// key / value, or gate / up) are independent of each other, so their add-ons
+// can share a launch.  A single add-on moves too little data to hide its fixed
+// costs (launch, first-load latency, the hand-off of the Split-K partial sums
+// between workgroups); here a workgroup works through several add-ons in turn
+// and keeps the NEXT one's loads in flight while it reduces, exchanges and
+// finishes the current one, so HBM stays busy through the phases in which a
+// single add-on leaves it idle.
+//
+// Work split: grid = (S, n_segs, Z).  Workgroup (s, seg, z) serves k-slice s /
+// column-slice s of segment seg for the projections z, z + Z, z + 2 Z, ...
+// (Z = n_proj: one projection per workgroup, all in parallel, for small
+// batches; Z = 1: one workgroup per (slice, segment) walks all projections).
+// Its work items are (row of the segment, projection); an item is exactly the
+// work of one workgroup of the single add-on kernel (fused_kernel.hip), with
+// the same arithmetic in the same order, so every result is bit-identical to a
+// separate call.  Two register sets alternate: item i+1's x, A slice, B slice
+// and y loads are issued before item i is processed.
+//
+// The per-projection pointers (x, y and the segment's A / B pointers) are put
+// into LDS once at the start, so that stepping to the next item costs no
+// dependent global load.  A projection whose A or B pointer is NULL for this
+// segment is skipped by all S workgroups alike.
+#include <type_traits>
+
+#include "device_common.h"
+#include "exchange.h"
+#include "launch.h"
+
+// Optional timeline probe for kernel tuning (empty in the library).
+#ifndef SGMV_TRACE_POINT
+#define SGMV_TRACE_DECL
+#define SGMV_TRACE_POINT(point)
+#define SGMV_TRACE_FLUSH(cond, first, last)
+#endif
+
+namespace sgmv {
+
+template <int LPR>
+__device__ __forceinline__ float multi_reduce_lanes8(const float (&a)[8], int lane, int& e_out) {
+  constexpr int M1 = LPR, M2 = LPR * 2, M3 = LPR * 4;
+  float b[4], c[2], d;
+  bool up = (lane & M1) != 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float send = up ? a[i] : a[i + 4];
+    float keep = up ? a[i + 4] : a[i];
+    b[i] = keep + __shfl_xor(send, M1, 64);
+  }
+  up = (lane & M2) != 0;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    float send = up ? b[i] : b[i + 2];
+    float keep = up ? b[i + 2] : b[i];
+    c[i] = keep + __shfl_xor(send, M2, 64);
+  }
+  up = (lane & M3) != 0;
+  {
+    float send = up ? c[0] : c[1];
+    float keep = up ? c[1] : c[0];
+    d = keep + __shfl_xor(send, M3, 64);
+  }
+#pragma unroll
+  for (int m = M3 * 2; m < 64; m <<= 1) d += __shfl_xor(d, m, 64);
+  e_out = ((lane & M1) ? 4 : 0) | ((lane & M2) ? 2 : 0) | ((lane & M3) ? 1 : 0);
+  return d;
+}
+
+__device__ __forceinline__ unsigned long long uniform64(unsigned long long v) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return ((unsigned long long)hi << 32) | lo;
+}
+
+// The host guarantees kslice * R / 8 <= 2048 (the A slice is one batch of loads) and
+// cslice / 8 <= 256 / G (the column slice is one pass).
+//   exch   [n_proj][S][n_tokens][R] 64-bit words {fp32 value (high), tag (low)}
+template <class DT, int R, int G>
+__global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
+    const int32_t* __restrict__ seg_starts, int kslice, int cslice, int h_in, int h_out, int n_tokens,
+    int S, int n_proj, long long offA, long long offB, unsigned long long* exch,
+    unsigned long long* header, float scale, int spin_limit, FusedTable tab) {
+  constexpr int NT = 256, NW = 4, U = 8;
+  constexpr int LPR = R / 8;
+  constexpr int CPW = NT / G;  // 8-column chunks of the column slice
+  constexpr int JL = R / G;    // weight rows per lane in the expand phase
+  constexpr int P = kMaxProjections;
+  static_assert(JL >= 1 && JL <= 8, "bad lane-group count");
+
+  __shared__ __align__(16) uint16_t xs[kMaxKSlice];
+  __shared__ float red[NW][R];
+  __shared__ float vs[R];
+  __shared__ __align__(16) float ex[(G > 1 ? (G - 1) : 1) * CPW * 8];
+  __shared__ unsigned long long ptr_x[P], ptr_y[P], ptr_a[P], ptr_b[P];
+  __shared__ uint32_t mine;  // bit p: projection p is this workgroup's and has both pointers set
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  SGMV_TRACE_DECL
+  SGMV_TRACE_POINT(0);
+  const int seg = blockIdx.y, s = blockIdx.x, z = blockIdx.z, zstep = gridDim.z;
+  const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
+  const int n_workgroups = (int)(gridDim.x * gridDim.y * gridDim.z);
+  if (lo >= hi || z >= n_proj) {
+    if (tid == 0) leave_launch(header, n_workgroups);
+    return;
+  }
+  // The first projection's pointers come through scalar loads (one round trip, as in the
+  // single add-on kernel) so that its loads can be issued at once; the pointers of all
+  // projections go into LDS meanwhile: one lane per projection, all lanes' loads in parallel.
+  const uint16_t* const x_first = reinterpret_cast<const uint16_t*>(tab.x[z]);
+  uint16_t* const y_first = reinterpret_cast<uint16_t*>(tab.y[z]);
+  // (read through the constant address space: a wave-uniform address then takes the scalar
+  // path, one short round trip, and the buffer resources built from the values are scalar)
+  typedef const __attribute__((address_space(4))) unsigned long long* const_u64_ptr;
+  const uint16_t* const a_first = reinterpret_cast<const uint16_t*>(
+      ((const_u64_ptr) reinterpret_cast<unsigned long long>(tab.A_ptrs[z]))[seg]);
+  const uint16_t* const b_first = reinterpret_cast<const uint16_t*>(
+      ((const_u64_ptr) reinterpret_cast<unsigned long long>(tab.B_ptrs[z]))[seg]);
+  const bool first_ok = a_first != nullptr && b_first != nullptr;
+  // run by the exchange wave, which has no bulk loads in flight to wait for
+  auto stage_pointers = [&]() {
+    unsigned long long xa = 0ull, ya = 0ull, ap = 0ull, bp = 0ull;
+#pragma unroll
+    for (int p = 0; p < P; ++p) {  // selects from the by-value table, no memory access
+      if (lane == p) {
+        xa = reinterpret_cast<unsigned long long>(tab.x[p]);
+        ya = reinterpret_cast<unsigned long long>(tab.y[p]);
+        ap = reinterpret_cast<unsigned long long>(tab.A_ptrs[p]);
+        bp = reinterpret_cast<unsigned long long>(tab.B_ptrs[p]);
+      }
+    }
+    bool take = false;
+    if (lane < n_proj) {
+      const unsigned long long a = reinterpret_cast<const unsigned long long*>(ap)[seg];
+      const unsigned long long b = reinterpret_cast<const unsigned long long*>(bp)[seg];
+      ptr_x[lane] = xa;
+      ptr_y[lane] = ya;
+      ptr_a[lane] = a;
+      ptr_b[lane] = b;
+      take = a != 0ull && b != 0ull && lane >= z && (lane - z) % zstep == 0;
+    }
+    const unsigned long long votes = __ballot(take);
+    if (lane == 0) mine = (uint32_t)votes;
+  };
+
+  const int k0 = s * kslice;
+  const int klen = max(0, min(h_in, k0 + kslice) - k0);
+  const int nchunks = klen * LPR;
+  const int col_lo = min(h_out, s * cslice);
+  const int ncols = max(0, min(h_out, col_lo + cslice) - col_lo);
+  const long long stride = (long long)n_tokens * R;
+
+  // Work items in order: rows of the segment, and for each row this workgroup's projections
+  // (the set bits of `mine`, ascending).  Every wave walks the same sequence, with scalars only.
+  struct Item {
+    int row;
+    uint32_t left;  // projections of this row still to do, the lowest set bit being the current one
+  };
+  auto item_p = [](const Item& it) { return __builtin_ctz(it.left); };
+  if (wave == NW) {
+    // ============================================================ exchange wave
+    const uint32_t tag = generation_tag(read_epoch(header, lane));
+    stage_pointers();
+    lds_barrier();  // (p) pointers staged
+    bool timed_out = false;
+    SGMV_TRACE_POINT(4);
+    const uint32_t all = __builtin_amdgcn_readfirstlane(mine);
+    for (int row = lo; row < hi && all != 0u; ++row)
+    for (uint32_t left = all; left != 0u; left &= left - 1u) {
+      const int pp = __builtin_ctz(left);
+      unsigned long long* ex_p = exch + (long long)pp * S * stride + (long long)row * R;
+      lds_barrier();  // (b) xs filled
+      SGMV_TRACE_POINT(5);
+      lds_barrier();  // (c) red filled
+      if (lane < R) {
+        float sum = red[0][lane];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) sum += red[w][lane];
+        const unsigned long long word = ((unsigned long long)__float_as_uint(sum) << 32) | tag;
+        __hip_atomic_store(ex_p + (long long)s * stride + lane, word, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+      }
+      // collect all S slices, ascending (only the R lanes that own an element poll:
+      // idle lanes polling the same words would multiply the traffic on them)
+      if (lane < R) {
+        const unsigned long long* src = ex_p + lane;
+        float sum = 0.f;
+        for (int s0 = 0; s0 < S; s0 += 8) {
+          unsigned long long wv[8];
+          int polls = 0;
+          bool ready;
+          do {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+              wv[i] = __hip_atomic_load(src + min(s0 + i, S - 1) * stride, __ATOMIC_RELAXED,
+                                        __HIP_MEMORY_SCOPE_AGENT);
+            ready = true;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) ready = ready && ((uint32_t)wv[i] == tag);
+            if (!ready && ++polls > spin_limit) {
+              timed_out = true;
+              break;
+            }
+          } while (!ready);
+#pragma unroll
+          for (int i = 0; i < 8; ++i)
+            sum += (s0 + i < S) ? __uint_as_float((uint32_t)(wv[i] >> 32)) : 0.f;
+        }
+        vs[lane] = sum;
+      }
+      lds_barrier();               // (e) vs filled
+      if (G > 1) lds_barrier();    // (g) ex filled
+    }
+    if (timed_out)
+      __hip_atomic_store((unsigned*)(header + kEpochCounters), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (lane == 0) leave_launch(header, n_workgroups);
+    SGMV_TRACE_POINT(7);
+    SGMV_TRACE_FLUSH(lane == 0, 4, 7);
+    return;
+  }
+
+  // ================================================================ stream waves
+  const int cpr = klen >> 3;                          // 128-bit chunks in one x row slice
+  const int cg = tid / CPW, cc = tid - cg * CPW;      // lane group, chunk within the column slice
+  const uint32_t b_row0 = (uint32_t)(cg * JL) * (uint32_t)h_out * 2u;
+  const uint32_t row_bytes_out = (uint32_t)h_out * 2u;
+  const bool col_active = cc * 8 < ncols;
+
+  struct Regs {
+    uint4 xr, yq;
+    uint4 a[U];
+    uint4 b[JL];
+  };
+  // all loads of one item, back to back: x, the A slice, then the B slice and y
+  auto issue_at = [&](Regs& r, int row, const uint16_t* xp, const uint16_t* yp, const uint16_t* A,
+                      const uint16_t* B) {
+    const __amdgpu_buffer_rsrc_t rX = make_buffer(xp + (long long)row * h_in + k0, (uint32_t)klen * 2u);
+    const __amdgpu_buffer_rsrc_t rA = make_buffer(A + offA + (long long)k0 * R, (uint32_t)nchunks * 16u);
+    const __amdgpu_buffer_rsrc_t rB = make_buffer(
+        B + offB + col_lo, ncols > 0 ? (uint32_t)((long long)(R - 1) * h_out + ncols) * 2u : 0u);
+    const __amdgpu_buffer_rsrc_t rY = make_buffer(yp + (long long)row * h_out + col_lo, (uint32_t)ncols * 2u);
+    r.xr = buffer_load128(rX, tid < cpr ? (uint32_t)tid * 16u : kOutOfRange);
+#pragma unroll
+    for (int u = 0; u < U; ++u) r.a[u] = buffer_load128(rA, (uint32_t)(u * NT + tid) * 16u);
+    __builtin_amdgcn_sched_barrier(0);  // keep x and A ahead of B and y in the memory pipe
+#pragma unroll
+    for (int j = 0; j < JL; ++j)
+      r.b[j] = buffer_load128(rB, col_active ? b_row0 + (uint32_t)j * row_bytes_out + (uint32_t)cc * 16u : kOutOfRange);
+    r.yq = buffer_load128(rY, (cg == 0 && col_active) ? (uint32_t)cc * 16u : kOutOfRange);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto issue = [&](Regs& r, const Item& it) {
+    const int pp = item_p(it);
+    issue_at(r, it.row, reinterpret_cast<const uint16_t*>(uniform64(ptr_x[pp])),
+             reinterpret_cast<const uint16_t*>(uniform64(ptr_y[pp])),
+             reinterpret_cast<const uint16_t*>(uniform64(ptr_a[pp])),
+             reinterpret_cast<const uint16_t*>(uniform64(ptr_b[pp])));
+  };
+  // shrink, hand-off, expand of one item (the arithmetic of the single add-on kernel)
+  auto process = [&](const Regs& r, const Item& it) {
+    SGMV_TRACE_POINT(9);
+    store128(&xs[tid * 8], r.xr);  // chunks that do not exist arrive as zeros
+    lds_barrier();                 // (b) xs filled
+    SGMV_TRACE_POINT(2);
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int q = u * NT + tid;
+      const int kk = (q / LPR) & (kMaxKSlice - 1);
+      float af[8];
+      unpack8<DT>(r.a[u], af);
+      const float xraw = decode1<DT>(xs[kk]);
+      const float xv = (q < nchunks) ? xraw : 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = fmaf(xv, af[e], acc[e]);
+    }
+    {
+      int e;
+      const float d = multi_reduce_lanes8<LPR>(acc, lane, e);
+      if (lane < R) red[wave][(lane % LPR) * 8 + e] = d;
+    }
+    SGMV_TRACE_POINT(3);
+    lds_barrier();  // (c) red filled
+    lds_barrier();  // (e) vs filled
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+#pragma unroll
+    for (int j = 0; j < JL; ++j) {
+      float bf[8];
+      unpack8<DT>(r.b[j], bf);
+      const float vj = vs[cg * JL + j];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = fmaf(vj, bf[e], acc[e]);
+    }
+    if (G > 1) {
+      if (cg > 0) {
+        float* dst = &ex[((cg - 1) * CPW + cc) * 8];
+        *reinterpret_cast<float4*>(dst) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        *reinterpret_cast<float4*>(dst + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+      }
+      lds_barrier();  // (g) ex filled
+      if (cg == 0) {
+#pragma unroll
+        for (int g = 1; g < G; ++g) {
+          const float* srcp = &ex[((g - 1) * CPW + cc) * 8];
+          const float4 p0 = *reinterpret_cast<const float4*>(srcp);
+          const float4 p1 = *reinterpret_cast<const float4*>(srcp + 4);
+          acc[0] += p0.x; acc[1] += p0.y; acc[2] += p0.z; acc[3] += p0.w;
+          acc[4] += p1.x; acc[5] += p1.y; acc[6] += p1.z; acc[7] += p1.w;
+        }
+      }
+    }
+    if (cg == 0) {
+      uint16_t* yp = reinterpret_cast<uint16_t*>(uniform64(ptr_y[item_p(it)]));
+      const __amdgpu_buffer_rsrc_t rY = make_buffer(yp + (long long)it.row * h_out + col_lo, (uint32_t)ncols * 2u);
+      float yf[8];
+      unpack8<DT>(r.yq, yf);
+      uint4 out;
+      out.x = pack2<DT>(yf[0] + scale * acc[0], yf[1] + scale * acc[1]);
+      out.y = pack2<DT>(yf[2] + scale * acc[2], yf[3] + scale * acc[3]);
+      out.z = pack2<DT>(yf[4] + scale * acc[4], yf[5] + scale * acc[5]);
+      out.w = pack2<DT>(yf[6] + scale * acc[6], yf[7] + scale * acc[7]);
+      buffer_store128(rY, col_active ? (uint32_t)cc * 16u : kOutOfRange, out);
+    }
+  };
+
+  Regs r0, r1;
+  if (first_ok) issue_at(r0, lo, x_first, y_first, a_first, b_first);
+  SGMV_TRACE_POINT(8);
+  lds_barrier();  // (p) pointers staged
+  SGMV_TRACE_POINT(1);
+  const uint32_t all = __builtin_amdgcn_readfirstlane(mine);
+  auto valid = [&](const Item& it) { return all != 0u && it.row < hi; };
+  auto next = [&](Item it) {
+    it.left &= it.left - 1u;
+    if (it.left == 0u) {
+      it.left = all;
+      ++it.row;
+    }
+    return it;
+  };
+  Item cur;
+  cur.row = lo;
+  cur.left = all;
+  // (if the first projection has both pointers it is the first item, already issued)
+  if (valid(cur) && !first_ok) issue(r0, cur);
+  while (valid(cur)) {
+    const Item nxt = next(cur);
+    if (valid(nxt)) issue(r1, nxt);
+    process(r0, cur);
+    if (!valid(nxt)) break;
+    cur = next(nxt);
+    if (valid(cur)) issue(r0, cur);
+    process(r1, nxt);
+  }
+  SGMV_TRACE_POINT(6);
+  SGMV_TRACE_FLUSH(tid == 0, 0, 3);
+  SGMV_TRACE_FLUSH(tid == 0, 6, 6);
+  SGMV_TRACE_FLUSH(tid == 0, 8, 9);
+}
+
+template <class DT, int R, int G>
+static hipError_t launch_multi_t(const FusedArgs& a, hipStream_t st) {
+  hipLaunchKernelGGL((add_lora_fused_multi_kernel<DT, R, G>),
+                     dim3((unsigned)a.S, (unsigned)a.n_segs, (unsigned)a.Z), dim3(320), 0, st, a.seg_starts,
+                     a.kslice, a.cslice, a.h_in, a.h_out, a.n_tokens, a.S, a.n_proj, a.offA, a.offB, a.exch,
+                     a.header, a.scale, a.spin_limit, a.table);
+  return hipGetLastError();
+}
+
+template <class DT, int R>
+static hipError_t launch_multi_g(const FusedArgs& a, hipStream_t st) {
+  // at most eight weight rows per lane in the expand phase: two register sets must fit
+  switch (a.G) {
+    case 1: if constexpr (R <= 8) return launch_multi_t<DT, R, 1>(a, st); break;
+    case 2: if constexpr (R <= 16) return launch_multi_t<DT, R, 2>(a, st); break;
+    case 4: if constexpr (R <= 32) return launch_multi_t<DT, R, 4>(a, st); break;
+    case 8: return launch_multi_t<DT, R, 8>(a, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+template <class DT>
+static hipError_t launch_multi_r(const FusedArgs& a, hipStream_t st) {
+  switch (a.r) {
+    case 8: return launch_multi_g<DT, 8>(a, st);
+    case 16: return launch_multi_g<DT, 16>(a, st);
+    case 32: return launch_multi_g<DT, 32>(a, st);
+    case 64: return launch_multi_g<DT, 64>(a, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+// True when the launch shape fits the kernel: the A slice is one batch of loads and the
+// column slice one pass.
+bool fused_multi_fits(const FusedArgs& a) {
+  return (long long)a.kslice * (a.r / 8) <= 2048 && a.cslice / 8 <= 256 / a.G && a.r / a.G <= 8;
+}
+
+hipError_t launch_add_lora_fused_multi(const FusedArgs& a, hipStream_t st) {
+  if (!fused_multi_fits(a) || a.n_proj < 1 || a.n_proj > kMaxProjections || a.Z < 1) return hipErrorInvalidValue;
+  return a.bf16 ? launch_multi_r<BF16>(a, st) : launch_multi_r<F16>(a, st);
+}
+
+}  // namespace sgmv

@@ -79,6 +79,7 @@ struct FusedArgs {
   unsigned long long* exch;  // [S][n_tokens][r] words {value, generation tag}
   unsigned long long* header;// kEpochCounters epoch counters, then the error word
   int n_proj;                // 0: one add-on (x, y, A_ptrs, B_ptrs above); else `table` holds n_proj of them
+  int Z;                     // multi-projection launch: grid depth (projections z, z + Z, ... per workgroup)
   FusedTable table;
 };
 
@@ -106,6 +107,8 @@ struct TileArgs {
 size_t tile_lds_bytes(int r, int kslice, int cslice);
 hipError_t launch_add_lora_tile(const TileArgs& a, hipStream_t st);
 hipError_t launch_add_lora_fused(const FusedArgs& a, hipStream_t st);
+bool fused_multi_fits(const FusedArgs& a);
+hipError_t launch_add_lora_fused_multi(const FusedArgs& a, hipStream_t st);
 hipError_t launch_workspace_init(void* p, size_t bytes, size_t header_offset, hipStream_t st);
 hipError_t launch_shrink_vector(const ShrinkArgs& a, hipStream_t st);
 hipError_t launch_shrink_reduce(float* v, const ShrinkArgs& a, hipStream_t st);
