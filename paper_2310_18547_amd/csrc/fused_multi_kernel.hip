@@ -13,13 +13,20 @@
 //
 // Work split: grid = (S, n_segs, Z).  Workgroup (s, seg, z) serves k-slice s /
 // column-slice s of segment seg for the projections z, z + Z, z + 2 Z, ...
-// (Z = n_proj: one projection per workgroup, all in parallel, for small
-// batches; Z = 1: one workgroup per (slice, segment) walks all projections).
+// (the host launches Z = 1: one workgroup per (slice, segment) walks all
+// projections; launches small enough for all workgroups to be resident side by
+// side take the plain kernel in fused_kernel.hip with one projection each).
 // Its work items are (row of the segment, projection); an item is exactly the
-// work of one workgroup of the single add-on kernel (fused_kernel.hip), with
-// the same arithmetic in the same order, so every result is bit-identical to a
-// separate call.  Two register sets alternate: item i+1's x, A slice, B slice
-// and y loads are issued before item i is processed.
+// work of one workgroup of the single add-on kernel, with the same arithmetic in
+// the same order, so every result is bit-identical to a separate call.
+//
+// Software pipeline.  The shrink of item i+1 runs BEFORE the expand of item i:
+// item i+1's partial sums are published before item i's are collected, so the
+// other workgroups' sums of item i have had a whole step to arrive and the poll
+// for them normally succeeds at once.  Two register sets for the shrink operands
+// (x, A slice) and two for the expand operands (B slice, y) alternate; a set is
+// refilled with the loads of the item two steps ahead as soon as the step that
+// read it is done, so about one item's worth of loads is always in flight.
 //
 // The per-projection pointers (x, y and the segment's A / B pointers) are put
 // into LDS once at the start, so that stepping to the next item costs no
@@ -169,25 +176,36 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
     bool timed_out = false;
     SGMV_TRACE_POINT(4);
     const uint32_t all = __builtin_amdgcn_readfirstlane(mine);
-    for (int row = lo; row < hi && all != 0u; ++row)
-    for (uint32_t left = all; left != 0u; left &= left - 1u) {
-      const int pp = __builtin_ctz(left);
-      unsigned long long* ex_p = exch + (long long)pp * S * stride + (long long)row * R;
+    auto valid = [&](const Item& it) { return all != 0u && it.row < hi; };
+    auto next = [&](Item it) {
+      it.left &= it.left - 1u;
+      if (it.left == 0u) {
+        it.left = all;
+        ++it.row;
+      }
+      return it;
+    };
+    auto words = [&](const Item& it) {
+      return exch + (long long)item_p(it) * S * stride + (long long)it.row * R;
+    };
+    // add the four waves' shrink sums of an item and publish them
+    auto publish = [&](const Item& it) {
       lds_barrier();  // (b) xs filled
-      SGMV_TRACE_POINT(5);
       lds_barrier();  // (c) red filled
       if (lane < R) {
         float sum = red[0][lane];
 #pragma unroll
         for (int w = 1; w < NW; ++w) sum += red[w][lane];
         const unsigned long long word = ((unsigned long long)__float_as_uint(sum) << 32) | tag;
-        __hip_atomic_store(ex_p + (long long)s * stride + lane, word, __ATOMIC_RELAXED,
+        __hip_atomic_store(words(it) + (long long)s * stride + lane, word, __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
       }
-      // collect all S slices, ascending (only the R lanes that own an element poll:
-      // idle lanes polling the same words would multiply the traffic on them)
+    };
+    // collect all S slices of an item, ascending (only the R lanes that own an element poll:
+    // idle lanes polling the same words would multiply the traffic on them)
+    auto collect = [&](const Item& it) {
       if (lane < R) {
-        const unsigned long long* src = ex_p + lane;
+        const unsigned long long* src = words(it) + lane;
         float sum = 0.f;
         for (int s0 = 0; s0 < S; s0 += 8) {
           unsigned long long wv[8];
@@ -214,6 +232,24 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
       }
       lds_barrier();               // (e) vs filled
       if (G > 1) lds_barrier();    // (g) ex filled
+    };
+    // the shrink runs one item ahead of the expand: item i+1 is published before item i is
+    // collected, so the other workgroups' sums of item i have had a whole step to arrive
+    Item it_e;
+    it_e.row = lo;
+    it_e.left = all;
+    Item it_s = it_e;
+    if (valid(it_s)) {
+      publish(it_s);
+      it_s = next(it_s);
+    }
+    while (valid(it_e)) {
+      if (valid(it_s)) {
+        publish(it_s);
+        it_s = next(it_s);
+      }
+      collect(it_e);
+      it_e = next(it_e);
     }
     if (timed_out)
       __hip_atomic_store((unsigned*)(header + kEpochCounters), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -230,38 +266,44 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
   const uint32_t row_bytes_out = (uint32_t)h_out * 2u;
   const bool col_active = cc * 8 < ncols;
 
-  struct Regs {
-    uint4 xr, yq;
+  struct ARegs {  // what the shrink of an item reads
+    uint4 xr;
     uint4 a[U];
+  };
+  struct BRegs {  // what the expand of an item reads
+    uint4 yq;
     uint4 b[JL];
   };
-  // all loads of one item, back to back: x, the A slice, then the B slice and y
-  auto issue_at = [&](Regs& r, int row, const uint16_t* xp, const uint16_t* yp, const uint16_t* A,
-                      const uint16_t* B) {
+  auto issue_a_at = [&](ARegs& r, int row, const uint16_t* xp, const uint16_t* A) {
     const __amdgpu_buffer_rsrc_t rX = make_buffer(xp + (long long)row * h_in + k0, (uint32_t)klen * 2u);
     const __amdgpu_buffer_rsrc_t rA = make_buffer(A + offA + (long long)k0 * R, (uint32_t)nchunks * 16u);
-    const __amdgpu_buffer_rsrc_t rB = make_buffer(
-        B + offB + col_lo, ncols > 0 ? (uint32_t)((long long)(R - 1) * h_out + ncols) * 2u : 0u);
-    const __amdgpu_buffer_rsrc_t rY = make_buffer(yp + (long long)row * h_out + col_lo, (uint32_t)ncols * 2u);
     r.xr = buffer_load128(rX, tid < cpr ? (uint32_t)tid * 16u : kOutOfRange);
 #pragma unroll
     for (int u = 0; u < U; ++u) r.a[u] = buffer_load128(rA, (uint32_t)(u * NT + tid) * 16u);
-    __builtin_amdgcn_sched_barrier(0);  // keep x and A ahead of B and y in the memory pipe
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto issue_b_at = [&](BRegs& r, int row, const uint16_t* yp, const uint16_t* B) {
+    const __amdgpu_buffer_rsrc_t rB = make_buffer(
+        B + offB + col_lo, ncols > 0 ? (uint32_t)((long long)(R - 1) * h_out + ncols) * 2u : 0u);
+    const __amdgpu_buffer_rsrc_t rY = make_buffer(yp + (long long)row * h_out + col_lo, (uint32_t)ncols * 2u);
 #pragma unroll
     for (int j = 0; j < JL; ++j)
       r.b[j] = buffer_load128(rB, col_active ? b_row0 + (uint32_t)j * row_bytes_out + (uint32_t)cc * 16u : kOutOfRange);
     r.yq = buffer_load128(rY, (cg == 0 && col_active) ? (uint32_t)cc * 16u : kOutOfRange);
     __builtin_amdgcn_sched_barrier(0);
   };
-  auto issue = [&](Regs& r, const Item& it) {
+  auto issue_a = [&](ARegs& r, const Item& it) {
     const int pp = item_p(it);
-    issue_at(r, it.row, reinterpret_cast<const uint16_t*>(uniform64(ptr_x[pp])),
-             reinterpret_cast<const uint16_t*>(uniform64(ptr_y[pp])),
-             reinterpret_cast<const uint16_t*>(uniform64(ptr_a[pp])),
-             reinterpret_cast<const uint16_t*>(uniform64(ptr_b[pp])));
+    issue_a_at(r, it.row, reinterpret_cast<const uint16_t*>(uniform64(ptr_x[pp])),
+               reinterpret_cast<const uint16_t*>(uniform64(ptr_a[pp])));
   };
-  // shrink, hand-off, expand of one item (the arithmetic of the single add-on kernel)
-  auto process = [&](const Regs& r, const Item& it) {
+  auto issue_b = [&](BRegs& r, const Item& it) {
+    const int pp = item_p(it);
+    issue_b_at(r, it.row, reinterpret_cast<const uint16_t*>(uniform64(ptr_y[pp])),
+               reinterpret_cast<const uint16_t*>(uniform64(ptr_b[pp])));
+  };
+  // shrink and expand of one item (the arithmetic of the single add-on kernel)
+  auto shrink = [&](const ARegs& r) {
     SGMV_TRACE_POINT(9);
     store128(&xs[tid * 8], r.xr);  // chunks that do not exist arrive as zeros
     lds_barrier();                 // (b) xs filled
@@ -287,7 +329,10 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
     }
     SGMV_TRACE_POINT(3);
     lds_barrier();  // (c) red filled
+  };
+  auto expand = [&](const BRegs& r, const Item& it) {
     lds_barrier();  // (e) vs filled
+    float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
 #pragma unroll
@@ -330,8 +375,12 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
     }
   };
 
-  Regs r0, r1;
-  if (first_ok) issue_at(r0, lo, x_first, y_first, a_first, b_first);
+  ARegs a0, a1;
+  BRegs b0, b1;
+  if (first_ok) {
+    issue_a_at(a0, lo, x_first, a_first);
+    issue_b_at(b0, lo, y_first, b_first);
+  }
   SGMV_TRACE_POINT(8);
   lds_barrier();  // (p) pointers staged
   SGMV_TRACE_POINT(1);
@@ -345,19 +394,55 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
     }
     return it;
   };
-  Item cur;
-  cur.row = lo;
-  cur.left = all;
-  // (if the first projection has both pointers it is the first item, already issued)
-  if (valid(cur) && !first_ok) issue(r0, cur);
-  while (valid(cur)) {
-    const Item nxt = next(cur);
-    if (valid(nxt)) issue(r1, nxt);
-    process(r0, cur);
-    if (!valid(nxt)) break;
-    cur = next(nxt);
-    if (valid(cur)) issue(r0, cur);
-    process(r1, nxt);
+  // Four cursors over the same item sequence: the next item to expand, to shrink (one
+  // ahead), and to fetch the shrink / expand operands of (two ahead of their use).  A
+  // register set is refilled as soon as the step that read it is done.
+  Item it_e;
+  it_e.row = lo;
+  it_e.left = all;
+  Item it_s = it_e, it_a = it_e, it_b = it_e;
+  if (valid(it_e)) {
+    // (if the first projection has both pointers it is the first item, already issued)
+    if (!first_ok) {
+      issue_a(a0, it_a);
+      issue_b(b0, it_b);
+    }
+    it_a = next(it_a);
+    it_b = next(it_b);
+    if (valid(it_a)) {
+      issue_a(a1, it_a);
+      it_a = next(it_a);
+      issue_b(b1, it_b);
+      it_b = next(it_b);
+    }
+    shrink(a0);
+    it_s = next(it_s);
+    if (valid(it_a)) {
+      issue_a(a0, it_a);
+      it_a = next(it_a);
+    }
+  }
+  // one step: shrink the item after the one that is expanded, refill what was read
+  auto step = [&](ARegs& a_sh, BRegs& b_ex) {
+    if (valid(it_s)) {
+      shrink(a_sh);
+      it_s = next(it_s);
+      if (valid(it_a)) {
+        issue_a(a_sh, it_a);
+        it_a = next(it_a);
+      }
+    }
+    expand(b_ex, it_e);
+    it_e = next(it_e);
+    if (valid(it_b)) {
+      issue_b(b_ex, it_b);
+      it_b = next(it_b);
+    }
+  };
+  while (valid(it_e)) {
+    step(a1, b0);
+    if (!valid(it_e)) break;
+    step(a0, b1);
   }
   SGMV_TRACE_POINT(6);
   SGMV_TRACE_FLUSH(tid == 0, 0, 3);
