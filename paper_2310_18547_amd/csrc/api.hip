@@ -155,6 +155,10 @@ bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f) {
   if (s < need) s = need;
   if (s < 1) s = 1;
   if ((long long)s * n_segs > kFusedMaxWorkgroups) return false;
+  // slices forced by a very wide input can outnumber the compute units several times over;
+  // from about two rounds of workgroups on the launch-per-step kernels are faster (measured)
+  if (p->path == SGMV_PATH_AUTO && p->ksplit == 0 && (long long)s * n_segs > 2 * kFusedWorkgroups)
+    return false;
   f->S = s;
   f->kslice = ceil_div(ceil_div(p->h_in, s), 8) * 8;
   f->cslice = ceil_div(ceil_div(p->h_out, s), 8) * 8;
