@@ -19,7 +19,7 @@ constexpr int kFusedWorkgroups = 256;  // one workgroup per compute unit
 constexpr int kFusedMaxWorkgroups = 1024;
 constexpr int kMultiWorkgroups = 512;  // workgroups of a multi-projection launch that run side by side (two per compute unit)
 constexpr int kFusedSpinLimit = 1 << 18;
-constexpr int kMatrixMinSegLen = 17;   // AUTO uses the MFMA kernels from this segment length on
+constexpr int kMatrixMinSegLen = 4;    // AUTO uses the MFMA kernels from this segment length on (measured crossover)
 constexpr int kMatrixWorkgroups = 448; // workgroups the MFMA shrink aims for
 
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -70,7 +70,9 @@ bool choose_split(const sgmv_problem* p, int n_segs, int* ksplit, int* kslice) {
   const int cap = split_cap(p->n_tokens);
   const int need = ceil_div(p->h_in, kMaxKSlice);
   if (need > cap) return false;
-  int s = p->ksplit > 0 ? p->ksplit : ceil_div(kTargetWorkgroups, n_segs);
+  // slices of about 1024 input features: measured best for 1 to 64 segments (more slices
+  // only lengthen the reduction that follows)
+  int s = p->ksplit > 0 ? p->ksplit : ceil_div(p->h_in, 1024);
   const int most = p->h_in / 64 > 0 ? p->h_in / 64 : 1;  // keep slices >= 64 elements
   if (s > most) s = most;
   if (s > cap) s = cap;

@@ -42,7 +42,8 @@ namespace sgmv {
 constexpr int kShrinkRows = 64;    // rows per shrink workgroup (four 16-row tiles)
 constexpr int kShrinkChunk = 256;  // k per LDS stage
 constexpr int kExpandCols = 256;   // columns per expand workgroup (64 per wave)
-constexpr int kExpandRows = 128;   // rows per expand workgroup pass
+constexpr int kExpandRows = 64;    // rows per expand workgroup pass (more, smaller workgroups measured faster)
+constexpr int kExpandTiles = 2;    // 16-row tiles a wave keeps in flight (deeper measured no faster)
 
 // ---------------------------------------------------------------- shrink
 //
@@ -385,15 +386,20 @@ __global__ __launch_bounds__(256) void expand_matrix_kernel(
       buffer_store128(rY, (ok && c_ok1) ? yoff + 64u : kOutOfRange, out1);
     };
 
-    // two row tiles in flight: the next tile's loads are issued before this one is finished
-    Tile cur, nxt;
-    fetch(0, cur);
-    for (int r0 = 0; r0 < nrows; r0 += 32) {
-      if (r0 + 16 < nrows) fetch(r0 + 16, nxt);
-      finish(r0, cur);
-      if (r0 + 16 < nrows) {
-        if (r0 + 32 < nrows) fetch(r0 + 32, cur);
-        finish(r0 + 16, nxt);
+    // kExpandTiles row tiles in flight: a tile's registers are refilled with the loads of the
+    // tile kExpandTiles further on as soon as it is finished
+    Tile tl[kExpandTiles];
+#pragma unroll
+    for (int i = 0; i < kExpandTiles; ++i)
+      if (i * 16 < nrows) fetch(i * 16, tl[i]);
+    for (int r0 = 0; r0 < nrows; r0 += 16 * kExpandTiles) {
+#pragma unroll
+      for (int i = 0; i < kExpandTiles; ++i) {
+        const int r = r0 + 16 * i;
+        if (r < nrows) {
+          finish(r, tl[i]);
+          if (r + 16 * kExpandTiles < nrows) fetch(r + 16 * kExpandTiles, tl[i]);
+        }
       }
     }
   }
