@@ -80,6 +80,50 @@ def cpu_baseline(w, budget_s: float):
                       f"fp32 accumulation, rows split over {cores} threads"}
 
 
+def time_comparators(d, w, stream, L, S, steps=200):
+    """Loop and Gather-BMM (library GEMMs through PyTorch) on the same device tensors:
+    microseconds per add-on, eager launches and, where capture works, a replayed HIP graph."""
+    import numpy as np
+    import torch
+    from paper_2310_18547_amd.comparators import Comparators
+    c = Comparators(d)
+    res = {"note": "PyTorch ops (rocBLAS / hipBLASLt), same GPU and inputs; 16-bit intermediate"}
+    for name, fn in (("loop", c.loop), ("gather_bmm", c.gather_bmm)):
+        with torch.cuda.stream(stream):
+            for i in range(5):
+                fn(i % L, i % S)
+            stream.synchronize()
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for i in range(steps):
+                fn(i % L, i % S)
+            e1.record(stream)
+            e1.synchronize()
+            res[name + "_eager_us"] = e0.elapsed_time(e1) / steps * 1e3
+            try:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    for i in range(steps):
+                        fn(i % L, i % S)
+                g.replay()
+                stream.synchronize()
+                ts = []
+                for _ in range(3):
+                    e0.record(stream)
+                    g.replay()
+                    e1.record(stream)
+                    e1.synchronize()
+                    ts.append(e0.elapsed_time(e1) / steps * 1e3)
+                res[name + "_graph_us"] = float(np.median(ts))
+            except Exception as exc:  # capture of library calls is not guaranteed
+                res[name + "_graph_us"] = None
+                res[name + "_graph_error"] = str(exc)[:120]
+                torch.cuda.synchronize()
+    d.reset_y()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -101,6 +145,9 @@ def main():
     ap.add_argument("--projections", type=int, default=1,
                     help="add-ons of the same shape per step through sgmv_add_lora_multi (q/k/v = 3); "
                          "1 = the headline metric, one sgmv_add_lora call per step")
+    ap.add_argument("--compare", action="store_true",
+                    help="also time the paper's two comparison implementations (Loop and Gather-BMM, "
+                         "PyTorch library ops) on the same inputs; reported under 'comparators'")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per launch measured with rocprofv3 --pmc (reported as "
                          "roofline.traffic)")
@@ -222,6 +269,8 @@ def main():
         "paper_a100_us": PAPER_A100_US.get(args.workload),
         "block_ms": times,
     }
+    if args.compare:
+        out["comparators"] = time_comparators(d, w, stream, L, S)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds)
     print(json.dumps(out), flush=True)

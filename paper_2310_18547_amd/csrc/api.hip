@@ -24,7 +24,7 @@ constexpr int kMatrixWorkgroups = 448; // workgroups the MFMA shrink aims for
 
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 // Most split-K slices the workspace is sized for at a given batch.
@@ -70,9 +70,14 @@ bool choose_split(const sgmv_problem* p, int n_segs, int* ksplit, int* kslice) {
   const int cap = split_cap(p->n_tokens);
   const int need = ceil_div(p->h_in, kMaxKSlice);
   if (need > cap) return false;
-  // slices of about 1024 input features: measured best for 1 to 64 segments (more slices
-  // only lengthen the reduction that follows)
-  int s = p->ksplit > 0 ? p->ksplit : ceil_div(p->h_in, 1024);
+  // enough workgroups to fill the chip, but slices of at least 32 KiB of weights: more
+  // slices than that only lengthen the reduction that follows (measured, 1 to 64 segments)
+  int s = p->ksplit;
+  if (s == 0) {
+    s = ceil_div(kTargetWorkgroups, n_segs);
+    const int by_size = ceil_div((long long)p->h_in * p->r, 16384);
+    if (s > by_size) s = by_size;
+  }
   const int most = p->h_in / 64 > 0 ? p->h_in / 64 : 1;  // keep slices >= 64 elements
   if (s > most) s = most;
   if (s > cap) s = cap;

@@ -507,6 +507,21 @@ def test_add_lora_multi_rejects_bad_arguments():
     assert B.sgmv_add_lora_multi(d0.problem, nine, nine, nine, nine, d0.seg_starts, 4, 0, 1.0, check=False) == 2
 
 
+# ------------------------------------ the paper's comparison implementations (library ops)
+@pytest.mark.parametrize("which", ["loop", "gather_bmm"])
+def test_comparators_match_oracle(which):
+    # Loop and Gather-BMM are bench comparators (PyTorch GEMMs, 16-bit intermediate): they
+    # must compute the same add-on, to a tolerance widened for the rounded intermediate
+    from paper_2310_18547_amd.comparators import Comparators
+    w = wl.custom([1, 3, 2, 0, 5, 1], 512, 384, 16, "f16", seed=77, num_layers=2, seg_adapter=[0, 1, 2, 3, 1, 4])
+    d = _dev(w)
+    c = Comparators(d)
+    getattr(c, which)(1)
+    got = decode64(d.y_bits(), "f16")
+    ref = decode64(oracle.run_workload(w, layer_idx=1), "f16")
+    assert np.all(np.abs(got - ref) <= 8e-3 + 2e-2 * np.abs(ref))
+
+
 # ------------------------------------------------------- MFMA (matrix) path
 def _matrix(w, **kw):
     from paper_2310_18547_amd import binding as B
