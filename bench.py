@@ -228,14 +228,16 @@ def main():
 
     T, n = w.n_tokens, w.n_distinct
     bytes_step = P * acc.algorithmic_bytes("add_lora", T, n, w.h_in, w.h_out, w.r)
-    single = w.max_seg_len == 1 and args.path in (0, 3)
-    tiled = 1 < w.max_seg_len <= 64 and args.path in (0, 3)
-    if single:
-        kernel, launches = ("add_lora_fused_multi_kernel" if P > 1 else "add_lora_fused_kernel"), 1
-    elif tiled:
-        kernel, launches = "add_lora_tile_kernel", P
-    else:
-        kernel, launches = "shrink / finalize_v / expand kernels of one sgmv_add_lora step", 3 * P
+    # which kernels the library launched for this call: asked of the library, not re-derived
+    from paper_2310_18547_amd import binding as B
+    plan = B.sgmv_plan_add_lora(d.problem, w.n_segs, P)
+    kernel = {B.KERNEL_FUSED: "add_lora_fused_kernel", B.KERNEL_TILE: "add_lora_tile_kernel",
+              B.KERNEL_MULTI_SIDE: "add_lora_fused_side_kernel",
+              B.KERNEL_MULTI_PIPELINED: "add_lora_fused_multi_kernel",
+              B.KERNEL_VECTOR: "shrink_vector_kernel + expand_vector_kernel",
+              B.KERNEL_MATRIX: "shrink_matrix_kernel + finalize_v_kernel + expand_matrix_kernel",
+              }[plan.kernel]
+    launches = plan.launches
     traffic = args.traffic_bytes
     if traffic is None and P == 1 and args.path == 0 and args.ksplit == 0:
         traffic = MEASURED_TRAFFIC.get(args.workload)
@@ -264,6 +266,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": gbs / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": kernel, "launches_per_step": launches,
+                     "slices_per_segment": plan.slices, "workgroups": plan.workgroups,
                      "algorithmic_bytes_per_step": bytes_step,
                      "avg_step_us": us},
         "paper_a100_us": PAPER_A100_US.get(args.workload),

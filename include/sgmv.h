@@ -112,6 +112,28 @@ typedef struct sgmv_problem {
   size_t  workspace_bytes;   /*   sgmv_workspace_bytes(n_tokens, r) bytes           */
 } sgmv_problem;
 
+/* Kernel family a call resolves to (sgmv_plan_add_lora). */
+typedef enum {
+  SGMV_KERNEL_NONE = 0,             /* nothing to launch (no segments or no rows)          */
+  SGMV_KERNEL_FUSED = 1,            /* single launch, one row per segment, vector ALUs     */
+  SGMV_KERNEL_TILE = 2,             /* single launch, sixteen-row MFMA tiles               */
+  SGMV_KERNEL_MULTI_SIDE = 3,       /* several projections side by side in one launch      */
+  SGMV_KERNEL_MULTI_PIPELINED = 4,  /* several projections walked by every workgroup       */
+  SGMV_KERNEL_VECTOR = 5,           /* one launch per step, vector ALUs                    */
+  SGMV_KERNEL_MATRIX = 6,           /* one launch per step, MFMA (long segments)           */
+  SGMV_KERNEL_SEQUENCE = 7          /* internal: multi-projection call run as single calls */
+} sgmv_kernel;
+
+/* What a call would launch: plain data filled by sgmv_plan_add_lora. */
+typedef struct sgmv_plan {
+  int32_t kernel;      /* sgmv_kernel of every add-on                                      */
+  int32_t launches;    /* kernel launches of the whole call                                */
+  int32_t slices;      /* workgroups per segment (single-launch kernels) or split-K factor */
+  int32_t workgroups;  /* workgroups of the (first) launch; 0 where it depends on lengths  */
+  int32_t lds_bytes;   /* dynamic LDS per workgroup (tile kernel), else 0                  */
+  int32_t reserved[3];
+} sgmv_plan;
+
 /* Text for a status code (static storage; never NULL). */
 const char* sgmv_status_string(int status);
 
@@ -199,6 +221,14 @@ int sgmv_add_lora_multi(const sgmv_problem* p, int32_t n_proj, void* const* ys,
                         const void* const* xs, const void* const* const* A_ptrs,
                         const void* const* const* B_ptrs, const int32_t* seg_starts,
                         int32_t n_segs, int32_t layer_idx, float scale, void* stream);
+
+/* Host-only, pure: which kernels sgmv_add_lora (n_proj == 1) or sgmv_add_lora_multi
+ * (n_proj > 1) would launch for this descriptor, number of segments and number of
+ * projections -- the same decision code the entry points run.  For benchmarks, logs and
+ * tests of the launch policy; touches no device memory (the workspace pointer and size are
+ * only checked as the entry points check them).  Returns the status the call itself would
+ * return for these arguments. */
+int sgmv_plan_add_lora(const sgmv_problem* p, int32_t n_segs, int32_t n_proj, sgmv_plan* plan);
 
 #ifdef __cplusplus
 }

@@ -47,6 +47,25 @@ def library_path() -> str:
     return _LIB_PATH
 
 
+class SgmvPlan(ctypes.Structure):
+    """Mirror of ``struct sgmv_plan``."""
+    _fields_ = [
+        ("kernel", ctypes.c_int32),
+        ("launches", ctypes.c_int32),
+        ("slices", ctypes.c_int32),
+        ("workgroups", ctypes.c_int32),
+        ("lds_bytes", ctypes.c_int32),
+        ("reserved", ctypes.c_int32 * 3),
+    ]
+
+
+KERNEL_NONE, KERNEL_FUSED, KERNEL_TILE, KERNEL_MULTI_SIDE, KERNEL_MULTI_PIPELINED, KERNEL_VECTOR, \
+    KERNEL_MATRIX, KERNEL_SEQUENCE = range(8)
+KERNEL_NAMES = {KERNEL_NONE: "none", KERNEL_FUSED: "fused", KERNEL_TILE: "tile",
+                KERNEL_MULTI_SIDE: "multi_side", KERNEL_MULTI_PIPELINED: "multi_pipelined",
+                KERNEL_VECTOR: "vector", KERNEL_MATRIX: "matrix"}
+
+
 def _load():
     if not os.path.exists(_LIB_PATH):
         raise ImportError(
@@ -77,6 +96,8 @@ def _load():
     L.sgmv_add_lora_multi.argtypes = [P, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
                                       c.c_void_p, c.c_int32, c.c_int32, c.c_float, c.c_void_p]
     L.sgmv_add_lora_multi.restype = c.c_int
+    L.sgmv_plan_add_lora.argtypes = [P, c.c_int32, c.c_int32, c.POINTER(SgmvPlan)]
+    L.sgmv_plan_add_lora.restype = c.c_int
     return L
 
 
@@ -171,3 +192,14 @@ def sgmv_add_lora_multi(p: SgmvProblem, ys, xs, A_ptrs, B_ptrs, seg_starts, n_se
     if check and rc != 0:
         raise SgmvError(rc, "sgmv_add_lora_multi")
     return rc
+
+
+def sgmv_plan_add_lora(p: SgmvProblem, n_segs: int, n_proj: int = 1, check: bool = True):
+    """Host-only: the ``SgmvPlan`` of the call (``check=False``: ``(status, plan)``)."""
+    plan = SgmvPlan()
+    rc = lib.sgmv_plan_add_lora(ctypes.byref(p), n_segs, n_proj, ctypes.byref(plan))
+    if not check:
+        return rc, plan
+    if rc != 0:
+        raise SgmvError(rc, "sgmv_plan_add_lora")
+    return plan

@@ -279,6 +279,50 @@ ExpandArgs make_expand(const sgmv_problem* p, void* y, const float* v_parts, int
   return a;
 }
 
+// What sgmv_add_lora will launch for a checked problem: the single source of the path
+// choice, shared by the entry points and by sgmv_plan_add_lora.
+struct SinglePlan {
+  int kernel;        // sgmv_kernel
+  TileArgs tile;     // SGMV_KERNEL_TILE
+  FusedArgs fused;   // SGMV_KERNEL_FUSED
+  int ksplit, kslice;  // SGMV_KERNEL_MATRIX / SGMV_KERNEL_VECTOR
+};
+
+int plan_single(const sgmv_problem* p, int n_segs, SinglePlan* pl) {
+  if ((p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->max_seg_len != 1 &&
+      choose_tile(p, n_segs, &pl->tile)) {
+    pl->kernel = SGMV_KERNEL_TILE;
+    return SGMV_OK;
+  }
+  if (p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) {
+    if (choose_fused(p, n_segs, &pl->fused)) {
+      pl->kernel = SGMV_KERNEL_FUSED;
+      return SGMV_OK;
+    }
+    if (p->path == SGMV_PATH_FUSED) return SGMV_ERR_UNSUPPORTED;
+  }
+  if (use_matrix(p, n_segs)) {
+    choose_split_matrix(p, n_segs, &pl->ksplit, &pl->kslice);
+    pl->kernel = SGMV_KERNEL_MATRIX;
+    return SGMV_OK;
+  }
+  if (!choose_split(p, n_segs, &pl->ksplit, &pl->kslice)) return SGMV_ERR_UNSUPPORTED;
+  pl->kernel = SGMV_KERNEL_VECTOR;
+  return SGMV_OK;
+}
+
+// Multi-projection call: SGMV_KERNEL_MULTI_SIDE / _PIPELINED with the launch shape in *f, or
+// SGMV_KERNEL_SEQUENCE (one sgmv_add_lora after the other).
+int plan_multi(const sgmv_problem* p, int n_segs, int n_proj, FusedArgs* f) {
+  if ((p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->max_seg_len == 1 && n_proj > 1 &&
+      p->workspace != nullptr && choose_fused(p, n_segs, f) && f->S * n_proj <= split_cap(p->n_tokens)) {
+    f->r = p->r;
+    if ((long long)f->S * n_segs * n_proj <= kMultiWorkgroups) return SGMV_KERNEL_MULTI_SIDE;
+    if (fused_multi_fits(*f)) return SGMV_KERNEL_MULTI_PIPELINED;
+  }
+  return SGMV_KERNEL_SEQUENCE;
+}
+
 }  // namespace
 
 extern "C" {
@@ -395,9 +439,12 @@ int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x, const void* con
   if (rc != SGMV_OK) return rc;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if ((p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->max_seg_len != 1) {
-    TileArgs t;
-    if (choose_tile(p, n_segs, &t)) {
+  SinglePlan pl;
+  rc = plan_single(p, n_segs, &pl);
+  if (rc != SGMV_OK) return rc;
+  switch (pl.kernel) {
+    case SGMV_KERNEL_TILE: {
+      TileArgs& t = pl.tile;
       t.bf16 = p->dtype == SGMV_BF16;
       t.r = p->r;
       t.h_in = p->h_in;
@@ -415,39 +462,37 @@ int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x, const void* con
       t.exch = exchange_base(p->workspace, p->n_tokens, p->r);
       t.header = static_cast<unsigned long long*>(p->workspace);
       t.scale = scale;
-      if (launch_add_lora_tile(t, st) != hipSuccess) return SGMV_ERR_LAUNCH;
-      return SGMV_OK;
+      return launch_add_lora_tile(t, st) == hipSuccess ? SGMV_OK : SGMV_ERR_LAUNCH;
     }
-  }
-  if (p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) {
-    FusedArgs f;
-    if (choose_fused(p, n_segs, &f)) {
+    case SGMV_KERNEL_FUSED: {
+      FusedArgs& f = pl.fused;
       fill_fused(&f, p, seg_starts, n_segs, layer_idx, scale);
       f.y = y;
       f.x = x;
       f.A_ptrs = A_ptrs;
       f.B_ptrs = B_ptrs;
-      if (launch_add_lora_fused(f, st) != hipSuccess) return SGMV_ERR_LAUNCH;
-      return SGMV_OK;
+      return launch_add_lora_fused(f, st) == hipSuccess ? SGMV_OK : SGMV_ERR_LAUNCH;
     }
-    if (p->path == SGMV_PATH_FUSED) return SGMV_ERR_UNSUPPORTED;
+    case SGMV_KERNEL_MATRIX: {
+      ShrinkArgs sa = make_shrink(p, x, A_ptrs, seg_starts, n_segs, layer_idx);
+      sa.ksplit = pl.ksplit;
+      sa.kslice = pl.kslice;
+      if (launch_shrink_matrix(sa, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+      ExpandArgs e = make_expand(p, y, sa.partials, sa.ksplit, A_ptrs, B_ptrs, seg_starts, n_segs,
+                                 layer_idx, scale);
+      set_operands(&e, p->workspace, p->n_tokens, p->r);
+      return launch_expand_matrix(e, st) == hipSuccess ? SGMV_OK : SGMV_ERR_LAUNCH;
+    }
+    default: {
+      ShrinkArgs sa = make_shrink(p, x, A_ptrs, seg_starts, n_segs, layer_idx);
+      sa.ksplit = pl.ksplit;
+      sa.kslice = pl.kslice;
+      if (launch_shrink_vector(sa, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+      ExpandArgs e = make_expand(p, y, sa.partials, sa.ksplit, A_ptrs, B_ptrs, seg_starts, n_segs,
+                                 layer_idx, scale);
+      return launch_expand_vector(e, st) == hipSuccess ? SGMV_OK : SGMV_ERR_LAUNCH;
+    }
   }
-  ShrinkArgs s = make_shrink(p, x, A_ptrs, seg_starts, n_segs, layer_idx);
-  if (use_matrix(p, n_segs)) {
-    choose_split_matrix(p, n_segs, &s.ksplit, &s.kslice);
-    if (launch_shrink_matrix(s, st) != hipSuccess) return SGMV_ERR_LAUNCH;
-    ExpandArgs e = make_expand(p, y, s.partials, s.ksplit, A_ptrs, B_ptrs, seg_starts, n_segs,
-                               layer_idx, scale);
-    set_operands(&e, p->workspace, p->n_tokens, p->r);
-    if (launch_expand_matrix(e, st) != hipSuccess) return SGMV_ERR_LAUNCH;
-    return SGMV_OK;
-  }
-  if (!choose_split(p, n_segs, &s.ksplit, &s.kslice)) return SGMV_ERR_UNSUPPORTED;
-  if (launch_shrink_vector(s, st) != hipSuccess) return SGMV_ERR_LAUNCH;
-  ExpandArgs e = make_expand(p, y, s.partials, s.ksplit, A_ptrs, B_ptrs, seg_starts, n_segs,
-                             layer_idx, scale);
-  if (launch_expand_vector(e, st) != hipSuccess) return SGMV_ERR_LAUNCH;
-  return SGMV_OK;
 }
 
 int sgmv_add_lora_multi(const sgmv_problem* p, int32_t n_proj, void* const* ys,
@@ -470,33 +515,24 @@ int sgmv_add_lora_multi(const sgmv_problem* p, int32_t n_proj, void* const* ys,
   if (rc != SGMV_OK) return rc;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if ((p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->max_seg_len == 1 && n_proj > 1) {
-    FusedArgs f;
-    // every projection exchanges through its own S slices of the workspace
-    bool ok = choose_fused(p, n_segs, &f) && f.S * n_proj <= split_cap(p->n_tokens);
-    if (ok) {
-      fill_fused(&f, p, seg_starts, n_segs, layer_idx, scale);
-      ok = (long long)f.S * n_segs * n_proj <= kMultiWorkgroups || fused_multi_fits(f);
+  FusedArgs f;
+  const int kernel = plan_multi(p, n_segs, n_proj, &f);
+  if (kernel != SGMV_KERNEL_SEQUENCE) {
+    fill_fused(&f, p, seg_starts, n_segs, layer_idx, scale);
+    f.n_proj = n_proj;
+    for (int i = 0; i < kMaxProjections; ++i) {
+      f.table.x[i] = i < n_proj ? xs[i] : nullptr;
+      f.table.y[i] = i < n_proj ? ys[i] : nullptr;
+      f.table.A_ptrs[i] = i < n_proj ? A_ptrs[i] : nullptr;
+      f.table.B_ptrs[i] = i < n_proj ? B_ptrs[i] : nullptr;
     }
-    if (ok) {
-      f.n_proj = n_proj;
-      for (int i = 0; i < kMaxProjections; ++i) {
-        f.table.x[i] = i < n_proj ? xs[i] : nullptr;
-        f.table.y[i] = i < n_proj ? ys[i] : nullptr;
-        f.table.A_ptrs[i] = i < n_proj ? A_ptrs[i] : nullptr;
-        f.table.B_ptrs[i] = i < n_proj ? B_ptrs[i] : nullptr;
-      }
-      // side by side while every workgroup of the launch is resident (two fit a compute
-      // unit); beyond that one workgroup per (slice, segment) walks the projections in
-      // turn, the next one's loads in flight
-      if ((long long)f.S * n_segs * n_proj <= kMultiWorkgroups) {
-        if (launch_add_lora_fused(f, st) != hipSuccess) return SGMV_ERR_LAUNCH;
-        return SGMV_OK;
-      }
-      f.Z = 1;
-      if (launch_add_lora_fused_multi(f, st) != hipSuccess) return SGMV_ERR_LAUNCH;
-      return SGMV_OK;
-    }
+    // side by side while every workgroup of the launch is resident (two fit a compute
+    // unit); beyond that one workgroup per (slice, segment) walks the projections in
+    // turn, the next one's loads in flight
+    f.Z = 1;
+    const hipError_t err = kernel == SGMV_KERNEL_MULTI_SIDE ? launch_add_lora_fused(f, st)
+                                                            : launch_add_lora_fused_multi(f, st);
+    return err == hipSuccess ? SGMV_OK : SGMV_ERR_LAUNCH;
   }
   // any other shape: one add-on after the other
   for (int i = 0; i < n_proj; ++i) {
@@ -504,6 +540,57 @@ int sgmv_add_lora_multi(const sgmv_problem* p, int32_t n_proj, void* const* ys,
                        stream);
     if (rc != SGMV_OK) return rc;
   }
+  return SGMV_OK;
+}
+
+int sgmv_plan_add_lora(const sgmv_problem* p, int32_t n_segs, int32_t n_proj, sgmv_plan* plan) {
+  if (plan == nullptr) return SGMV_ERR_NULL;
+  *plan = sgmv_plan{};
+  static const int32_t no_segments[2] = {0, 0};  // only tested for being non-NULL
+  int rc = check_common(p, no_segments, n_segs, 0, true, true);
+  if (rc != SGMV_OK) return rc;
+  if (n_proj < 1 || n_proj > kMaxProjections) return SGMV_ERR_SHAPE;
+  if (n_segs == 0 || p->n_tokens == 0) return SGMV_OK;  // nothing is launched
+  rc = check_workspace(p);
+  if (rc != SGMV_OK) return rc;
+  if (n_proj > 1) {
+    FusedArgs f;
+    const int kernel = plan_multi(p, n_segs, n_proj, &f);
+    if (kernel != SGMV_KERNEL_SEQUENCE) {
+      plan->kernel = kernel;
+      plan->launches = 1;
+      plan->slices = f.S;
+      plan->workgroups = kernel == SGMV_KERNEL_MULTI_SIDE ? f.S * n_segs * n_proj : f.S * n_segs;
+      return SGMV_OK;
+    }
+  }
+  SinglePlan pl;
+  rc = plan_single(p, n_segs, &pl);
+  if (rc != SGMV_OK) return rc;
+  plan->kernel = pl.kernel;
+  switch (pl.kernel) {
+    case SGMV_KERNEL_TILE:
+      plan->launches = 1;
+      plan->slices = pl.tile.S;
+      plan->workgroups = pl.tile.S * n_segs * pl.tile.Z;
+      plan->lds_bytes = (int32_t)pl.tile.lds_bytes;
+      break;
+    case SGMV_KERNEL_FUSED:
+      plan->launches = 1;
+      plan->slices = pl.fused.S;
+      plan->workgroups = pl.fused.S * n_segs;
+      break;
+    case SGMV_KERNEL_MATRIX:
+      plan->launches = 3;  // shrink, operand preparation, expand
+      plan->slices = pl.ksplit;
+      break;
+    default:
+      plan->launches = 2;
+      plan->slices = pl.ksplit;
+      plan->workgroups = pl.ksplit * n_segs;
+      break;
+  }
+  plan->launches *= n_proj;  // a multi-projection call that is not batched runs them in turn
   return SGMV_OK;
 }
 

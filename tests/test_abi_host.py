@@ -143,3 +143,80 @@ def test_accounting_against_paper_closed_forms():
     # it differs from the paper's form only by counting y twice and v as fp32
     paper = acc.paper_io_bytes(64, 64, 4096, 16) + acc.paper_io_bytes(64, 64, 16, 4096)
     assert acc.algorithmic_bytes("add_lora", 64, 64, 4096, 4096, 16) - paper == 64 * 4096 * 2 + 2 * 64 * 16 * 2
+
+
+def _plan(n_segs, n_proj=1, **kw):
+    kw.setdefault("workspace_ready", 1)
+    p = _prob(**kw)
+    rc, plan = sg.sgmv_plan_add_lora(p, n_segs, n_proj, check=False)
+    return rc, plan
+
+
+def test_plan_single_launch_shapes():
+    """Launch policy of sgmv_add_lora, asked of the library (host-only, no device)."""
+    # one row per segment: the row kernel, S a power of two with S * segments <= 256 units
+    # (256 rows of 4096: two slices, since a slice holds at most 2048 input features)
+    for batch, S in ((1, 8), (8, 8), (16, 8), (32, 8), (48, 4), (64, 4), (128, 2), (256, 2)):
+        rc, pl = _plan(batch, n_tokens=batch, max_seg_len=1)
+        assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and pl.launches == 1
+        assert (pl.slices, pl.workgroups) == (S, S * batch), (batch, pl.slices)
+    # short multi-row segments: sixteen-row tiles, every workgroup resident
+    rc, pl = _plan(39, n_tokens=64, max_seg_len=5)
+    assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.launches == 1
+    assert pl.slices * 39 <= 256 and pl.workgroups == pl.slices * 39
+    assert 0 < pl.lds_bytes <= 160 * 1024
+    rc, pl = _plan(1, n_tokens=64, max_seg_len=64)
+    assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.workgroups == pl.slices * 4
+    # without the prepared workspace the single-launch kernels are not taken
+    rc, pl = _plan(64, n_tokens=64, max_seg_len=1, workspace_ready=0)
+    assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR and pl.launches == 2
+    # long segments: the MFMA kernels, three launches
+    rc, pl = _plan(4, n_tokens=3450, max_seg_len=891)
+    assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX and pl.launches == 3
+    # forced paths
+    rc, pl = _plan(64, n_tokens=64, max_seg_len=1, path=sg.PATH_VECTOR)
+    assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR
+    rc, pl = _plan(64, n_tokens=64, max_seg_len=1, path=sg.PATH_MATRIX)
+    assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX
+    rc, pl = _plan(4, n_tokens=400, max_seg_len=100, path=sg.PATH_FUSED)
+    assert rc == 3                                   # unsupported: too long for a tile launch
+    # nothing to do
+    rc, pl = _plan(0, n_tokens=0)
+    assert rc == 0 and pl.kernel == sg.KERNEL_NONE and pl.launches == 0
+
+
+def test_plan_multi_projection_shapes():
+    # few enough workgroups for all projections side by side (two workgroups per unit)
+    rc, pl = _plan(64, 2, n_tokens=64, max_seg_len=1)
+    assert rc == 0 and pl.kernel == sg.KERNEL_MULTI_SIDE and pl.launches == 1
+    assert pl.workgroups == 4 * 64 * 2
+    # more: every workgroup walks the projections
+    rc, pl = _plan(64, 3, n_tokens=64, max_seg_len=1)
+    assert rc == 0 and pl.kernel == sg.KERNEL_MULTI_PIPELINED and pl.launches == 1
+    assert pl.workgroups == 4 * 64
+    rc, pl = _plan(16, 4, n_tokens=16, max_seg_len=1)
+    assert rc == 0 and pl.kernel == sg.KERNEL_MULTI_SIDE and pl.workgroups == 8 * 16 * 4
+    # multi-row segments are run one add-on after the other
+    rc, pl = _plan(39, 3, n_tokens=64, max_seg_len=5)
+    assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.launches == 3
+    rc, pl = _plan(64, 9, n_tokens=64, max_seg_len=1)
+    assert rc == 2
+    rc, pl = _plan(64, 0, n_tokens=64, max_seg_len=1)
+    assert rc == 2
+
+
+def test_plan_agrees_with_the_resource_limits():
+    """Every single-launch plan keeps all its workgroups resident: at most 256 (one per
+    compute unit), or 512 for the side-by-side kernel; LDS within 160 KiB."""
+    for r in (8, 16, 32, 64):
+        for h_in, h_out in ((4096, 4096), (4096, 11008), (13824, 5120), (64, 64), (5120, 13824)):
+            for n_segs, n_tokens, m in ((1, 1, 1), (7, 7, 1), (64, 64, 1), (200, 200, 1), (256, 256, 1),
+                                        (3, 40, 16), (39, 64, 5), (64, 640, 29), (100, 300, 3), (2, 128, 64)):
+                rc, pl = _plan(n_segs, r=r, h_in=h_in, h_out=h_out, n_tokens=n_tokens, max_seg_len=m)
+                assert rc == 0
+                if pl.kernel in (sg.KERNEL_FUSED, sg.KERNEL_TILE):
+                    assert pl.launches == 1 and 0 < pl.workgroups <= 512, (r, h_in, n_segs, pl.workgroups)
+                    if pl.kernel == sg.KERNEL_TILE:
+                        assert pl.workgroups <= 256 and pl.lds_bytes <= 160 * 1024
+                else:
+                    assert pl.kernel in (sg.KERNEL_VECTOR, sg.KERNEL_MATRIX)
