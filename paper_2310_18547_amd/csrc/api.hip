@@ -105,6 +105,10 @@ void choose_split_matrix(const sgmv_problem* p, int n_segs, int* ksplit, int* ks
   int s = p->ksplit > 0 ? p->ksplit : ceil_div(kMatrixWorkgroups, blocks > 0 ? blocks : 1);
   const int most = p->h_in / 256 > 0 ? p->h_in / 256 : 1;  // keep slices >= one LDS chunk
   if (s > most) s = most;
+  // slices no deeper than what stays resident in LDS (the streaming shrink), if the
+  // workspace has room for that many partial sums
+  const int need = ceil_div(p->h_in, 512);
+  if (p->ksplit == 0 && s < need) s = need;
   if (s > cap) s = cap;
   if (s < 1) s = 1;
   const int len = ceil_div(ceil_div(p->h_in, s), 32) * 32;

@@ -100,6 +100,16 @@ __device__ __forceinline__ uint4 buffer_load128(__amdgpu_buffer_rsrc_t rsrc, uin
   u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)byte_off, 0, AUX);
   return make_uint4(v.x, v.y, v.z, v.w);
 }
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint2 buffer_load64(__amdgpu_buffer_rsrc_t rsrc, uint32_t byte_off) {
+  u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)byte_off, 0, 0);
+  return make_uint2(v.x, v.y);
+}
+__device__ __forceinline__ void buffer_store64(__amdgpu_buffer_rsrc_t rsrc, uint32_t byte_off,
+                                               const uint2& q) {
+  u32x2 v = {q.x, q.y};
+  __builtin_amdgcn_raw_buffer_store_b64(v, rsrc, (int)byte_off, 0, 0);
+}
 __device__ __forceinline__ void buffer_store128(__amdgpu_buffer_rsrc_t rsrc, uint32_t byte_off,
                                                 const uint4& q) {
   u32x4 v = {q.x, q.y, q.z, q.w};

@@ -37,13 +37,21 @@
 #include "launch.h"
 #include "mfma.h"
 
+// Timeline probes for development builds; empty in the library.
+#ifndef SGMV_TRACE_POINT
+#define SGMV_TRACE_DECL
+#define SGMV_TRACE_POINT(point)
+#define SGMV_TRACE_FLUSH(cond, first, last)
+#endif
+
 namespace sgmv {
 
 constexpr int kShrinkRows = 64;    // rows per shrink workgroup (four 16-row tiles)
 constexpr int kShrinkChunk = 256;  // k per LDS stage
 constexpr int kExpandCols = 256;   // columns per expand workgroup (64 per wave)
-constexpr int kExpandRows = 64;    // rows per expand workgroup pass (more, smaller workgroups measured faster)
-constexpr int kExpandTiles = 2;    // 16-row tiles a wave keeps in flight (deeper measured no faster)
+constexpr int kExpandRows = 64;    // fewest rows per expand workgroup
+constexpr int kExpandRowsMost = 64;      // most
+constexpr int kExpandWorkgroups = 1536;  // workgroups beyond which a workgroup takes more rows
 
 // ---------------------------------------------------------------- shrink
 //
@@ -69,7 +77,9 @@ __global__ __launch_bounds__(256) void shrink_matrix_kernel(
   __shared__ __align__(16) uint32_t at[(KC / 8) * BLK * 4];
 
   const int seg = blockIdx.z, s = blockIdx.x, tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  // the wave index decides the base of the wave's x buffer: told to be wave-uniform, it
+  // stays in scalar registers (a per-lane base would make every load a loop over lanes)
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
   if (lo >= hi) return;
   const uint16_t* A = A_ptrs[seg];
@@ -93,6 +103,7 @@ __global__ __launch_bounds__(256) void shrink_matrix_kernel(
     const __amdgpu_buffer_rsrc_t rX = make_buffer(
         x + (long long)row0 * h_in + k0,
         rows_here > 0 ? (uint32_t)((long long)(rows_here - 1) * h_in + klen) * 2u : 0u);
+    const int k_end = m < rows_here ? klen : 0;  // one compare per load, no branches between loads
     f32x4 acc[NTILE];
 #pragma unroll
     for (int t = 0; t < NTILE; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -106,7 +117,7 @@ __global__ __launch_bounds__(256) void shrink_matrix_kernel(
 #pragma unroll
       for (int ks = 0; ks < KSTEPS; ++ks) {
         const int k = kc + ks * 32 + g * 8;  // row m, k .. k+7
-        xn[ks] = buffer_load128(rX, (m < rows_here && k < klen) ? (uint32_t)(m * h_in + k) * 2u : kOutOfRange);
+        xn[ks] = buffer_load128(rX, k < k_end ? (uint32_t)(m * h_in + k) * 2u : kOutOfRange);
       }
 #pragma unroll
       for (int it = 0; it < ITEMS; ++it) {
@@ -165,6 +176,195 @@ __global__ __launch_bounds__(256) void shrink_matrix_kernel(
       }
     }
   }
+}
+
+// ---------------------------------------------------------------- shrink, streaming
+//
+// Same split-K shape and the same partial sums as shrink_matrix_kernel, for slices of
+// A_i small enough to stay in LDS for the lifetime of the workgroup
+// (shrink_stream_lds_bytes): the slice is transposed once, and after the one barrier
+// that follows the four waves never meet again.  Each wave walks its sixteen-row tiles
+// (row blocks blockIdx.y, + gridDim.y, ...) as one sequence of register banks of
+// kStreamBank k-steps; two banks are in flight, one being consumed by the matrix cores
+// while the other loads, across tile boundaries as well, so the x stream never drains.
+constexpr int kStreamBank = 8;  // 32-deep k-steps per register bank (eight 128-bit loads per lane)
+
+// LDS holds the slice rounded up to whole banks, the surplus zero, so that the
+// matrix-core loop needs no guards.
+__host__ __device__ constexpr int stream_kpad(int kslice) {
+  return (kslice + 32 * kStreamBank - 1) / (32 * kStreamBank) * (32 * kStreamBank);
+}
+size_t shrink_stream_lds_bytes(int r, int kslice) {
+  return (size_t)(stream_kpad(kslice) / 8) * ((r + 15) / 16 * 16 + 1) * 16;
+}
+
+template <class DT, int R>
+__global__ __launch_bounds__(256) void shrink_stream_kernel(
+    const uint16_t* __restrict__ x, const uint16_t* const* __restrict__ A_ptrs,
+    const int32_t* __restrict__ seg_starts, float* __restrict__ partials, int h_in, int kslice,
+    int n_tokens, long long layer_off) {
+  constexpr int NT = 256;
+  constexpr int NTILE = (R + 15) / 16;
+  constexpr int RPAD = NTILE * 16;
+  constexpr int CG = R / 8;
+  constexpr int BLK = RPAD + 1;  // 16-byte slots per block of 8 k (layout: see shrink_matrix_kernel)
+  constexpr int XB = kStreamBank;
+  constexpr int AB = 4;          // staging items (two 128-bit loads each) per thread and batch
+  extern __shared__ __align__(16) uint32_t at[];  // (stream_kpad(kslice) / 8) * BLK slots
+  SGMV_TRACE_DECL
+  SGMV_TRACE_POINT(0);
+
+  const int seg = blockIdx.z, s = blockIdx.x, tid = threadIdx.x;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
+  if ((int)blockIdx.y * kShrinkRows >= hi - lo) return;
+  const uint16_t* A = A_ptrs[seg];
+  if (A == nullptr) return;
+  const int k0 = s * kslice;
+  const int klen = min(h_in, k0 + kslice) - k0;
+  if (klen <= 0) return;
+  const int m = lane & 15, g = lane >> 4;
+  SGMV_TRACE_POINT(1);
+
+  // this wave's tiles: rows lo + 64 (blockIdx.y + j gridDim.y) + 16 wave .. +15, j = 0 .. my_tiles-1
+  const int span = hi - lo - wave * 16;
+  const int wave_blocks = span > 0 ? (span + kShrinkRows - 1) / kShrinkRows : 0;
+  const int my_tiles = wave_blocks > (int)blockIdx.y
+                           ? (wave_blocks - (int)blockIdx.y + (int)gridDim.y - 1) / (int)gridDim.y
+                           : 0;
+  const int nsteps = (klen + 31) >> 5;
+  const int nb = (nsteps + XB - 1) / XB;  // banks per tile
+  const int total = my_tiles * nb;        // banks of this wave
+  const uint32_t x_lane = (uint32_t)(m * h_in + g * 8) * 2u;
+
+  // bank b of tile j: k-steps XB b .. XB b + XB - 1; lane (m, g) takes row m, k = 32 step + 8 g .. +7
+  auto load_bank = [&](uint4 (&q)[XB], int j, int b) {
+    const int row0 = lo + ((int)blockIdx.y + j * (int)gridDim.y) * kShrinkRows + wave * 16;
+    const int rows_here = min(16, hi - row0);
+    const __amdgpu_buffer_rsrc_t rX = make_buffer(
+        x + (long long)row0 * h_in + k0, (uint32_t)((long long)(rows_here - 1) * h_in + klen) * 2u);
+    const int k_end = m < rows_here ? klen - g * 8 : 0;  // rows past the segment read as zeros
+#pragma unroll
+    for (int i = 0; i < XB; ++i) {
+      const int k = (b * XB + i) * 32;
+      q[i] = buffer_load128(rX, k < k_end ? x_lane + (uint32_t)k * 2u : kOutOfRange);
+    }
+  };
+
+  // ---- stage the slice of A_i, transposed; the first two banks of x follow the first
+  // batch of its loads, so they are in flight while the slice is placed
+  uint4 q0[XB], q1[XB];
+  {
+    const __amdgpu_buffer_rsrc_t rA =
+        make_buffer(A + layer_off + (long long)k0 * R, (uint32_t)klen * R * 2u);
+    const int kpad = stream_kpad(kslice);
+    const int items = (kpad >> 1) * CG;  // (pair of k, eight columns); rows past klen read as zeros
+    uint4 a0[AB], a1[AB];
+    for (int base = 0; base < items; base += NT * AB) {
+#pragma unroll
+      for (int u = 0; u < AB; ++u) {
+        // item = kp * CG + cg -> rows 2 kp, 2 kp + 1, columns 8 cg .. +7
+        const int item = base + u * NT + tid;
+        const uint32_t o = item < items ? (uint32_t)(2 * item - item % CG) * 16u : kOutOfRange;
+        a0[u] = buffer_load128(rA, o);
+        a1[u] = buffer_load128(rA, item < items ? o + (uint32_t)R * 2u : kOutOfRange);
+      }
+      if (base == 0) {
+        if (total > 0) load_bank(q0, 0, 0);
+        if (total > 1) load_bank(q1, nb > 1 ? 0 : 1, nb > 1 ? 1 : 0);
+        SGMV_TRACE_POINT(2);
+      }
+#pragma unroll
+      for (int u = 0; u < AB; ++u) {
+        const int item = base + u * NT + tid;
+        if (item < items) {
+          const int cg = item % CG, kp = item / CG;
+          const uint32_t w0[4] = {a0[u].x, a0[u].y, a0[u].z, a0[u].w};
+          const uint32_t w1[4] = {a1[u].x, a1[u].y, a1[u].z, a1[u].w};
+          uint32_t* blk = &at[(kp >> 2) * BLK * 4 + (kp & 3)];  // k block, dword of the k pair
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {  // columns 8 cg + 2 i and + 2 i + 1
+            blk[((2 * i) * CG + cg) * 4] = (w0[i] & 0xFFFFu) | (w1[i] << 16);
+            blk[((2 * i + 1) * CG + cg) * 4] = (w0[i] >> 16) | (w1[i] & 0xFFFF0000u);
+          }
+        }
+      }
+    }
+    if (R < RPAD) {  // slots no column of A_i fills
+      for (int i = tid; i < (kpad >> 3) * (RPAD - R) * 4; i += NT) {
+        const int blk = i / ((RPAD - R) * 4), w = i % ((RPAD - R) * 4);
+        at[(blk * BLK + R) * 4 + w] = 0u;
+      }
+    }
+  }
+  // LDS-only barrier: the x loads stay in flight
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  SGMV_TRACE_POINT(3);
+
+  // ---- stream
+  f32x4 acc[NTILE];
+  int cj = 0, cb = 0;                            // bank being consumed: tile, bank of the tile
+  int lj = nb > 2 ? 0 : (nb == 2 ? 1 : 2);       // next bank to load
+  int lb = nb > 2 ? 2 : 0;
+  auto consume = [&](const uint4 (&q)[XB]) {
+    if (cb == 0) {
+#pragma unroll
+      for (int t = 0; t < NTILE; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll
+    for (int i = 0; i < XB; ++i) {
+      const int step = cb * XB + i;  // steps past the slice multiply zeros
+#pragma unroll
+      for (int t = 0; t < NTILE; ++t) {
+        const uint4 bt = *reinterpret_cast<const uint4*>(&at[((step * 4 + g) * BLK + t * 16 + m) * 4]);
+        acc[t] = mfma16x16x32<DT>(q[i], bt, acc[t]);
+      }
+    }
+    if (cb == nb - 1) {
+      // D[row 4g+i][slot m] of every tile; slot p holds column 8 (p % CG) + p / CG
+      const int row0 = lo + ((int)blockIdx.y + cj * (int)gridDim.y) * kShrinkRows + wave * 16;
+#pragma unroll
+      for (int t = 0; t < NTILE; ++t) {
+        const int p = t * 16 + m;
+        const int n = (p % CG) * 8 + p / CG;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int row = row0 + 4 * g + i;
+          if (p < R && row < hi) partials[((long long)s * n_tokens + row) * R + n] = acc[t][i];
+        }
+      }
+    }
+    if (++cb == nb) {
+      cb = 0;
+      ++cj;
+    }
+  };
+  auto refill = [&](uint4 (&q)[XB]) {
+    load_bank(q, lj, lb);
+    if (++lb == nb) {
+      lb = 0;
+      ++lj;
+    }
+  };
+  // steady state without conditions around the loads, so that waiting for one bank
+  // leaves the other's eight loads in flight
+  int i = 0;
+  for (; i + 3 < total; i += 2) {
+    consume(q0);
+    refill(q0);
+    consume(q1);
+    refill(q1);
+  }
+  SGMV_TRACE_POINT(4);
+  const int rem = total - i;  // 0..3 banks left
+  if (rem > 0) consume(q0);
+  if (rem > 2) refill(q0);
+  if (rem > 1) consume(q1);
+  if (rem > 2) consume(q0);
+  SGMV_TRACE_POINT(5);
+  SGMV_TRACE_FLUSH(tid == 0, 0, 5);
 }
 
 // ---------------------------------------------------------------- expand
@@ -232,46 +432,106 @@ __global__ __launch_bounds__(256) void finalize_v_kernel(
   }
 }
 
-// grid = (column strips, row blocks, n_segs); the row-block dimension is walked
-// with a stride.  vh / vl / undo come from finalize_v_kernel.
+// grid = (column strips, row blocks of rows_per_wg rows, n_segs); the row-block dimension
+// is walked with a stride.  vh / vl / undo come from finalize_v_kernel.
+//
+// The product is taken as D = v B_i with the token rows in the first operand: lane
+// (n = l % 16, g = l / 16) receives D[row 4 g + i][column slot n] of every 16-column tile.
+// A wave owns 64 columns as four tiles, tile t holding columns 4 n + t, so a lane ends up
+// with four consecutive columns (8 bytes) of rows 4 g .. 4 g + 3, and each of its four
+// 64-bit accesses of y covers four rows x 128 contiguous bytes across the wave: whole
+// cache lines in both directions.  (Measured on plain read-modify-write kernels of this
+// shape: 5.0 TB/s, against 3.3 TB/s for 128-bit accesses that cover sixteen rows x 64
+// bytes, the layout the transposed product D = B_i^T v^T would give.)
+// The strip of B_i is transposed through LDS once and kept in registers as operands.  Two
+// row tiles are in flight; the first two are requested before the strip is staged.
 template <class DT, int R>
-__global__ __launch_bounds__(256) void expand_matrix_kernel(
+__global__ __launch_bounds__(256, (R <= 32 ? 4 : 3) - (std::is_same<DT, F16>::value ? 1 : 0)) void expand_matrix_kernel(
     uint16_t* __restrict__ y, const uint16_t* __restrict__ vh, const uint16_t* __restrict__ vl,
     const float* __restrict__ undo, const uint16_t* const* __restrict__ A_ptrs,
     const uint16_t* const* __restrict__ B_ptrs, const int32_t* __restrict__ seg_starts, int h_out,
-    int n_tokens, long long layer_off, float scale) {
-  constexpr int NT = 256;
+    int n_tokens, long long layer_off, float scale, int rows_per_wg) {
   constexpr int KPAD = R < 32 ? 32 : R;  // k padded to the MFMA depth
   constexpr int KSTEPS = KPAD / 32;
-  constexpr int NC = kExpandCols;
+  constexpr int NC = kExpandCols;        // columns per workgroup
+  constexpr int NT = 256;
+  constexpr int CT = 4;                  // 16-column tiles (and columns per lane) of a wave
   constexpr int KPAIRS = R / 2;
   // B_i strip, transposed, as 16-byte slots {8 consecutive k of one column}:
-  // bt[k / 8][slot], NC + 1 slots per k block; column 8 cg + c of the strip sits in
-  // slot c * (NC / 8) + cg, so the lanes of a staging load write consecutive slots.
+  // bt[k / 8][slot], NC + 1 slots per k block; column c of the strip sits in slot
+  // (c % 4) * (NC / 4) + c / 4, so the sixteen lanes of an operand read (columns 4 n + t,
+  // n = 0..15) read consecutive slots.
   constexpr int BLK = NC + 1;
   __shared__ __align__(16) uint32_t bt[(KPAD / 8) * BLK * 4];
+  SGMV_TRACE_DECL
+  SGMV_TRACE_POINT(0);
 
   const int seg = blockIdx.z, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
-  if (lo >= hi) return;
+  if ((long long)blockIdx.y * rows_per_wg >= hi - lo) return;
   const uint16_t* B = B_ptrs[seg];
   if (B == nullptr) return;
   if (A_ptrs != nullptr && A_ptrs[seg] == nullptr) return;
-  const int nblocks = (hi - lo + kExpandRows - 1) / kExpandRows;
-  if ((int)blockIdx.y >= nblocks) return;
   const int c0 = blockIdx.x * NC;
   const int ncols = min(NC, h_out - c0);
   const __amdgpu_buffer_rsrc_t rB = make_buffer(
       B + layer_off + c0, (uint32_t)((long long)(R - 1) * h_out + ncols) * 2u);
+  SGMV_TRACE_POINT(1);
+
+  // this lane: token rows 4 g + i of a tile (i = 0..3), columns cw .. cw + 3
+  const int n = lane & 15, g = lane >> 4;
+  const int cw = c0 + wave * (16 * CT) + n * CT;
+  const bool c_ok = cw < h_out;
+
+  struct Tile {  // everything one row tile reads from memory
+    uint2 yq[4];
+    uint4 h[KSTEPS], l[KSTEPS];
+    float un[4];
+  };
+  // the block of rows being walked
+  int rbeg = lo + (int)blockIdx.y * rows_per_wg;
+  int nrows = min(hi, rbeg + rows_per_wg) - rbeg;
+  __amdgpu_buffer_rsrc_t rY, rH, rL;
+  auto open_block = [&]() {
+    rY = make_buffer(y + (long long)rbeg * h_out, (uint32_t)((long long)nrows * h_out) * 2u);
+    rH = make_buffer(vh + (long long)rbeg * R, (uint32_t)(nrows * R) * 2u);
+    rL = make_buffer(vl + (long long)rbeg * R, (uint32_t)(nrows * R) * 2u);
+  };
+  auto fetch = [&](int r0, Tile& T) {  // rows r0 .. r0+15 relative to rbeg
+    // one compare per access: rows past the block and columns past h_out read as zeros
+    const int ylim = c_ok ? nrows : 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = r0 + 4 * g + i;
+      T.yq[i] = buffer_load64(rY, row < ylim ? (uint32_t)(row * h_out + cw) * 2u : kOutOfRange);
+    }
+    const int vrow = r0 + n;  // first operand: row n of the tile, k = 32 ks + 8 g .. + 7
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      const int k = ks * 32 + g * 8;
+      const uint32_t voff = vrow < (k < R ? nrows : 0) ? (uint32_t)(vrow * R + k) * 2u : kOutOfRange;
+      T.h[ks] = buffer_load128(rH, voff);
+      T.l[ks] = buffer_load128(rL, voff);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      T.un[i] = std::is_same<DT, F16>::value ? undo[rbeg + min(r0 + 4 * g + i, nrows - 1)] : 1.f;
+  };
+  Tile t0, t1;
+  open_block();
+  fetch(0, t0);
+  if (nrows > 16) fetch(16, t1);
 
   // ---- stage the strip transposed: a thread takes a pair of k and eight columns
   if (R < KPAD) {
     for (int i = tid; i < (KPAD / 8) * BLK * 4; i += NT) bt[i] = 0u;
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
   }
   {
     constexpr int TOTAL = KPAIRS * (NC / 8);  // (k pair, 8 columns) items
-    constexpr int BATCH = 4;                  // items per thread with their loads in flight together
+    constexpr int BATCH = TOTAL / NT >= 4 ? 4 : TOTAL / NT >= 1 ? TOTAL / NT : 1;  // items per thread with their loads in flight together
     for (int base = 0; base < TOTAL; base += NT * BATCH) {
       uint4 r0[BATCH], r1[BATCH];
 #pragma unroll
@@ -291,118 +551,88 @@ __global__ __launch_bounds__(256) void expand_matrix_kernel(
           const uint32_t a1[4] = {r1[b].x, r1[b].y, r1[b].z, r1[b].w};
           uint32_t* blk = &bt[(kp >> 2) * BLK * 4 + (kp & 3)];  // k block, dword of the k pair
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {  // columns 8 cg + 2 i and + 2 i + 1
-            blk[((2 * i) * (NC / 8) + cg) * 4] = (a0[i] & 0xFFFFu) | (a1[i] << 16);
-            blk[((2 * i + 1) * (NC / 8) + cg) * 4] = (a0[i] >> 16) | (a1[i] & 0xFFFF0000u);
+          for (int i = 0; i < 4; ++i) {  // columns 8 cg + 2 i and + 2 i + 1, i.e. c % 4 = 2 (i % 2) (+ 1), c / 4 = 2 cg + i / 2
+            blk[((2 * (i & 1)) * (NC / 4) + 2 * cg + (i >> 1)) * 4] = (a0[i] & 0xFFFFu) | (a1[i] << 16);
+            blk[((2 * (i & 1) + 1) * (NC / 4) + 2 * cg + (i >> 1)) * 4] = (a0[i] >> 16) | (a1[i] & 0xFFFF0000u);
           }
         }
       }
     }
   }
-  __syncthreads();
+  // LDS-only barrier: the tile loads stay in flight
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  SGMV_TRACE_POINT(2);
 
-  // ---- operands: tile t, slot (lane % 16) = 4 q + i  <->  column 32 (t / 2) + 8 q + 4 (t % 2) + i
-  // of the wave's 64, so that lane group q ends up with columns 8 q .. 8 q + 7 (tiles 0, 1)
-  // and 32 + 8 q .. + 7 (tiles 2, 3): each 128-bit access of the wave is a dense 64-byte run per row
-  const int slot = lane & 15, g = lane >> 4;
-  uint4 bop[KSTEPS][4];
+  // ---- second operands: tile t, lane (n, g): column 4 n + t of the wave's 64, k block 4 ks + g
+  uint4 bop[KSTEPS][CT];
 #pragma unroll
   for (int ks = 0; ks < KSTEPS; ++ks)
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const int col = wave * 64 + (t >> 1) * 32 + (slot >> 2) * 8 + (t & 1) * 4 + (slot & 3);
-      const int pos = (col & 7) * (NC / 8) + (col >> 3);
+    for (int t = 0; t < CT; ++t) {
+      const int pos = t * (NC / 4) + wave * 16 + n;  // column wave * 64 + 4 n + t
       bop[ks][t] = *reinterpret_cast<const uint4*>(&bt[((ks * 4 + g) * BLK + pos) * 4]);
     }
+  SGMV_TRACE_POINT(3);
 
-  // this lane's output: row (lane % 16) of the tile, columns cw .. cw+7 and cw+32 .. cw+39
-  const int m = lane & 15;
-  const int cw = c0 + wave * 64 + g * 8;
-  const bool c_ok0 = cw < h_out, c_ok1 = cw + 32 < h_out;
-
-  struct Tile {  // everything one row tile reads from memory
-    uint4 y0, y1, h[KSTEPS], l[KSTEPS];
-    float un;
-  };
-  for (int rb = blockIdx.y; rb < nblocks; rb += gridDim.y) {
-    const int rbeg = lo + rb * kExpandRows, rend = min(hi, rbeg + kExpandRows);
-    const int nrows = rend - rbeg;
-    const __amdgpu_buffer_rsrc_t rY = make_buffer(y + (long long)rbeg * h_out, (uint32_t)((long long)nrows * h_out) * 2u);
-    const __amdgpu_buffer_rsrc_t rH = make_buffer(vh + (long long)rbeg * R, (uint32_t)(nrows * R) * 2u);
-    const __amdgpu_buffer_rsrc_t rL = make_buffer(vl + (long long)rbeg * R, (uint32_t)(nrows * R) * 2u);
-
-    auto fetch = [&](int r0, Tile& T) {  // rows r0 .. r0+15 relative to rbeg
-      const int row = r0 + m;
-      const bool ok = row < nrows;
-      const uint32_t yoff = (uint32_t)(row * h_out + cw) * 2u;
-      T.y0 = buffer_load128(rY, (ok && c_ok0) ? yoff : kOutOfRange);
-      T.y1 = buffer_load128(rY, (ok && c_ok1) ? yoff + 64u : kOutOfRange);
+  auto finish = [&](int r0, const Tile& T) {
+    f32x4 acc[CT];
+#pragma unroll
+    for (int t = 0; t < CT; ++t) {
+      acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks = 0; ks < KSTEPS; ++ks) {
-        const int k = ks * 32 + g * 8;
-        const uint32_t voff = (ok && k < R) ? (uint32_t)(row * R + k) * 2u : kOutOfRange;
-        T.h[ks] = buffer_load128(rH, voff);
-        T.l[ks] = buffer_load128(rL, voff);
-      }
-      T.un = std::is_same<DT, F16>::value ? undo[rbeg + min(row, nrows - 1)] : 1.f;
-    };
-    auto finish = [&](int r0, const Tile& T) {
-      f32x4 acc[4];
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-          acc[t] = mfma16x16x32<DT>(bop[ks][t], T.l[ks], acc[t]);
-          acc[t] = mfma16x16x32<DT>(bop[ks][t], T.h[ks], acc[t]);
-        }
-      }
-      // acc[t][i] is column cw + 32 (t / 2) + 4 (t % 2) + i of row m, i.e. element 4 t + i of {y0, y1}
-      float yf[16];
-      {
-        float a8[8];
-        unpack8<DT>(T.y0, a8);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) yf[i] = a8[i];
-        unpack8<DT>(T.y1, a8);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) yf[8 + i] = a8[i];
-      }
-      const float sc = scale * T.un;
-      float o[16];
-#pragma unroll
-      for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) o[t * 4 + i] = yf[t * 4 + i] + sc * acc[t][i];
-      uint4 out0, out1;
-      out0.x = pack2<DT>(o[0], o[1]);   out0.y = pack2<DT>(o[2], o[3]);
-      out0.z = pack2<DT>(o[4], o[5]);   out0.w = pack2<DT>(o[6], o[7]);
-      out1.x = pack2<DT>(o[8], o[9]);   out1.y = pack2<DT>(o[10], o[11]);
-      out1.z = pack2<DT>(o[12], o[13]); out1.w = pack2<DT>(o[14], o[15]);
-      const int row = r0 + m;
-      const bool ok = row < nrows;
-      const uint32_t yoff = (uint32_t)(row * h_out + cw) * 2u;
-      buffer_store128(rY, (ok && c_ok0) ? yoff : kOutOfRange, out0);
-      buffer_store128(rY, (ok && c_ok1) ? yoff + 64u : kOutOfRange, out1);
-    };
-
-    // kExpandTiles row tiles in flight: a tile's registers are refilled with the loads of the
-    // tile kExpandTiles further on as soon as it is finished
-    Tile tl[kExpandTiles];
-#pragma unroll
-    for (int i = 0; i < kExpandTiles; ++i)
-      if (i * 16 < nrows) fetch(i * 16, tl[i]);
-    for (int r0 = 0; r0 < nrows; r0 += 16 * kExpandTiles) {
-#pragma unroll
-      for (int i = 0; i < kExpandTiles; ++i) {
-        const int r = r0 + 16 * i;
-        if (r < nrows) {
-          finish(r, tl[i]);
-          if (r + 16 * kExpandTiles < nrows) fetch(r + 16 * kExpandTiles, tl[i]);
-        }
+        acc[t] = mfma16x16x32<DT>(T.l[ks], bop[ks][t], acc[t]);
+        acc[t] = mfma16x16x32<DT>(T.h[ks], bop[ks][t], acc[t]);
       }
     }
+    // acc[t][i] is column cw + t of row 4 g + i
+    const int ylim = c_ok ? nrows : 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float yf[4];
+      unpack2<DT>(T.yq[i].x, yf[0], yf[1]);
+      unpack2<DT>(T.yq[i].y, yf[2], yf[3]);
+      const float sc = scale * T.un[i];
+      float o[4];
+#pragma unroll
+      for (int t = 0; t < CT; ++t) o[t] = yf[t] + sc * acc[t][i];
+      const uint2 out = make_uint2(pack2<DT>(o[0], o[1]), pack2<DT>(o[2], o[3]));
+      const int row = r0 + 4 * g + i;
+      buffer_store64(rY, row < ylim ? (uint32_t)(row * h_out + cw) * 2u : kOutOfRange, out);
+    }
+  };
+
+  for (bool first = true;; first = false) {
+    if (!first) {
+      open_block();
+      fetch(0, t0);
+      if (nrows > 16) fetch(16, t1);
+    }
+    // steady state without conditions around the loads: waiting for one tile leaves the
+    // other tile's loads in flight
+    int r = 0;
+    for (; r + 48 < nrows; r += 32) {
+      finish(r, t0);
+      fetch(r + 32, t0);
+      finish(r + 16, t1);
+      fetch(r + 48, t1);
+    }
+    if (first) SGMV_TRACE_POINT(4);
+    const int rem = nrows - r;  // 1..48 rows left
+    finish(r, t0);
+    if (rem > 32) fetch(r + 32, t0);
+    if (rem > 16) finish(r + 16, t1);
+    if (rem > 32) finish(r + 32, t0);
+    // next block of this workgroup (only when the grid is smaller than the longest segment needs)
+    const long long next = (long long)rbeg - lo + (long long)gridDim.y * rows_per_wg;
+    if (next >= hi - lo) break;
+    rbeg = lo + (int)next;
+    nrows = min(hi, rbeg + rows_per_wg) - rbeg;
   }
+  SGMV_TRACE_POINT(5);
+  SGMV_TRACE_FLUSH(tid == 0, 0, 5);
 }
 
 // ---------------------------------------------------------------- launchers
@@ -415,9 +645,33 @@ static unsigned row_blocks(int max_seg_len, int n_tokens, int rows_per_block) {
   return (unsigned)b;
 }
 
+// Largest LDS footprint of the streaming shrink (two workgroups per compute unit fit).
+constexpr size_t kStreamMaxLds = 68 * 1024;
+
+bool shrink_stream_fits(const ShrinkArgs& a) {
+  return a.kslice % 32 == 0 && shrink_stream_lds_bytes(a.r, a.kslice) <= kStreamMaxLds;
+}
+
 template <class DT, int R>
 static hipError_t launch_shrink_matrix_t(const ShrinkArgs& a, hipStream_t st) {
   dim3 grid((unsigned)a.ksplit, row_blocks(a.max_seg_len, a.n_tokens, kShrinkRows), (unsigned)a.n_segs);
+  if (shrink_stream_fits(a)) {
+    auto kernel = shrink_stream_kernel<DT, R>;
+    static bool enabled[64] = {};  // more than 64 KiB of dynamic LDS is enabled once per device
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!enabled[dev]) {
+      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               (int)kStreamMaxLds);
+      if (e != hipSuccess) return e;
+      enabled[dev] = true;
+    }
+    hipLaunchKernelGGL(kernel, grid, dim3(256), shrink_stream_lds_bytes(R, a.kslice), st,
+                       (const uint16_t*)a.x, (const uint16_t* const*)a.A_ptrs, a.seg_starts, a.partials,
+                       a.h_in, a.kslice, a.n_tokens, a.layer_off);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL((shrink_matrix_kernel<DT, R>), grid, dim3(256), 0, st, (const uint16_t*)a.x,
                      (const uint16_t* const*)a.A_ptrs, a.seg_starts, a.partials, a.h_in, a.kslice,
                      a.n_tokens, a.layer_off);
@@ -440,10 +694,21 @@ hipError_t launch_shrink_matrix(const ShrinkArgs& a, hipStream_t st) {
   return a.bf16 ? launch_shrink_matrix_r<BF16>(a, st) : launch_shrink_matrix_r<F16>(a, st);
 }
 
+// Rows per expand workgroup: 64, or more when that would launch several rounds of
+// workgroups, so that a workgroup's set-up (lookup, staging the strip of B_i) is spread
+// over more rows.  Depends only on the shape, so results do not depend on it.
+int expand_rows_per_wg(const ExpandArgs& a) {
+  const long long strips = (a.h_out + kExpandCols - 1) / kExpandCols;
+  int rows = kExpandRows;
+  while (rows < kExpandRowsMost && strips * (a.n_tokens / rows + a.n_segs) > kExpandWorkgroups) rows *= 2;
+  return rows;
+}
+
 template <class DT, int R>
 static hipError_t launch_expand_matrix_t(const ExpandArgs& a, hipStream_t st) {
+  const int rows = expand_rows_per_wg(a);
   dim3 grid((unsigned)((a.h_out + kExpandCols - 1) / kExpandCols),
-            row_blocks(a.max_seg_len, a.n_tokens, kExpandRows), (unsigned)a.n_segs);
+            row_blocks(a.max_seg_len, a.n_tokens, rows), (unsigned)a.n_segs);
   // v -> 16-bit operand pairs, then the expand proper
   const long long items = (long long)a.n_tokens * (R / 8);
   hipLaunchKernelGGL((finalize_v_kernel<DT, R>), dim3((unsigned)((items + 255) / 256)), dim3(256), 0,
@@ -453,7 +718,7 @@ static hipError_t launch_expand_matrix_t(const ExpandArgs& a, hipStream_t st) {
   hipLaunchKernelGGL((expand_matrix_kernel<DT, R>), grid, dim3(256), 0, st, (uint16_t*)a.y, a.vh,
                      a.vl, a.undo, (const uint16_t* const*)a.A_ptrs,
                      (const uint16_t* const*)a.B_ptrs, a.seg_starts, a.h_out, a.n_tokens,
-                     a.layer_off, a.scale);
+                     a.layer_off, a.scale, rows);
   return hipGetLastError();
 }
 
