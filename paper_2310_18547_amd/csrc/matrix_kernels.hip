@@ -183,7 +183,7 @@ __global__ __launch_bounds__(256) void shrink_matrix_kernel(
 // Same split-K shape and the same partial sums as shrink_matrix_kernel, for slices of
 // A_i small enough to stay in LDS for the lifetime of the workgroup
 // (shrink_stream_lds_bytes): the slice is transposed once, and after the one barrier
-// that follows the four waves never meet again.  Each wave walks its sixteen-row tiles
+// that follows the waves never meet again.  Each wave walks its sixteen-row tiles
 // (row blocks blockIdx.y, + gridDim.y, ...) as one sequence of register banks of
 // kStreamBank k-steps; two banks are in flight, one being consumed by the matrix cores
 // while the other loads, across tile boundaries as well, so the x stream never drains.
@@ -198,12 +198,18 @@ size_t shrink_stream_lds_bytes(int r, int kslice) {
   return (size_t)(stream_kpad(kslice) / 8) * ((r + 15) / 16 * 16 + 1) * 16;
 }
 
+// Waves (sixteen-row tiles) per workgroup: at rank 64 the slice of A_i is 65 KiB, so eight
+// waves share it, which lets all workgroups of a prefill-sized call be resident at once.
+constexpr int stream_waves(int r) { return r > 32 ? 8 : 4; }
+
 template <class DT, int R>
-__global__ __launch_bounds__(256) void shrink_stream_kernel(
+__global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
     const uint16_t* __restrict__ x, const uint16_t* const* __restrict__ A_ptrs,
     const int32_t* __restrict__ seg_starts, float* __restrict__ partials, int h_in, int kslice,
     int n_tokens, long long layer_off) {
-  constexpr int NT = 256;
+  constexpr int NW = stream_waves(R);
+  constexpr int NT = 64 * NW;
+  constexpr int ROWS = 16 * NW;  // rows per workgroup and step
   constexpr int NTILE = (R + 15) / 16;
   constexpr int RPAD = NTILE * 16;
   constexpr int CG = R / 8;
@@ -217,7 +223,7 @@ __global__ __launch_bounds__(256) void shrink_stream_kernel(
   const int seg = blockIdx.z, s = blockIdx.x, tid = threadIdx.x;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
-  if ((int)blockIdx.y * kShrinkRows >= hi - lo) return;
+  if ((int)blockIdx.y * ROWS >= hi - lo) return;
   const uint16_t* A = A_ptrs[seg];
   if (A == nullptr) return;
   const int k0 = s * kslice;
@@ -226,9 +232,9 @@ __global__ __launch_bounds__(256) void shrink_stream_kernel(
   const int m = lane & 15, g = lane >> 4;
   SGMV_TRACE_POINT(1);
 
-  // this wave's tiles: rows lo + 64 (blockIdx.y + j gridDim.y) + 16 wave .. +15, j = 0 .. my_tiles-1
+  // this wave's tiles: rows lo + ROWS (blockIdx.y + j gridDim.y) + 16 wave .. +15, j = 0 .. my_tiles-1
   const int span = hi - lo - wave * 16;
-  const int wave_blocks = span > 0 ? (span + kShrinkRows - 1) / kShrinkRows : 0;
+  const int wave_blocks = span > 0 ? (span + ROWS - 1) / ROWS : 0;
   const int my_tiles = wave_blocks > (int)blockIdx.y
                            ? (wave_blocks - (int)blockIdx.y + (int)gridDim.y - 1) / (int)gridDim.y
                            : 0;
@@ -239,7 +245,7 @@ __global__ __launch_bounds__(256) void shrink_stream_kernel(
 
   // bank b of tile j: k-steps XB b .. XB b + XB - 1; lane (m, g) takes row m, k = 32 step + 8 g .. +7
   auto load_bank = [&](uint4 (&q)[XB], int j, int b) {
-    const int row0 = lo + ((int)blockIdx.y + j * (int)gridDim.y) * kShrinkRows + wave * 16;
+    const int row0 = lo + ((int)blockIdx.y + j * (int)gridDim.y) * ROWS + wave * 16;
     const int rows_here = min(16, hi - row0);
     const __amdgpu_buffer_rsrc_t rX = make_buffer(
         x + (long long)row0 * h_in + k0, (uint32_t)((long long)(rows_here - 1) * h_in + klen) * 2u);
@@ -324,7 +330,7 @@ __global__ __launch_bounds__(256) void shrink_stream_kernel(
     }
     if (cb == nb - 1) {
       // D[row 4g+i][slot m] of every tile; slot p holds column 8 (p % CG) + p / CG
-      const int row0 = lo + ((int)blockIdx.y + cj * (int)gridDim.y) * kShrinkRows + wave * 16;
+      const int row0 = lo + ((int)blockIdx.y + cj * (int)gridDim.y) * ROWS + wave * 16;
 #pragma unroll
       for (int t = 0; t < NTILE; ++t) {
         const int p = t * 16 + m;
@@ -374,44 +380,38 @@ __global__ __launch_bounds__(256) void shrink_stream_kernel(
 //   vh, vl  [n_tokens][R] 16-bit, undo [n_tokens] fp32.
 // binary16 has a narrow range, so for F16 a row whose largest |v| reaches 2^14 is
 // scaled down by an exact power of two; `undo` is the factor that restores the
-// fp32 result (1 otherwise).  One thread handles eight consecutive k of a row.
+// fp32 result (1 otherwise).  One thread handles four consecutive k of a row, with the
+// loads of sixteen parts in flight together: the kernel is one memory latency long.
 template <class DT, int R>
 __global__ __launch_bounds__(256) void finalize_v_kernel(
     const float* __restrict__ v_parts, int nparts, uint16_t* __restrict__ vh,
     uint16_t* __restrict__ vl, float* __restrict__ undo, int n_tokens) {
-  constexpr int GPR = R / 8;  // threads per row
+  constexpr int GPR = R / 4;   // threads per row
+  constexpr int PB = 16;       // parts per batch
   const long long item = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   const long long total = (long long)n_tokens * GPR;
   const bool live = item < total;
-  const long long e0 = (live ? item : total - 1) * 8;  // first element (row * R + k)
+  const long long e0 = (live ? item : total - 1) * 4;  // first element (row * R + k)
   const long long pstride = (long long)n_tokens * R;
-  float f[8];
-  {
-    float4 p0 = make_float4(0.f, 0.f, 0.f, 0.f), p1 = p0;
-    for (int pb = 0; pb < nparts; pb += 4) {  // four parts' loads in flight together, added in order
-      float4 q0[4], q1[4];
+  float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int pb = 0; pb < nparts; pb += PB) {
+    float4 q[PB];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int p = min(pb + i, nparts - 1);
-        q0[i] = *reinterpret_cast<const float4*>(v_parts + p * pstride + e0);
-        q1[i] = *reinterpret_cast<const float4*>(v_parts + p * pstride + e0 + 4);
-      }
+    for (int i = 0; i < PB; ++i)
+      q[i] = *reinterpret_cast<const float4*>(v_parts + min(pb + i, nparts - 1) * pstride + e0);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        if (pb + i < nparts) {
-          p0.x += q0[i].x; p0.y += q0[i].y; p0.z += q0[i].z; p0.w += q0[i].w;
-          p1.x += q1[i].x; p1.y += q1[i].y; p1.z += q1[i].z; p1.w += q1[i].w;
-        }
+    for (int i = 0; i < PB; ++i) {  // added in ascending order
+      if (pb + i < nparts) {
+        sum.x += q[i].x; sum.y += q[i].y; sum.z += q[i].z; sum.w += q[i].w;
       }
     }
-    f[0] = p0.x; f[1] = p0.y; f[2] = p0.z; f[3] = p0.w;
-    f[4] = p1.x; f[5] = p1.y; f[6] = p1.z; f[7] = p1.w;
   }
+  float f[4] = {sum.x, sum.y, sum.z, sum.w};
   float un = 1.f;
   if (std::is_same<DT, F16>::value) {
     float amax = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(f[i]));
+    for (int i = 0; i < 4; ++i) amax = fmaxf(amax, fabsf(f[i]));
 #pragma unroll
     for (int msk = 1; msk < GPR; msk <<= 1) amax = fmaxf(amax, __shfl_xor(amax, msk, 64));  // the row's threads
     if (amax >= 16384.f && amax < 3.0e38f) {
@@ -419,15 +419,15 @@ __global__ __launch_bounds__(256) void finalize_v_kernel(
       const float down = __uint_as_float((uint32_t)(127 - e) << 23);
       un = __uint_as_float((uint32_t)(127 + e) << 23);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) f[i] *= down;
+      for (int i = 0; i < 4; ++i) f[i] *= down;
     }
   }
-  uint32_t h[8], l[8];
+  uint32_t h[4], l[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) split16<DT>(f[i], h[i], l[i]);
+  for (int i = 0; i < 4; ++i) split16<DT>(f[i], h[i], l[i]);
   if (live) {
-    store128(vh + e0, make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)));
-    store128(vl + e0, make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16)));
+    *reinterpret_cast<uint2*>(vh + e0) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+    *reinterpret_cast<uint2*>(vl + e0) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
     if (item % GPR == 0) undo[item / GPR] = un;
   }
 }
@@ -656,6 +656,7 @@ template <class DT, int R>
 static hipError_t launch_shrink_matrix_t(const ShrinkArgs& a, hipStream_t st) {
   dim3 grid((unsigned)a.ksplit, row_blocks(a.max_seg_len, a.n_tokens, kShrinkRows), (unsigned)a.n_segs);
   if (shrink_stream_fits(a)) {
+    grid.y = row_blocks(a.max_seg_len, a.n_tokens, 16 * stream_waves(R));
     auto kernel = shrink_stream_kernel<DT, R>;
     static bool enabled[64] = {};  // more than 64 KiB of dynamic LDS is enabled once per device
     int dev = 0;
@@ -667,7 +668,7 @@ static hipError_t launch_shrink_matrix_t(const ShrinkArgs& a, hipStream_t st) {
       if (e != hipSuccess) return e;
       enabled[dev] = true;
     }
-    hipLaunchKernelGGL(kernel, grid, dim3(256), shrink_stream_lds_bytes(R, a.kslice), st,
+    hipLaunchKernelGGL(kernel, grid, dim3(64 * stream_waves(R)), shrink_stream_lds_bytes(R, a.kslice), st,
                        (const uint16_t*)a.x, (const uint16_t* const*)a.A_ptrs, a.seg_starts, a.partials,
                        a.h_in, a.kslice, a.n_tokens, a.layer_off);
     return hipGetLastError();
@@ -710,7 +711,7 @@ static hipError_t launch_expand_matrix_t(const ExpandArgs& a, hipStream_t st) {
   dim3 grid((unsigned)((a.h_out + kExpandCols - 1) / kExpandCols),
             row_blocks(a.max_seg_len, a.n_tokens, rows), (unsigned)a.n_segs);
   // v -> 16-bit operand pairs, then the expand proper
-  const long long items = (long long)a.n_tokens * (R / 8);
+  const long long items = (long long)a.n_tokens * (R / 4);
   hipLaunchKernelGGL((finalize_v_kernel<DT, R>), dim3((unsigned)((items + 255) / 256)), dim3(256), 0,
                      st, a.v_parts, a.nparts, a.vh, a.vl, a.undo, a.n_tokens);
   hipError_t err = hipGetLastError();

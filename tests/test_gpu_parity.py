@@ -608,3 +608,38 @@ def test_matrix_path_deterministic():
     w = wl.custom([200, 77], 1024, 512, 64, "bf16", seed=73)
     a = run_add_lora(w, path=2)
     assert np.array_equal(run_add_lora(w, path=2), a)
+
+
+@pytest.mark.parametrize("r,hint", [(16, 16), (16, 100), (64, 16), (64, 130), (32, 64)])
+def test_matrix_path_short_length_hint_strides_over_row_blocks(r, hint):
+    # a hint shorter than the longest segment only makes the grid smaller: every wave then
+    # walks several row tiles (the register banks of the streaming shrink run across tile
+    # boundaries, the expand opens further row blocks)
+    w = wl.custom([300, 17, 1, 129, 400, 64], 1024 + 64, 520, r, "bf16", seed=80 + r, num_layers=2)
+    ref = oracle.run_workload(w, layer_idx=1, n_threads=8)
+    d = _matrix(w, max_seg_len=hint)
+    d.add_lora(1)
+    assert_parity(d.y_bits(), ref, "bf16", f"matrix hint={hint} r={r}")
+    v = torch.zeros(w.n_tokens, r, dtype=torch.float32, device="cuda:0")
+    d2 = _matrix(w, max_seg_len=hint)
+    d2.shrink(v, 1)
+    v_ref = oracle.run_workload(w, op="shrink", layer_idx=1, n_threads=8)
+    assert np.all(np.abs(v.cpu().numpy() - v_ref) <= 2e-3 + 2e-2 * np.abs(v_ref))
+
+
+@pytest.mark.parametrize("r", [16, 64])
+def test_matrix_path_guard_rows_are_not_written(r):
+    # y sits inside a larger buffer filled with a canary; ragged tiles at both ends
+    from paper_2310_18547_amd import binding as B
+    w = wl.custom([33, 5, 70], 544, 264, r, "bf16", seed=85)
+    d = _matrix(w)
+    T, H = w.n_tokens, w.h_out
+    big = torch.full(((T + 4) * H,), 0x5A5A, dtype=torch.int16, device="cuda:0")
+    ybuf = big[2 * H:(T + 2) * H].view(T, H)
+    ybuf.copy_(d.y0)
+    B.sgmv_add_lora(d.problem, ybuf, d.x[0], d.A_ptrs, d.B_ptrs, d.seg_starts, w.n_segs, 0, w.scale)
+    torch.cuda.synchronize()
+    host = big.cpu().numpy()
+    assert np.all(host[:2 * H] == 0x5A5A) and np.all(host[(T + 2) * H:] == 0x5A5A)
+    assert_parity(host[2 * H:(T + 2) * H].reshape(T, H).view(np.uint16), oracle.run_workload(w),
+                  "bf16", "guarded y, matrix path")
