@@ -202,6 +202,56 @@ size_t shrink_stream_lds_bytes(int r, int kslice) {
 // waves share it, which lets all workgroups of a prefill-sized call be resident at once.
 constexpr int stream_waves(int r) { return r > 32 ? 8 : 4; }
 
+// Sum of the split-K parts of four consecutive k of one row (ascending order), then the two
+// 16-bit operand parts of the MFMA expand and the row's range factor: binary16 has a narrow
+// range, so for F16 a row whose largest |v| reaches 2^14 is scaled down by an exact power of
+// two and `undo` restores the fp32 result (1 otherwise).  The R / 4 lanes that hold a row are
+// consecutive lanes of a wave, and every lane of the wave calls this (live or not).
+template <class DT, int R>
+__device__ __forceinline__ void finalize_quad(const float* __restrict__ first_part, int nparts,
+                                              long long pstride, bool live, uint16_t* vh_at,
+                                              uint16_t* vl_at, float* undo_at, bool row_leader) {
+  constexpr int GPR = R / 4;  // lanes per row
+  constexpr int PB = 16;      // parts with their loads in flight together
+  float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int pb = 0; pb < nparts; pb += PB) {
+    float4 q[PB];
+#pragma unroll
+    for (int i = 0; i < PB; ++i)
+      q[i] = *reinterpret_cast<const float4*>(first_part + min(pb + i, nparts - 1) * pstride);
+#pragma unroll
+    for (int i = 0; i < PB; ++i) {
+      if (pb + i < nparts) {
+        sum.x += q[i].x; sum.y += q[i].y; sum.z += q[i].z; sum.w += q[i].w;
+      }
+    }
+  }
+  float f[4] = {sum.x, sum.y, sum.z, sum.w};
+  float un = 1.f;
+  if (std::is_same<DT, F16>::value) {
+    float amax = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) amax = fmaxf(amax, fabsf(f[i]));
+#pragma unroll
+    for (int msk = 1; msk < GPR; msk <<= 1) amax = fmaxf(amax, __shfl_xor(amax, msk, 64));
+    if (amax >= 16384.f && amax < 3.0e38f) {
+      const int e = ((__float_as_uint(amax) >> 23) & 0xFF) - 127 - 13;  // amax * 2^-e < 2^14
+      const float down = __uint_as_float((uint32_t)(127 - e) << 23);
+      un = __uint_as_float((uint32_t)(127 + e) << 23);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) f[i] *= down;
+    }
+  }
+  uint32_t h[4], l[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) split16<DT>(f[i], h[i], l[i]);
+  if (live) {
+    *reinterpret_cast<uint2*>(vh_at) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+    *reinterpret_cast<uint2*>(vl_at) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
+    if (row_leader) *undo_at = un;
+  }
+}
+
 template <class DT, int R>
 __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
     const uint16_t* __restrict__ x, const uint16_t* const* __restrict__ A_ptrs,
@@ -213,7 +263,7 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
   constexpr int NTILE = (R + 15) / 16;
   constexpr int RPAD = NTILE * 16;
   constexpr int CG = R / 8;
-  constexpr int BLK = RPAD + 1;  // 16-byte slots per block of 8 k (layout: see shrink_matrix_kernel)
+  constexpr int BLK = RPAD + 1;  // 16-byte slots per block of 8 k: column n of A_i in slot n
   constexpr int XB = kStreamBank;
   constexpr int AB = 4;          // staging items (two 128-bit loads each) per thread and batch
   extern __shared__ __align__(16) uint32_t at[];  // (stream_kpad(kslice) / 8) * BLK slots
@@ -245,10 +295,13 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
 
   // bank b of tile j: k-steps XB b .. XB b + XB - 1; lane (m, g) takes row m, k = 32 step + 8 g .. +7
   auto load_bank = [&](uint4 (&q)[XB], int j, int b) {
-    const int row0 = lo + ((int)blockIdx.y + j * (int)gridDim.y) * ROWS + wave * 16;
-    const int rows_here = min(16, hi - row0);
+    // a bank past the wave's last tile (j >= my_tiles) has no rows: an empty buffer, every
+    // lane out of range, no memory traffic
+    const int row0 = j < my_tiles ? lo + ((int)blockIdx.y + j * (int)gridDim.y) * ROWS + wave * 16 : lo;
+    const int rows_here = j < my_tiles ? min(16, hi - row0) : 0;
     const __amdgpu_buffer_rsrc_t rX = make_buffer(
-        x + (long long)row0 * h_in + k0, (uint32_t)((long long)(rows_here - 1) * h_in + klen) * 2u);
+        x + (long long)row0 * h_in + k0,
+        rows_here > 0 ? (uint32_t)((long long)(rows_here - 1) * h_in + klen) * 2u : 0u);
     const int k_end = m < rows_here ? klen - g * 8 : 0;  // rows past the segment read as zeros
 #pragma unroll
     for (int i = 0; i < XB; ++i) {
@@ -276,8 +329,8 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
         a1[u] = buffer_load128(rA, item < items ? o + (uint32_t)R * 2u : kOutOfRange);
       }
       if (base == 0) {
-        if (total > 0) load_bank(q0, 0, 0);
-        if (total > 1) load_bank(q1, nb > 1 ? 0 : 1, nb > 1 ? 1 : 0);
+        load_bank(q0, 0, 0);  // banks past the wave's tiles load nothing
+        load_bank(q1, nb > 1 ? 0 : 1, nb > 1 ? 1 : 0);
         SGMV_TRACE_POINT(2);
       }
 #pragma unroll
@@ -289,9 +342,9 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
           const uint32_t w1[4] = {a1[u].x, a1[u].y, a1[u].z, a1[u].w};
           uint32_t* blk = &at[(kp >> 2) * BLK * 4 + (kp & 3)];  // k block, dword of the k pair
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {  // columns 8 cg + 2 i and + 2 i + 1
-            blk[((2 * i) * CG + cg) * 4] = (w0[i] & 0xFFFFu) | (w1[i] << 16);
-            blk[((2 * i + 1) * CG + cg) * 4] = (w0[i] >> 16) | (w1[i] & 0xFFFF0000u);
+          for (int i = 0; i < 4; ++i) {  // columns 8 cg + 2 i and + 2 i + 1, column n in slot n
+            blk[(8 * cg + 2 * i) * 4] = (w0[i] & 0xFFFFu) | (w1[i] << 16);
+            blk[(8 * cg + 2 * i + 1) * 4] = (w0[i] >> 16) | (w1[i] & 0xFFFF0000u);
           }
         }
       }
@@ -324,21 +377,22 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
       const int step = cb * XB + i;  // steps past the slice multiply zeros
 #pragma unroll
       for (int t = 0; t < NTILE; ++t) {
+        // A_i^T first: D[column 16 t + 4 g + i][token m], four consecutive columns of a row per lane
         const uint4 bt = *reinterpret_cast<const uint4*>(&at[((step * 4 + g) * BLK + t * 16 + m) * 4]);
-        acc[t] = mfma16x16x32<DT>(q[i], bt, acc[t]);
+        acc[t] = mfma16x16x32<DT>(bt, q[i], acc[t]);
       }
     }
-    if (cb == nb - 1) {
-      // D[row 4g+i][slot m] of every tile; slot p holds column 8 (p % CG) + p / CG
+    if (cb == nb - 1 && cj < my_tiles) {
+      // lane (m, g): row m of the tile, columns 16 t + 4 g .. + 3 of every column tile: the
+      // wave's stores cover the tile's rows in runs of 64 contiguous bytes (all of it, 1 KiB
+      // contiguous, at rank 16)
       const int row0 = lo + ((int)blockIdx.y + cj * (int)gridDim.y) * ROWS + wave * 16;
 #pragma unroll
       for (int t = 0; t < NTILE; ++t) {
-        const int p = t * 16 + m;
-        const int n = (p % CG) * 8 + p / CG;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int row = row0 + 4 * g + i;
-          if (p < R && row < hi) partials[((long long)s * n_tokens + row) * R + n] = acc[t][i];
+        const int n = t * 16 + 4 * g;
+        if (n < R && row0 + m < hi) {
+          float* dst = &partials[((long long)s * n_tokens + row0 + m) * R + n];
+          *reinterpret_cast<float4*>(dst) = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
         }
       }
     }
@@ -354,82 +408,38 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
       ++lj;
     }
   };
-  // steady state without conditions around the loads, so that waiting for one bank
-  // leaves the other's eight loads in flight
-  int i = 0;
-  for (; i + 3 < total; i += 2) {
+  // No conditions around the loads, so that waiting for one bank leaves the other's eight
+  // loads in flight: the sequence is padded to pairs with banks that load and store
+  // nothing (past the wave's last tile), which cost a few matrix-core steps on zeros.
+  for (int i = 0; i < total; i += 2) {
     consume(q0);
     refill(q0);
     consume(q1);
     refill(q1);
   }
   SGMV_TRACE_POINT(4);
-  const int rem = total - i;  // 0..3 banks left
-  if (rem > 0) consume(q0);
-  if (rem > 2) refill(q0);
-  if (rem > 1) consume(q1);
-  if (rem > 2) consume(q0);
   SGMV_TRACE_POINT(5);
   SGMV_TRACE_FLUSH(tid == 0, 0, 5);
 }
 
 // ---------------------------------------------------------------- expand
 
-// v[row][k] = sum over the split-K parts (ascending), written out as the two
-// 16-bit operands the expand kernel feeds to the matrix cores:
-//   vh, vl  [n_tokens][R] 16-bit, undo [n_tokens] fp32.
-// binary16 has a narrow range, so for F16 a row whose largest |v| reaches 2^14 is
-// scaled down by an exact power of two; `undo` is the factor that restores the
-// fp32 result (1 otherwise).  One thread handles four consecutive k of a row, with the
-// loads of sixteen parts in flight together: the kernel is one memory latency long.
+// v[row][k] = sum over the split-K parts (ascending), written out as the two 16-bit
+// operands the expand kernel feeds to the matrix cores: vh, vl [n_tokens][R] 16-bit,
+// undo [n_tokens] fp32 (finalize_quad).  One thread handles four consecutive k of a row;
+// the kernel is one memory latency long.  Used when the shrink launch did not prepare them.
 template <class DT, int R>
 __global__ __launch_bounds__(256) void finalize_v_kernel(
     const float* __restrict__ v_parts, int nparts, uint16_t* __restrict__ vh,
     uint16_t* __restrict__ vl, float* __restrict__ undo, int n_tokens) {
-  constexpr int GPR = R / 4;   // threads per row
-  constexpr int PB = 16;       // parts per batch
+  constexpr int GPR = R / 4;  // threads per row
   const long long item = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   const long long total = (long long)n_tokens * GPR;
   const bool live = item < total;
-  const long long e0 = (live ? item : total - 1) * 4;  // first element (row * R + k)
-  const long long pstride = (long long)n_tokens * R;
-  float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int pb = 0; pb < nparts; pb += PB) {
-    float4 q[PB];
-#pragma unroll
-    for (int i = 0; i < PB; ++i)
-      q[i] = *reinterpret_cast<const float4*>(v_parts + min(pb + i, nparts - 1) * pstride + e0);
-#pragma unroll
-    for (int i = 0; i < PB; ++i) {  // added in ascending order
-      if (pb + i < nparts) {
-        sum.x += q[i].x; sum.y += q[i].y; sum.z += q[i].z; sum.w += q[i].w;
-      }
-    }
-  }
-  float f[4] = {sum.x, sum.y, sum.z, sum.w};
-  float un = 1.f;
-  if (std::is_same<DT, F16>::value) {
-    float amax = 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) amax = fmaxf(amax, fabsf(f[i]));
-#pragma unroll
-    for (int msk = 1; msk < GPR; msk <<= 1) amax = fmaxf(amax, __shfl_xor(amax, msk, 64));  // the row's threads
-    if (amax >= 16384.f && amax < 3.0e38f) {
-      const int e = ((__float_as_uint(amax) >> 23) & 0xFF) - 127 - 13;  // amax * 2^-e < 2^14
-      const float down = __uint_as_float((uint32_t)(127 - e) << 23);
-      un = __uint_as_float((uint32_t)(127 + e) << 23);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) f[i] *= down;
-    }
-  }
-  uint32_t h[4], l[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) split16<DT>(f[i], h[i], l[i]);
-  if (live) {
-    *reinterpret_cast<uint2*>(vh + e0) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
-    *reinterpret_cast<uint2*>(vl + e0) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
-    if (item % GPR == 0) undo[item / GPR] = un;
-  }
+  const long long it = live ? item : total - 1;
+  const long long e0 = it * 4;  // first element (row * R + k)
+  finalize_quad<DT, R>(v_parts + e0, nparts, (long long)n_tokens * R, live, vh + e0, vl + e0,
+                       undo + it / GPR, it % GPR == 0);
 }
 
 // grid = (column strips, row blocks of rows_per_wg rows, n_segs); the row-block dimension
@@ -714,7 +724,7 @@ static hipError_t launch_expand_matrix_t(const ExpandArgs& a, hipStream_t st) {
   const long long items = (long long)a.n_tokens * (R / 4);
   hipLaunchKernelGGL((finalize_v_kernel<DT, R>), dim3((unsigned)((items + 255) / 256)), dim3(256), 0,
                      st, a.v_parts, a.nparts, a.vh, a.vl, a.undo, a.n_tokens);
-  hipError_t err = hipGetLastError();
+  const hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   hipLaunchKernelGGL((expand_matrix_kernel<DT, R>), grid, dim3(256), 0, st, (uint16_t*)a.y, a.vh,
                      a.vl, a.undo, (const uint16_t* const*)a.A_ptrs,
