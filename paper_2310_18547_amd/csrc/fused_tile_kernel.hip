@@ -288,32 +288,35 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
     a1[b] = buffer_load128(rA, o + (uint32_t)R * 2u);
   }
   __builtin_amdgcn_sched_barrier(0);  // keep x and A ahead of B and y in the memory pipe
-  const float inv_ncg = 1.0f / (float)ncg;
-  // (the division sits here, behind the x and A loads, so that it does not delay them)
-  b_step_kp = (int)(((float)NT + 0.5f) * inv_ncg);  // NT / ncg, wave-uniform
-  b_step_cg = NT - b_step_kp * ncg;
-  b_kp = (int)(((float)tid + 0.5f) * inv_ncg);      // tid / ncg, exact for these sizes
-  b_cg = tid - b_kp * ncg;
   uint4 b0[BB], b1[BB];
   int bkp[BB], bcg[BB];
-#pragma unroll
-  for (int b = 0; b < BB; ++b) {
-    const uint32_t o = b_offset();
-    bkp[b] = b_kp;
-    bcg[b] = b_cg;
-    b0[b] = buffer_load128(rB, o);
-    b1[b] = buffer_load128(rB, o + row_bytes_out);
-    b_next();
-  }
   uint4 yq[YB][2];
-  {
+  auto issue_b_y = [&]() {
+    const float inv_ncg = 1.0f / (float)ncg;
+    // (the division sits here, behind the x and A loads, so that it does not delay them)
+    b_step_kp = (int)(((float)NT + 0.5f) * inv_ncg);  // NT / ncg, wave-uniform
+    b_step_cg = NT - b_step_kp * ncg;
+    b_kp = (int)(((float)tid + 0.5f) * inv_ncg);      // tid / ncg, exact for these sizes
+    b_cg = tid - b_kp * ncg;
+#pragma unroll
+    for (int b = 0; b < BB; ++b) {
+      const uint32_t o = b_offset();
+      bkp[b] = b_kp;
+      bcg[b] = b_cg;
+      b0[b] = buffer_load128(rB, o);
+      b1[b] = buffer_load128(rB, o + row_bytes_out);
+      b_next();
+    }
     const __amdgpu_buffer_rsrc_t rY = y_rsrc(row_first, nrows_first);
 #pragma unroll
     for (int gi = 0; gi < YB; ++gi) {
       yq[gi][0] = buffer_load128(rY, y_offset(wave + NW * gi, 0, nrows_first));
       yq[gi][1] = buffer_load128(rY, y_offset(wave + NW * gi, 1, nrows_first));
     }
-  }
+  };
+  // (issuing B and y only after the A slice is staged was measured: the partial sums are
+  // published no earlier and the expand starts later)
+  issue_b_y();
   __builtin_amdgcn_sched_barrier(0);
   SGMV_TRACE_POINT(1);
 
