@@ -188,25 +188,38 @@ bool choose_tile(const sgmv_problem* p, int n_segs, TileArgs* t) {
   if (p->max_seg_len <= 0 || p->max_seg_len > kTileMaxSegLen) return false;
   if (n_segs > kFusedMaxWorkgroups) return false;
   const int cap = split_cap(p->n_tokens);
+  const int narrow = p->h_in < p->h_out ? p->h_in : p->h_out;
   int z = ceil_div(p->max_seg_len, 16);
   if ((long long)n_segs * z > kFusedWorkgroups) z = kFusedWorkgroups / n_segs > 0 ? kFusedWorkgroups / n_segs : 1;
-  int s = p->ksplit > 0 ? p->ksplit : kFusedWorkgroups / (n_segs * z);
-  if (p->ksplit == 0 && s > kFusedSlices) s = kFusedSlices;
-  const int narrow = p->h_in < p->h_out ? p->h_in : p->h_out;
-  if (s > narrow / 64) s = narrow / 64;  // no slice thinner than 64
-  if (s > cap) s = cap;
-  if (s < 1) s = 1;
-  // more slices make the LDS-resident weight slices smaller
-  for (;; ++s) {
-    t->kslice = ceil_div(ceil_div(p->h_in, s), 32) * 32;
-    t->cslice = ceil_div(ceil_div(p->h_out, s), 64) * 64;
-    t->lds_bytes = tile_lds_bytes(p->r, t->kslice, t->cslice);
-    if (t->lds_bytes <= kTileMaxLds) break;
-    if (p->ksplit > 0 || s + 1 > cap || (long long)(s + 1) * n_segs * z > kFusedWorkgroups) return false;
+  // Every workgroup of the launch is resident at once: n_segs * z * s <= 256.  (Fewer row
+  // blocks per segment than the longest one needs would leave room for more slices where
+  // the weight slices do not fit the LDS, but workgroups that walk several blocks in turn
+  // measured slower than the launch-per-step kernels.)
+  {
+    int s = p->ksplit > 0 ? p->ksplit : kFusedWorkgroups / (n_segs * z);
+    if (p->ksplit == 0 && s > kFusedSlices) s = kFusedSlices;
+    if (s > narrow / 64) s = narrow / 64;  // no slice thinner than 64
+    if (s > cap) s = cap;
+    if (s < 1) s = 1;
+    if ((long long)s * n_segs * z > kFusedWorkgroups) return false;  // (a forced slice count)
+    bool fits = false;
+    for (;; ++s) {  // more slices make the LDS-resident weight slices smaller
+      t->kslice = ceil_div(ceil_div(p->h_in, s), 32) * 32;
+      t->cslice = ceil_div(ceil_div(p->h_out, s), 64) * 64;
+      t->lds_bytes = tile_lds_bytes(p->r, t->kslice, t->cslice);
+      if (t->lds_bytes <= kTileMaxLds) {
+        fits = true;
+        break;
+      }
+      if (p->ksplit > 0 || s + 1 > cap || (long long)(s + 1) * n_segs * z > kFusedWorkgroups) break;
+    }
+    if (fits) {
+      t->S = s;
+      t->Z = z;
+      return true;
+    }
   }
-  t->S = s;
-  t->Z = z;
-  return true;
+  return false;
 }
 
 void fill_fused(FusedArgs* f, const sgmv_problem* p, const int32_t* seg_starts, int n_segs,

@@ -32,6 +32,7 @@
 // part (two MFMAs, ~16-22 significant bits); for binary16 a row whose |v|
 // reaches 2^14 is scaled by an exact power of two that the epilogue undoes.
 // All barriers order LDS only, so outstanding global loads are never drained.
+#include <atomic>
 #include <type_traits>
 
 #include "device_common.h"
@@ -536,16 +537,16 @@ template <class DT, int R>
 static hipError_t launch_tile_t(const TileArgs& a, hipStream_t st) {
   auto kernel = add_lora_tile_kernel<DT, R>;
   // LDS beyond 64 KiB per workgroup has to be enabled per kernel, once per device
-  static bool enabled[64] = {};
+  static std::atomic<bool> enabled[64];  // zero-initialised; setting the attribute twice is harmless
   int dev = 0;
   hipError_t err = hipGetDevice(&dev);
   if (err != hipSuccess) return err;
   if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-  if (!enabled[dev]) {
+  if (!enabled[dev].load(std::memory_order_acquire)) {
     err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kTileMaxLds);
     if (err != hipSuccess) return err;
-    enabled[dev] = true;
+    enabled[dev].store(true, std::memory_order_release);
   }
   hipLaunchKernelGGL(kernel, dim3((unsigned)a.S, (unsigned)a.n_segs, (unsigned)a.Z), dim3(320),
                      a.lds_bytes, st, a.seg_starts, (const uint16_t* const*)a.A_ptrs,

@@ -31,6 +31,7 @@
 //           y is read and written with 128-bit accesses.  v stays fp32 in the
 //           workspace; it enters the matrix cores as a high and a low 16-bit
 //           part (two MFMAs), which keeps ~16 significant bits.
+#include <atomic>
 #include <type_traits>
 
 #include "device_common.h"
@@ -668,15 +669,17 @@ static hipError_t launch_shrink_matrix_t(const ShrinkArgs& a, hipStream_t st) {
   if (shrink_stream_fits(a)) {
     grid.y = row_blocks(a.max_seg_len, a.n_tokens, 16 * stream_waves(R));
     auto kernel = shrink_stream_kernel<DT, R>;
-    static bool enabled[64] = {};  // more than 64 KiB of dynamic LDS is enabled once per device
+    // more than 64 KiB of dynamic LDS is enabled once per device (zero-initialised flags;
+    // setting the attribute twice is harmless)
+    static std::atomic<bool> enabled[64];
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-    if (!enabled[dev]) {
+    if (!enabled[dev].load(std::memory_order_acquire)) {
       const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                                hipFuncAttributeMaxDynamicSharedMemorySize,
                                                (int)kStreamMaxLds);
       if (e != hipSuccess) return e;
-      enabled[dev] = true;
+      enabled[dev].store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(kernel, grid, dim3(64 * stream_waves(R)), shrink_stream_lds_bytes(R, a.kslice), st,
                        (const uint16_t*)a.x, (const uint16_t* const*)a.A_ptrs, a.seg_starts, a.partials,

@@ -220,3 +220,13 @@ def test_plan_agrees_with_the_resource_limits():
                         assert pl.workgroups <= 256 and pl.lds_bytes <= 160 * 1024
                 else:
                     assert pl.kernel in (sg.KERNEL_VECTOR, sg.KERNEL_MATRIX)
+
+
+def test_plan_tile_needs_resident_workgroups_and_lds():
+    # 32 segments of up to 64 rows: four row blocks per segment leave two slices, whose weight
+    # slices do not fit the LDS: the launch-per-step kernels take the call
+    rc, pl = _plan(32, n_tokens=248, max_seg_len=64)
+    assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX
+    # a forced slice count that cannot be resident is not taken by the single-launch kernels
+    rc, pl = _plan(64, n_tokens=640, max_seg_len=29, ksplit=8, path=sg.PATH_FUSED)
+    assert rc == 3
