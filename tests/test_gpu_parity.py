@@ -643,3 +643,12 @@ def test_matrix_path_guard_rows_are_not_written(r):
     assert np.all(host[:2 * H] == 0x5A5A) and np.all(host[(T + 2) * H:] == 0x5A5A)
     assert_parity(host[2 * H:(T + 2) * H].reshape(T, H).view(np.uint16), oracle.run_workload(w),
                   "bf16", "guarded y, matrix path")
+
+
+@pytest.mark.parametrize("h_in,h_out,r", [(8, 8, 8), (40, 24, 16), (16, 520, 64), (264, 8, 32)])
+def test_matrix_path_narrow_widths(h_in, h_out, r):
+    # widths far below one k-step (32) or one column strip (256): everything past the edge is masked
+    w = wl.custom([19, 2, 33], h_in, h_out, r, "f16", seed=90 + r)
+    d = _matrix(w)
+    d.add_lora()
+    assert_parity(d.y_bits(), oracle.run_workload(w), "f16", f"matrix {h_in}->{h_out} r={r}")
