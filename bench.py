@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a
 # 64 MiB + 64 MiB copy kernel), from the summaries under profiles/; reported as roofline.traffic
-MEASURED_TRAFFIC = {"distinct_b64": 18738076.0}
+MEASURED_TRAFFIC = {"distinct_b64": 18736662.0}
 
 # the paper's own latencies for this operator (one A100 80 GB, fp16, r = 16), context only
 PAPER_A100_US = {"distinct_b64": [116.0, 75.0], "distinct_b1": [37.0, 42.0]}

@@ -25,6 +25,8 @@
 //
 // The segment lookup (row range and weight pointers) is resolved once per
 // workgroup from wave-uniform values.
+#include <type_traits>
+
 #include "device_common.h"
 #include "launch.h"
 
@@ -164,7 +166,8 @@ __global__ __launch_bounds__(NT) void shrink_vector_kernel(
 
 // v[row][j] += sum over slices of partials[s][row][j], slices in ascending order.
 // grid = (n_segs, chunks): the chunk dimension strides over the segment's elements,
-// four per thread; rows of segments without an adapter are left alone.
+// four per thread, up to sixteen slices' loads in flight; rows of segments without an
+// adapter are left alone.
 template <int R>
 __global__ __launch_bounds__(256) void shrink_reduce_kernel(
     float* __restrict__ v, const float* __restrict__ partials,
@@ -178,20 +181,28 @@ __global__ __launch_bounds__(256) void shrink_reduce_kernel(
   for (long long i = ((long long)blockIdx.y * blockDim.x + threadIdx.x) * 4; i < count;
        i += (long long)gridDim.y * blockDim.x * 4) {
     float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int s0 = 0; s0 < ksplit; s0 += 4) {  // four slices' loads in flight together, added in order
-      float4 q[4];
+    float4 cur = *reinterpret_cast<const float4*>(v + first + i);  // in flight with the first batch
+    // SB slices' loads in flight together, added in order
+    auto add_slices = [&](auto sb_tag) {
+      constexpr int SB = decltype(sb_tag)::value;
+      for (int s0 = 0; s0 < ksplit; s0 += SB) {
+        float4 q[SB];
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        q[j] = *reinterpret_cast<const float4*>(partials + (long long)min(s0 + j, ksplit - 1) * pstride + first + i);
+        for (int j = 0; j < SB; ++j)
+          q[j] = *reinterpret_cast<const float4*>(partials + (long long)min(s0 + j, ksplit - 1) * pstride + first + i);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if (s0 + j < ksplit) {
-          sum.x += q[j].x; sum.y += q[j].y; sum.z += q[j].z; sum.w += q[j].w;
+        for (int j = 0; j < SB; ++j) {
+          if (s0 + j < ksplit) {
+            sum.x += q[j].x; sum.y += q[j].y; sum.z += q[j].z; sum.w += q[j].w;
+          }
         }
       }
-    }
+    };
+    if (ksplit <= 4)
+      add_slices(std::integral_constant<int, 4>{});
+    else
+      add_slices(std::integral_constant<int, 16>{});
     float4* dst = reinterpret_cast<float4*>(v + first + i);
-    float4 cur = *dst;
     cur.x += sum.x; cur.y += sum.y; cur.z += sum.z; cur.w += sum.w;
     *dst = cur;
   }
