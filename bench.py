@@ -74,8 +74,11 @@ def cpu_baseline(w, budget_s: float):
         el = time.perf_counter() - t0
         if el >= budget_s or calls >= 2000:
             break
-    return {"value": calls / el, "unit": "add_lora calls/s", "cores": cores, "kind": "oracle",
-            "us_per_call": el / calls * 1e6,
+    from paper_2310_18547_amd import accounting as acc
+    by = acc.algorithmic_bytes("add_lora", w.n_tokens, w.n_distinct, w.h_in, w.h_out, w.r)
+    # the metric's unit: algorithmic bytes of the same call per second
+    return {"value": by * calls / el / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "us_per_call": el / calls * 1e6, "calls_per_s": calls / el,
             "sample": f"{calls} add_lora calls of the same workload ({w.name}), layers cycled, "
                       f"fp32 accumulation, rows split over {cores} threads"}
 
