@@ -84,9 +84,10 @@ typedef enum {
   SGMV_PATH_VECTOR = 1,      /* bandwidth path: vector ALU, one launch per step    */
   SGMV_PATH_MATRIX = 2,      /* MFMA path: for long (prefill-like) segments        */
   SGMV_PATH_FUSED = 3        /* sgmv_add_lora only: shrink and expand in a single  */
-                             /* launch; needs workspace_ready and 0 < max_seg_len  */
-                             /* <= 64 (and, beyond one row per segment, weight     */
-                             /* slices that fit the LDS), else SGMV_ERR_UNSUPPORTED*/
+                             /* launch; needs workspace_ready, max_seg_len > 0 and */
+                             /* a launch whose workgroups (segments x sixteen-row  */
+                             /* blocks x slices) are all resident with their weight*/
+                             /* slices in LDS, else SGMV_ERR_UNSUPPORTED           */
 } sgmv_path;
 
 /* Problem descriptor: plain data, host memory, read during the call only. */
@@ -192,10 +193,11 @@ int sgmv_expand(const sgmv_problem* p, void* y, const float* v,
 /* The whole LoRA add-on, y += scale * (x A_i) B_i per segment, i.e. v := 0,
  * shrink, expand in one call; v lives in the workspace in fp32 and is never
  * rounded.  A segment is skipped when either of its pointers is NULL.
- * With workspace_ready set and 0 < max_seg_len <= 64 both steps run in a
- * single kernel launch (vector ALUs for one row per segment, matrix cores on
- * sixteen-row tiles otherwise); longer segments, or no hint, take one launch
- * per step. */
+ * With workspace_ready set and a max_seg_len hint both steps run in a single
+ * kernel launch where that launch fits the chip (vector ALUs for one row per
+ * segment; matrix cores on sixteen-row tiles otherwise, up to about 64 such
+ * tiles in all at h = 4096); larger batches of long segments, or no hint, take
+ * one launch per step.  sgmv_plan_add_lora tells which. */
 int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x,
                   const void* const* A_ptrs, const void* const* B_ptrs,
                   const int32_t* seg_starts, int32_t n_segs, int32_t layer_idx,

@@ -13,7 +13,10 @@ using namespace sgmv;
 
 constexpr int kMinSplitCap = 16;       // the workspace always allows this many slices
 constexpr int kTargetWorkgroups = 512; // about two workgroups per compute unit
-constexpr int kTileMaxSegLen = 64;     // longest segment the single-launch MFMA kernel is used for
+// Longest segment the single-launch MFMA kernel is considered for.  What really limits it is
+// that every (segment, sixteen-row block, slice) workgroup must be resident at once with its
+// weight slices in LDS (choose_tile): about 64 row blocks in all at h = 4096.
+constexpr int kTileMaxSegLen = 4096;
 constexpr int kFusedSlices = 8;        // most slices per segment the single-launch kernels pick
 constexpr int kFusedWorkgroups = 256;  // one workgroup per compute unit
 constexpr int kFusedMaxWorkgroups = 1024;

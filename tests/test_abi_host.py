@@ -100,7 +100,7 @@ def test_argument_errors_are_reported_without_a_device():
     assert _add(_prob(path=9)) == 3
     assert _add(_prob(path=sg.PATH_FUSED)) == 3            # workspace not declared ready
     assert _add(_prob(path=sg.PATH_FUSED, workspace_ready=1, max_seg_len=0)) == 3
-    assert _add(_prob(path=sg.PATH_FUSED, workspace_ready=1, max_seg_len=65)) == 3
+    assert _add(_prob(path=sg.PATH_FUSED, workspace_ready=1, max_seg_len=5000)) == 3
     assert sg.sgmv_workspace_init(None, 1024, check=False) == 1
     assert sg.sgmv_workspace_init(FAKE + 8, 1024, check=False) == 4
     assert sg.sgmv_workspace_check(None) == 1
@@ -179,7 +179,14 @@ def test_plan_single_launch_shapes():
     rc, pl = _plan(64, n_tokens=64, max_seg_len=1, path=sg.PATH_MATRIX)
     assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX
     rc, pl = _plan(4, n_tokens=400, max_seg_len=100, path=sg.PATH_FUSED)
-    assert rc == 3                                   # unsupported: too long for a tile launch
+    assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.workgroups == 8 * 4 * 7
+    rc, pl = _plan(4, n_tokens=3450, max_seg_len=891, path=sg.PATH_FUSED)
+    assert rc == 3                                   # unsupported: too many row blocks to be resident
+    # a few long segments still fit one launch
+    rc, pl = _plan(1, n_tokens=1024, max_seg_len=1024)
+    assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.slices == 4 and pl.workgroups == 256
+    rc, pl = _plan(4, n_tokens=2048, max_seg_len=512)
+    assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX
     # nothing to do
     rc, pl = _plan(0, n_tokens=0)
     assert rc == 0 and pl.kernel == sg.KERNEL_NONE and pl.launches == 0

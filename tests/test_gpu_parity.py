@@ -652,3 +652,16 @@ def test_matrix_path_narrow_widths(h_in, h_out, r):
     d = _matrix(w)
     d.add_lora()
     assert_parity(d.y_bits(), oracle.run_workload(w), "f16", f"matrix {h_in}->{h_out} r={r}")
+
+
+@pytest.mark.parametrize("lens,r,dtype", [([300, 17], 16, "f16"), ([1024], 16, "bf16"), ([130, 129, 1, 64], 64, "bf16"),
+                                          ([257], 8, "f16")])
+def test_tile_kernel_takes_a_few_long_segments(lens, r, dtype):
+    # many sixteen-row blocks per segment (grid z up to 64), every workgroup resident
+    from paper_2310_18547_amd import binding as B
+    w = wl.custom(lens, 1024, 1096, r, dtype, seed=95 + r, num_layers=2)
+    d = _dev(w)
+    assert B.sgmv_plan_add_lora(d.problem, w.n_segs, 1).kernel == B.KERNEL_TILE
+    d.add_lora(1)
+    assert_parity(d.y_bits(), oracle.run_workload(w, layer_idx=1, n_threads=8), dtype, f"tile, long segments {lens}")
+    assert d.check() == 0
