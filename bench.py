@@ -33,6 +33,7 @@ HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a
 # 64 MiB + 64 MiB copy kernel), from the summaries under profiles/; reported as roofline.traffic
 MEASURED_TRAFFIC = {"distinct_b64": 18736662.0}
+MFMA_PEAK_TFLOPS = 2500.0   # dense bf16 / fp16, MI355X
 
 # the paper's own latencies for this operator (one A100 80 GB, fp16, r = 16), context only
 PAPER_A100_US = {"distinct_b64": [116.0, 75.0], "distinct_b1": [37.0, 42.0]}
@@ -238,7 +239,7 @@ def main():
               B.KERNEL_MULTI_SIDE: "add_lora_fused_side_kernel",
               B.KERNEL_MULTI_PIPELINED: "add_lora_fused_multi_kernel",
               B.KERNEL_VECTOR: "shrink_vector_kernel + expand_vector_kernel",
-              B.KERNEL_MATRIX: "shrink_matrix_kernel + finalize_v_kernel + expand_matrix_kernel",
+              B.KERNEL_MATRIX: "shrink_stream_kernel + finalize_v_kernel + expand_matrix_kernel",
               }[plan.kernel]
     launches = plan.launches
     traffic = args.traffic_bytes
@@ -275,6 +276,13 @@ def main():
         "paper_a100_us": PAPER_A100_US.get(args.workload),
         "block_ms": times,
     }
+    if plan.kernel in (B.KERNEL_MATRIX, B.KERNEL_TILE):
+        # the contraction runs on the matrix cores; at r FLOP per byte of x and r/2 per byte of
+        # y it sits far left of the MFMA ridge (~312 FLOP/B), so HBM stays the binding roofline
+        tf = out["config"]["flops_per_step"] / (ms_per_step * 1e-3) / 1e12
+        out["roofline"]["mfma"] = {"achieved": tf, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                   "frac": tf / MFMA_PEAK_TFLOPS,
+                                   "flop_per_byte": out["config"]["flops_per_step"] / bytes_step}
     if args.compare:
         out["comparators"] = time_comparators(d, w, stream, L, S)
     if not args.no_cpu_baseline:
