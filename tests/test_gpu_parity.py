@@ -665,3 +665,19 @@ def test_tile_kernel_takes_a_few_long_segments(lens, r, dtype):
     d.add_lora(1)
     assert_parity(d.y_bits(), oracle.run_workload(w, layer_idx=1, n_threads=8), dtype, f"tile, long segments {lens}")
     assert d.check() == 0
+
+
+@pytest.mark.parametrize("n_segs,seg_len,expect", [(2500, 1, "vector"), (1100, 2, "vector"), (300, 5, "matrix"),
+                                                   (512, 1, "fused"), (1024, 1, "vector"), (256, 3, "tile")])
+def test_many_segments_take_a_path_that_fits(n_segs, seg_len, expect):
+    # more segments than the single-launch kernels can keep resident: the call still resolves
+    # to a kernel family that covers it (seven adapters shared by all segments)
+    from paper_2310_18547_amd import binding as B
+    rng = np.random.default_rng(5)
+    w = wl.custom([seg_len] * n_segs, 256, 264, 16, "f16", seed=99,
+                  seg_adapter=rng.integers(0, 7, n_segs).tolist())
+    d = _dev(w)
+    assert B.KERNEL_NAMES[B.sgmv_plan_add_lora(d.problem, w.n_segs, 1).kernel] == expect
+    d.add_lora()
+    assert_parity(d.y_bits(), oracle.run_workload(w, n_threads=8), "f16", f"{n_segs} segments of {seg_len}")
+    assert d.check() == 0
