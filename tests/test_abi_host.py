@@ -155,8 +155,15 @@ def _plan(n_segs, n_proj=1, **kw):
 def test_plan_single_launch_shapes():
     """Launch policy of sgmv_add_lora, asked of the library (host-only, no device)."""
     # one row per segment: the row kernel, S a power of two with S * segments <= 256 units
-    # (256 rows of 4096: two slices, since a slice holds at most 2048 input features)
-    for batch, S in ((1, 8), (8, 8), (16, 8), (32, 8), (48, 4), (64, 4), (128, 2), (256, 2)):
+    # (beyond 128 rows of 4096 features, which would need two slices each and two workgroups per
+    # unit, the launch-per-step kernels are faster; a forced path still takes the single launch)
+    rc, pl = _plan(256, n_tokens=256, max_seg_len=1)
+    assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR
+    rc, pl = _plan(256, n_tokens=256, max_seg_len=1, path=sg.PATH_FUSED)
+    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and (pl.slices, pl.workgroups) == (2, 512)
+    rc, pl = _plan(256, n_tokens=256, max_seg_len=1, h_in=2048)
+    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and (pl.slices, pl.workgroups) == (1, 256)
+    for batch, S in ((1, 8), (8, 8), (16, 8), (32, 8), (48, 4), (64, 4), (128, 2)):
         rc, pl = _plan(batch, n_tokens=batch, max_seg_len=1)
         assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and pl.launches == 1
         assert (pl.slices, pl.workgroups) == (S, S * batch), (batch, pl.slices)
