@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a
 # 64 MiB + 64 MiB copy kernel), from the summaries under profiles/; reported as roofline.traffic
-MEASURED_TRAFFIC = {"distinct_b64": 18736662.0}
+MEASURED_TRAFFIC = {"distinct_b64": 18733837.0}
 MFMA_PEAK_TFLOPS = 2500.0   # dense bf16 / fp16, MI355X
 
 # the paper's own latencies for this operator (one A100 80 GB, fp16, r = 16), context only
