@@ -17,6 +17,10 @@ constexpr int kTargetWorkgroups = 512; // about two workgroups per compute unit
 // that every (segment, sixteen-row block, slice) workgroup must be resident at once with its
 // weight slices in LDS (choose_tile): about 64 row blocks in all at h = 4096.
 constexpr int kTileMaxSegLen = 4096;
+// Workgroups of a tile launch, those without rows included: launches with many more than one
+// per compute unit measured slower than the launch-per-step kernels (456 workgroups for 171
+// with rows: 25.8 us against 14.8 us) even though the surplus leaves at once.
+constexpr int kTileMaxGrid = 320;
 constexpr int kFusedSlices = 8;        // most slices per segment the single-launch kernels pick
 constexpr int kFusedWorkgroups = 256;  // one workgroup per compute unit
 constexpr int kFusedMaxWorkgroups = 1024;
@@ -198,36 +202,36 @@ bool choose_tile(const sgmv_problem* p, int n_segs, TileArgs* t) {
   const int cap = split_cap(p->n_tokens);
   const int narrow = p->h_in < p->h_out ? p->h_in : p->h_out;
   int z = ceil_div(p->max_seg_len, 16);
-  if ((long long)n_segs * z > kFusedWorkgroups) z = kFusedWorkgroups / n_segs > 0 ? kFusedWorkgroups / n_segs : 1;
-  // Every workgroup of the launch is resident at once: n_segs * z * s <= 256.  (Fewer row
-  // blocks per segment than the longest one needs would leave room for more slices where
-  // the weight slices do not fit the LDS, but workgroups that walk several blocks in turn
-  // measured slower than the launch-per-step kernels.)
-  {
-    int s = p->ksplit > 0 ? p->ksplit : kFusedWorkgroups / (n_segs * z);
-    if (p->ksplit == 0 && s > kFusedSlices) s = kFusedSlices;
-    if (s > narrow / 64) s = narrow / 64;  // no slice thinner than 64
-    if (s > cap) s = cap;
-    if (s < 1) s = 1;
-    if ((long long)s * n_segs * z > kFusedWorkgroups) return false;  // (a forced slice count)
-    bool fits = false;
-    for (;; ++s) {  // more slices make the LDS-resident weight slices smaller
-      t->kslice = ceil_div(ceil_div(p->h_in, s), 32) * 32;
-      t->cslice = ceil_div(ceil_div(p->h_out, s), 64) * 64;
-      t->lds_bytes = tile_lds_bytes(p->r, t->kslice, t->cslice);
-      if (t->lds_bytes <= kTileMaxLds) {
-        fits = true;
-        break;
-      }
-      if (p->ksplit > 0 || s + 1 > cap || (long long)(s + 1) * n_segs * z > kFusedWorkgroups) break;
-    }
-    if (fits) {
-      t->S = s;
-      t->Z = z;
-      return true;
-    }
+  // The launch has n_segs * z row blocks, but only those that hold rows keep a compute unit
+  // (the others leave at once): at most n_segs + n_tokens / 16 of them.  These, times the
+  // slices, must all be resident together (one workgroup per unit).
+  long long blocks = (long long)n_segs * z;
+  long long live = blocks < (long long)n_segs + p->n_tokens / 16 ? blocks : (long long)n_segs + p->n_tokens / 16;
+  if (live > kFusedWorkgroups) {  // too many even with one slice: fewer row blocks, walked with a stride
+    z = kFusedWorkgroups / n_segs > 0 ? kFusedWorkgroups / n_segs : 1;
+    blocks = live = (long long)n_segs * z;
   }
-  return false;
+  // (Fewer row blocks per segment than the longest one needs would leave room for more slices
+  // where the weight slices do not fit the LDS, but workgroups that walk several blocks in turn
+  // measured slower than the launch-per-step kernels.)
+  int s = p->ksplit > 0 ? p->ksplit : (int)(kFusedWorkgroups / live);
+  if (p->ksplit == 0 && s > kFusedSlices) s = kFusedSlices;
+  if (p->ksplit == 0 && s > kTileMaxGrid / blocks) s = (int)(kTileMaxGrid / blocks);  // workgroups launched in all
+  if (s > narrow / 64) s = narrow / 64;  // no slice thinner than 64
+  if (s > cap) s = cap;
+  if (s < 1) s = 1;
+  if (s * live > kFusedWorkgroups || s * blocks > kTileMaxGrid) return false;
+  for (;; ++s) {  // more slices make the LDS-resident weight slices smaller
+    t->kslice = ceil_div(ceil_div(p->h_in, s), 32) * 32;
+    t->cslice = ceil_div(ceil_div(p->h_out, s), 64) * 64;
+    t->lds_bytes = tile_lds_bytes(p->r, t->kslice, t->cslice);
+    if (t->lds_bytes <= kTileMaxLds) break;
+    if (p->ksplit > 0 || s + 1 > cap || (s + 1) * live > kFusedWorkgroups || (s + 1) * blocks > kTileMaxGrid)
+      return false;
+  }
+  t->S = s;
+  t->Z = z;
+  return true;
 }
 
 void fill_fused(FusedArgs* f, const sgmv_problem* p, const int32_t* seg_starts, int n_segs,

@@ -244,3 +244,13 @@ def test_plan_tile_needs_resident_workgroups_and_lds():
     # a forced slice count that cannot be resident is not taken by the single-launch kernels
     rc, pl = _plan(64, n_tokens=640, max_seg_len=29, ksplit=8, path=sg.PATH_FUSED)
     assert rc == 3
+
+
+def test_plan_tile_counts_only_row_blocks_with_rows():
+    # 17 segments, the longest of 29 rows (two row blocks): 34 blocks in the grid, but at most
+    # 17 + 64/16 = 21 hold rows, so eight slices are resident (8 * 21 <= 256) in a grid of 272
+    rc, pl = _plan(17, n_tokens=64, max_seg_len=29)
+    assert rc == 0 and pl.kernel == sg.KERNEL_TILE and (pl.slices, pl.workgroups) == (8, 272)
+    # a grid far beyond one workgroup per compute unit is not taken
+    rc, pl = _plan(8, n_tokens=1000, max_seg_len=300)
+    assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX
