@@ -74,7 +74,9 @@ typedef enum {
   SGMV_ERR_WORKSPACE = 5,    /* workspace missing or smaller than required         */
   SGMV_ERR_RANGE = 6,        /* layer_idx outside [0, num_layers)                  */
   SGMV_ERR_LAUNCH = 7,       /* the HIP runtime rejected a kernel launch           */
-  SGMV_ERR_TIMEOUT = 8       /* a workgroup gave up waiting (sgmv_workspace_check) */
+  SGMV_ERR_TIMEOUT = 8,      /* a workgroup gave up waiting (sgmv_workspace_check) */
+  SGMV_ERR_STATE = 9         /* workspace never initialised, or its launch counter */
+                             /* is inconsistent (sgmv_workspace_check)             */
 } sgmv_status;
 
 /* Kernel family selection.  AUTO picks from max_seg_len; the others force one
@@ -155,11 +157,13 @@ size_t sgmv_workspace_bytes(int32_t n_tokens, int32_t r);
 int sgmv_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 
 /* Synchronous health check of a workspace used by the single-launch path:
- * waits for `stream`, reads the workspace's error word and returns
+ * waits for `stream`, reads the workspace's header and returns
  * SGMV_ERR_TIMEOUT if any workgroup ever gave up its (bounded) wait for a
- * neighbour's partial sums -- results of that call are then invalid and the
- * workspace must be re-initialised.  Returns SGMV_OK otherwise.  Not meant for
- * the hot path. */
+ * neighbour's partial sums -- results of that call are then invalid -- and
+ * SGMV_ERR_STATE if the workspace was never initialised or the launch counter
+ * is not at a launch boundary (no call may be running on another stream).  In
+ * both cases the workspace must be re-initialised.  Returns SGMV_OK otherwise.
+ * Not meant for the hot path. */
 int sgmv_workspace_check(const void* workspace, void* stream);
 
 /* Host-side check of a HOST copy of the segment index sequence against the

@@ -367,6 +367,7 @@ const char* sgmv_status_string(int status) {
     case SGMV_ERR_RANGE: return "layer_idx out of range";
     case SGMV_ERR_LAUNCH: return "kernel launch failed";
     case SGMV_ERR_TIMEOUT: return "a workgroup gave up waiting for partial sums";
+    case SGMV_ERR_STATE: return "workspace not initialised or its launch accounting is inconsistent";
   }
   return "unknown status";
 }
@@ -390,12 +391,19 @@ int sgmv_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
 int sgmv_workspace_check(const void* workspace, void* stream) {
   if (workspace == nullptr) return SGMV_ERR_NULL;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  unsigned word = 0;
-  const unsigned* src = static_cast<const unsigned*>(workspace) + 2 * kEpochCounters;  // after the epoch counters
-  if (hipMemcpyAsync(&word, src, sizeof word, hipMemcpyDeviceToHost, st) != hipSuccess)
+  // the epoch counters and, right after them, the error word
+  unsigned long long head[kEpochCounters + 1];
+  if (hipMemcpyAsync(head, workspace, sizeof head, hipMemcpyDeviceToHost, st) != hipSuccess)
     return SGMV_ERR_LAUNCH;
   if (hipStreamSynchronize(st) != hipSuccess) return SGMV_ERR_LAUNCH;
-  return word == 0 ? SGMV_OK : SGMV_ERR_TIMEOUT;
+  // between launches the epoch is a whole number of steps; anything else means the workspace was
+  // never initialised, or a launch did not account for all of its workgroups and later launches
+  // may disagree about their generation
+  unsigned long long epoch = 0;
+  for (int i = 0; i < kEpochCounters; ++i) epoch += head[i];
+  if (epoch == 0 || epoch % kEpochStep != 0) return SGMV_ERR_STATE;
+  if ((unsigned)head[kEpochCounters] != 0) return SGMV_ERR_TIMEOUT;
+  return SGMV_OK;
 }
 
 int sgmv_validate_segments(const int32_t* host_seg_starts, int32_t n_segs, int32_t n_tokens) {

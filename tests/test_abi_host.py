@@ -34,8 +34,8 @@ def test_struct_layout_matches_header():
 
 
 def test_status_strings():
-    seen = {sg.sgmv_status_string(i) for i in range(9)}
-    assert len(seen) == 9 and "unknown status" not in seen
+    seen = {sg.sgmv_status_string(i) for i in range(10)}
+    assert len(seen) == 10 and "unknown status" not in seen
     assert sg.sgmv_status_string(99) == "unknown status"
 
 

@@ -274,6 +274,26 @@ def test_fused_every_slice_count(ksplit):
     assert d.check() == 0
 
 
+def test_workspace_check_sees_launch_accounting():
+    # a workspace that was never initialised is reported; after any mix of single-launch kernels
+    # the epoch sits on a launch boundary again (every workgroup accounted for exactly once)
+    from paper_2310_18547_amd import binding as B
+    w = wl.custom([1, 1, 1, 1, 1], 512, 512, 16, "f16", seed=41, num_layers=2)
+    raw = _dev(w, init_workspace=False)
+    assert raw.check() == 9
+    d = _dev(w)
+    assert d.check() == 0
+    for i in range(7):
+        d.add_lora(i % 2)
+    assert d.check() == 0
+    w2 = wl.custom([3, 20, 1, 7], 512, 512, 16, "f16", seed=42, num_layers=2)   # tile kernel, ragged blocks
+    w2.seg_adapter = np.asarray([0, -1, 2, 3], np.int64)                        # and a segment that leaves at once
+    d2 = _dev(w2)
+    for i in range(5):
+        d2.add_lora(i % 2)
+    assert d2.check() == 0
+
+
 def test_fused_counters_reset_between_calls():
     # many back-to-back calls on one workspace: each must see fresh counters
     w = wl.decode_distinct(batch=64, h_in=4096, r=16, dtype="f16", num_layers=4, seed=46)
