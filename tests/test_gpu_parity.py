@@ -701,3 +701,78 @@ def test_many_segments_take_a_path_that_fits(n_segs, seg_len, expect):
     d.add_lora()
     assert_parity(d.y_bits(), oracle.run_workload(w, n_threads=8), "f16", f"{n_segs} segments of {seg_len}")
     assert d.check() == 0
+
+
+# ------------------------------------------------------------------ seeded random shapes
+def _random_case(seed):
+    rng = np.random.default_rng(1000 + seed)
+    r = int(rng.choice([8, 16, 32, 64]))
+    h_in = int(rng.integers(1, 150)) * 8
+    h_out = int(rng.integers(1, 150)) * 8
+    n = int(rng.integers(1, 13))
+    kind = seed % 4
+    if kind == 0:
+        lens = [1] * n                                            # one row per segment
+    elif kind == 1:
+        lens = [int(v) for v in rng.integers(0, 6, n)]            # a few rows, empties
+    elif kind == 2:
+        lens = [int(v) for v in rng.integers(0, 70, n)]           # several row blocks
+    else:
+        lens = [int(v) for v in rng.integers(1, 40, n)]
+        lens[int(rng.integers(0, n))] = int(rng.integers(100, 330))   # one long segment
+    if sum(lens) == 0:
+        lens[0] = 3
+    dtype = "f16" if seed % 2 == 0 else "bf16"
+    adapters = [int(v) for v in rng.integers(-1, 4, n)]           # shared adapters, some missing
+    if all(a < 0 for a in adapters):
+        adapters[0] = 0
+    w = wl.custom(lens, h_in, h_out, r, dtype, seed=2000 + seed, num_layers=2,
+                  scale=float(rng.choice([1.0, 0.5, -2.0])), seg_adapter=adapters)
+    hint = [None, 0, max(1, max(lens) // 3)][int(rng.integers(0, 3))]   # exact, none, too short
+    return w, dtype, hint
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_random_shapes_every_path(seed):
+    from paper_2310_18547_amd import binding as B
+    w, dtype, hint = _random_case(seed)
+    ref = oracle.run_workload(w, layer_idx=1, n_threads=8)
+    for path in (B.PATH_AUTO, B.PATH_VECTOR, B.PATH_MATRIX, B.PATH_FUSED):
+        d = _dev(w, path=path, max_seg_len=hint)
+        try:
+            d.add_lora(1)
+        except B.SgmvError as e:
+            assert path == B.PATH_FUSED and e.status == 3, (seed, path, e)   # single launch not applicable
+            continue
+        assert_parity(d.y_bits(), ref, dtype, f"seed {seed} path {path} hint {hint} lens {w.seg_starts.tolist()}")
+        assert d.check() == 0
+
+
+@pytest.mark.parametrize("seed", range(48, 72))
+def test_random_shapes_two_step_and_multi(seed):
+    from paper_2310_18547_amd import binding as B
+    w, dtype, hint = _random_case(seed)
+    ref = oracle.run_workload(w, layer_idx=1, n_threads=8)
+    v_ref = oracle.run_workload(w, op="shrink", layer_idx=1, n_threads=8)
+    for path in (B.PATH_AUTO, B.PATH_VECTOR, B.PATH_MATRIX):
+        d = _dev(w, path=path, max_seg_len=hint)
+        v = torch.zeros(w.n_tokens, w.r, dtype=torch.float32, device="cuda:0")
+        d.shrink(v, 1)
+        assert np.all(np.abs(v.cpu().numpy() - v_ref) <= 2e-3 + 2e-2 * np.abs(v_ref)), (seed, path)
+        d.expand(v, 1)
+        assert_parity(d.y_bits(), ref, dtype, f"two-step seed {seed} path {path} hint {hint}")
+    # several add-ons of this shape in one call: equal to separate calls, whatever path they take
+    P = 2 + seed % 3
+    ds = [_dev(w, max_seg_len=hint)] + [_dev(wl.custom(np.diff(w.seg_starts).tolist(), w.h_in, w.h_out, w.r, dtype,
+                                                        seed=3000 + seed + k, num_layers=2, scale=w.scale,
+                                                        seg_adapter=w.seg_adapter.tolist()), max_seg_len=hint)
+                                         for k in range(P - 1)]
+    d0 = ds[0]
+    B.sgmv_add_lora_multi(d0.problem, [q.y[0] for q in ds], [q.x[0] for q in ds], [q.A_ptrs for q in ds],
+                          [q.B_ptrs for q in ds], d0.seg_starts, w.n_segs, 1, w.scale)
+    torch.cuda.synchronize()
+    for q in ds:
+        single = _dev(q.w, max_seg_len=hint)
+        single.add_lora(1)
+        assert np.array_equal(q.y_bits(), single.y_bits()), f"multi differs from single, seed {seed}"
+    assert d0.check() == 0
