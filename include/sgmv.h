@@ -84,7 +84,8 @@ typedef enum {
 typedef enum {
   SGMV_PATH_AUTO = 0,
   SGMV_PATH_VECTOR = 1,      /* bandwidth path: vector ALU, one launch per step    */
-  SGMV_PATH_MATRIX = 2,      /* MFMA path: for long (prefill-like) segments        */
+  SGMV_PATH_MATRIX = 2,      /* MFMA path: for long (prefill-like) segments; at    */
+                             /* most 65535 segments, else SGMV_ERR_UNSUPPORTED     */
   SGMV_PATH_FUSED = 3        /* sgmv_add_lora only: shrink and expand in a single  */
                              /* launch; needs workspace_ready, max_seg_len > 0 and */
                              /* a launch whose workgroups (segments x sixteen-row  */

@@ -17,6 +17,7 @@ constexpr int kTargetWorkgroups = 512; // about two workgroups per compute unit
 // that every (segment, sixteen-row block, slice) workgroup must be resident at once with its
 // weight slices in LDS (choose_tile): about 64 row blocks in all at h = 4096.
 constexpr int kTileMaxSegLen = 4096;
+constexpr int kMatrixMaxSegments = 65535;  // the MFMA kernels put the segment on a grid dimension limited to this
 // Workgroups of a tile launch, those without rows included: launches with many more than one
 // per compute unit measured slower than the launch-per-step kernels (456 workgroups for 171
 // with rows: 25.8 us against 14.8 us) even though the surplus leaves at once.
@@ -58,6 +59,7 @@ int check_common(const sgmv_problem* p, const int32_t* seg_starts, int32_t n_seg
   if (p->expand_threads != 0 && p->expand_threads != 64 && p->expand_threads != 128 &&
       p->expand_threads != 256)
     return SGMV_ERR_UNSUPPORTED;
+  if (p->path == SGMV_PATH_MATRIX && n_segs > 65535) return SGMV_ERR_UNSUPPORTED;  // grid dimension of the MFMA kernels
   if (layer_idx < 0 || layer_idx >= p->num_layers) return SGMV_ERR_RANGE;
   if (n_segs > 0 && p->n_tokens > 0 && seg_starts == nullptr) return SGMV_ERR_NULL;
   return SGMV_OK;
@@ -100,6 +102,7 @@ bool choose_split(const sgmv_problem* p, int n_segs, int* ksplit, int* kslice) {
 bool use_matrix(const sgmv_problem* p, int n_segs) {
   if (p->path == SGMV_PATH_MATRIX) return true;
   if (p->path != SGMV_PATH_AUTO) return false;
+  if (n_segs > kMatrixMaxSegments) return false;  // the vector kernels take any number of segments
   const int len = p->max_seg_len > 0 ? p->max_seg_len : p->n_tokens / (n_segs > 0 ? n_segs : 1);
   return len >= kMatrixMinSegLen;
 }

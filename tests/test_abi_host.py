@@ -98,6 +98,7 @@ def test_argument_errors_are_reported_without_a_device():
     assert _add(_prob(workspace=FAKE + 16)) == 4
     assert _add(_prob(workspace_bytes=16)) == 5
     assert _add(_prob(path=9)) == 3
+    assert _add(_prob(path=sg.PATH_MATRIX, n_tokens=70000), n=70000) == 3   # more segments than the MFMA grid takes
     assert _add(_prob(path=sg.PATH_FUSED)) == 3            # workspace not declared ready
     assert _add(_prob(path=sg.PATH_FUSED, workspace_ready=1, max_seg_len=0)) == 3
     assert _add(_prob(path=sg.PATH_FUSED, workspace_ready=1, max_seg_len=5000)) == 3
