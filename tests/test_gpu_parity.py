@@ -688,7 +688,7 @@ def test_tile_kernel_takes_a_few_long_segments(lens, r, dtype):
 
 
 @pytest.mark.parametrize("n_segs,seg_len,expect", [(2500, 1, "vector"), (1100, 2, "vector"), (300, 5, "matrix"),
-                                                   (256, 1, "fused"), (512, 1, "vector"), (256, 3, "tile")])
+                                                   (256, 1, "fused"), (512, 1, "vector"), (256, 3, "tile"), (70000, 1, "vector"), (66000, 4, "vector")])
 def test_many_segments_take_a_path_that_fits(n_segs, seg_len, expect):
     # more segments than the single-launch kernels can keep resident: the call still resolves
     # to a kernel family that covers it (seven adapters shared by all segments)
