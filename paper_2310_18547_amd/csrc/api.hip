@@ -169,6 +169,12 @@ bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f) {
     while (pw * 2 <= s) pw *= 2;
     s = pw;
   }
+  // Small batches at high rank: where a slice of A_i at eight slices takes more than one batch
+  // of loads (2048 128-bit chunks), sixteen slices are faster while they are all resident
+  // (measured at r = 64, h = 4096 / 5120, 1..8 segments: 5.1 / 5.8 us against 5.4 / 6.7 us)
+  if (p->ksplit == 0 && s == kFusedSlices && 2 * s * n_segs <= kFusedWorkgroups &&
+      (long long)ceil_div(p->h_in, s) * (p->r / 8) > 2048)
+    s = 2 * kFusedSlices;
   const int wide = p->h_in > p->h_out ? p->h_in : p->h_out;
   if (s > wide / 64) s = wide / 64;
   if (s > cap) s = cap;

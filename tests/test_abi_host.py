@@ -255,3 +255,15 @@ def test_plan_tile_counts_only_row_blocks_with_rows():
     # a grid far beyond one workgroup per compute unit is not taken
     rc, pl = _plan(8, n_tokens=1000, max_seg_len=300)
     assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX
+
+
+def test_plan_sixteen_slices_for_small_batches_at_high_rank():
+    # a slice of A_i at eight slices would take more than one batch of loads: sixteen slices
+    for kw, S in ((dict(r=64), 16), (dict(r=64, h_in=5120, h_out=5120), 16), (dict(r=32, h_in=5120, h_out=5120), 16),
+                  (dict(r=32), 8), (dict(r=16), 8)):
+        rc, pl = _plan(4, n_tokens=4, max_seg_len=1, **kw)
+        assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and pl.slices == S, (kw, pl.slices)
+    rc, pl = _plan(16, n_tokens=16, max_seg_len=1, r=64)
+    assert rc == 0 and (pl.slices, pl.workgroups) == (16, 256)
+    rc, pl = _plan(32, n_tokens=32, max_seg_len=1, r=64)      # 512 workgroups would not be resident
+    assert rc == 0 and pl.slices == 8
