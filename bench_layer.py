@@ -61,8 +61,21 @@ def main():
               "down": (ffn, h)}
     W = {n: [rnd(i, o, std=i ** -0.5) for _ in range(L)] for n, (i, o) in shapes.items()}
     # adapters: one per request and projection, stacked over the cycled layers
-    A = {n: [rnd(L, i, r, std=i ** -0.5) for _ in range(T)] for n, (i, o) in shapes.items()}
-    Bw = {n: [rnd(L, r, o, std=r ** -0.5) for _ in range(T)] for n, (i, o) in shapes.items()}
+    def pool(count, shape, std):
+        # one allocation per weight kind, adapter i at i * (size + 64 KiB): equal power-of-two
+        # sizes back to back would start every adapter's slices on the same HBM channels
+        size = 2
+        for d in shape:
+            size *= d
+        stride = (size + 65536 + 255) // 256 * 256
+        buf = torch.empty(count * stride, dtype=torch.uint8, device=dev)
+        views = [buf[k * stride:k * stride + size].view(f16).view(*shape) for k in range(count)]
+        for v in views:
+            v.copy_(rnd(*shape, std=std))
+        return views
+
+    A = {n: pool(T, (L, i, r), i ** -0.5) for n, (i, o) in shapes.items()}
+    Bw = {n: pool(T, (L, r, o), r ** -0.5) for n, (i, o) in shapes.items()}
     A_ptrs = {n: torch.tensor([t.data_ptr() for t in A[n]], dtype=torch.int64, device=dev) for n in shapes}
     B_ptrs = {n: torch.tensor([t.data_ptr() for t in Bw[n]], dtype=torch.int64, device=dev) for n in shapes}
     seg_starts = torch.arange(T + 1, dtype=torch.int32, device=dev)
