@@ -25,6 +25,7 @@ constexpr int kTileMaxGrid = 320;
 constexpr int kFusedSlices = 8;        // most slices per segment the single-launch kernels pick
 constexpr int kFusedWorkgroups = 256;  // one workgroup per compute unit
 constexpr int kFusedMaxWorkgroups = 1024;
+constexpr int kMultiWorkgroupsMost = 768;  // ... where the pipelined kernel does not apply (three per compute unit)
 constexpr int kMultiWorkgroups = 512;  // workgroups of a multi-projection launch that run side by side (two per compute unit)
 constexpr int kFusedSpinLimit = 1 << 18;
 constexpr int kMatrixMinSegLen = 4;    // AUTO uses the MFMA kernels from this segment length on (measured crossover)
@@ -357,6 +358,11 @@ int plan_multi(const sgmv_problem* p, int n_segs, int n_proj, FusedArgs* f) {
     f->r = p->r;
     if ((long long)f->S * n_segs * n_proj <= kMultiWorkgroups) return SGMV_KERNEL_MULTI_SIDE;
     if (fused_multi_fits(*f)) return SGMV_KERNEL_MULTI_PIPELINED;
+    // slices too deep for the pipelined kernel's register sets (h_in = 5120 at four slices):
+    // three workgroups per compute unit still beat one launch per add-on (measured, three
+    // projections of 64 segments at h = 5120: 22.7 us against 24.8 us)
+    // (ranks up to 16 only: the kernels of the higher ranks use more registers and fit two per unit)
+    if (p->r <= 16 && (long long)f->S * n_segs * n_proj <= kMultiWorkgroupsMost) return SGMV_KERNEL_MULTI_SIDE;
   }
   return SGMV_KERNEL_SEQUENCE;
 }

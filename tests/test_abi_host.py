@@ -267,3 +267,12 @@ def test_plan_sixteen_slices_for_small_batches_at_high_rank():
     assert rc == 0 and (pl.slices, pl.workgroups) == (16, 256)
     rc, pl = _plan(32, n_tokens=32, max_seg_len=1, r=64)      # 512 workgroups would not be resident
     assert rc == 0 and pl.slices == 8
+
+
+def test_plan_multi_at_width_5120():
+    # four slices of 1280 features are too deep for the pipelined kernel: three projections of 64
+    # segments run side by side (768 workgroups, three per compute unit); rank 64 runs them in turn
+    rc, pl = _plan(64, 3, n_tokens=64, max_seg_len=1, h_in=5120, h_out=5120)
+    assert rc == 0 and pl.kernel == sg.KERNEL_MULTI_SIDE and pl.workgroups == 768 and pl.launches == 1
+    rc, pl = _plan(64, 3, n_tokens=64, max_seg_len=1, h_in=5120, h_out=5120, r=64)
+    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and pl.launches == 3

@@ -776,3 +776,25 @@ def test_random_shapes_two_step_and_multi(seed):
         single.add_lora(1)
         assert np.array_equal(q.y_bits(), single.y_bits()), f"multi differs from single, seed {seed}"
     assert d0.check() == 0
+
+
+def test_add_lora_multi_three_workgroups_per_unit():
+    # h = 5120: the slices are too deep for the pipelined kernel, so three projections of 64
+    # segments run side by side in 768 workgroups; equal to single calls bit for bit
+    from paper_2310_18547_amd import binding as B
+    ws, ds = _multi_setup(3, 64, 5120, 5120, 16, "bf16", 2, True)
+    d0 = ds[0]
+    pl = B.sgmv_plan_add_lora(d0.problem, ws[0].n_segs, 3)
+    assert pl.kernel == B.KERNEL_MULTI_SIDE and pl.workgroups == 768
+    for rep in range(3):
+        for d in ds:
+            d.reset_y()
+        B.sgmv_add_lora_multi(d0.problem, [d.y[0] for d in ds], [d0.x[0]] * 3, [d.A_ptrs for d in ds],
+                              [d.B_ptrs for d in ds], d0.seg_starts, ws[0].n_segs, 1, ws[0].scale)
+        got = [d.y_bits() for d in ds]
+    assert d0.check() == 0
+    for i, (w, d) in enumerate(zip(ws, ds)):
+        assert_parity(got[i], oracle.run_workload(w, layer_idx=1, n_threads=8), "bf16", f"multi 768 proj {i}")
+        d.reset_y()
+        d.add_lora(1)
+        assert np.array_equal(d.y_bits(), got[i]), f"projection {i} differs from a single call"
