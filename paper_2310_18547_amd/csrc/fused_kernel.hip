@@ -60,36 +60,6 @@
 
 namespace sgmv {
 
-template <int LPR>
-__device__ __forceinline__ float fused_reduce_lanes8(const float (&a)[8], int lane, int& e_out) {
-  constexpr int M1 = LPR, M2 = LPR * 2, M3 = LPR * 4;
-  float b[4], c[2], d;
-  bool up = (lane & M1) != 0;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    float send = up ? a[i] : a[i + 4];
-    float keep = up ? a[i + 4] : a[i];
-    b[i] = keep + __shfl_xor(send, M1, 64);
-  }
-  up = (lane & M2) != 0;
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    float send = up ? b[i] : b[i + 2];
-    float keep = up ? b[i + 2] : b[i];
-    c[i] = keep + __shfl_xor(send, M2, 64);
-  }
-  up = (lane & M3) != 0;
-  {
-    float send = up ? c[0] : c[1];
-    float keep = up ? c[1] : c[0];
-    d = keep + __shfl_xor(send, M3, 64);
-  }
-#pragma unroll
-  for (int m = M3 * 2; m < 64; m <<= 1) d += __shfl_xor(d, m, 64);
-  e_out = ((lane & M1) ? 4 : 0) | ((lane & M2) ? 2 : 0) | ((lane & M3) ? 1 : 0);
-  return d;
-}
-
 // Body of the kernels below.  grid = (S, n_segs[, projections]) workgroups of 320 threads: blockIdx.y is the segment,
 // blockIdx.x its slice index (so the S workgroups of a segment are neighbours
 // in dispatch order and no division is needed to find them).
@@ -115,6 +85,7 @@ __device__ __forceinline__ void add_lora_fused_body(
   __shared__ __align__(16) uint16_t xs[RB][kMaxKSlice];
   __shared__ float red[NW][RB][R];
   __shared__ float vs[RB][R];
+  __shared__ int vs_complete;  // 0: a slice of this row block never arrived, its rows of y stay as they are
   __shared__ __align__(16) float ex[(G > 1 ? (G - 1) : 1) * RB * CPW * 8];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -162,6 +133,7 @@ __device__ __forceinline__ void add_lora_fused_body(
     for (int row0 = lo; row0 < hi; row0 += RB) {
       const int nrows = min(RB, hi - row0);
       if (row0 != lo) lds_barrier();  // (d) vs / ex free
+      bool block_timed_out = false;
       for (int idx = lane; idx < nrows * R; idx += 64) {
         const int rb = idx / R, j = idx - rb * R;
         const unsigned long long* src = exch + (long long)(row0 + rb) * R + j;
@@ -179,7 +151,7 @@ __device__ __forceinline__ void add_lora_fused_body(
 #pragma unroll
             for (int i = 0; i < 8; ++i) ready = ready && ((uint32_t)wv[i] == tag);
             if (!ready && ++polls > spin_limit) {
-              timed_out = true;
+              block_timed_out = true;
               break;
             }
           } while (!ready);
@@ -189,6 +161,9 @@ __device__ __forceinline__ void add_lora_fused_body(
         }
         vs[rb][j] = sum;
       }
+      block_timed_out = __any(block_timed_out);
+      timed_out = timed_out || block_timed_out;
+      if (lane == 0) vs_complete = block_timed_out ? 0 : 1;
       SGMV_TRACE_POINT(5);
       lds_barrier();  // (e) vs filled
       if (G > 1) {
@@ -299,7 +274,7 @@ __device__ __forceinline__ void add_lora_fused_body(
     for (int rb = 0; rb < RB; ++rb) {
       if (RB == 1 || rb < nrows) {
         int e;
-        const float d = fused_reduce_lanes8<LPR>(acc[rb], lane, e);
+        const float d = reduce_lanes8<LPR>(acc[rb], lane, e);
         if (lane < R) red[wave][rb][(lane % LPR) * 8 + e] = d;
       }
     }
@@ -319,6 +294,7 @@ __device__ __forceinline__ void add_lora_fused_body(
         y + (long long)row0 * h_out + col_lo,
         ncols > 0 ? (uint32_t)((long long)(nrows - 1) * h_out + ncols) * 2u : 0u);
     lds_barrier();  // (e) vs filled
+    const bool complete = vs_complete != 0;
     for (int pass = 0; pass < npass; ++pass) {
       const int c = pass * CPW + cc;  // 8-column chunk within the slice
       const bool active = c * 8 < ncols;
@@ -389,7 +365,7 @@ __device__ __forceinline__ void add_lora_fused_body(
           out.y = pack2<DT>(yf[2] + scale * acc[rb][2], yf[3] + scale * acc[rb][3]);
           out.z = pack2<DT>(yf[4] + scale * acc[rb][4], yf[5] + scale * acc[rb][5]);
           out.w = pack2<DT>(yf[6] + scale * acc[rb][6], yf[7] + scale * acc[rb][7]);
-          buffer_store128(rY, (active && rb < nrows) ? (uint32_t)rb * row_bytes_out + (uint32_t)c * 16u : kOutOfRange, out);
+          buffer_store128(rY, (active && rb < nrows && complete) ? (uint32_t)rb * row_bytes_out + (uint32_t)c * 16u : kOutOfRange, out);
         }
       }
     }

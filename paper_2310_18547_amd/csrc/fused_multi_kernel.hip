@@ -47,36 +47,6 @@
 
 namespace sgmv {
 
-template <int LPR>
-__device__ __forceinline__ float multi_reduce_lanes8(const float (&a)[8], int lane, int& e_out) {
-  constexpr int M1 = LPR, M2 = LPR * 2, M3 = LPR * 4;
-  float b[4], c[2], d;
-  bool up = (lane & M1) != 0;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    float send = up ? a[i] : a[i + 4];
-    float keep = up ? a[i + 4] : a[i];
-    b[i] = keep + __shfl_xor(send, M1, 64);
-  }
-  up = (lane & M2) != 0;
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    float send = up ? b[i] : b[i + 2];
-    float keep = up ? b[i + 2] : b[i];
-    c[i] = keep + __shfl_xor(send, M2, 64);
-  }
-  up = (lane & M3) != 0;
-  {
-    float send = up ? c[0] : c[1];
-    float keep = up ? c[1] : c[0];
-    d = keep + __shfl_xor(send, M3, 64);
-  }
-#pragma unroll
-  for (int m = M3 * 2; m < 64; m <<= 1) d += __shfl_xor(d, m, 64);
-  e_out = ((lane & M1) ? 4 : 0) | ((lane & M2) ? 2 : 0) | ((lane & M3) ? 1 : 0);
-  return d;
-}
-
 __device__ __forceinline__ unsigned long long uniform64(unsigned long long v) {
   const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
   const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
@@ -101,6 +71,7 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
   __shared__ __align__(16) uint16_t xs[kMaxKSlice];
   __shared__ float red[NW][R];
   __shared__ float vs[R];
+  __shared__ int vs_complete;  // 0: a slice of the item never arrived, its row of y stays as it is
   __shared__ __align__(16) float ex[(G > 1 ? (G - 1) : 1) * CPW * 8];
   __shared__ unsigned long long ptr_x[P], ptr_y[P], ptr_a[P], ptr_b[P];
   __shared__ uint32_t mine;  // bit p: projection p is this workgroup's and has both pointers set
@@ -204,6 +175,7 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
     // collect all S slices of an item, ascending (only the R lanes that own an element poll:
     // idle lanes polling the same words would multiply the traffic on them)
     auto collect = [&](const Item& it) {
+      bool item_timed_out = false;
       if (lane < R) {
         const unsigned long long* src = words(it) + lane;
         float sum = 0.f;
@@ -220,7 +192,7 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
 #pragma unroll
             for (int i = 0; i < 8; ++i) ready = ready && ((uint32_t)wv[i] == tag);
             if (!ready && ++polls > spin_limit) {
-              timed_out = true;
+              item_timed_out = true;
               break;
             }
           } while (!ready);
@@ -230,6 +202,9 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
         }
         vs[lane] = sum;
       }
+      item_timed_out = __any(item_timed_out);
+      timed_out = timed_out || item_timed_out;
+      if (lane == 0) vs_complete = item_timed_out ? 0 : 1;
       lds_barrier();               // (e) vs filled
       if (G > 1) lds_barrier();    // (g) ex filled
     };
@@ -324,7 +299,7 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
     }
     {
       int e;
-      const float d = multi_reduce_lanes8<LPR>(acc, lane, e);
+      const float d = reduce_lanes8<LPR>(acc, lane, e);
       if (lane < R) red[wave][(lane % LPR) * 8 + e] = d;
     }
     SGMV_TRACE_POINT(3);
@@ -332,6 +307,7 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
   };
   auto expand = [&](const BRegs& r, const Item& it) {
     lds_barrier();  // (e) vs filled
+    const bool complete = vs_complete != 0;
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
@@ -371,7 +347,7 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
       out.y = pack2<DT>(yf[2] + scale * acc[2], yf[3] + scale * acc[3]);
       out.z = pack2<DT>(yf[4] + scale * acc[4], yf[5] + scale * acc[5]);
       out.w = pack2<DT>(yf[6] + scale * acc[6], yf[7] + scale * acc[7]);
-      buffer_store128(rY, col_active ? (uint32_t)cc * 16u : kOutOfRange, out);
+      buffer_store128(rY, (col_active && complete) ? (uint32_t)cc * 16u : kOutOfRange, out);
     }
   };
 

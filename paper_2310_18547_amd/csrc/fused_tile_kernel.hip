@@ -53,7 +53,7 @@ namespace sgmv {
 size_t tile_lds_bytes(int r, int kslice, int cslice) {
   const int rpad = (r + 15) / 16 * 16, kpad = r < 32 ? 32 : r;
   return (size_t)(kslice / 8) * (rpad + 1) * 16 + (size_t)(kpad / 8) * (cslice + 1) * 16 +
-         (size_t)2 * 4 * 16 * r * 4 + (size_t)2 * 16 * r * 4 + 2 * 16 * 4;
+         (size_t)2 * 4 * 16 * r * 4 + (size_t)2 * 16 * r * 4 + 2 * 16 * 4 + 16;
 }
 
 // kslice is a multiple of 32, cslice a multiple of 64 (host).
@@ -94,6 +94,8 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
   float* const red = reinterpret_cast<float*>(bt + (KPAD / 8) * BBLK * 4);  // [2][NW][TILE]
   float* const vs = red + 2 * NW * TILE;                                   // [2][TILE]
   float* const un = vs + 2 * TILE;                                         // [2][16]
+  // [2] 0: a slice of the row block never arrived, its rows of y stay as they are
+  int* const vs_complete = reinterpret_cast<int*>(un + 2 * 16);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   SGMV_TRACE_DECL
@@ -146,6 +148,7 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
       const int nel = min(16, hi - row0) * R;
       float* vd = vs + (it & 1) * TILE;
       const unsigned long long* src0 = exch + (long long)row0 * R;
+      bool block_timed_out = false;
       auto collect = [&](int e0, auto eb_tag) {
         constexpr int EN = decltype(eb_tag)::value;
         float sum[EN];
@@ -170,7 +173,7 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
 #pragma unroll
               for (int i = 0; i < 8; ++i) ready = ready && ((uint32_t)wv[e][i] == tag);
             if (!ready && ++polls > spin_limit) {
-              timed_out = true;
+              block_timed_out = true;
               break;
             }
           } while (!ready);
@@ -207,6 +210,9 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
       } else {
         for (int e0 = 0; e0 < nel; e0 += 64 * EB) collect(e0, std::integral_constant<int, EB>{});
       }
+      block_timed_out = __any(block_timed_out);
+      timed_out = timed_out || block_timed_out;
+      if (lane == 0) vs_complete[it & 1] = block_timed_out ? 0 : 1;
       SGMV_TRACE_POINT(5);
       lds_barrier();  // (E) vs[it & 1] filled
     }
@@ -447,6 +453,7 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
     const int nrows = min(16, hi - row0);
     const __amdgpu_buffer_rsrc_t rY = y_rsrc(row0, nrows);
     lds_barrier();  // (E) vs[it & 1] filled (and, the first time, the B slice staged)
+    const int nrows_store = vs_complete[it & 1] != 0 ? nrows : 0;
     uint4 vh[KSTEPS], vl[KSTEPS];
     {
       const float* vd = vs + (it & 1) * TILE + m * R;
@@ -516,8 +523,8 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
           out0.z = pack2<DT>(o[4], o[5]);   out0.w = pack2<DT>(o[6], o[7]);
           out1.x = pack2<DT>(o[8], o[9]);   out1.y = pack2<DT>(o[10], o[11]);
           out1.z = pack2<DT>(o[12], o[13]); out1.w = pack2<DT>(o[14], o[15]);
-          buffer_store128(rY, y_offset(grp, 0, nrows), out0);
-          buffer_store128(rY, y_offset(grp, 1, nrows), out1);
+          buffer_store128(rY, y_offset(grp, 0, nrows_store), out0);
+          buffer_store128(rY, y_offset(grp, 1, nrows_store), out1);
         }
       }
     }

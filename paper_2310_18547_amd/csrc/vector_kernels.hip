@@ -32,43 +32,6 @@
 
 namespace sgmv {
 
-// Sum eight per-lane accumulators over all lanes that hold the same rank
-// columns.  Lane l of a wave works on column group (l % LPR); lanes that differ
-// in the bits above log2(LPR) hold partial sums of the same eight columns.
-// Three exchange steps halve the number of live values per lane (8 -> 4 -> 2
-// -> 1) while doubling the span each value covers; plain butterflies finish.
-// On return every lane holds the complete sum of column
-//   (l % LPR) * 8 + e_out.
-template <int LPR>
-__device__ __forceinline__ float reduce_lanes8(const float (&a)[8], int lane, int& e_out) {
-  constexpr int M1 = LPR, M2 = LPR * 2, M3 = LPR * 4;
-  float b[4], c[2], d;
-  bool up = (lane & M1) != 0;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    float send = up ? a[i] : a[i + 4];
-    float keep = up ? a[i + 4] : a[i];
-    b[i] = keep + __shfl_xor(send, M1, 64);
-  }
-  up = (lane & M2) != 0;
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    float send = up ? b[i] : b[i + 2];
-    float keep = up ? b[i + 2] : b[i];
-    c[i] = keep + __shfl_xor(send, M2, 64);
-  }
-  up = (lane & M3) != 0;
-  {
-    float send = up ? c[0] : c[1];
-    float keep = up ? c[1] : c[0];
-    d = keep + __shfl_xor(send, M3, 64);
-  }
-#pragma unroll
-  for (int m = M3 * 2; m < 64; m <<= 1) d += __shfl_xor(d, m, 64);
-  e_out = ((lane & M1) ? 4 : 0) | ((lane & M2) ? 2 : 0) | ((lane & M3) ? 1 : 0);
-  return d;
-}
-
 // ---------------------------------------------------------------- shrink
 //
 // grid = (n_segs, ksplit).  Slice s covers k in [s*kslice, min(h_in, (s+1)*kslice)).

@@ -159,22 +159,36 @@ def test_rank_width_sweep(dtype, h, r):
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
-@pytest.mark.parametrize("r", [8, 16, 64])
-def test_mlp_shapes_one_sided(dtype, r):
+@pytest.mark.parametrize("r", [8, 16, 32, 64])
+@pytest.mark.parametrize("batch", [1, 16, 64])
+def test_mlp_shapes_one_sided(dtype, r, batch):
     # shrink 13824 -> r on its own
-    w = wl.decode_distinct(batch=16, h_in=13824, h_out=8, r=r, dtype=dtype, num_layers=1, seed=r)
+    w = wl.decode_distinct(batch=batch, h_in=13824, h_out=8, r=r, dtype=dtype, num_layers=1, seed=r + batch)
     d = _dev(w)
-    v = torch.zeros(16, r, dtype=torch.float32, device="cuda:0")
+    v = torch.zeros(batch, r, dtype=torch.float32, device="cuda:0")
     d.shrink(v)
     ref = oracle.run_workload(w, op="shrink", n_threads=8)
     assert np.all(np.abs(v.cpu().numpy() - ref) <= 2e-3 + 2e-2 * np.abs(ref))
     # expand r -> 13824 on its own
-    w = wl.decode_distinct(batch=16, h_in=8, h_out=13824, r=r, dtype=dtype, num_layers=1, seed=r)
-    vin = np.random.Generator(np.random.PCG64(r)).standard_normal((16, r)).astype(np.float32)
+    w = wl.decode_distinct(batch=batch, h_in=8, h_out=13824, r=r, dtype=dtype, num_layers=1, seed=r + batch)
+    vin = np.random.Generator(np.random.PCG64(r)).standard_normal((batch, r)).astype(np.float32)
     d = _dev(w)
     d.expand(torch.from_numpy(vin).to("cuda:0"))
     assert_parity(d.y_bits(), oracle.run_workload(w, op="expand", v=vin, n_threads=8), dtype,
-                  f"mlp expand r={r}")
+                  f"mlp expand r={r} B={batch}")
+
+
+# the projection shapes of the Llama-7B / 13B MLP block as whole add-ons (what the decoder-layer
+# benchmark times), Distinct batch of 64
+@pytest.mark.parametrize("r", [16, 64])
+@pytest.mark.parametrize("h_in,h_out", [(4096, 11008), (11008, 4096), (5120, 13824), (13824, 5120)])
+def test_mlp_projection_add_lora(h_in, h_out, r):
+    w = wl.decode_distinct(batch=64, h_in=h_in, h_out=h_out, r=r, dtype="f16", num_layers=2, seed=r)
+    d = _dev(w)
+    d.add_lora(1)
+    assert_parity(d.y_bits(), oracle.run_workload(w, layer_idx=1, n_threads=8), "f16",
+                  f"mlp add_lora {h_in}->{h_out} r={r}")
+    assert d.check() == 0
 
 
 # ---------------------------------------------------------------- config 5
@@ -195,10 +209,22 @@ def _row_sample(w, per_seg=6, seed=0):
     return rows, sub
 
 
+def _one_segment(w, i):
+    """Sub-problem holding every row of segment i alone."""
+    lo, hi = int(w.seg_starts[i]), int(w.seg_starts[i + 1])
+    sub = wl.custom([hi - lo], w.h_in, w.h_out, w.r, w.dtype, seed=0, seg_adapter=[int(w.seg_adapter[i])])
+    sub.A, sub.B = w.A, w.B
+    sub.x, sub.y0 = w.x[lo:hi].copy(), w.y0[lo:hi].copy()
+    sub.scale, sub.num_layers = w.scale, w.num_layers
+    return lo, hi, sub
+
+
+@pytest.mark.parametrize("seed", [1, 2])
 @pytest.mark.parametrize("r", [16, 64])
-def test_prefill_long_segments_reduced_width(r):
-    # whole output against the oracle at a width the oracle finishes in seconds
-    w = wl.prefill(h_in=1024, h_out=1536, r=r, dtype="bf16", seed=1)
+def test_prefill_long_segments_reduced_width(r, seed):
+    # whole output against the oracle at a width the oracle finishes in seconds; seed 2 gives
+    # the very segment lengths of the full-size test below
+    w = wl.prefill(h_in=1024, h_out=1536, r=r, dtype="bf16", seed=seed)
     assert_parity(run_add_lora(w), oracle.run_workload(w, n_threads=8), "bf16", f"prefill r={r}")
 
 
@@ -206,10 +232,17 @@ def test_prefill_long_segments_reduced_width(r):
 @pytest.mark.parametrize("r", [16, 64])
 def test_prefill_full_size_sampled_rows(h_out, r):
     w = wl.prefill(h_in=8192, h_out=h_out, r=r, dtype="bf16", seed=2)
+    assert w.notes["seg_lens"] == wl.prefill(h_in=1024, h_out=1536, r=r, dtype="bf16", seed=2).notes["seg_lens"]
     got = run_add_lora(w)
     rows, sub = _row_sample(w)
     ref = oracle.run_workload(sub, n_threads=8)
     assert_parity(got[rows], ref, "bf16", f"prefill 8192x{h_out} r={r}")
+    # every row of the first segment and of the shortest one (here also the batch's ragged tail)
+    lens = np.diff(w.seg_starts)
+    for i in sorted({0, int(np.argmin(lens))}):
+        lo, hi, one = _one_segment(w, i)
+        assert_parity(got[lo:hi], oracle.run_workload(one, n_threads=8), "bf16",
+                      f"prefill 8192x{h_out} r={r} segment {i} ({hi - lo} rows)")
     # rows are only ever modified through the add-on: every row must have moved
     assert np.all(np.any(got != w.y0, axis=1))
 

@@ -326,3 +326,82 @@ def test_fp32_and_fp64_accumulation_agree_within_rounding():
     # of that the two may round to neighbouring 16-bit values
     assert np.all(np.abs(a - b) <= ulp(y64, "f16") + 2e-5)
     assert np.mean(y32 == y64) > 0.97
+
+
+# ------------------------------------------- single rounding of the fp64 variant
+def _round16_exact(value, dtype):
+    """Round an exact rational to the 16-bit format, nearest-even, by comparing it with
+    the format's own values (numpy float16 / the upper half of a binary32)."""
+    from fractions import Fraction
+    if dtype == "f16":
+        cands = np.arange(0x0000, 0x7C00, dtype=np.uint32).astype(np.uint16)   # finite, >= 0
+    else:
+        cands = np.arange(0x0000, 0x7F80, dtype=np.uint32).astype(np.uint16)
+    vals = decode64(cands, dtype)
+    sign = 0x8000 if value < 0 else 0
+    mag = abs(value)
+    hi = int(np.searchsorted(vals, float(mag), side="left"))
+    hi = min(max(hi, 1), len(vals) - 1)
+    best = None
+    for i in (hi - 1, hi, min(hi + 1, len(vals) - 1)):
+        err = abs(Fraction(float(vals[i])) - mag)
+        key = (err, int(cands[i]) & 1)            # nearest, then even significand
+        if best is None or key < best[0]:
+            best = (key, int(cands[i]))
+    return best[1] | sign
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_fp64_variant_rounds_once_across_16_bit_ties(dtype):
+    # y + v.B built so that the exact sum sits a hair (2^-40) above or below a tie of the
+    # 16-bit format, or exactly on it.  Rounding the fp64 sum to fp32 first and then to 16
+    # bits lands on the tie and picks the wrong neighbour; one rounding does not.
+    from fractions import Fraction
+    half_ulp = Fraction(1, 2 ** 11) if dtype == "f16" else Fraction(1, 2 ** 8)   # at 1.0
+    tiny = Fraction(1, 2 ** 40)
+    cases = []
+    for sgn in (1, -1):
+        for odd_multiple in (1, 3, 5):
+            for nudge in (tiny, -tiny, 0):
+                cases.append((sgn, odd_multiple, nudge))
+    T, r = len(cases), 8
+    one = {"f16": 0x3C00, "bf16": 0x3F80}[dtype]
+    B = np.zeros((1, r, 8), np.uint16)
+    B[0, :, :] = one                                   # every B entry is 1.0
+    y0 = np.zeros((T, 8), np.uint16)
+    v = np.zeros((T, r), np.float32)
+    want = np.zeros((T, 8), np.uint16)
+    for t, (sgn, m, nudge) in enumerate(cases):
+        y0[t, :] = one | (0x8000 if sgn < 0 else 0)    # +-1.0
+        v[t, 0] = sgn * float(m * half_ulp)            # exact in fp32
+        v[t, 1] = sgn * float(nudge)                   # +-2^-40 or 0, exact in fp32
+        exact = sgn * (1 + m * half_ulp + nudge)
+        want[t, :] = _round16_exact(exact, dtype)
+    got = oracle.expand(dtype, y0.copy(), v, [B], [0, T], acc64=True)
+    assert np.array_equal(got, want)
+    # the nudged cases really are ones where two roundings go wrong
+    twice = wl.encode((decode64(y0, dtype)[:, 0] + v.astype(np.float64).sum(axis=1)).astype(np.float32), dtype)
+    assert np.any(twice != want[:, 0])
+
+
+# ------------------------------------------- fp32 "v +=" on top of what is there
+def test_fp32_shrink_adds_into_nonzero_v_with_one_fp32_addition():
+    # small integers: x.A is exact in fp32 whatever the order, so v0 + x.A has one rounding
+    rng = np.random.Generator(np.random.PCG64(31))
+    T, h_in, r = 7, 48, 8
+    xi = rng.integers(-3, 4, (T, h_in)).astype(np.float32)
+    Ai = rng.integers(-3, 4, (2, 1, h_in, r)).astype(np.float32)
+    x = wl.encode(xi, "f16")
+    A = [wl.encode(Ai[0], "f16"), wl.encode(Ai[1], "f16")]
+    starts = [0, 3, 7]
+    prod = np.concatenate([xi[:3].astype(np.int64) @ Ai[0, 0].astype(np.int64),
+                           xi[3:].astype(np.int64) @ Ai[1, 0].astype(np.int64)])
+    # starting values: fractions, a negative, and 2^24 (+3 is then inexact in fp32: ties to even)
+    v0 = np.tile(np.asarray([1.5, -2.25, 0.0, 16777216.0, -16777216.0, 1e-3, 3.0e7, -0.5], np.float32), (T, 1))
+    got = oracle.shrink("f16", v0.copy(), x, A, starts, acc64=False)
+    want = v0 + prod.astype(np.float32)                # numpy's fp32 addition, one rounding
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    assert not np.array_equal(got, prod.astype(np.float32))          # it did add, not overwrite
+    # a second call accumulates again
+    got2 = oracle.shrink("f16", got.copy(), x, A, starts, acc64=False)
+    assert np.array_equal(got2.view(np.uint32), (want + prod.astype(np.float32)).view(np.uint32))
