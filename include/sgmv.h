@@ -8,8 +8,9 @@
  * index sequence s_0 = 0 <= s_1 <= ... <= s_n = number of rows delimits n
  * segments, segment i owning rows s_i .. s_{i+1}-1 (zero based).  Rows of
  * segment i receive x * A_i * B_i on top of the backbone projection already
- * stored in y, evaluated as two steps ("v := 0; v += x A; y += v B", the
- * sentence after the section's displayed equation):
+ * stored in y, evaluated as two steps (v starts at zero, is accumulated from
+ * x A, and y is accumulated from v B: the sentence after the section's
+ * displayed equation):
  *
  *     shrink :  v[rows of i] += x[rows of i] * A_i            (h_in  -> r)
  *     expand :  y[rows of i] += scale * v[rows of i] * B_i    (r -> h_out)
@@ -22,9 +23,12 @@
  *   - Every data pointer (x, y, v, A_ptrs, B_ptrs, seg_starts, workspace, and
  *     whatever A_ptrs[i] / B_ptrs[i] point to) is DEVICE memory owned by the
  *     caller.  The sgmv_problem struct itself is HOST memory, read during the
- *     call only.  The library allocates nothing, frees nothing and keeps no
- *     state of its own between calls (the single-launch path keeps an
- *     epoch word in the caller's workspace, see sgmv_workspace_init).
+ *     call only.  The library allocates nothing and frees nothing.  The only
+ *     state it keeps between calls is per-device bookkeeping that changes no
+ *     result (which kernels have had their LDS limit raised, the number of
+ *     compute units); the
+ *     single-launch path keeps an epoch in the caller's workspace, see
+ *     sgmv_workspace_init.
  *   - x is [n_tokens][h_in], y is [n_tokens][h_out], row-major, 16-bit floats
  *     of type `dtype` (IEEE binary16 or bfloat16), 16-byte aligned.
  *   - A_ptrs[i] points to segment i's shrink weights stacked over layers,
@@ -39,8 +43,13 @@
  *     allowed.  Its *contents* are not checked on the device path; use
  *     sgmv_validate_segments() on a host copy if they are not trusted.
  *   - v (shrink output / expand input) is fp32 [n_tokens][r], 16-byte aligned.
- *   - All products and sums are taken in fp32; y is rounded once, to nearest
- *     even, when it is stored.  Results are deterministic run to run (no
+ *   - Sums are accumulated in fp32 and y is rounded once, to nearest even,
+ *     when it is stored.  v is kept in fp32 between the two steps.  On the
+ *     vector-ALU kernels every product is an fp32 product too; the MFMA
+ *     kernels (segments of several rows) feed v to the matrix cores as a high
+ *     plus a low 16-bit part, which keeps 16 significant bits of v for
+ *     bfloat16 and 22 for binary16 -- well inside the accuracy the 16-bit
+ *     result can show.  Results are deterministic run to run (no
  *     floating-point atomics).
  *   - Supported shapes: r in {8, 16, 32, 64}; h_in and h_out positive
  *     multiples of 8.  Anything else returns SGMV_ERR_UNSUPPORTED; there is no
@@ -111,7 +120,10 @@ typedef struct sgmv_problem {
   int32_t workspace_ready;   /* nonzero: sgmv_workspace_init() has been run on this */
                              /* workspace (and no call on it was ever aborted);     */
                              /* enables the single-launch path                      */
-  int32_t reserved;          /* must be 0                                           */
+  int32_t spin_limit;        /* single-launch path: polls after which a workgroup   */
+                             /* gives up waiting for its neighbours' partial sums;  */
+                             /* 0 = the library's default (2^18).  Small values are */
+                             /* for tests of the give-up path only.                 */
   void*   workspace;         /* device scratch, 256-byte aligned, at least          */
   size_t  workspace_bytes;   /*   sgmv_workspace_bytes(n_tokens, r) bytes           */
 } sgmv_problem;
@@ -160,7 +172,10 @@ int sgmv_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 /* Synchronous health check of a workspace used by the single-launch path:
  * waits for `stream`, reads the workspace's header and returns
  * SGMV_ERR_TIMEOUT if any workgroup ever gave up its (bounded) wait for a
- * neighbour's partial sums -- results of that call are then invalid -- and
+ * neighbour's partial sums -- that call's result is then incomplete: the rows
+ * and columns of y such a workgroup was responsible for were left as they
+ * were (nothing is ever stored from an incomplete sum), the others hold the
+ * finished result -- and
  * SGMV_ERR_STATE if the workspace was never initialised or the launch counter
  * is not at a launch boundary (no call may be running on another stream).  In
  * both cases the workspace must be re-initialised.  Returns SGMV_OK otherwise.
@@ -196,8 +211,8 @@ int sgmv_expand(const sgmv_problem* p, void* y, const float* v,
                 int32_t n_segs, int32_t layer_idx, float scale, void* stream);
 
 /* The whole LoRA add-on, y += scale * (x A_i) B_i per segment, i.e. v := 0,
- * shrink, expand in one call; v lives in the workspace in fp32 and is never
- * rounded.  A segment is skipped when either of its pointers is NULL.
+ * shrink, expand in one call; v lives in the workspace (or in LDS) in fp32
+ * (see the general conventions for how the MFMA kernels consume it).  A segment is skipped when either of its pointers is NULL.
  * With workspace_ready set and a max_seg_len hint both steps run in a single
  * kernel launch where that launch fits the chip (vector ALUs for one row per
  * segment; matrix cores on sixteen-row tiles otherwise, up to about 64 such
@@ -236,6 +251,17 @@ int sgmv_add_lora_multi(const sgmv_problem* p, int32_t n_proj, void* const* ys,
  * only checked as the entry points check them).  Returns the status the call itself would
  * return for these arguments. */
 int sgmv_plan_add_lora(const sgmv_problem* p, int32_t n_segs, int32_t n_proj, sgmv_plan* plan);
+
+/* Measurement aid, not part of the operator: enqueue one plain kernel of known traffic on
+ * `stream`, for the benchmark's attainable-bandwidth figure and for scaling a profiler's HBM
+ * byte counters (the roofline analysis of the paper's microbenchmark section compares the
+ * kernel with the memory system's limits; these kernels measure those limits on this GPU).
+ *   kind 0  empty kernel in the launch shape of the single-launch add-on (src, dst, bytes unused)
+ *   kind 1  streaming read of `bytes` device bytes at `src` (16-byte aligned, multiple of 16);
+ *           `dst` may be NULL or point to at least 4 writable device bytes
+ *   kind 2  copy of `bytes` device bytes from `src` to `dst` (reads and writes `bytes`)
+ * Returns SGMV_OK, SGMV_ERR_NULL, SGMV_ERR_ALIGN, SGMV_ERR_UNSUPPORTED or SGMV_ERR_LAUNCH. */
+int sgmv_probe(int kind, const void* src, void* dst, size_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -11,7 +11,9 @@ import os
 from typing import Optional
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libsgmv.so")
+# SGMV_LIBRARY names another build of the same sources in this directory (the tuning build
+# with the in-kernel timeline, libsgmv_trace.so); the default is the library proper
+_LIB_PATH = os.path.join(_HERE, os.path.basename(os.environ.get("SGMV_LIBRARY", "libsgmv.so")))
 
 F16, BF16 = 0, 1
 PATH_AUTO, PATH_VECTOR, PATH_MATRIX, PATH_FUSED = 0, 1, 2, 3
@@ -37,7 +39,7 @@ class SgmvProblem(ctypes.Structure):
         ("ksplit", ctypes.c_int32),
         ("expand_threads", ctypes.c_int32),
         ("workspace_ready", ctypes.c_int32),
-        ("reserved", ctypes.c_int32),
+        ("spin_limit", ctypes.c_int32),
         ("workspace", ctypes.c_void_p),
         ("workspace_bytes", ctypes.c_size_t),
     ]
@@ -96,6 +98,8 @@ def _load():
     L.sgmv_add_lora_multi.argtypes = [P, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
                                       c.c_void_p, c.c_int32, c.c_int32, c.c_float, c.c_void_p]
     L.sgmv_add_lora_multi.restype = c.c_int
+    L.sgmv_probe.argtypes = [c.c_int, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+    L.sgmv_probe.restype = c.c_int
     L.sgmv_plan_add_lora.argtypes = [P, c.c_int32, c.c_int32, c.POINTER(SgmvPlan)]
     L.sgmv_plan_add_lora.restype = c.c_int
     return L
@@ -125,9 +129,9 @@ def _stream(s) -> Optional[int]:
 def make_problem(dtype: int, h_in: int, h_out: int, r: int, num_layers: int, n_tokens: int,
                  workspace=None, workspace_bytes: int = 0, max_seg_len: int = 0,
                  path: int = PATH_AUTO, ksplit: int = 0, expand_threads: int = 0,
-                 workspace_ready: int = 0) -> SgmvProblem:
+                 workspace_ready: int = 0, spin_limit: int = 0) -> SgmvProblem:
     return SgmvProblem(dtype, h_in, h_out, r, num_layers, n_tokens, max_seg_len, path, ksplit,
-                       expand_threads, workspace_ready, 0, _addr(workspace), workspace_bytes)
+                       expand_threads, workspace_ready, spin_limit, _addr(workspace), workspace_bytes)
 
 
 def sgmv_status_string(status: int) -> str:
@@ -191,6 +195,16 @@ def sgmv_add_lora_multi(p: SgmvProblem, ys, xs, A_ptrs, B_ptrs, seg_starts, n_se
         n_segs, layer_idx, scale, _stream(stream))
     if check and rc != 0:
         raise SgmvError(rc, "sgmv_add_lora_multi")
+    return rc
+
+
+PROBE_EMPTY, PROBE_READ, PROBE_COPY = 0, 1, 2
+
+
+def sgmv_probe(kind: int, src=None, dst=None, nbytes: int = 0, stream=None, check: bool = True) -> int:
+    rc = lib.sgmv_probe(kind, _addr(src), _addr(dst), nbytes, _stream(stream))
+    if check and rc != 0:
+        raise SgmvError(rc, "sgmv_probe")
     return rc
 
 

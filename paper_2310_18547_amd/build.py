@@ -28,11 +28,17 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build(verbose: bool = True, extra=()) -> str:
-    """Compile every csrc/*.hip to an object (in parallel) and link libsgmv.so."""
+def build(verbose: bool = True, extra=(), trace: bool = False) -> str:
+    """Compile every csrc/*.hip to an object (in parallel) and link libsgmv.so.
+
+    ``trace=True`` builds the tuning variant libsgmv_trace.so instead: the same sources with
+    -DSGMV_TRACE, whose single-launch kernels record an in-kernel timeline (csrc/trace.h)."""
     from concurrent.futures import ThreadPoolExecutor
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    objdir = os.path.join(HERE, "_build")
+    objdir = os.path.join(HERE, "_build_trace" if trace else "_build")
+    lib = os.path.join(HERE, "libsgmv_trace.so") if trace else LIB
+    if trace:
+        extra = tuple(extra) + ("-DSGMV_TRACE",)
     os.makedirs(objdir, exist_ok=True)
     flags = [f for f in HIPCC_FLAGS if f != "-shared"]
 
@@ -46,14 +52,15 @@ def build(verbose: bool = True, extra=()) -> str:
 
     with ThreadPoolExecutor(max_workers=min(8, len(sources()))) as pool:
         objs = list(pool.map(compile_one, sources()))
-    tmp = LIB + f".tmp{os.getpid()}"
+    tmp = lib + f".tmp{os.getpid()}"
     link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs]
     if verbose:
         print(" ".join(link), flush=True)
     subprocess.check_call(link)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, lib)
+    return lib
 
 
 if __name__ == "__main__":
-    build(extra=sys.argv[1:])
+    args = sys.argv[1:]
+    build(extra=[a for a in args if a != "--trace"], trace="--trace" in args)

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/sgmv.h"
 #include "launch.h"
 
@@ -18,16 +20,50 @@ constexpr int kTargetWorkgroups = 512; // about two workgroups per compute unit
 // weight slices in LDS (choose_tile): about 64 row blocks in all at h = 4096.
 constexpr int kTileMaxSegLen = 4096;
 constexpr int kMatrixMaxSegments = 65535;  // the MFMA kernels put the segment on a grid dimension limited to this
-// Workgroups of a tile launch, those without rows included: launches with many more than one
-// per compute unit measured slower than the launch-per-step kernels (456 workgroups for 171
-// with rows: 25.8 us against 14.8 us) even though the surplus leaves at once.
-constexpr int kTileMaxGrid = 320;
 constexpr int kFusedSlices = 8;        // most slices per segment the single-launch kernels pick
-constexpr int kFusedWorkgroups = 256;  // one workgroup per compute unit
 constexpr int kFusedMaxWorkgroups = 1024;
-constexpr int kMultiWorkgroupsMost = 768;  // ... where the pipelined kernel does not apply (three per compute unit)
-constexpr int kMultiWorkgroups = 512;  // workgroups of a multi-projection launch that run side by side (two per compute unit)
 constexpr int kFusedSpinLimit = 1 << 18;
+constexpr int kMaxDevices = 64;
+constexpr int kDefaultComputeUnits = 256;  // MI355X; assumed where no device can be asked
+
+// Residency limits of the single-launch kernels.  They follow from the compute units of the
+// current device (asked once per device): a workgroup that waits for the partial sums of a
+// workgroup that has not started yet only idles, so these launches stay within what is
+// resident at once.
+struct Limits {
+  int fused_workgroups;       // one workgroup per compute unit
+  int tile_max_grid;          // tile launch, workgroups without rows included (5/4 per unit)
+  int multi_workgroups;       // multi-projection launch side by side (two per unit)
+  int multi_workgroups_most;  // ... where the pipelined kernel does not apply (three per unit)
+};
+
+int compute_units() {
+  static std::atomic<int> cached[kMaxDevices];  // zero-initialised
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();  // no device here (a host-only query): leave no sticky error behind
+    return kDefaultComputeUnits;
+  }
+  int cu = cached[dev].load(std::memory_order_relaxed);
+  if (cu == 0) {
+    if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu <= 0) {
+      (void)hipGetLastError();
+      cu = kDefaultComputeUnits;
+    }
+    cached[dev].store(cu, std::memory_order_relaxed);
+  }
+  return cu;
+}
+
+Limits limits() {
+  const int cu = compute_units();
+  // launches far beyond one workgroup per unit measured slower than the launch-per-step kernels
+  // (tile kernel, 456 workgroups for 171 with rows: 25.8 us against 14.8 us) even though the
+  // surplus leaves at once
+  return Limits{cu, cu + cu / 4, 2 * cu, 3 * cu};
+}
+
+int spin_limit_of(const sgmv_problem* p) { return p->spin_limit > 0 ? p->spin_limit : kFusedSpinLimit; }
 constexpr int kMatrixMinSegLen = 4;    // AUTO uses the MFMA kernels from this segment length on (measured crossover)
 constexpr int kMatrixWorkgroups = 448; // workgroups the MFMA shrink aims for
 
@@ -55,7 +91,7 @@ int check_common(const sgmv_problem* p, const int32_t* seg_starts, int32_t n_seg
   if ((need_in && (p->h_in % 8) != 0) || (need_out && (p->h_out % 8) != 0))
     return SGMV_ERR_UNSUPPORTED;
   if (p->path < SGMV_PATH_AUTO || p->path > SGMV_PATH_FUSED) return SGMV_ERR_UNSUPPORTED;
-  if (p->reserved != 0) return SGMV_ERR_UNSUPPORTED;
+  if (p->spin_limit < 0) return SGMV_ERR_UNSUPPORTED;
   if (p->ksplit < 0 || p->ksplit > kMaxKSplit) return SGMV_ERR_UNSUPPORTED;
   if (p->expand_threads != 0 && p->expand_threads != 64 && p->expand_threads != 128 &&
       p->expand_threads != 256)
@@ -131,22 +167,29 @@ size_t partial_bytes(int n_tokens, int r) {
   return round_up((size_t)split_cap(n_tokens) * (size_t)n_tokens * (size_t)r * sizeof(float), 256);
 }
 
-// Workspace layout: [header: epoch, error word][split-K partials of the
-// one-launch-per-step kernels][exchange words of the single-launch kernel].
-float* partials_base(void* workspace) {
-  return reinterpret_cast<float*>(static_cast<char*>(workspace) + kWorkspaceHeader);
-}
-unsigned long long* exchange_base(void* workspace, int n_tokens, int r) {
-  return reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + kWorkspaceHeader +
-                                               partial_bytes(n_tokens, r));
+// Where a call keeps its intermediate results.
+struct Scratch {
+  unsigned long long* header;  // epoch counters, error word
+  float* partials;             // split-K partial sums of the launch-per-step kernels
+  unsigned long long* exch;    // exchange words of the single-launch kernels
+  char* operands;              // 16-bit operand pairs of v and a range factor per row (MFMA expand)
+};
+
+// Caller's workspace: [header][partials][exchange words, twice the bytes][operands].
+Scratch caller_scratch(const sgmv_problem* p) {
+  char* base = static_cast<char*>(p->workspace);
+  const size_t parts = partial_bytes(p->n_tokens, p->r);
+  return Scratch{reinterpret_cast<unsigned long long*>(base),
+                 reinterpret_cast<float*>(base + kWorkspaceHeader),
+                 reinterpret_cast<unsigned long long*>(base + kWorkspaceHeader + parts),
+                 base + kWorkspaceHeader + 3 * parts};
 }
 
 // Operands of the MFMA expand: v as high and low 16-bit parts, one range factor per row.
 size_t operand_bytes(int n_tokens, int r) {
   return 2 * round_up((size_t)n_tokens * r * 2, 256) + round_up((size_t)n_tokens * 4, 256);
 }
-void set_operands(ExpandArgs* a, void* workspace, int n_tokens, int r) {
-  char* base = static_cast<char*>(workspace) + kWorkspaceHeader + 3 * partial_bytes(n_tokens, r);
+void set_operands(ExpandArgs* a, char* base, int n_tokens, int r) {
   const size_t half = round_up((size_t)n_tokens * r * 2, 256);
   a->vh = reinterpret_cast<uint16_t*>(base);
   a->vl = reinterpret_cast<uint16_t*>(base + half);
@@ -156,6 +199,7 @@ void set_operands(ExpandArgs* a, void* workspace, int n_tokens, int r) {
 // Launch shape of the single-launch path; false when it does not apply.
 bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f) {
   if (!p->workspace_ready) return false;
+  const Limits lim = limits();
   if (p->max_seg_len != 1) return false;  // one row per segment; longer ones go to the tile kernel
   if (n_segs > kFusedMaxWorkgroups) return false;
   const int cap = split_cap(p->n_tokens);
@@ -163,7 +207,7 @@ bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f) {
   if (need > cap) return false;
   // every workgroup of a launch must be resident at once (one per compute unit): a
   // workgroup that waits for a slice of a workgroup not yet started only idles
-  int s = p->ksplit > 0 ? p->ksplit : kFusedWorkgroups / n_segs;
+  int s = p->ksplit > 0 ? p->ksplit : lim.fused_workgroups / n_segs;
   if (p->ksplit == 0 && s > kFusedSlices) s = kFusedSlices;
   if (p->ksplit == 0) {  // a power of two: measured 5-20 % faster than the odd counts in between
     int pw = 1;
@@ -173,7 +217,7 @@ bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f) {
   // Small batches at high rank: where a slice of A_i at eight slices takes more than one batch
   // of loads (2048 128-bit chunks), sixteen slices are faster while they are all resident
   // (measured at r = 64, h = 4096 / 5120, 1..8 segments: 5.1 / 5.8 us against 5.4 / 6.7 us)
-  if (p->ksplit == 0 && s == kFusedSlices && 2 * s * n_segs <= kFusedWorkgroups &&
+  if (p->ksplit == 0 && s == kFusedSlices && 2 * s * n_segs <= lim.fused_workgroups &&
       (long long)ceil_div(p->h_in, s) * (p->r / 8) > 2048)
     s = 2 * kFusedSlices;
   const int wide = p->h_in > p->h_out ? p->h_in : p->h_out;
@@ -185,12 +229,12 @@ bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f) {
   if ((long long)s * n_segs > kFusedMaxWorkgroups) return false;
   // slices forced by a very wide input can outnumber the compute units several times over;
   // from about two rounds of workgroups on the launch-per-step kernels are faster (measured)
-  if (p->path == SGMV_PATH_AUTO && p->ksplit == 0 && (long long)s * n_segs > 2 * kFusedWorkgroups)
+  if (p->path == SGMV_PATH_AUTO && p->ksplit == 0 && (long long)s * n_segs > 2 * lim.fused_workgroups)
     return false;
   // likewise batches of more than 128 segments that need two slices each (measured at
   // h = 4096, r = 16: 192 segments 17.3 us here against 15.5 us, 256 segments 20.0 against 18.3)
-  if (p->path == SGMV_PATH_AUTO && p->ksplit == 0 && n_segs > kFusedWorkgroups / 2 &&
-      (long long)s * n_segs > kFusedWorkgroups)
+  if (p->path == SGMV_PATH_AUTO && p->ksplit == 0 && n_segs > lim.fused_workgroups / 2 &&
+      (long long)s * n_segs > lim.fused_workgroups)
     return false;
   f->S = s;
   f->kslice = ceil_div(ceil_div(p->h_in, s), 8) * 8;
@@ -207,6 +251,7 @@ bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f) {
 // Launch shape of the single-launch MFMA kernel; false when it does not apply.
 bool choose_tile(const sgmv_problem* p, int n_segs, TileArgs* t) {
   if (!p->workspace_ready) return false;
+  const Limits lim = limits();
   if (p->max_seg_len <= 0 || p->max_seg_len > kTileMaxSegLen) return false;
   if (n_segs > kFusedMaxWorkgroups) return false;
   const int cap = split_cap(p->n_tokens);
@@ -217,26 +262,26 @@ bool choose_tile(const sgmv_problem* p, int n_segs, TileArgs* t) {
   // slices, must all be resident together (one workgroup per unit).
   long long blocks = (long long)n_segs * z;
   long long live = blocks < (long long)n_segs + p->n_tokens / 16 ? blocks : (long long)n_segs + p->n_tokens / 16;
-  if (live > kFusedWorkgroups) {  // too many even with one slice: fewer row blocks, walked with a stride
-    z = kFusedWorkgroups / n_segs > 0 ? kFusedWorkgroups / n_segs : 1;
+  if (live > lim.fused_workgroups) {  // too many even with one slice: fewer row blocks, walked with a stride
+    z = lim.fused_workgroups / n_segs > 0 ? lim.fused_workgroups / n_segs : 1;
     blocks = live = (long long)n_segs * z;
   }
   // (Fewer row blocks per segment than the longest one needs would leave room for more slices
   // where the weight slices do not fit the LDS, but workgroups that walk several blocks in turn
   // measured slower than the launch-per-step kernels.)
-  int s = p->ksplit > 0 ? p->ksplit : (int)(kFusedWorkgroups / live);
+  int s = p->ksplit > 0 ? p->ksplit : (int)(lim.fused_workgroups / live);
   if (p->ksplit == 0 && s > kFusedSlices) s = kFusedSlices;
-  if (p->ksplit == 0 && s > kTileMaxGrid / blocks) s = (int)(kTileMaxGrid / blocks);  // workgroups launched in all
+  if (p->ksplit == 0 && s > lim.tile_max_grid / blocks) s = (int)(lim.tile_max_grid / blocks);  // workgroups launched in all
   if (s > narrow / 64) s = narrow / 64;  // no slice thinner than 64
   if (s > cap) s = cap;
   if (s < 1) s = 1;
-  if (s * live > kFusedWorkgroups || s * blocks > kTileMaxGrid) return false;
+  if (s * live > lim.fused_workgroups || s * blocks > lim.tile_max_grid) return false;
   for (;; ++s) {  // more slices make the LDS-resident weight slices smaller
     t->kslice = ceil_div(ceil_div(p->h_in, s), 32) * 32;
     t->cslice = ceil_div(ceil_div(p->h_out, s), 64) * 64;
     t->lds_bytes = tile_lds_bytes(p->r, t->kslice, t->cslice);
     if (t->lds_bytes <= kTileMaxLds) break;
-    if (p->ksplit > 0 || s + 1 > cap || (s + 1) * live > kFusedWorkgroups || (s + 1) * blocks > kTileMaxGrid)
+    if (p->ksplit > 0 || s + 1 > cap || (s + 1) * live > lim.fused_workgroups || (s + 1) * blocks > lim.tile_max_grid)
       return false;
   }
   t->S = s;
@@ -244,20 +289,20 @@ bool choose_tile(const sgmv_problem* p, int n_segs, TileArgs* t) {
   return true;
 }
 
-void fill_fused(FusedArgs* f, const sgmv_problem* p, const int32_t* seg_starts, int n_segs,
-                int layer_idx, float scale) {
+void fill_fused(FusedArgs* f, const sgmv_problem* p, const Scratch& sc, const int32_t* seg_starts,
+                int n_segs, int layer_idx, float scale) {
   f->bf16 = p->dtype == SGMV_BF16;
   f->r = p->r;
   f->h_in = p->h_in;
   f->h_out = p->h_out;
   f->n_tokens = p->n_tokens;
   f->n_segs = n_segs;
-  f->spin_limit = kFusedSpinLimit;
+  f->spin_limit = spin_limit_of(p);
   f->offA = (long long)layer_idx * p->h_in * p->r;
   f->offB = (long long)layer_idx * p->r * p->h_out;
   f->seg_starts = seg_starts;
-  f->exch = exchange_base(p->workspace, p->n_tokens, p->r);
-  f->header = static_cast<unsigned long long*>(p->workspace);
+  f->exch = sc.exch;
+  f->header = sc.header;
   f->scale = scale;
   f->n_proj = 0;
   f->Z = 1;
@@ -276,8 +321,9 @@ int choose_expand_threads(const sgmv_problem* p, int n_segs) {
   return 64;
 }
 
-ShrinkArgs make_shrink(const sgmv_problem* p, const void* x, const void* const* A_ptrs,
-                       const int32_t* seg_starts, int n_segs, int layer_idx) {
+ShrinkArgs make_shrink(const sgmv_problem* p, const Scratch& sc, const void* x,
+                       const void* const* A_ptrs, const int32_t* seg_starts, int n_segs,
+                       int layer_idx) {
   ShrinkArgs a;
   a.bf16 = p->dtype == SGMV_BF16;
   a.r = p->r;
@@ -290,7 +336,7 @@ ShrinkArgs make_shrink(const sgmv_problem* p, const void* x, const void* const* 
   a.x = x;
   a.A_ptrs = A_ptrs;
   a.seg_starts = seg_starts;
-  a.partials = partials_base(p->workspace);
+  a.partials = sc.partials;
   return a;
 }
 
@@ -353,16 +399,17 @@ int plan_single(const sgmv_problem* p, int n_segs, SinglePlan* pl) {
 // Multi-projection call: SGMV_KERNEL_MULTI_SIDE / _PIPELINED with the launch shape in *f, or
 // SGMV_KERNEL_SEQUENCE (one sgmv_add_lora after the other).
 int plan_multi(const sgmv_problem* p, int n_segs, int n_proj, FusedArgs* f) {
+  const Limits lim = limits();
   if ((p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->max_seg_len == 1 && n_proj > 1 &&
       p->workspace != nullptr && choose_fused(p, n_segs, f) && f->S * n_proj <= split_cap(p->n_tokens)) {
     f->r = p->r;
-    if ((long long)f->S * n_segs * n_proj <= kMultiWorkgroups) return SGMV_KERNEL_MULTI_SIDE;
+    if ((long long)f->S * n_segs * n_proj <= lim.multi_workgroups) return SGMV_KERNEL_MULTI_SIDE;
     if (fused_multi_fits(*f)) return SGMV_KERNEL_MULTI_PIPELINED;
     // slices too deep for the pipelined kernel's register sets (h_in = 5120 at four slices):
     // three workgroups per compute unit still beat one launch per add-on (measured, three
     // projections of 64 segments at h = 5120: 22.7 us against 24.8 us)
     // (ranks up to 16 only: the kernels of the higher ranks use more registers and fit two per unit)
-    if (p->r <= 16 && (long long)f->S * n_segs * n_proj <= kMultiWorkgroupsMost) return SGMV_KERNEL_MULTI_SIDE;
+    if (p->r <= 16 && (long long)f->S * n_segs * n_proj <= lim.multi_workgroups_most) return SGMV_KERNEL_MULTI_SIDE;
   }
   return SGMV_KERNEL_SEQUENCE;
 }
@@ -443,7 +490,7 @@ int sgmv_shrink(const sgmv_problem* p, float* v, const void* x, const void* cons
   if (p->path == SGMV_PATH_FUSED) return SGMV_ERR_UNSUPPORTED;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
-  ShrinkArgs a = make_shrink(p, x, A_ptrs, seg_starts, n_segs, layer_idx);
+  ShrinkArgs a = make_shrink(p, caller_scratch(p), x, A_ptrs, seg_starts, n_segs, layer_idx);
   if (use_matrix(p, n_segs)) {
     choose_split_matrix(p, n_segs, &a.ksplit, &a.kslice);
     if (launch_shrink_matrix(a, st) != hipSuccess) return SGMV_ERR_LAUNCH;
@@ -471,7 +518,7 @@ int sgmv_expand(const sgmv_problem* p, void* y, const float* v, const void* cons
   const bool have_ws = check_workspace(p) == SGMV_OK;
   if (p->path == SGMV_PATH_MATRIX && !have_ws) return check_workspace(p);
   if (have_ws && use_matrix(p, n_segs)) {
-    set_operands(&a, p->workspace, p->n_tokens, p->r);
+    set_operands(&a, caller_scratch(p).operands, p->n_tokens, p->r);
     if (launch_expand_matrix(a, st) != hipSuccess) return SGMV_ERR_LAUNCH;
   } else {
     if (launch_expand_vector(a, st) != hipSuccess) return SGMV_ERR_LAUNCH;
@@ -479,20 +526,33 @@ int sgmv_expand(const sgmv_problem* p, void* y, const float* v, const void* cons
   return SGMV_OK;
 }
 
-int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x, const void* const* A_ptrs,
-                  const void* const* B_ptrs, const int32_t* seg_starts, int32_t n_segs,
-                  int32_t layer_idx, float scale, void* stream) {
-  int rc = check_common(p, seg_starts, n_segs, layer_idx, true, true);
+}  // extern "C"
+
+namespace {
+
+// Argument checks of the whole add-on that do not concern the scratch memory.
+int check_add_lora(const sgmv_problem* p, const void* y, const void* x, const void* const* A_ptrs,
+                   const void* const* B_ptrs, const int32_t* seg_starts, int32_t n_segs,
+                   int32_t layer_idx, bool* nothing_to_do) {
+  *nothing_to_do = false;
+  const int rc = check_common(p, seg_starts, n_segs, layer_idx, true, true);
   if (rc != SGMV_OK) return rc;
-  if (n_segs == 0 || p->n_tokens == 0) return SGMV_OK;
+  if (n_segs == 0 || p->n_tokens == 0) {
+    *nothing_to_do = true;
+    return SGMV_OK;
+  }
   if (y == nullptr || x == nullptr || A_ptrs == nullptr || B_ptrs == nullptr) return SGMV_ERR_NULL;
   if (!aligned(y, 16) || !aligned(x, 16)) return SGMV_ERR_ALIGN;
-  rc = check_workspace(p);
-  if (rc != SGMV_OK) return rc;
+  return SGMV_OK;
+}
 
-  hipStream_t st = static_cast<hipStream_t>(stream);
+// The add-on on checked arguments, its intermediate results in `sc`.
+int add_lora_launch(const sgmv_problem* p, const Scratch& sc, void* y, const void* x,
+                    const void* const* A_ptrs, const void* const* B_ptrs,
+                    const int32_t* seg_starts, int32_t n_segs, int32_t layer_idx, float scale,
+                    hipStream_t st) {
   SinglePlan pl;
-  rc = plan_single(p, n_segs, &pl);
+  const int rc = plan_single(p, n_segs, &pl);
   if (rc != SGMV_OK) return rc;
   switch (pl.kernel) {
     case SGMV_KERNEL_TILE: {
@@ -503,7 +563,7 @@ int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x, const void* con
       t.h_out = p->h_out;
       t.n_tokens = p->n_tokens;
       t.n_segs = n_segs;
-      t.spin_limit = kFusedSpinLimit;
+      t.spin_limit = spin_limit_of(p);
       t.offA = (long long)layer_idx * p->h_in * p->r;
       t.offB = (long long)layer_idx * p->r * p->h_out;
       t.y = y;
@@ -511,14 +571,14 @@ int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x, const void* con
       t.A_ptrs = A_ptrs;
       t.B_ptrs = B_ptrs;
       t.seg_starts = seg_starts;
-      t.exch = exchange_base(p->workspace, p->n_tokens, p->r);
-      t.header = static_cast<unsigned long long*>(p->workspace);
+      t.exch = sc.exch;
+      t.header = sc.header;
       t.scale = scale;
       return launch_add_lora_tile(t, st) == hipSuccess ? SGMV_OK : SGMV_ERR_LAUNCH;
     }
     case SGMV_KERNEL_FUSED: {
       FusedArgs& f = pl.fused;
-      fill_fused(&f, p, seg_starts, n_segs, layer_idx, scale);
+      fill_fused(&f, p, sc, seg_starts, n_segs, layer_idx, scale);
       f.y = y;
       f.x = x;
       f.A_ptrs = A_ptrs;
@@ -526,17 +586,17 @@ int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x, const void* con
       return launch_add_lora_fused(f, st) == hipSuccess ? SGMV_OK : SGMV_ERR_LAUNCH;
     }
     case SGMV_KERNEL_MATRIX: {
-      ShrinkArgs sa = make_shrink(p, x, A_ptrs, seg_starts, n_segs, layer_idx);
+      ShrinkArgs sa = make_shrink(p, sc, x, A_ptrs, seg_starts, n_segs, layer_idx);
       sa.ksplit = pl.ksplit;
       sa.kslice = pl.kslice;
       if (launch_shrink_matrix(sa, st) != hipSuccess) return SGMV_ERR_LAUNCH;
       ExpandArgs e = make_expand(p, y, sa.partials, sa.ksplit, A_ptrs, B_ptrs, seg_starts, n_segs,
                                  layer_idx, scale);
-      set_operands(&e, p->workspace, p->n_tokens, p->r);
+      set_operands(&e, sc.operands, p->n_tokens, p->r);
       return launch_expand_matrix(e, st) == hipSuccess ? SGMV_OK : SGMV_ERR_LAUNCH;
     }
     default: {
-      ShrinkArgs sa = make_shrink(p, x, A_ptrs, seg_starts, n_segs, layer_idx);
+      ShrinkArgs sa = make_shrink(p, sc, x, A_ptrs, seg_starts, n_segs, layer_idx);
       sa.ksplit = pl.ksplit;
       sa.kslice = pl.kslice;
       if (launch_shrink_vector(sa, st) != hipSuccess) return SGMV_ERR_LAUNCH;
@@ -545,6 +605,22 @@ int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x, const void* con
       return launch_expand_vector(e, st) == hipSuccess ? SGMV_OK : SGMV_ERR_LAUNCH;
     }
   }
+}
+
+}  // namespace
+
+extern "C" {
+
+int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x, const void* const* A_ptrs,
+                  const void* const* B_ptrs, const int32_t* seg_starts, int32_t n_segs,
+                  int32_t layer_idx, float scale, void* stream) {
+  bool nothing = false;
+  int rc = check_add_lora(p, y, x, A_ptrs, B_ptrs, seg_starts, n_segs, layer_idx, &nothing);
+  if (rc != SGMV_OK || nothing) return rc;
+  rc = check_workspace(p);
+  if (rc != SGMV_OK) return rc;
+  return add_lora_launch(p, caller_scratch(p), y, x, A_ptrs, B_ptrs, seg_starts, n_segs, layer_idx,
+                         scale, static_cast<hipStream_t>(stream));
 }
 
 int sgmv_add_lora_multi(const sgmv_problem* p, int32_t n_proj, void* const* ys,
@@ -570,7 +646,7 @@ int sgmv_add_lora_multi(const sgmv_problem* p, int32_t n_proj, void* const* ys,
   FusedArgs f;
   const int kernel = plan_multi(p, n_segs, n_proj, &f);
   if (kernel != SGMV_KERNEL_SEQUENCE) {
-    fill_fused(&f, p, seg_starts, n_segs, layer_idx, scale);
+    fill_fused(&f, p, caller_scratch(p), seg_starts, n_segs, layer_idx, scale);
     f.n_proj = n_proj;
     for (int i = 0; i < kMaxProjections; ++i) {
       f.table.x[i] = i < n_proj ? xs[i] : nullptr;

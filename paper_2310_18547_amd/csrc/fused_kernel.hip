@@ -48,15 +48,8 @@
 #include "device_common.h"
 #include "exchange.h"
 #include "launch.h"
+#include "trace.h"
 
-// Optional timeline probe for kernel tuning: a tuning build defines this macro to
-// record a timestamp per (workgroup, point) in registers and to write them out when a
-// wave leaves; it is empty in the library.
-#ifndef SGMV_TRACE_POINT
-#define SGMV_TRACE_DECL
-#define SGMV_TRACE_POINT(point)
-#define SGMV_TRACE_FLUSH(cond, first, last)
-#endif
 
 namespace sgmv {
 

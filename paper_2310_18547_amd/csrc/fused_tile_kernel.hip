@@ -1,9 +1,9 @@
 // Single-launch LoRA add-on for batches whose segments hold a few rows each
 // (mixed adapter popularity: some requests share an adapter, most do not), gfx950.
 //
-// Same idea as the single-row kernel in fused_kernel.hip -- shrink and expand
-// of the paper's "two launches of the SGMV kernel" share ONE launch, and the
-// Split-K partial sums are handed from workgroup to workgroup per segment
+// Same idea as the single-row kernel in fused_kernel.hip -- the paper runs the
+// LoRA add-on as two SGMV launches (shrink, then expand); here both share ONE
+// launch, and the Split-K partial sums are handed from workgroup to workgroup per segment
 // instead of through a grid synchronisation -- but a segment's rows are
 // processed sixteen at a time on the matrix cores: with more than one row per
 // adapter the per-segment product is a small dense contraction (the paper's
@@ -38,13 +38,9 @@
 #include "device_common.h"
 #include "exchange.h"
 #include "launch.h"
+#include "trace.h"
 #include "mfma.h"
 
-#ifndef SGMV_TRACE_POINT
-#define SGMV_TRACE_DECL
-#define SGMV_TRACE_POINT(point)
-#define SGMV_TRACE_FLUSH(cond, first, last)
-#endif
 
 namespace sgmv {
 

@@ -1,15 +1,16 @@
 // MFMA path of SGMV for long (prefill-shaped) segments, gfx950.
 //
 // When a segment holds hundreds of rows, the per-segment product really is a
-// dense contraction (the paper groups requests "to increase operational
-// intensity and use Tensor Cores"), and at ranks up to 64 the vector ALUs can no
-// longer keep up with HBM: the shrink needs r FLOP per byte of x and the expand
-// r/2 FLOP per byte of y.  Both kernels are still bound by HBM (x is read once,
-// y is read and written once); the matrix cores only have to be fast enough not
-// to matter, so the code is organised around streaming x and y, not around
-// MFMA utilisation.
+// dense contraction -- the reason the paper gives for grouping the requests of
+// one adapter (section "Segmented Gather Matrix-Vector Multiplication", kernel
+// schedule paragraph: higher operational intensity, matrix units) -- and at
+// ranks up to 64 the vector ALUs can no longer keep up with HBM: the shrink
+// needs r FLOP per byte of x and the expand r/2 FLOP per byte of y.  All
+// kernels here are still bound by HBM (x is read once, y is read and written
+// once); the matrix cores only have to be fast enough not to matter, so the
+// code is organised around how x and y stream, not around MFMA utilisation.
 //
-// Both kernels use v_mfma_f32_16x16x32_{f16,bf16}.  Its operands want eight
+// The kernels use v_mfma_f32_16x16x32_{f16,bf16}.  Its operands want eight
 // consecutive k per lane: lane l of a wave holds row (l % 16), k = 8 (l / 16) ..
 // +7 of the first operand and column (l % 16), same k, of the second; it
 // receives D[4 (l / 16) + i][l % 16], i = 0..3.  x and v are k-contiguous in
@@ -18,19 +19,23 @@
 // on the way in, so the LDS writes are conflict-free dword writes) and are then
 // reused for every row tile of the workgroup.
 //
-//   shrink  workgroup = (segment, block of 64 rows, k-slice); wave w owns rows
-//           16w..16w+15 of the block.  The k-slice is walked in chunks of 256:
-//           the chunk of A_i is staged transposed in LDS while the wave's x
-//           loads (eight 128-bit loads per lane) are in flight.  Split-K
-//           partial sums go to the workspace exactly like the vector path's.
-//   expand  workgroup = (segment, strip of 256 columns, block of rows); wave w
-//           owns 64 columns.  The strip of B_i is staged once and kept in
-//           registers as MFMA operands.  The product is taken transposed
-//           (D = B_i^T v^T) with the columns of four 16-wide tiles interleaved,
-//           so that a lane ends up with 16 consecutive columns of one row and
-//           y is read and written with 128-bit accesses.  v stays fp32 in the
-//           workspace; it enters the matrix cores as a high and a low 16-bit
-//           part (two MFMAs), which keeps ~16 significant bits.
+//   shrink_stream_kernel   workgroup = (k-slice, row block, segment).  The slice of A_i
+//           (at most 512 deep) stays in LDS for the workgroup's lifetime; each wave walks
+//           its sixteen-row tiles of x as one sequence of register banks, two in flight,
+//           and never meets the other waves again after the one staging barrier.  A_i^T
+//           is the first operand, so a lane ends with four consecutive columns of one
+//           row and the split-K partial sums leave as 128-bit stores.
+//   shrink_matrix_kernel   the same partial sums for slices too deep for the LDS: the
+//           slice is walked in chunks of 256 k that are restaged between barriers.
+//   finalize_v_kernel      sums the split-K partial sums in ascending order and writes v
+//           as a high and a low 16-bit part plus a range factor per row (binary16).
+//   expand_matrix_kernel   workgroup = (strip of 256 columns, block of rows, segment);
+//           v is the first operand and the strip of B_i (kept in registers) the second,
+//           tile t of a wave holding columns 4 n + t, so a lane ends with four
+//           consecutive columns (8 bytes) of four rows and every 64-bit access of y by
+//           a wave covers four rows x 128 contiguous bytes.  v stays fp32 in the
+//           workspace between the kernels; it enters the matrix cores as the two 16-bit
+//           parts (two MFMAs, 16 significant bits for bfloat16, 22 for binary16).
 #include <atomic>
 #include <type_traits>
 
@@ -38,12 +43,6 @@
 #include "launch.h"
 #include "mfma.h"
 
-// Timeline probes for development builds; empty in the library.
-#ifndef SGMV_TRACE_POINT
-#define SGMV_TRACE_DECL
-#define SGMV_TRACE_POINT(point)
-#define SGMV_TRACE_FLUSH(cond, first, last)
-#endif
 
 namespace sgmv {
 
@@ -268,8 +267,6 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
   constexpr int XB = kStreamBank;
   constexpr int AB = 4;          // staging items (two 128-bit loads each) per thread and batch
   extern __shared__ __align__(16) uint32_t at[];  // (stream_kpad(kslice) / 8) * BLK slots
-  SGMV_TRACE_DECL
-  SGMV_TRACE_POINT(0);
 
   const int seg = blockIdx.z, s = blockIdx.x, tid = threadIdx.x;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -281,7 +278,6 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
   const int klen = min(h_in, k0 + kslice) - k0;
   if (klen <= 0) return;
   const int m = lane & 15, g = lane >> 4;
-  SGMV_TRACE_POINT(1);
 
   // this wave's tiles: rows lo + ROWS (blockIdx.y + j gridDim.y) + 16 wave .. +15, j = 0 .. my_tiles-1
   const int span = hi - lo - wave * 16;
@@ -332,7 +328,6 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
       if (base == 0) {
         load_bank(q0, 0, 0);  // banks past the wave's tiles load nothing
         load_bank(q1, nb > 1 ? 0 : 1, nb > 1 ? 1 : 0);
-        SGMV_TRACE_POINT(2);
       }
 #pragma unroll
       for (int u = 0; u < AB; ++u) {
@@ -361,7 +356,6 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-  SGMV_TRACE_POINT(3);
 
   // ---- stream
   f32x4 acc[NTILE];
@@ -418,9 +412,6 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
     consume(q1);
     refill(q1);
   }
-  SGMV_TRACE_POINT(4);
-  SGMV_TRACE_POINT(5);
-  SGMV_TRACE_FLUSH(tid == 0, 0, 5);
 }
 
 // ---------------------------------------------------------------- expand
@@ -428,7 +419,7 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
 // v[row][k] = sum over the split-K parts (ascending), written out as the two 16-bit
 // operands the expand kernel feeds to the matrix cores: vh, vl [n_tokens][R] 16-bit,
 // undo [n_tokens] fp32 (finalize_quad).  One thread handles four consecutive k of a row;
-// the kernel is one memory latency long.  Used when the shrink launch did not prepare them.
+// the kernel is one memory latency long.
 template <class DT, int R>
 __global__ __launch_bounds__(256) void finalize_v_kernel(
     const float* __restrict__ v_parts, int nparts, uint16_t* __restrict__ vh,
@@ -474,8 +465,6 @@ __global__ __launch_bounds__(256, (R <= 32 ? 4 : 3) - (std::is_same<DT, F16>::va
   // n = 0..15) read consecutive slots.
   constexpr int BLK = NC + 1;
   __shared__ __align__(16) uint32_t bt[(KPAD / 8) * BLK * 4];
-  SGMV_TRACE_DECL
-  SGMV_TRACE_POINT(0);
 
   const int seg = blockIdx.z, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
@@ -487,7 +476,6 @@ __global__ __launch_bounds__(256, (R <= 32 ? 4 : 3) - (std::is_same<DT, F16>::va
   const int ncols = min(NC, h_out - c0);
   const __amdgpu_buffer_rsrc_t rB = make_buffer(
       B + layer_off + c0, (uint32_t)((long long)(R - 1) * h_out + ncols) * 2u);
-  SGMV_TRACE_POINT(1);
 
   // this lane: token rows 4 g + i of a tile (i = 0..3), columns cw .. cw + 3
   const int n = lane & 15, g = lane >> 4;
@@ -574,7 +562,6 @@ __global__ __launch_bounds__(256, (R <= 32 ? 4 : 3) - (std::is_same<DT, F16>::va
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-  SGMV_TRACE_POINT(2);
 
   // ---- second operands: tile t, lane (n, g): column 4 n + t of the wave's 64, k block 4 ks + g
   uint4 bop[KSTEPS][CT];
@@ -585,7 +572,6 @@ __global__ __launch_bounds__(256, (R <= 32 ? 4 : 3) - (std::is_same<DT, F16>::va
       const int pos = t * (NC / 4) + wave * 16 + n;  // column wave * 64 + 4 n + t
       bop[ks][t] = *reinterpret_cast<const uint4*>(&bt[((ks * 4 + g) * BLK + pos) * 4]);
     }
-  SGMV_TRACE_POINT(3);
 
   auto finish = [&](int r0, const Tile& T) {
     f32x4 acc[CT];
@@ -630,7 +616,6 @@ __global__ __launch_bounds__(256, (R <= 32 ? 4 : 3) - (std::is_same<DT, F16>::va
       finish(r + 16, t1);
       fetch(r + 48, t1);
     }
-    if (first) SGMV_TRACE_POINT(4);
     const int rem = nrows - r;  // 1..48 rows left
     finish(r, t0);
     if (rem > 32) fetch(r + 32, t0);
@@ -642,8 +627,6 @@ __global__ __launch_bounds__(256, (R <= 32 ? 4 : 3) - (std::is_same<DT, F16>::va
     rbeg = lo + (int)next;
     nrows = min(hi, rbeg + rows_per_wg) - rbeg;
   }
-  SGMV_TRACE_POINT(5);
-  SGMV_TRACE_FLUSH(tid == 0, 0, 5);
 }
 
 // ---------------------------------------------------------------- launchers

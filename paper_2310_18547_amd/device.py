@@ -54,7 +54,8 @@ class DeviceWorkload:
 
     def __init__(self, w, device="cuda:0", n_sets: int = 1, max_seg_len_hint: bool = True,
                  path: int = B.PATH_AUTO, ksplit: int = 0, expand_threads: int = 0,
-                 init_workspace: bool = True, max_seg_len: Optional[int] = None):
+                 init_workspace: bool = True, max_seg_len: Optional[int] = None,
+                 spin_limit: int = 0):
         self.w = w
         self.device = torch.device(device)
         self.A: List[torch.Tensor] = _pool_to_dev(list(w.A), self.device)
@@ -78,7 +79,8 @@ class DeviceWorkload:
             workspace=self.workspace, workspace_bytes=self.ws_bytes,
             max_seg_len=(max_seg_len if max_seg_len is not None else
                          w.max_seg_len if max_seg_len_hint else 0), path=path, ksplit=ksplit,
-            expand_threads=expand_threads, workspace_ready=1 if init_workspace else 0)
+            expand_threads=expand_threads, workspace_ready=1 if init_workspace else 0,
+            spin_limit=spin_limit)
 
     # -- the three entry points, on set `k` ---------------------------------
     def add_lora(self, layer_idx: int = 0, k: int = 0, stream=None, scale: Optional[float] = None):

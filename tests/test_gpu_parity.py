@@ -344,6 +344,58 @@ def test_fused_counters_reset_between_calls():
     assert np.array_equal(d.y_bits(0), a)
 
 
+@pytest.mark.parametrize("kind", ["fused", "tile", "multi"])
+def test_give_up_is_reported_and_never_stores_an_incomplete_sum(kind):
+    # The bounded wait, forced from the host: with a poll limit of one a workgroup gives up as
+    # soon as a neighbour's partial sums are not there at its first look.  Every kernel still
+    # runs to its end; the rows of a workgroup that gave up keep their old value, all others
+    # hold the finished result, and the workspace's health check reports the give-up.
+    from paper_2310_18547_amd import binding as B
+    if kind == "tile":
+        ws = [wl.popularity("uniform", batch=64, h_in=4096, r=16, dtype="f16", num_layers=1, seed=7)]
+    else:
+        ws = [wl.decode_distinct(batch=32, h_in=4096, r=16, dtype="f16", num_layers=1, seed=70 + i)
+              for i in range(3 if kind == "multi" else 1)]
+    ds = [_dev(w, spin_limit=1) for w in ws]
+    d0 = ds[0]
+    plan = B.sgmv_plan_add_lora(d0.problem, ws[0].n_segs, len(ws))
+    assert plan.launches == 1 and plan.slices > 1
+    refs = [decode64(oracle.run_workload(w, n_threads=8), "f16") for w in ws]
+    seen = False
+    for attempt in range(5):
+        for d in ds:
+            d.reset_y()
+        if kind == "multi":
+            B.sgmv_add_lora_multi(d0.problem, [d.y[0] for d in ds], [d.x[0] for d in ds],
+                                  [d.A_ptrs for d in ds], [d.B_ptrs for d in ds], d0.seg_starts,
+                                  ws[0].n_segs, 0, 1.0)
+        else:
+            d0.add_lora(0)
+        status = d0.check()
+        assert status in (0, 8)                              # SGMV_OK or SGMV_ERR_TIMEOUT
+        for w, d, ref in zip(ws, ds, refs):
+            got_bits = d.y_bits()
+            got = decode64(got_bits, "f16")
+            untouched = got_bits == w.y0
+            finished = np.abs(got - ref) <= tolerance(ref)
+            assert np.all(untouched | finished), f"{kind}: a value that is neither old nor finished"
+            if status == 0:
+                assert np.all(finished)
+        if status == 8:
+            seen = True
+            break
+        B.sgmv_workspace_init(d0.workspace, d0.ws_bytes)
+    assert seen, "no workgroup ever gave up at a poll limit of one"
+    # the workspace is usable again once it has been initialised anew
+    B.sgmv_workspace_init(d0.workspace, d0.ws_bytes)
+    torch.cuda.synchronize()
+    d0.problem.spin_limit = 0
+    d0.reset_y()
+    d0.add_lora(0)
+    assert_parity(d0.y_bits(), oracle.run_workload(ws[0], n_threads=8), "f16", f"{kind} after re-initialisation")
+    assert d0.check() == 0
+
+
 def test_fused_graph_replay():
     # the bench's launch configuration: calls recorded into a HIP graph and replayed
     w = wl.decode_distinct(batch=64, h_in=4096, r=16, dtype="f16", num_layers=8, seed=47)
