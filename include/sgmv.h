@@ -26,7 +26,7 @@
  *     call only.  The library allocates nothing and frees nothing.  The only
  *     state it keeps between calls is per-device bookkeeping that changes no
  *     result (which kernels have had their LDS limit raised, the number of
- *     compute units); the
+ *     compute units, the address of sgmv_add_lora_static's array); the
  *     single-launch path keeps an epoch in the caller's workspace, see
  *     sgmv_workspace_init.
  *   - x is [n_tokens][h_in], y is [n_tokens][h_out], row-major, 16-bit floats
@@ -222,6 +222,33 @@ int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x,
                   const void* const* A_ptrs, const void* const* B_ptrs,
                   const int32_t* seg_starts, int32_t n_segs, int32_t layer_idx,
                   float scale, void* stream);
+
+/* sgmv_add_lora for callers that cannot allocate device memory or hand a workspace over:
+ * code under HIP graph capture that owns no buffer, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels and same result as sgmv_add_lora, but the
+ * intermediate results (split-K partial sums, exchange words, operands of v) live in a fixed
+ * array inside the library, SGMV_STATIC_SCRATCH_BYTES per GPU, held until the process ends;
+ * p->workspace, p->workspace_bytes and p->workspace_ready are ignored.  The call allocates
+ * and frees nothing.
+ *   - Limit: sgmv_workspace_bytes(p->n_tokens, p->r) <= SGMV_STATIC_MAX_WORKSPACE_BYTES
+ *     (for instance 64 tokens at rank 64, 256 at rank 16); larger batches return
+ *     SGMV_ERR_WORKSPACE.
+ *   - The first call on a GPU looks the array up and clears it with a small kernel on
+ *     `stream`; that call must not be made while `stream` is being captured into a graph
+ *     (SGMV_ERR_STATE).  Later calls may be captured.
+ *   - All calls on one GPU share that GPU's array, which keeps the previous call's contents
+ *     (the single-launch kernels tell calls apart by a generation number, so nothing has to
+ *     be cleared in between).  Calls that overlap in time on one GPU -- two streams, two
+ *     threads -- race on it: order them, or give the others a workspace of their own
+ *     through sgmv_add_lora.
+ *   - There is no health check for the array (sgmv_workspace_check takes a caller's
+ *     workspace); a give-up of the bounded wait leaves the affected rows of y unchanged. */
+#define SGMV_STATIC_SCRATCH_BYTES ((size_t)9 << 20)
+#define SGMV_STATIC_MAX_WORKSPACE_BYTES ((size_t)8 << 20)
+int sgmv_add_lora_static(const sgmv_problem* p, void* y, const void* x,
+                         const void* const* A_ptrs, const void* const* B_ptrs,
+                         const int32_t* seg_starts, int32_t n_segs, int32_t layer_idx,
+                         float scale, void* stream);
 
 /* Several LoRA add-ons of ONE shape in a single call: n_proj (at most 8)
  * independent add-ons y_i += scale * (x_i A^(i)_seg) B^(i)_seg that share the

@@ -95,6 +95,8 @@ def _load():
     L.sgmv_add_lora.argtypes = [P, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
                                 c.c_int32, c.c_int32, c.c_float, c.c_void_p]
     L.sgmv_add_lora.restype = c.c_int
+    L.sgmv_add_lora_static.argtypes = L.sgmv_add_lora.argtypes
+    L.sgmv_add_lora_static.restype = c.c_int
     L.sgmv_add_lora_multi.argtypes = [P, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
                                       c.c_void_p, c.c_int32, c.c_int32, c.c_float, c.c_void_p]
     L.sgmv_add_lora_multi.restype = c.c_int
@@ -182,6 +184,19 @@ def sgmv_add_lora(p: SgmvProblem, y, x, A_ptrs, B_ptrs, seg_starts, n_segs: int,
     if check and rc != 0:
         raise SgmvError(rc, "sgmv_add_lora")
     return rc
+
+
+def sgmv_add_lora_static(p: SgmvProblem, y, x, A_ptrs, B_ptrs, seg_starts, n_segs: int,
+                         layer_idx: int, scale: float, stream=None, check: bool = True) -> int:
+    rc = lib.sgmv_add_lora_static(ctypes.byref(p), _addr(y), _addr(x), _addr(A_ptrs), _addr(B_ptrs),
+                                  _addr(seg_starts), n_segs, layer_idx, scale, _stream(stream))
+    if check and rc != 0:
+        raise SgmvError(rc, "sgmv_add_lora_static")
+    return rc
+
+
+STATIC_SCRATCH_BYTES = 9 << 20
+STATIC_MAX_WORKSPACE_BYTES = 8 << 20
 
 
 def sgmv_add_lora_multi(p: SgmvProblem, ys, xs, A_ptrs, B_ptrs, seg_starts, n_segs: int,

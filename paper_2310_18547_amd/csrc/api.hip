@@ -5,9 +5,23 @@
 #include <stdint.h>
 
 #include <atomic>
+#include <mutex>
 
 #include "../../include/sgmv.h"
 #include "launch.h"
+
+// Scratch of sgmv_add_lora_static, one copy per GPU, held until the process ends:
+//   [0, 1 KiB)       header (epoch counters, error word)
+//   [1 KiB, 6 MiB)   exchange words of the single-launch kernels -- at a fixed place whatever
+//                    the batch, so that a word found there was always written as an exchange
+//                    word, with the generation tag of an earlier call
+//   [6 MiB, 9 MiB)   split-K partial sums and the MFMA expand's operands of v
+// In host code the array's name is only a handle for hipGetSymbolAddress; kernels get the
+// address that call returned.
+constexpr size_t kStaticExchangeEnd = (size_t)6 << 20;
+constexpr size_t kStaticBytes = (size_t)9 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+static_assert(kStaticBytes == SGMV_STATIC_SCRATCH_BYTES, "the header states the array's size");
 
 namespace {
 
@@ -607,6 +621,37 @@ int add_lora_launch(const sgmv_problem* p, const Scratch& sc, void* y, const voi
   }
 }
 
+// The device address of this GPU's copy of `scratch`, prepared for the single-launch kernels
+// the first time the GPU is seen: asked of the runtime once per device (every GPU holds its
+// own copy at its own address), then header and exchange words are cleared and the epoch set
+// by a small kernel on `st`.  Calls no allocator.
+int static_scratch(hipStream_t st, char** base) {
+  static std::mutex mutex;
+  static char* address[kMaxDevices];  // zero-initialised
+  static bool ready[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return SGMV_ERR_LAUNCH;
+  if (dev < 0 || dev >= kMaxDevices) return SGMV_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(mutex);
+  if (address[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return SGMV_ERR_LAUNCH;
+    address[dev] = static_cast<char*>(ptr);
+  }
+  if (!ready[dev]) {
+    // the clearing kernel must run once, not once per replay of a graph that captured it
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &capture) != hipSuccess || capture != hipStreamCaptureStatusNone) {
+      (void)hipGetLastError();
+      return SGMV_ERR_STATE;
+    }
+    if (launch_workspace_init(address[dev], kStaticExchangeEnd, 0, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+    ready[dev] = true;
+  }
+  *base = address[dev];
+  return SGMV_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -621,6 +666,34 @@ int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x, const void* con
   if (rc != SGMV_OK) return rc;
   return add_lora_launch(p, caller_scratch(p), y, x, A_ptrs, B_ptrs, seg_starts, n_segs, layer_idx,
                          scale, static_cast<hipStream_t>(stream));
+}
+
+int sgmv_add_lora_static(const sgmv_problem* p, void* y, const void* x, const void* const* A_ptrs,
+                         const void* const* B_ptrs, const int32_t* seg_starts, int32_t n_segs,
+                         int32_t layer_idx, float scale, void* stream) {
+  bool nothing = false;
+  int rc = check_add_lora(p, y, x, A_ptrs, B_ptrs, seg_starts, n_segs, layer_idx, &nothing);
+  if (rc != SGMV_OK || nothing) return rc;
+  if (sgmv_workspace_bytes(p->n_tokens, p->r) > SGMV_STATIC_MAX_WORKSPACE_BYTES) return SGMV_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* base = nullptr;
+  rc = static_scratch(st, &base);
+  if (rc != SGMV_OK) return rc;
+  // within the size limit both regions of the array hold what this batch needs (exchange
+  // words: twice the partial sums' bytes); checked all the same
+  const size_t parts = partial_bytes(p->n_tokens, p->r);
+  if (2 * parts > kStaticExchangeEnd - kWorkspaceHeader ||
+      parts + operand_bytes(p->n_tokens, p->r) > kStaticBytes - kStaticExchangeEnd)
+    return SGMV_ERR_WORKSPACE;
+  sgmv_problem q = *p;
+  q.workspace = base;
+  q.workspace_bytes = kStaticBytes;
+  q.workspace_ready = 1;
+  const Scratch sc{reinterpret_cast<unsigned long long*>(base),
+                   reinterpret_cast<float*>(base + kStaticExchangeEnd),
+                   reinterpret_cast<unsigned long long*>(base + kWorkspaceHeader),
+                   base + kStaticExchangeEnd + parts};
+  return add_lora_launch(&q, sc, y, x, A_ptrs, B_ptrs, seg_starts, n_segs, layer_idx, scale, st);
 }
 
 int sgmv_add_lora_multi(const sgmv_problem* p, int32_t n_proj, void* const* ys,

@@ -276,3 +276,16 @@ def test_plan_multi_at_width_5120():
     assert rc == 0 and pl.kernel == sg.KERNEL_MULTI_SIDE and pl.workgroups == 768 and pl.launches == 1
     rc, pl = _plan(64, 3, n_tokens=64, max_seg_len=1, h_in=5120, h_out=5120, r=64)
     assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and pl.launches == 3
+
+
+def test_static_entry_point_rejects_before_touching_a_device():
+    # the size limit and the plain argument errors are decided on the host
+    big = sg.make_problem(sg.F16, 256, 256, 64, 1, 4096, max_seg_len=1)
+    assert sg.sgmv_workspace_bytes(4096, 64) > sg.STATIC_MAX_WORKSPACE_BYTES
+    assert sg.sgmv_add_lora_static(big, 16, 16, 16, 16, 16, 4, 0, 1.0, check=False) == 5     # too large
+    small = sg.make_problem(sg.F16, 256, 256, 16, 1, 4, max_seg_len=1)
+    assert sg.sgmv_add_lora_static(small, None, 16, 16, 16, 16, 4, 0, 1.0, check=False) == 1  # y is NULL
+    assert sg.sgmv_add_lora_static(small, 24, 16, 16, 16, 16, 4, 0, 1.0, check=False) == 4    # y misaligned
+    assert sg.sgmv_add_lora_static(small, 16, 16, 16, 16, 16, 4, 3, 1.0, check=False) == 6    # layer out of range
+    assert sg.sgmv_add_lora_static(small, 16, 16, 16, 16, 16, 0, 0, 1.0, check=False) == 0    # nothing to do
+    assert sg.STATIC_SCRATCH_BYTES == 9 << 20
