@@ -275,7 +275,7 @@ def run_timeline(args):
     import torch
     from paper_2310_18547_amd import binding as B
     from paper_2310_18547_amd.device import DeviceWorkload
-    assert os.path.basename(B.library_path()) == "libsgmv_trace.so"
+    assert "trace" in os.path.basename(B.library_path()), "the timeline needs the trace build"
     w = make_workload(args.workload, args.seed, args.layers)
     d = DeviceWorkload(w, "cuda:0", n_sets=args.sets, path=args.path, ksplit=args.ksplit)
     plan = B.sgmv_plan_add_lora(d.problem, w.n_segs, 1)
@@ -523,7 +523,7 @@ def main():
     if args.table:
         return run_table(args)
     if args.timeline:
-        os.environ["SGMV_LIBRARY"] = "libsgmv_trace.so"
+        os.environ.setdefault("SGMV_LIBRARY", "libsgmv_trace.so")
 
     import torch
     from paper_2310_18547_amd import binding as B

@@ -55,4 +55,39 @@ __device__ __forceinline__ unsigned long long read_epoch(const unsigned long lon
   return v;
 }
 
+// Consumer side of the hand-off for one element: poll the S words at src, src + stride, ...
+// until all carry `tag`, and return the sum of their values in ascending slice order.  Gives
+// up after spin_limit incomplete polls (sets timed_out; the sum is then meaningless).
+//
+// One poll is a round trip to the memory side (about half a microsecond), so fresh data is
+// seen up to one round trip late.  Keeping several polls in flight, a fraction of a round
+// trip apart, was tried: hipcc's wait-count insertion loses track of the ring in the loop
+// and waits for every outstanding poll before each examination, which made the call 0.5 us
+// slower; the plain loop stays.
+__device__ __forceinline__ float collect_slices(const unsigned long long* src, long long stride, int S,
+                                                uint32_t tag, int spin_limit, bool& timed_out) {
+  float sum = 0.f;
+  for (int s0 = 0; s0 < S; s0 += 8) {
+    unsigned long long wv[8];
+    int polls = 0;
+    bool ready;
+    do {
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        wv[i] = __hip_atomic_load(src + (long long)min(s0 + i, S - 1) * stride, __ATOMIC_RELAXED,
+                                  __HIP_MEMORY_SCOPE_AGENT);
+      ready = true;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ready = ready && ((uint32_t)wv[i] == tag);
+      if (!ready && ++polls > spin_limit) {
+        timed_out = true;
+        break;
+      }
+    } while (!ready);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sum += (s0 + i < S) ? __uint_as_float((uint32_t)(wv[i] >> 32)) : 0.f;
+  }
+  return sum;
+}
+
 }  // namespace sgmv

@@ -130,28 +130,7 @@ __device__ __forceinline__ void add_lora_fused_body(
       for (int idx = lane; idx < nrows * R; idx += 64) {
         const int rb = idx / R, j = idx - rb * R;
         const unsigned long long* src = exch + (long long)(row0 + rb) * R + j;
-        float sum = 0.f;
-        for (int s0 = 0; s0 < S; s0 += 8) {
-          unsigned long long wv[8];
-          int polls = 0;
-          bool ready;
-          do {
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-              wv[i] = __hip_atomic_load(src + min(s0 + i, S - 1) * stride, __ATOMIC_RELAXED,
-                                        __HIP_MEMORY_SCOPE_AGENT);
-            ready = true;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) ready = ready && ((uint32_t)wv[i] == tag);
-            if (!ready && ++polls > spin_limit) {
-              block_timed_out = true;
-              break;
-            }
-          } while (!ready);
-#pragma unroll
-          for (int i = 0; i < 8; ++i)
-            sum += (s0 + i < S) ? __uint_as_float((uint32_t)(wv[i] >> 32)) : 0.f;
-        }
+        const float sum = collect_slices(src, stride, S, tag, spin_limit, block_timed_out);
         vs[rb][j] = sum;
       }
       block_timed_out = __any(block_timed_out);
@@ -197,22 +176,25 @@ __device__ __forceinline__ void add_lora_fused_body(
   for (int u = 0; u < U; ++u) a[u] = buffer_load128(rA, (uint32_t)(u * NT + tid) * 16u);
   __builtin_amdgcn_sched_barrier(0);  // keep x and A ahead of B and y in the memory pipe
   uint4 b[JL];
-  {
-    const bool active = cc * 8 < ncols;
-#pragma unroll
-    for (int j = 0; j < JL; ++j)
-      b[j] = buffer_load128(rB, active ? b_row0 + (uint32_t)j * row_bytes_out + (uint32_t)cc * 16u : kOutOfRange);
-  }
   uint4 yq[RB];
-  {
-    const __amdgpu_buffer_rsrc_t rY = make_buffer(
-        y + (long long)lo * h_out + col_lo,
-        ncols > 0 ? (uint32_t)((long long)(nrows_first - 1) * h_out + ncols) * 2u : 0u);
-    const bool active = cg == 0 && cc * 8 < ncols;
+  auto issue_b_y = [&]() {
+    {
+      const bool active = cc * 8 < ncols;
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-      yq[rb] = buffer_load128(rY, (active && rb < nrows_first) ? (uint32_t)rb * row_bytes_out + (uint32_t)cc * 16u : kOutOfRange);
-  }
+      for (int j = 0; j < JL; ++j)
+        b[j] = buffer_load128(rB, active ? b_row0 + (uint32_t)j * row_bytes_out + (uint32_t)cc * 16u : kOutOfRange);
+    }
+    {
+      const __amdgpu_buffer_rsrc_t rY = make_buffer(
+          y + (long long)lo * h_out + col_lo,
+          ncols > 0 ? (uint32_t)((long long)(nrows_first - 1) * h_out + ncols) * 2u : 0u);
+      const bool active = cg == 0 && cc * 8 < ncols;
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+        yq[rb] = buffer_load128(rY, (active && rb < nrows_first) ? (uint32_t)rb * row_bytes_out + (uint32_t)cc * 16u : kOutOfRange);
+    }
+  };
+  issue_b_y();
   __builtin_amdgcn_sched_barrier(0);
   SGMV_TRACE_POINT(1);
 

@@ -172,29 +172,7 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
     auto collect = [&](const Item& it) {
       bool item_timed_out = false;
       if (lane < R) {
-        const unsigned long long* src = words(it) + lane;
-        float sum = 0.f;
-        for (int s0 = 0; s0 < S; s0 += 8) {
-          unsigned long long wv[8];
-          int polls = 0;
-          bool ready;
-          do {
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-              wv[i] = __hip_atomic_load(src + min(s0 + i, S - 1) * stride, __ATOMIC_RELAXED,
-                                        __HIP_MEMORY_SCOPE_AGENT);
-            ready = true;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) ready = ready && ((uint32_t)wv[i] == tag);
-            if (!ready && ++polls > spin_limit) {
-              item_timed_out = true;
-              break;
-            }
-          } while (!ready);
-#pragma unroll
-          for (int i = 0; i < 8; ++i)
-            sum += (s0 + i < S) ? __uint_as_float((uint32_t)(wv[i] >> 32)) : 0.f;
-        }
+        const float sum = collect_slices(words(it) + lane, stride, S, tag, spin_limit, item_timed_out);
         vs[lane] = sum;
       }
       item_timed_out = __any(item_timed_out);
