@@ -296,10 +296,11 @@ def run_timeline(args):
         header[65] = 0
         rows.append(trace.cpu().numpy().reshape(n_wg, 10).astype(np.float64) * 0.01)  # 100 MHz -> us
     assert d.check() == 0
-    names = {0: "workgroup started", 8: "segment bounds and pointers known", 1: "all loads issued",
+    names = {0: "workgroup started", 8: "segment bounds and pointers known",
+             9: "first load about to issue", 1: "all loads issued",
              2: "x staged in LDS (first data)", 3: "shrink of the slice done", 4: "partial sums published",
              5: "all slices collected", 6: "y stored", 7: "exchange wave leaves"}
-    order = [0, 8, 1, 2, 3, 4, 5, 6, 7]
+    order = [0, 8, 9, 1, 2, 3, 4, 5, 6, 7] if plan.kernel == B.KERNEL_TILE else [0, 8, 1, 2, 3, 4, 5, 6, 7]
     points = []
     for p_ in order:
         per_rep = []

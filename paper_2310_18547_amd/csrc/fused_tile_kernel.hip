@@ -278,6 +278,9 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
   const int row_first = lo + (int)blockIdx.z * 16;
   const int nrows_first = min(16, hi - row_first);
   uint4 xq[XB];
+  __builtin_amdgcn_sched_barrier(0);
+  SGMV_TRACE_POINT(9);
+  __builtin_amdgcn_sched_barrier(0);
   {
     const __amdgpu_buffer_rsrc_t rX = x_rsrc(row_first, nrows_first);
 #pragma unroll
@@ -551,8 +554,14 @@ static hipError_t launch_tile_t(const TileArgs& a, hipStream_t st) {
     if (err != hipSuccess) return err;
     enabled[dev].store(true, std::memory_order_release);
   }
+  // A workgroup asks for more than half of the unit's LDS even when it uses less, so that no
+  // two of them share a compute unit: the grid has a workgroup per segment and block of the
+  // LONGEST segment, and the ones without rows, although they leave at once, hold unit slots
+  // at dispatch, so that live ones were doubled up on some units while others stayed empty
+  // (one long and many short segments: 10.1 us, the issue phase of every workgroup twice as long)
+  const size_t lds = a.lds_bytes > kTileExclusiveLds ? a.lds_bytes : kTileExclusiveLds;
   hipLaunchKernelGGL(kernel, dim3((unsigned)a.S, (unsigned)a.n_segs, (unsigned)a.Z), dim3(320),
-                     a.lds_bytes, st, a.seg_starts, (const uint16_t* const*)a.A_ptrs,
+                     lds, st, a.seg_starts, (const uint16_t* const*)a.A_ptrs,
                      (const uint16_t* const*)a.B_ptrs, (const uint16_t*)a.x, (uint16_t*)a.y, a.kslice,
                      a.cslice, a.h_in, a.h_out, a.n_tokens, a.S, a.offA, a.offB, a.exch, a.header,
                      a.scale, a.spin_limit);

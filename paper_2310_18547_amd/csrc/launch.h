@@ -85,6 +85,7 @@ struct FusedArgs {
 
 // Single-launch kernel for segments of a few rows (sixteen-row MFMA tiles).
 constexpr size_t kTileMaxLds = 160 * 1024;  // LDS of one compute unit
+constexpr size_t kTileExclusiveLds = 81 * 1024;  // more than half of it: one workgroup per unit
 struct TileArgs {
   bool bf16;
   int r, h_in, h_out, n_tokens, n_segs;

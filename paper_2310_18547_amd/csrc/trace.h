@@ -13,7 +13,8 @@
 //   1 all up-front loads issued    2 x (and, tile kernel, the A slice) staged in LDS
 //   3 shrink of the slice done     4 partial sums published (exchange wave)
 //   5 all slices collected         6 y stored (stream waves done)
-//   7 exchange wave leaves
+//   7 exchange wave leaves          9 address arithmetic done, first load about to issue
+//                                     (tile kernel only)
 #pragma once
 #include <hip/hip_runtime.h>
 
