@@ -285,22 +285,26 @@ def run_timeline(args):
     for i in range(64):                       # warm, untraced
         d.add_lora(i % w.num_layers, i % args.sets)
     torch.cuda.synchronize()
-    header = d.workspace[:1024].view(torch.int64)
+    header = d.workspace[:4352].view(torch.int64)  # generation copies (4 KiB), error word, trace word
     rows = []
     for rep in range(args.blocks):
         trace.zero_()
-        header[65] = trace.data_ptr()         # the word after the error word: trace on
+        header[513] = trace.data_ptr()        # eight bytes behind the error word: trace on
         torch.cuda.synchronize()
         d.add_lora((7 + rep) % w.num_layers, rep % args.sets)
         torch.cuda.synchronize()
-        header[65] = 0
+        header[513] = 0
         rows.append(trace.cpu().numpy().reshape(n_wg, 10).astype(np.float64) * 0.01)  # 100 MHz -> us
     assert d.check() == 0
     names = {0: "workgroup started", 8: "segment bounds and pointers known",
-             9: "first load about to issue", 1: "all loads issued",
+             9: "first load about to issue" if plan.kernel == B.KERNEL_TILE else "generation tag known (exchange wave)",
+             1: "all loads issued",
              2: "x staged in LDS (first data)", 3: "shrink of the slice done", 4: "partial sums published",
              5: "all slices collected", 6: "y stored", 7: "exchange wave leaves"}
-    order = [0, 8, 9, 1, 2, 3, 4, 5, 6, 7] if plan.kernel == B.KERNEL_TILE else [0, 8, 1, 2, 3, 4, 5, 6, 7]
+    order = [0, 8, 9, 1, 2, 3, 4, 5, 6, 7] if plan.kernel == B.KERNEL_TILE else [0, 8, 1, 9, 2, 3, 4, 5, 6, 7]
+    if plan.kernel == B.KERNEL_WHOLE:          # no hand-off: the workgroup has v once its own waves are summed
+        order = [0, 8, 1, 2, 3, 5, 6]
+        names[3], names[5] = "shrink done (all of A_i consumed)", "v summed over the waves"
     points = []
     for p_ in order:
         per_rep = []
@@ -326,6 +330,7 @@ def validate(d, w, op, sh):
                         (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64))
     layer = w.num_layers - 1
     d.reset_y(0)
+    torch.cuda.synchronize()          # the reset ran on torch's stream, the call below runs on `sh`
     if op == "shrink":
         v = torch.zeros(w.n_tokens, w.r, dtype=torch.float32, device="cuda:0")
         d.shrink(v, layer, 0, stream=sh)
@@ -448,7 +453,7 @@ def bench_one(args, op, d, w, probe):
             "what": "sgmv_probe streaming read of the same bytes in one launch, same timing protocol",
             "us": pus, "GB/s": bytes_step / pus / 1e3, "frac_of_peak": bytes_step / pus / 1e3 / HBM_PEAK_GBS,
             "step_over_probe": us / pus, "empty_launch_us": probe.time_us(B.PROBE_EMPTY, 0)}
-    if "MFMA" in kernel or "tile" in kernel or "matrix" in kernel or "stream" in kernel:
+    if "tile" in kernel or "matrix" in kernel or "stream" in kernel:
         # the contraction runs on the matrix cores; at r FLOP per byte of x and r/2 per byte of
         # y it sits far left of the MFMA ridge (~312 FLOP/B), so HBM stays the binding roofline
         tf = flops_step / (ms_per_step * 1e-3) / 1e12
@@ -533,7 +538,8 @@ def main():
                     B.KERNEL_MULTI_SIDE: "add_lora_fused_side_kernel",
                     B.KERNEL_MULTI_PIPELINED: "add_lora_fused_multi_kernel",
                     B.KERNEL_VECTOR: "shrink_vector_kernel + expand_vector_kernel",
-                    B.KERNEL_MATRIX: "shrink_stream_kernel + finalize_v_kernel + expand_matrix_kernel"}
+                    B.KERNEL_MATRIX: "shrink_stream_kernel + finalize_v_kernel + expand_matrix_kernel",
+                    B.KERNEL_WHOLE: "add_lora_whole_kernel"}
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.probe:
         return run_probe(args)

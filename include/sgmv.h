@@ -95,11 +95,17 @@ typedef enum {
   SGMV_PATH_VECTOR = 1,      /* bandwidth path: vector ALU, one launch per step    */
   SGMV_PATH_MATRIX = 2,      /* MFMA path: for long (prefill-like) segments; at    */
                              /* most 65535 segments, else SGMV_ERR_UNSUPPORTED     */
-  SGMV_PATH_FUSED = 3        /* sgmv_add_lora only: shrink and expand in a single  */
+  SGMV_PATH_FUSED = 3,       /* sgmv_add_lora only: shrink and expand in a single  */
                              /* launch; needs workspace_ready, max_seg_len > 0 and */
                              /* a launch whose workgroups (segments x sixteen-row  */
                              /* blocks x slices) are all resident with their weight*/
                              /* slices in LDS, else SGMV_ERR_UNSUPPORTED           */
+  SGMV_PATH_WHOLE = 4        /* sgmv_add_lora only: single launch for one-row      */
+                             /* segments (max_seg_len == 1) in which every         */
+                             /* workgroup computes its segment's whole shrink, so  */
+                             /* workgroups never wait for each other and no        */
+                             /* workspace is touched; h_in at most 8192, else      */
+                             /* SGMV_ERR_UNSUPPORTED                               */
 } sgmv_path;
 
 /* Problem descriptor: plain data, host memory, read during the call only. */
@@ -137,7 +143,8 @@ typedef enum {
   SGMV_KERNEL_MULTI_PIPELINED = 4,  /* several projections walked by every workgroup       */
   SGMV_KERNEL_VECTOR = 5,           /* one launch per step, vector ALUs                    */
   SGMV_KERNEL_MATRIX = 6,           /* one launch per step, MFMA (long segments)           */
-  SGMV_KERNEL_SEQUENCE = 7          /* internal: multi-projection call run as single calls */
+  SGMV_KERNEL_SEQUENCE = 7,         /* internal: multi-projection call run as single calls */
+  SGMV_KERNEL_WHOLE = 8             /* single launch, whole shrink in every workgroup      */
 } sgmv_kernel;
 
 /* What a call would launch: plain data filled by sgmv_plan_add_lora. */

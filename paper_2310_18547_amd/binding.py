@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, os.path.basename(os.environ.get("SGMV_LIBRARY", "libsgmv.so")))
 
 F16, BF16 = 0, 1
-PATH_AUTO, PATH_VECTOR, PATH_MATRIX, PATH_FUSED = 0, 1, 2, 3
+PATH_AUTO, PATH_VECTOR, PATH_MATRIX, PATH_FUSED, PATH_WHOLE = 0, 1, 2, 3, 4
 
 
 class SgmvError(RuntimeError):
@@ -62,10 +62,10 @@ class SgmvPlan(ctypes.Structure):
 
 
 KERNEL_NONE, KERNEL_FUSED, KERNEL_TILE, KERNEL_MULTI_SIDE, KERNEL_MULTI_PIPELINED, KERNEL_VECTOR, \
-    KERNEL_MATRIX, KERNEL_SEQUENCE = range(8)
+    KERNEL_MATRIX, KERNEL_SEQUENCE, KERNEL_WHOLE = range(9)
 KERNEL_NAMES = {KERNEL_NONE: "none", KERNEL_FUSED: "fused", KERNEL_TILE: "tile",
                 KERNEL_MULTI_SIDE: "multi_side", KERNEL_MULTI_PIPELINED: "multi_pipelined",
-                KERNEL_VECTOR: "vector", KERNEL_MATRIX: "matrix"}
+                KERNEL_VECTOR: "vector", KERNEL_MATRIX: "matrix", KERNEL_WHOLE: "whole"}
 
 
 def _load():

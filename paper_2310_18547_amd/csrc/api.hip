@@ -35,7 +35,7 @@ constexpr int kTargetWorkgroups = 512; // about two workgroups per compute unit
 constexpr int kTileMaxSegLen = 4096;
 constexpr int kMatrixMaxSegments = 65535;  // the MFMA kernels put the segment on a grid dimension limited to this
 constexpr int kFusedSlices = 8;        // most slices per segment the single-launch kernels pick
-constexpr int kFusedMaxWorkgroups = 1024;
+constexpr int kFusedMaxWorkgroups = kGenerationCopies;  // every workgroup of a launch has its own generation copy
 constexpr int kFusedSpinLimit = 1 << 18;
 constexpr int kMaxDevices = 64;
 constexpr int kDefaultComputeUnits = 256;  // MI355X; assumed where no device can be asked
@@ -104,7 +104,7 @@ int check_common(const sgmv_problem* p, const int32_t* seg_starts, int32_t n_seg
   if (p->r != 8 && p->r != 16 && p->r != 32 && p->r != 64) return SGMV_ERR_UNSUPPORTED;
   if ((need_in && (p->h_in % 8) != 0) || (need_out && (p->h_out % 8) != 0))
     return SGMV_ERR_UNSUPPORTED;
-  if (p->path < SGMV_PATH_AUTO || p->path > SGMV_PATH_FUSED) return SGMV_ERR_UNSUPPORTED;
+  if (p->path < SGMV_PATH_AUTO || p->path > SGMV_PATH_WHOLE) return SGMV_ERR_UNSUPPORTED;
   if (p->spin_limit < 0) return SGMV_ERR_UNSUPPORTED;
   if (p->ksplit < 0 || p->ksplit > kMaxKSplit) return SGMV_ERR_UNSUPPORTED;
   if (p->expand_threads != 0 && p->expand_threads != 64 && p->expand_threads != 128 &&
@@ -240,7 +240,9 @@ bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f) {
   if (s > kFusedMaxWorkgroups / n_segs) s = kFusedMaxWorkgroups / n_segs;
   if (s < need) s = need;
   if (s < 1) s = 1;
-  if ((long long)s * n_segs > kFusedMaxWorkgroups) return false;
+  // the grid is padded to whole rows of segments (launch.h, fused_grid_x)
+  const int gx = fused_grid_x(n_segs);
+  if ((long long)s * ceil_div(n_segs, gx) * gx > kFusedMaxWorkgroups) return false;
   // slices forced by a very wide input can outnumber the compute units several times over;
   // from about two rounds of workgroups on the launch-per-step kernels are faster (measured)
   if (p->path == SGMV_PATH_AUTO && p->ksplit == 0 && (long long)s * n_segs > 2 * lim.fused_workgroups)
@@ -259,6 +261,35 @@ bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f) {
   while (p->r / g > 16) g *= 2;
   f->G = g;
   f->rows_per_pass = 1;
+  return true;
+}
+
+// Launch shape of the single-launch kernel without hand-off (one-row segments, every workgroup
+// computes the whole shrink); false when it does not apply.
+bool choose_whole(const sgmv_problem* p, int n_segs, WholeArgs* w) {
+  if (p->max_seg_len != 1) return false;
+  if (p->h_in > kWholeMaxHin) return false;
+  // A_i is walked in whole steps of 256 128-bit loads, four or more to a batch
+  if ((long long)p->h_in * (p->r / 8) % (4 * 256) != 0) return false;
+  if (n_segs > 8 * 65535) return false;  // grid depth
+  const Limits lim = limits();
+  // as many column slices as keep the launch within one workgroup per compute unit
+  int s = p->ksplit > 0 ? p->ksplit : lim.fused_workgroups / n_segs;
+  if (p->ksplit == 0 && s > kFusedSlices) s = kFusedSlices;
+  if (p->ksplit == 0) {
+    int pw = 1;
+    while (pw * 2 <= s) pw *= 2;
+    s = pw;
+  }
+  if (s > p->h_out / 64) s = p->h_out / 64;
+  if (s < 1) s = 1;
+  w->S = s;
+  w->cslice = ceil_div(ceil_div(p->h_out, s), 8) * 8;
+  const int chunks = w->cslice / 8;
+  int g = 1;
+  while (g * 2 <= 8 && 256 / (g * 2) >= chunks) g *= 2;
+  while (p->r / g > 16) g *= 2;
+  w->G = g;
   return true;
 }
 
@@ -382,19 +413,40 @@ ExpandArgs make_expand(const sgmv_problem* p, void* y, const float* v_parts, int
 // choice, shared by the entry points and by sgmv_plan_add_lora.
 struct SinglePlan {
   int kernel;        // sgmv_kernel
+  WholeArgs whole;   // SGMV_KERNEL_WHOLE
   TileArgs tile;     // SGMV_KERNEL_TILE
   FusedArgs fused;   // SGMV_KERNEL_FUSED
   int ksplit, kslice;  // SGMV_KERNEL_MATRIX / SGMV_KERNEL_VECTOR
 };
 
 int plan_single(const sgmv_problem* p, int n_segs, SinglePlan* pl) {
+  if (p->path == SGMV_PATH_WHOLE) {
+    if (!choose_whole(p, n_segs, &pl->whole)) return SGMV_ERR_UNSUPPORTED;
+    pl->kernel = SGMV_KERNEL_WHOLE;
+    return SGMV_OK;
+  }
   if ((p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->max_seg_len != 1 &&
       choose_tile(p, n_segs, &pl->tile)) {
     pl->kernel = SGMV_KERNEL_TILE;
     return SGMV_OK;
   }
   if (p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) {
-    if (choose_fused(p, n_segs, &pl->fused)) {
+    const bool fused = choose_fused(p, n_segs, &pl->fused);
+    // One-row segments, measured on MI355X at h = 4096 (us per add-on, whole-shrink kernel
+    // against the alternative): at rank 8, where A_i is small, it beats the kernel with the
+    // hand-off at every batch (1 / 16 / 64 / 128 segments: 3.7 / 4.0 / 4.8 / 6.0 against 4.1 /
+    // 4.7 / 5.2 / 6.2) and the launch-per-step kernels beyond (256: 9.5 against 12.4); where the
+    // hand-off kernel does not apply (no prepared workspace, or more segments than it takes) it
+    // beats the launch-per-step kernels up to rank 16 and several hundred segments (192 / 256 /
+    // 512: 13.5 / 16.4 / 28.8 against 16.2 / 18.6 / 29.9; 1024: 53.9 against 51.2), without a
+    // workspace also at rank 32 (64 segments: 13.0 against 14.2; rank 64: 23.8 against 22.5).
+    if (p->path == SGMV_PATH_AUTO && p->ksplit == 0 && choose_whole(p, n_segs, &pl->whole) &&
+        ((p->r == 8 && n_segs <= 512) ||
+         (!fused && n_segs <= 640 && p->r <= (p->workspace_ready ? 16 : 32)))) {
+      pl->kernel = SGMV_KERNEL_WHOLE;
+      return SGMV_OK;
+    }
+    if (fused) {
       pl->kernel = SGMV_KERNEL_FUSED;
       return SGMV_OK;
     }
@@ -467,18 +519,19 @@ int sgmv_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
 int sgmv_workspace_check(const void* workspace, void* stream) {
   if (workspace == nullptr) return SGMV_ERR_NULL;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  // the epoch counters and, right after them, the error word
-  unsigned long long head[kEpochCounters + 1];
+  // the generation copies and, right after them, the error word and the initialisation mark
+  static_assert(kWorkspaceErrorOffset == (size_t)kGenerationCopies * 4, "error word follows the copies");
+  uint32_t head[kGenerationCopies + 2];
   if (hipMemcpyAsync(head, workspace, sizeof head, hipMemcpyDeviceToHost, st) != hipSuccess)
     return SGMV_ERR_LAUNCH;
   if (hipStreamSynchronize(st) != hipSuccess) return SGMV_ERR_LAUNCH;
-  // between launches the epoch is a whole number of steps; anything else means the workspace was
+  // between launches all copies of the generation agree; anything else means the workspace was
   // never initialised, or a launch did not account for all of its workgroups and later launches
   // may disagree about their generation
-  unsigned long long epoch = 0;
-  for (int i = 0; i < kEpochCounters; ++i) epoch += head[i];
-  if (epoch == 0 || epoch % kEpochStep != 0) return SGMV_ERR_STATE;
-  if ((unsigned)head[kEpochCounters] != 0) return SGMV_ERR_TIMEOUT;
+  if (head[kGenerationCopies + 1] != kWorkspaceMagic || head[0] == 0) return SGMV_ERR_STATE;
+  for (int i = 1; i < kGenerationCopies; ++i)
+    if (head[i] != head[0]) return SGMV_ERR_STATE;
+  if (head[kGenerationCopies] != 0) return SGMV_ERR_TIMEOUT;
   return SGMV_OK;
 }
 
@@ -501,7 +554,7 @@ int sgmv_shrink(const sgmv_problem* p, float* v, const void* x, const void* cons
   if (!aligned(v, 16) || !aligned(x, 16)) return SGMV_ERR_ALIGN;
   rc = check_workspace(p);
   if (rc != SGMV_OK) return rc;
-  if (p->path == SGMV_PATH_FUSED) return SGMV_ERR_UNSUPPORTED;
+  if (p->path == SGMV_PATH_FUSED || p->path == SGMV_PATH_WHOLE) return SGMV_ERR_UNSUPPORTED;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   ShrinkArgs a = make_shrink(p, caller_scratch(p), x, A_ptrs, seg_starts, n_segs, layer_idx);
@@ -524,7 +577,7 @@ int sgmv_expand(const sgmv_problem* p, void* y, const float* v, const void* cons
   if (n_segs == 0 || p->n_tokens == 0) return SGMV_OK;
   if (y == nullptr || v == nullptr || B_ptrs == nullptr) return SGMV_ERR_NULL;
   if (!aligned(v, 16) || !aligned(y, 16)) return SGMV_ERR_ALIGN;
-  if (p->path == SGMV_PATH_FUSED) return SGMV_ERR_UNSUPPORTED;
+  if (p->path == SGMV_PATH_FUSED || p->path == SGMV_PATH_WHOLE) return SGMV_ERR_UNSUPPORTED;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   ExpandArgs a = make_expand(p, y, v, 1, nullptr, B_ptrs, seg_starts, n_segs, layer_idx, scale);
@@ -569,6 +622,24 @@ int add_lora_launch(const sgmv_problem* p, const Scratch& sc, void* y, const voi
   const int rc = plan_single(p, n_segs, &pl);
   if (rc != SGMV_OK) return rc;
   switch (pl.kernel) {
+    case SGMV_KERNEL_WHOLE: {
+      WholeArgs& w = pl.whole;
+      w.bf16 = p->dtype == SGMV_BF16;
+      w.r = p->r;
+      w.h_in = p->h_in;
+      w.h_out = p->h_out;
+      w.n_segs = n_segs;
+      w.offA = (long long)layer_idx * p->h_in * p->r;
+      w.offB = (long long)layer_idx * p->r * p->h_out;
+      w.scale = scale;
+      w.y = y;
+      w.x = x;
+      w.A_ptrs = A_ptrs;
+      w.B_ptrs = B_ptrs;
+      w.seg_starts = seg_starts;
+      w.header = sc.header;
+      return launch_add_lora_whole(w, st) == hipSuccess ? SGMV_OK : SGMV_ERR_LAUNCH;
+    }
     case SGMV_KERNEL_TILE: {
       TileArgs& t = pl.tile;
       t.bf16 = p->dtype == SGMV_BF16;
@@ -662,6 +733,9 @@ int sgmv_add_lora(const sgmv_problem* p, void* y, const void* x, const void* con
   bool nothing = false;
   int rc = check_add_lora(p, y, x, A_ptrs, B_ptrs, seg_starts, n_segs, layer_idx, &nothing);
   if (rc != SGMV_OK || nothing) return rc;
+  if (p->path == SGMV_PATH_WHOLE && p->workspace == nullptr)  // that kernel keeps nothing in memory
+    return add_lora_launch(p, Scratch{nullptr, nullptr, nullptr, nullptr}, y, x, A_ptrs, B_ptrs, seg_starts,
+                           n_segs, layer_idx, scale, static_cast<hipStream_t>(stream));
   rc = check_workspace(p);
   if (rc != SGMV_OK) return rc;
   return add_lora_launch(p, caller_scratch(p), y, x, A_ptrs, B_ptrs, seg_starts, n_segs, layer_idx,
@@ -752,8 +826,10 @@ int sgmv_plan_add_lora(const sgmv_problem* p, int32_t n_segs, int32_t n_proj, sg
   if (rc != SGMV_OK) return rc;
   if (n_proj < 1 || n_proj > kMaxProjections) return SGMV_ERR_SHAPE;
   if (n_segs == 0 || p->n_tokens == 0) return SGMV_OK;  // nothing is launched
-  rc = check_workspace(p);
-  if (rc != SGMV_OK) return rc;
+  if (!(p->path == SGMV_PATH_WHOLE && p->workspace == nullptr && n_proj == 1)) {
+    rc = check_workspace(p);
+    if (rc != SGMV_OK) return rc;
+  }
   if (n_proj > 1) {
     FusedArgs f;
     const int kernel = plan_multi(p, n_segs, n_proj, &f);
@@ -770,6 +846,12 @@ int sgmv_plan_add_lora(const sgmv_problem* p, int32_t n_segs, int32_t n_proj, sg
   if (rc != SGMV_OK) return rc;
   plan->kernel = pl.kernel;
   switch (pl.kernel) {
+    case SGMV_KERNEL_WHOLE:
+      plan->launches = 1;
+      plan->slices = pl.whole.S;
+      plan->workgroups = 8 * pl.whole.S * ceil_div(n_segs, 8);
+      plan->lds_bytes = 0;
+      break;
     case SGMV_KERNEL_TILE:
       plan->launches = 1;
       plan->slices = pl.tile.S;
@@ -779,7 +861,7 @@ int sgmv_plan_add_lora(const sgmv_problem* p, int32_t n_segs, int32_t n_proj, sg
     case SGMV_KERNEL_FUSED:
       plan->launches = 1;
       plan->slices = pl.fused.S;
-      plan->workgroups = pl.fused.S * n_segs;
+      plan->workgroups = pl.fused.S * ceil_div(n_segs, fused_grid_x(n_segs)) * fused_grid_x(n_segs);
       break;
     case SGMV_KERNEL_MATRIX:
       plan->launches = 3;  // shrink, operand preparation, expand

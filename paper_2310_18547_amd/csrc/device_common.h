@@ -137,6 +137,13 @@ __device__ __forceinline__ uint4 buffer_load128(__amdgpu_buffer_rsrc_t rsrc, uin
   u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)byte_off, 0, AUX);
   return make_uint4(v.x, v.y, v.z, v.w);
 }
+// The same with a wave-uniform byte offset added to the lane's (kept in a scalar register, so
+// that many loads of one lane share a single offset register).
+__device__ __forceinline__ uint4 buffer_load128_at(__amdgpu_buffer_rsrc_t rsrc, uint32_t lane_byte_off,
+                                                   uint32_t uniform_byte_off) {
+  u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)lane_byte_off, (int)uniform_byte_off, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint2 buffer_load64(__amdgpu_buffer_rsrc_t rsrc, uint32_t byte_off) {
   u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)byte_off, 0, 0);

@@ -3,10 +3,21 @@
 // Partial sums travel between the workgroups of one launch as 64-bit words
 // {fp32 value (high half), generation tag (low half)} written and read with
 // agent-scope accesses (the L2s of the eight XCDs are not coherent with each
-// other).  The tag is the launch's generation number, derived from an epoch
-// kept in the workspace: every workgroup of a launch adds to the epoch on exit
-// so that the launch advances it by exactly kEpochStep in total; while a launch
-// runs, epoch / kEpochStep is therefore the same for all of its workgroups.
+// other).  The tag is the workspace's generation: the number of single-launch
+// kernels that have run on it (never zero).  A consumer polls a word until its
+// tag is the running launch's generation, so there is no separate flag and
+// nothing to reset: what an earlier launch left behind carries an older tag.
+//
+// The generation lives at the start of the workspace in kGenerationCopies
+// identical copies.  Workgroup i (linear id) of a launch of n workgroups reads
+// copy i when it starts and writes generation + 1 to the copies i, i + n,
+// i + 2n, ... when it leaves.  Only workgroup i of the running launch writes
+// copy i, and only on its way out, so every workgroup reads the value the
+// previous launch left; and when a launch has ended all copies agree again,
+// whatever its size.  (The first design summed 64 counters to which the
+// workgroups added on exit: every workgroup's read then went to the same 512
+// bytes, which with 256 workgroups took 2.4 us at the median and held up the
+// hand-off by 0.45 us.)
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -23,36 +34,37 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-__device__ __forceinline__ uint32_t generation_tag(unsigned long long epoch) {
-  return (uint32_t)((epoch / kEpochStep) % 0xFFFFFFFFull) + 1u;  // never 0
+__device__ __forceinline__ unsigned workgroup_linear_id() {
+  return (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+}
+__device__ __forceinline__ uint32_t* generation_copies(unsigned long long* header) {
+  return reinterpret_cast<uint32_t*>(header);
+}
+__device__ __forceinline__ uint32_t* error_word(unsigned long long* header) {
+  return reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(header) + kWorkspaceErrorOffset);
+}
+__device__ __forceinline__ void raise_timeout(unsigned long long* header) {
+  __hip_atomic_store(error_word(header), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Each workgroup adds to the epoch exactly once, on its way out; the first
-// workgroup adds the remainder so that the launch's total is kEpochStep.  The
-// epoch is the sum of kEpochCounters words and a workgroup adds to the word
-// its id selects, which spreads the atomics over many addresses.
-__device__ __forceinline__ void leave_launch(unsigned long long* epoch, int n_workgroups) {
-  const unsigned id = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
-  const unsigned long long inc =
-      id == 0 ? (unsigned long long)kEpochStep - (n_workgroups - 1) : 1ull;
-  __hip_atomic_fetch_add(epoch + (id % kEpochCounters), inc, __ATOMIC_RELAXED,
-                         __HIP_MEMORY_SCOPE_AGENT);
+// The running launch's generation tag (wave-uniform); call with a whole wave.
+__device__ __forceinline__ uint32_t launch_tag(unsigned long long* header) {
+  const uint32_t g = __hip_atomic_load(generation_copies(header) + workgroup_linear_id(), __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+  return __builtin_amdgcn_readfirstlane(g);
 }
 
-// Read the epoch with one wave: lane l reads counter l, the lanes are summed.
-// The counters only grow, and this workgroup has not added its share yet, so
-// whatever mixture of old and new counter values the lanes see, the sum lies
-// in the running launch's window.
-__device__ __forceinline__ unsigned long long read_epoch(const unsigned long long* epoch, int lane) {
-  static_assert(kEpochCounters == 64, "one counter per lane");
-  unsigned long long v = __hip_atomic_load(epoch + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-  for (int m = 1; m < 64; m <<= 1) {
-    const unsigned lo = __shfl_xor((unsigned)v, m, 64);
-    const unsigned hi = __shfl_xor((unsigned)(v >> 32), m, 64);
-    v += ((unsigned long long)hi << 32) | lo;
-  }
-  return v;
+// A workgroup's last act, by one whole wave: advance its copies of the generation.
+__device__ __forceinline__ void leave_launch(unsigned long long* header, int n_workgroups, uint32_t tag,
+                                             int lane) {
+  const uint32_t next = tag + 1u == 0u ? 1u : tag + 1u;
+  uint32_t* copies = generation_copies(header);
+  for (int k = (int)workgroup_linear_id() + lane * n_workgroups; k < kGenerationCopies; k += 64 * n_workgroups)
+    __hip_atomic_store(copies + k, next, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// The same for a workgroup that has nothing to do and never asked for the tag.
+__device__ __forceinline__ void leave_launch_idle(unsigned long long* header, int n_workgroups, int lane) {
+  leave_launch(header, n_workgroups, launch_tag(header), lane);
 }
 
 // Consumer side of the hand-off for one element: poll the S words at src, src + stride, ...
@@ -79,7 +91,7 @@ __device__ __forceinline__ float collect_slices(const unsigned long long* src, l
       ready = true;
 #pragma unroll
       for (int i = 0; i < 8; ++i) ready = ready && ((uint32_t)wv[i] == tag);
-      if (!ready && ++polls > spin_limit) {
+      if (!ready && ++polls >= spin_limit) {
         timed_out = true;
         break;
       }

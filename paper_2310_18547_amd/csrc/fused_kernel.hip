@@ -26,15 +26,10 @@
 // Hand-off.  The L2s of the eight XCDs are not coherent with each other, so
 // the exchanged words are written and read with agent-scope accesses that
 // bypass them.  A partial sum travels as one 64-bit word {value, tag}; the tag
-// is the call's generation number, so a consumer simply polls the S words it
-// needs until their tags match -- there is no separate flag, no ordering
-// between separate stores to get wrong, and nothing to reset afterwards.  The
-// generation comes from a 64-bit epoch word in the workspace: every workgroup
-// of a launch adds to it on exit so that each launch advances it by exactly
-// kEpochStep in total; while a launch is running the epoch therefore stays
-// inside one window of kEpochStep values and epoch / kEpochStep is the same
-// for every workgroup of the launch, whenever it reads it.  Calls that share a
-// workspace must be stream-ordered.
+// is the workspace's generation (exchange.h), so a consumer simply polls the S
+// words it needs until their tags match -- there is no separate flag, no
+// ordering between separate stores to get wrong, and nothing to reset
+// afterwards.  Calls that share a workspace must be stream-ordered.
 //
 // Every consumer adds the S slices in the same ascending order, so results are
 // deterministic.  Producers never wait before publishing, the S workgroups of
@@ -53,11 +48,10 @@
 
 namespace sgmv {
 
-// Body of the kernels below.  grid = (S, n_segs[, projections]) workgroups of 320 threads: blockIdx.y is the segment,
-// blockIdx.x its slice index (so the S workgroups of a segment are neighbours
-// in dispatch order and no division is needed to find them).
+// Body of the kernels below: workgroup of 320 threads that serves slice `s` of segment `seg`
+// (the kernels derive both from blockIdx without a division).
 //   exch   [S][n_tokens][R] 64-bit words {fp32 value (high), tag (low)}
-//   header kEpochCounters 64-bit counters whose sum is the epoch, then the error flag
+//   header the workspace's generation copies, then the error flag
 // G  = lane groups of the expand phase: group g multiplies weight rows
 //      g*R/G .. (g+1)*R/G-1; the groups are summed through LDS.
 // RB = rows handled per pass over the weights (1 when every segment is one row).
@@ -67,7 +61,7 @@ __device__ __forceinline__ void add_lora_fused_body(
     const uint16_t* const* __restrict__ B_ptrs, const uint16_t* __restrict__ x,
     uint16_t* __restrict__ y, int kslice, int cslice, int h_in, int h_out, int n_tokens, int S,
     long long offA, long long offB, unsigned long long* exch, unsigned long long* header,
-    float scale, int spin_limit) {
+    float scale, int spin_limit, int seg, int s) {
   constexpr int NT = 256, NW = 4, U = 8;  // stream threads / waves, A loads per lane and batch
   constexpr int LPR = R / 8;
   constexpr int CPW = NT / G;  // 8-column chunks per pass
@@ -84,12 +78,11 @@ __device__ __forceinline__ void add_lora_fused_body(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   SGMV_TRACE_DECL
   SGMV_TRACE_POINT(0);
-  const int seg = blockIdx.y, s = blockIdx.x;
   const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
   const uint16_t* A = A_ptrs[seg];
   const uint16_t* B = B_ptrs[seg];
   if (lo >= hi || A == nullptr || B == nullptr) {  // same decision in all S workgroups
-    if (tid == 0) leave_launch(header, (int)(gridDim.x * gridDim.y * gridDim.z));
+    if (wave == 0) leave_launch_idle(header, (int)(gridDim.x * gridDim.y * gridDim.z), lane);
     return;
   }
   SGMV_TRACE_POINT(8);
@@ -102,7 +95,8 @@ __device__ __forceinline__ void add_lora_fused_body(
 
   if (wave == NW) {
     // ============================================================ exchange wave
-    const uint32_t tag = generation_tag(read_epoch(header, lane));
+    const uint32_t tag = launch_tag(header);
+    SGMV_TRACE_POINT(9);
     const long long stride = (long long)n_tokens * R;
     // ---- shrink phase: publish this workgroup's partial sums
     for (int row0 = lo; row0 < hi; row0 += RB) {
@@ -145,10 +139,11 @@ __device__ __forceinline__ void add_lora_fused_body(
         }
       }
     }
-    if (timed_out) __hip_atomic_store((unsigned*)(header + kEpochCounters), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (lane == 0) leave_launch(header, (int)(gridDim.x * gridDim.y * gridDim.z));
+    if (timed_out) raise_timeout(header);
+    leave_launch(header, (int)(gridDim.x * gridDim.y * gridDim.z), tag, lane);
     SGMV_TRACE_POINT(7);
     SGMV_TRACE_FLUSH(lane == 0, 4, 7);
+    SGMV_TRACE_FLUSH(lane == 0, 9, 9);
     return;
   }
 
@@ -351,7 +346,7 @@ __device__ __forceinline__ void add_lora_fused_body(
   SGMV_TRACE_POINT(6);
   SGMV_TRACE_FLUSH(tid == 0, 0, 3);
   SGMV_TRACE_FLUSH(tid == 0, 6, 6);
-  SGMV_TRACE_FLUSH(tid == 0, 8, 9);
+  SGMV_TRACE_FLUSH(tid == 0, 8, 8);
 }
 
 // One add-on per launch.
@@ -363,9 +358,17 @@ __global__ __launch_bounds__(320) void add_lora_fused_kernel(
     const uint16_t* const* __restrict__ B_ptrs, const uint16_t* __restrict__ x,
     uint16_t* __restrict__ y, int kslice, int cslice, int h_in, int h_out, int n_tokens, int S,
     long long offA, long long offB, unsigned long long* exch, unsigned long long* header,
-    float scale, int spin_limit) {
+    float scale, int spin_limit, int n_segs) {
+  // grid (fused_grid_x, S, rows): blockIdx.x is the fastest-varying part of the linear id by
+  // which workgroups are dealt to the XCDs, so the S workgroups of a segment share an XCD
+  const int seg = blockIdx.z * gridDim.x + blockIdx.x;
+  if (seg >= n_segs) {  // the grid is padded to whole rows of segments
+    if (threadIdx.x < 64) leave_launch_idle(header, (int)(gridDim.x * gridDim.y * gridDim.z), (int)threadIdx.x);
+    return;
+  }
   add_lora_fused_body<DT, R, G, RB>(seg_starts, A_ptrs, B_ptrs, x, y, kslice, cslice, h_in, h_out,
-                                    n_tokens, S, offA, offB, exch, header, scale, spin_limit);
+                                    n_tokens, S, offA, offB, exch, header, scale, spin_limit, seg,
+                                    (int)blockIdx.y);
 }
 
 // Several independent add-ons of one shape per launch, side by side: blockIdx.z selects
@@ -383,16 +386,19 @@ __global__ __launch_bounds__(320) void add_lora_fused_side_kernel(
       reinterpret_cast<const uint16_t* const*>(tab.B_ptrs[z]),
       reinterpret_cast<const uint16_t*>(tab.x[z]), reinterpret_cast<uint16_t*>(tab.y[z]), kslice, cslice,
       h_in, h_out, n_tokens, S, offA, offB, exch + (long long)z * S * n_tokens * R, header, scale,
-      spin_limit);
+      spin_limit, (int)blockIdx.y, (int)blockIdx.x);
 }
 
-// Workspace initialisation: zero everything, then start the epoch one full
-// step above zero so that the zeroed exchange words (tag 0) never match.
+// Workspace initialisation: zero everything, then start the generation at one so that the
+// zeroed exchange words (tag 0) never match.
 __global__ __launch_bounds__(256) void workspace_init_kernel(uint32_t* p, size_t n_words,
                                                              size_t header_word) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (; i < n_words; i += stride) p[i] = (i == header_word) ? (uint32_t)kEpochStep : 0u;
+  for (; i < n_words; i += stride)
+    p[i] = (i >= header_word && i < header_word + kGenerationCopies) ? 1u
+           : i == header_word + kGenerationCopies + 1                 ? kWorkspaceMagic
+                                                                      : 0u;
 }
 
 hipError_t launch_workspace_init(void* p, size_t bytes, size_t header_offset, hipStream_t st) {
@@ -407,11 +413,13 @@ hipError_t launch_workspace_init(void* p, size_t bytes, size_t header_offset, hi
 
 template <class DT, int R, int G, int RB>
 static hipError_t launch_fused_t(const FusedArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL((add_lora_fused_kernel<DT, R, G, RB>), dim3((unsigned)a.S, (unsigned)a.n_segs),
+  hipLaunchKernelGGL((add_lora_fused_kernel<DT, R, G, RB>),
+                     dim3((unsigned)fused_grid_x(a.n_segs), (unsigned)a.S,
+                          (unsigned)((a.n_segs + fused_grid_x(a.n_segs) - 1) / fused_grid_x(a.n_segs))),
                      dim3(320), 0, st, a.seg_starts, (const uint16_t* const*)a.A_ptrs,
                      (const uint16_t* const*)a.B_ptrs, (const uint16_t*)a.x, (uint16_t*)a.y,
                      a.kslice, a.cslice, a.h_in, a.h_out, a.n_tokens, a.S, a.offA, a.offB, a.exch,
-                     a.header, a.scale, a.spin_limit);
+                     a.header, a.scale, a.spin_limit, a.n_segs);
   return hipGetLastError();
 }
 

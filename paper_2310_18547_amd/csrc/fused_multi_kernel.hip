@@ -78,7 +78,7 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
   const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
   const int n_workgroups = (int)(gridDim.x * gridDim.y * gridDim.z);
   if (lo >= hi || z >= n_proj) {
-    if (tid == 0) leave_launch(header, n_workgroups);
+    if (wave == 0) leave_launch_idle(header, n_workgroups, lane);
     return;
   }
   // The first projection's pointers come through scalar loads (one round trip, as in the
@@ -136,7 +136,7 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
   auto item_p = [](const Item& it) { return __builtin_ctz(it.left); };
   if (wave == NW) {
     // ============================================================ exchange wave
-    const uint32_t tag = generation_tag(read_epoch(header, lane));
+    const uint32_t tag = launch_tag(header);
     stage_pointers();
     lds_barrier();  // (p) pointers staged
     bool timed_out = false;
@@ -200,8 +200,8 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
       it_e = next(it_e);
     }
     if (timed_out)
-      __hip_atomic_store((unsigned*)(header + kEpochCounters), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (lane == 0) leave_launch(header, n_workgroups);
+      raise_timeout(header);
+    leave_launch(header, n_workgroups, tag, lane);
     SGMV_TRACE_POINT(7);
     SGMV_TRACE_FLUSH(lane == 0, 4, 7);
     return;

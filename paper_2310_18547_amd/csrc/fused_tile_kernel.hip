@@ -54,7 +54,7 @@ size_t tile_lds_bytes(int r, int kslice, int cslice) {
 
 // kslice is a multiple of 32, cslice a multiple of 64 (host).
 //   exch   [S][n_tokens][R] 64-bit words {fp32 value (high), tag (low)}
-//   header kEpochCounters 64-bit counters whose sum is the epoch, then the error flag
+//   header the workspace's generation copies, then the error flag
 template <class DT, int R>
 __global__ __launch_bounds__(320) void add_lora_tile_kernel(
     // the first sixteen dwords are preloaded into SGPRs at wave launch
@@ -104,7 +104,7 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
   const int nrb = (hi - lo + 15) >> 4;  // row blocks of this segment
   // same decision in every workgroup that could wait for this one
   if ((int)blockIdx.z >= nrb || A == nullptr || B == nullptr) {
-    if (tid == 0) leave_launch(header, n_workgroups);
+    if (wave == 0) leave_launch_idle(header, n_workgroups, lane);
     return;
   }
   SGMV_TRACE_POINT(8);
@@ -116,7 +116,7 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
 
   if (wave == NW) {
     // ============================================================ exchange wave
-    const uint32_t tag = generation_tag(read_epoch(header, lane));
+    const uint32_t tag = launch_tag(header);
     const long long stride = (long long)n_tokens * R;
     lds_barrier();  // (A) transposed A slice ready (nothing to do with it here)
     // ---- shrink phase: add the four waves' tiles, publish
@@ -168,7 +168,7 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
             for (int e = 0; e < EN; ++e)
 #pragma unroll
               for (int i = 0; i < 8; ++i) ready = ready && ((uint32_t)wv[e][i] == tag);
-            if (!ready && ++polls > spin_limit) {
+            if (!ready && ++polls >= spin_limit) {
               block_timed_out = true;
               break;
             }
@@ -213,8 +213,8 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
       lds_barrier();  // (E) vs[it & 1] filled
     }
     if (timed_out)
-      __hip_atomic_store((unsigned*)(header + kEpochCounters), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (lane == 0) leave_launch(header, n_workgroups);
+      raise_timeout(header);
+    leave_launch(header, n_workgroups, tag, lane);
     SGMV_TRACE_POINT(7);
     SGMV_TRACE_FLUSH(lane == 0, 4, 7);
     return;

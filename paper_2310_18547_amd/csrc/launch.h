@@ -7,16 +7,20 @@ namespace sgmv {
 
 // Longest k-slice one shrink workgroup stages in LDS (elements of one x row).
 constexpr int kMaxKSlice = 2048;
-// Every single-launch call advances the workspace's epoch word by exactly this
-// much; it also bounds the grid of that kernel.
-constexpr unsigned long long kEpochStep = 1ull << 16;
-// The epoch is kept as the sum of this many 64-bit counters so that the
-// workgroups of a launch do not all add to one address (same-address atomics
-// serialise at the memory side, ~10 ns each).
-constexpr int kEpochCounters = 64;
-// Bytes reserved at the start of a workspace: the epoch counters, then the
-// error word.
-constexpr size_t kWorkspaceHeader = 1024;
+// Generation of a workspace: the number of single-launch kernels that have run on it, kept
+// in this many identical 32-bit copies at its start (workgroup i of a launch reads copy i, so
+// the reads of a launch do not all go to one address, and rewrites the copies i, i + n, ...
+// on its way out, n being the launch's workgroup count).  Also the most workgroups such a
+// launch may have.
+constexpr int kGenerationCopies = 1024;
+// Bytes reserved at the start of a workspace: the generation copies, then the error word
+// (32 bits), the initialisation mark (32 bits) and a 64-bit word for tuning builds
+// (csrc/trace.h).
+constexpr size_t kWorkspaceErrorOffset = (size_t)kGenerationCopies * 4;
+// The 32-bit word after the error word holds this once sgmv_workspace_init has run.
+constexpr uint32_t kWorkspaceMagic = 0x564D4753u;  // "SGMV"
+constexpr size_t kWorkspaceTraceOffset = kWorkspaceErrorOffset + 8;
+constexpr size_t kWorkspaceHeader = kWorkspaceErrorOffset + 256;
 // Upper bound of the split-K factor.
 constexpr int kMaxKSplit = 64;
 
@@ -77,7 +81,7 @@ struct FusedArgs {
   const void* const* B_ptrs;
   const int32_t* seg_starts;
   unsigned long long* exch;  // [S][n_tokens][r] words {value, generation tag}
-  unsigned long long* header;// kEpochCounters epoch counters, then the error word
+  unsigned long long* header;// generation copies, then the error word
   int n_proj;                // 0: one add-on (x, y, A_ptrs, B_ptrs above); else `table` holds n_proj of them
   int Z;                     // multi-projection launch: grid depth (projections z, z + Z, ... per workgroup)
   FusedTable table;
@@ -105,7 +109,33 @@ struct TileArgs {
   unsigned long long* header;
 };
 
+// Single-launch kernel for one-row segments in which every workgroup computes the whole
+// shrink of its segment (no hand-off between workgroups, no workspace).
+constexpr int kWholeMaxHin = 8192;  // widest input row a workgroup stages in LDS
+struct WholeArgs {
+  bool bf16;
+  int r, h_in, h_out, n_segs;
+  int S;                     // workgroups per segment = column slices of the expand
+  int cslice;                // columns per slice
+  int G;                     // lane groups of the expand phase (1, 2, 4 or 8)
+  long long offA, offB;      // layer offsets in elements
+  float scale;
+  void* y;
+  const void* x;
+  const void* const* A_ptrs;
+  const void* const* B_ptrs;
+  const int32_t* seg_starts;
+  unsigned long long* header;  // workspace header or nullptr (only trace builds look at it)
+};
+
+// Grid of add_lora_fused_kernel: (fused_grid_x, S, rows of fused_grid_x segments).  Workgroups
+// are dealt to the eight XCDs round-robin by linear id, so with eight segments to a grid row
+// the S workgroups of a segment all run on one XCD: they start together (the XCDs of a launch
+// start up to 0.6 us apart) and none of them waits for a partial sum from a later XCD.
+inline int fused_grid_x(int n_segs) { return n_segs < 8 ? (n_segs > 0 ? n_segs : 1) : 8; }
+
 size_t tile_lds_bytes(int r, int kslice, int cslice);
+hipError_t launch_add_lora_whole(const WholeArgs& a, hipStream_t st);
 hipError_t launch_add_lora_tile(const TileArgs& a, hipStream_t st);
 hipError_t launch_add_lora_fused(const FusedArgs& a, hipStream_t st);
 bool fused_multi_fits(const FusedArgs& a);

@@ -4,8 +4,8 @@
 // every workgroup records the constant-rate device clock (100 MHz) at up to ten marked
 // points in registers and writes them out when its waves leave:
 //     buffer[workgroup * 10 + point]
-// where `buffer` is the device address found in the 64-bit word that follows the error word
-// of the workspace header (zero = tracing off; sgmv_workspace_init clears it).  Without the
+// where `buffer` is the device address found in the 64-bit word eight bytes behind the error
+// word of the workspace header (zero = tracing off; sgmv_workspace_init clears it).  Without the
 // macro SGMV_TRACE the three hooks expand to nothing and the library carries no trace code.
 //
 // Points of add_lora_fused_kernel / add_lora_tile_kernel:
@@ -30,8 +30,9 @@
 #define SGMV_TRACE_FLUSH(cond, first, last)                                                       \
   do {                                                                                            \
     unsigned long long* trace_buf = reinterpret_cast<unsigned long long*>(                        \
-        __hip_atomic_load(header + sgmv::kEpochCounters + 1, __ATOMIC_RELAXED,                    \
-                          __HIP_MEMORY_SCOPE_AGENT));                                             \
+        __hip_atomic_load(reinterpret_cast<unsigned long long*>(                                  \
+                              reinterpret_cast<char*>(header) + sgmv::kWorkspaceTraceOffset),     \
+                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));                           \
     if (trace_buf != nullptr && (cond)) {                                                         \
       const size_t trace_wg =                                                                     \
           ((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;                 \

@@ -39,15 +39,18 @@ def test_status_strings():
     assert sg.sgmv_status_string(99) == "unknown status"
 
 
+HEADER = 1024 * 4 + 256   # generation copies (1024 x 32 bit), error word and padding
+
+
 def test_workspace_bytes():
     assert sg.sgmv_workspace_bytes(0, 16) == 0
     assert sg.sgmv_workspace_bytes(-3, 16) == 0
     for T in (1, 7, 64, 1000, 4608, 100000):
         for r in (8, 16, 32, 64):
             b = sg.sgmv_workspace_bytes(T, r)
-            assert b >= 1024 + 3 * 16 * T * r * 4 + T * r * 4 + T * 4   # header, >= 16 slices, exchange, operands
-            assert b <= 1024 + 3 * (64 * T * r * 4 + 256) + T * r * 4 + T * 4 + 768 and b % 256 == 0
-    assert sg.sgmv_workspace_bytes(64, 16) == 1024 + 3 * 64 * 64 * 16 * 4 + 2 * 2048 + 256
+            assert b >= HEADER + 3 * 16 * T * r * 4 + T * r * 4 + T * 4   # header, >= 16 slices, exchange, operands
+            assert b <= HEADER + 3 * (64 * T * r * 4 + 256) + T * r * 4 + T * 4 + 768 and b % 256 == 0
+    assert sg.sgmv_workspace_bytes(64, 16) == HEADER + 3 * 64 * 64 * 16 * 4 + 2 * 2048 + 256
 
 
 def test_validate_segments():
@@ -155,10 +158,14 @@ def _plan(n_segs, n_proj=1, **kw):
 
 def test_plan_single_launch_shapes():
     """Launch policy of sgmv_add_lora, asked of the library (host-only, no device)."""
-    # one row per segment: the row kernel, S a power of two with S * segments <= 256 units
-    # (beyond 128 rows of 4096 features, which would need two slices each and two workgroups per
-    # unit, the launch-per-step kernels are faster; a forced path still takes the single launch)
+    # one row per segment: the row kernel with the hand-off, S a power of two with S * segments <=
+    # 256 units; its grid is padded to whole rows of eight segments (a segment's workgroups share an XCD).
+    # Beyond 128 rows of 4096 features, which would need two slices each and two workgroups per unit,
+    # the single-launch kernel without hand-off takes over up to several hundred segments, then the
+    # launch-per-step kernels; a forced path still takes what was asked for
     rc, pl = _plan(256, n_tokens=256, max_seg_len=1)
+    assert rc == 0 and pl.kernel == sg.KERNEL_WHOLE and (pl.launches, pl.slices, pl.workgroups) == (1, 1, 256)
+    rc, pl = _plan(1024, n_tokens=1024, max_seg_len=1)
     assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR
     rc, pl = _plan(256, n_tokens=256, max_seg_len=1, path=sg.PATH_FUSED)
     assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and (pl.slices, pl.workgroups) == (2, 512)
@@ -168,6 +175,23 @@ def test_plan_single_launch_shapes():
         rc, pl = _plan(batch, n_tokens=batch, max_seg_len=1)
         assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and pl.launches == 1
         assert (pl.slices, pl.workgroups) == (S, S * batch), (batch, pl.slices)
+    rc, pl = _plan(12, n_tokens=12, max_seg_len=1)
+    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and (pl.slices, pl.workgroups) == (8, 8 * 16)   # two rows of eight
+    # rank 8 (small A_i): every workgroup computes the whole shrink itself, no hand-off
+    for batch, S in ((1, 8), (16, 8), (64, 4), (256, 1)):
+        rc, pl = _plan(batch, n_tokens=batch, max_seg_len=1, r=8)
+        assert rc == 0 and pl.kernel == sg.KERNEL_WHOLE and (pl.launches, pl.slices) == (1, S)
+        assert pl.workgroups == 8 * S * ((batch + 7) // 8)
+    # that kernel needs no workspace: it is what a caller without a prepared one gets, and forced
+    # it runs without any
+    rc, pl = _plan(64, n_tokens=64, max_seg_len=1, workspace_ready=0)
+    assert rc == 0 and pl.kernel == sg.KERNEL_WHOLE and pl.launches == 1
+    rc, pl = _plan(64, n_tokens=64, max_seg_len=1, path=sg.PATH_WHOLE, workspace=None, workspace_bytes=0)
+    assert rc == 0 and pl.kernel == sg.KERNEL_WHOLE
+    rc, pl = _plan(64, n_tokens=64, max_seg_len=3, path=sg.PATH_WHOLE)
+    assert rc == 3                                   # one-row segments only
+    rc, pl = _plan(64, n_tokens=64, max_seg_len=1, path=sg.PATH_WHOLE, h_in=11008)
+    assert rc == 3                                   # input rows wider than a workgroup stages
     # short multi-row segments: sixteen-row tiles, every workgroup resident
     rc, pl = _plan(39, n_tokens=64, max_seg_len=5)
     assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.launches == 1
@@ -175,9 +199,11 @@ def test_plan_single_launch_shapes():
     assert 0 < pl.lds_bytes <= 160 * 1024
     rc, pl = _plan(1, n_tokens=64, max_seg_len=64)
     assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.workgroups == pl.slices * 4
-    # without the prepared workspace the single-launch kernels are not taken
-    rc, pl = _plan(64, n_tokens=64, max_seg_len=1, workspace_ready=0)
+    # without the prepared workspace the kernels with a hand-off are not taken
+    rc, pl = _plan(64, n_tokens=64, max_seg_len=1, workspace_ready=0, r=64)
     assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR and pl.launches == 2
+    rc, pl = _plan(39, n_tokens=64, max_seg_len=5, workspace_ready=0)
+    assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX
     # long segments: the MFMA kernels, three launches
     rc, pl = _plan(4, n_tokens=3450, max_seg_len=891)
     assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX and pl.launches == 3
@@ -233,6 +259,8 @@ def test_plan_agrees_with_the_resource_limits():
                     assert pl.launches == 1 and 0 < pl.workgroups <= 512, (r, h_in, n_segs, pl.workgroups)
                     if pl.kernel == sg.KERNEL_TILE:
                         assert pl.workgroups <= 256 and pl.lds_bytes <= 160 * 1024
+                elif pl.kernel == sg.KERNEL_WHOLE:   # its workgroups never wait for each other: any grid
+                    assert pl.launches == 1 and m == 1 and pl.lds_bytes == 0
                 else:
                     assert pl.kernel in (sg.KERNEL_VECTOR, sg.KERNEL_MATRIX)
 

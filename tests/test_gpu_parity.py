@@ -354,9 +354,14 @@ def test_give_up_is_reported_and_never_stores_an_incomplete_sum(kind):
     if kind == "tile":
         ws = [wl.popularity("uniform", batch=64, h_in=4096, r=16, dtype="f16", num_layers=1, seed=7)]
     else:
-        ws = [wl.decode_distinct(batch=32, h_in=4096, r=16, dtype="f16", num_layers=1, seed=70 + i)
+        ws = [wl.decode_distinct(batch=32 if kind == "multi" else 64, h_in=4096, r=16, dtype="f16", num_layers=1,
+                                 seed=70 + i)
               for i in range(3 if kind == "multi" else 1)]
-    ds = [_dev(w, spin_limit=1) for w in ws]
+    # one add-on of one-row segments: its workgroups of a segment run on one XCD, start together and
+    # find each other's sums at the first look; twice as many workgroups as compute units make the
+    # second half start one by one, as units come free
+    kw = dict(path=B.PATH_FUSED, ksplit=8) if kind == "fused" else {}
+    ds = [_dev(w, spin_limit=1, **kw) for w in ws]
     d0 = ds[0]
     plan = B.sgmv_plan_add_lora(d0.problem, ws[0].n_segs, len(ws))
     assert plan.launches == 1 and plan.slices > 1
@@ -441,10 +446,97 @@ def test_fused_null_adapter():
 
 
 def test_auto_uses_two_launches_without_ready_workspace():
+    from paper_2310_18547_amd import binding as B
     w = wl.tiny()
     d = _dev(w, init_workspace=False)
+    assert B.sgmv_plan_add_lora(d.problem, w.n_segs, 1).launches == 2
     d.add_lora()
     assert_parity(d.y_bits(), oracle.run_workload(w), "f16", "workspace not initialised")
+
+
+# ------------------- single launch without hand-off (every workgroup computes the whole shrink)
+def _whole(w, **kw):
+    from paper_2310_18547_amd import binding as B
+    kw.setdefault("max_seg_len", 1)
+    return _dev(w, path=B.PATH_WHOLE, **kw)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("r,h_in", [(8, 1024), (8, 4096), (16, 512), (16, 1024), (16, 1536), (16, 4096), (32, 1024),
+                                    (32, 4096), (64, 640), (64, 4096), (16, 8192)])
+def test_whole_matches_oracle(dtype, r, h_in):
+    # every batch size of the walk over A_i (4, 8, 16, 32 loads per lane in flight; one and several
+    # batches), thirteen segments (a padded grid row), a width that the column slices do not divide
+    from paper_2310_18547_amd import binding as B
+    w = wl.custom([1] * 13, h_in, 1544, r, dtype, seed=300 + r, num_layers=2, scale=0.5)
+    d = _whole(w, init_workspace=False)
+    plan = B.sgmv_plan_add_lora(d.problem, w.n_segs, 1)
+    assert plan.kernel == B.KERNEL_WHOLE and plan.launches == 1
+    d.add_lora(1)
+    assert_parity(d.y_bits(), oracle.run_workload(w, layer_idx=1, n_threads=8), dtype, f"whole r={r} h_in={h_in}")
+
+
+@pytest.mark.parametrize("ksplit", [1, 2, 3, 5, 8, 16])
+def test_whole_every_slice_count(ksplit):
+    w = wl.custom([1] * 6, 2048, 1024, 16, "f16", seed=345)
+    d = _whole(w, ksplit=ksplit)
+    d.add_lora()
+    assert_parity(d.y_bits(), oracle.run_workload(w), "f16", f"whole S={ksplit}")
+
+
+def test_whole_needs_no_workspace():
+    from paper_2310_18547_amd import binding as B
+    w = wl.decode_distinct(batch=9, h_in=1024, h_out=520, r=16, dtype="bf16", num_layers=3, seed=346)
+    d = _dev(w, init_workspace=False)
+    prob = B.make_problem(B.BF16, w.h_in, w.h_out, w.r, w.num_layers, w.n_tokens, workspace=None,
+                          workspace_bytes=0, max_seg_len=1, path=B.PATH_WHOLE)
+    B.sgmv_add_lora(prob, d.y[0], d.x[0], d.A_ptrs, d.B_ptrs, d.seg_starts, w.n_segs, 2, w.scale)
+    assert_parity(d.y_bits(), oracle.run_workload(w, layer_idx=2), "bf16", "whole without a workspace")
+    # what a caller without a prepared workspace gets on its own
+    d2 = _dev(w, init_workspace=False)
+    assert B.sgmv_plan_add_lora(d2.problem, w.n_segs, 1).kernel == B.KERNEL_WHOLE
+    d2.add_lora(2)
+    assert np.array_equal(d2.y_bits(), d.y_bits())
+
+
+def test_whole_wrong_length_hint_is_still_correct():
+    # the hint says one row per segment, the segments hold up to five; empty ones in between
+    w = wl.custom([1, 3, 2, 0, 5, 1, 0, 4], 1024, 776, 16, "f16", seed=347, num_layers=2)
+    d = _whole(w)
+    d.add_lora(1)
+    assert_parity(d.y_bits(), oracle.run_workload(w, layer_idx=1), "f16", "whole, multi-row segments")
+
+
+def test_whole_fingerprint_bit_exact_and_null_adapter():
+    lens = [1, 0, 1, 1, 0, 0, 1, 1, 1, 1, 1, 1, 1]
+    w = wl.fingerprint(lens, 512, 192, 16, "bf16", num_layers=3)
+    for layer in range(3):
+        d = _whole(w)
+        d.add_lora(layer)
+        assert np.array_equal(d.y_bits(), oracle.run_workload(w, layer_idx=layer))
+    w = wl.custom([1] * 5, 512, 264, 16, "f16", seed=348)
+    w.seg_adapter = np.asarray([0, 1, -1, 3, 4], np.int64)
+    d = _whole(w)
+    d.add_lora()
+    got = d.y_bits()
+    assert np.array_equal(got[2], w.y0[2])
+    assert_parity(got, oracle.run_workload(w), "f16", "whole with a missing adapter")
+
+
+@pytest.mark.parametrize("batch,r", [(64, 8), (1, 8), (256, 16), (200, 8)])
+def test_whole_is_what_auto_takes_at_full_size(batch, r):
+    # Llama-7B decode shapes where the library prefers this kernel: rank 8, and batches beyond
+    # what the kernel with the hand-off takes
+    from paper_2310_18547_amd import binding as B
+    w = wl.decode_distinct(batch=batch, h_in=4096, r=r, dtype="f16", num_layers=2, seed=349)
+    d = _dev(w)
+    assert B.sgmv_plan_add_lora(d.problem, w.n_segs, 1).kernel == B.KERNEL_WHOLE
+    d.add_lora(1)
+    assert_parity(d.y_bits(), oracle.run_workload(w, layer_idx=1, n_threads=8), "f16", f"whole B={batch} r={r}")
+    d.reset_y(0); d.add_lora(1); a = d.y_bits()
+    d.reset_y(0); d.add_lora(1)
+    assert np.array_equal(d.y_bits(), a)          # bit-identical from call to call
+    assert d.check() == 0
 
 
 # ---------------------------------- single-launch MFMA (tile) kernel, segments of a few rows
@@ -822,12 +914,12 @@ def test_random_shapes_every_path(seed):
     from paper_2310_18547_amd import binding as B
     w, dtype, hint = _random_case(seed)
     ref = oracle.run_workload(w, layer_idx=1, n_threads=8)
-    for path in (B.PATH_AUTO, B.PATH_VECTOR, B.PATH_MATRIX, B.PATH_FUSED):
-        d = _dev(w, path=path, max_seg_len=hint)
+    for path in (B.PATH_AUTO, B.PATH_VECTOR, B.PATH_MATRIX, B.PATH_FUSED, B.PATH_WHOLE):
+        d = _dev(w, path=path, max_seg_len=1 if path == B.PATH_WHOLE else hint)   # that kernel insists on the hint
         try:
             d.add_lora(1)
         except B.SgmvError as e:
-            assert path == B.PATH_FUSED and e.status == 3, (seed, path, e)   # single launch not applicable
+            assert path in (B.PATH_FUSED, B.PATH_WHOLE) and e.status == 3, (seed, path, e)   # single launch not applicable
             continue
         assert_parity(d.y_bits(), ref, dtype, f"seed {seed} path {path} hint {hint} lens {w.seg_starts.tolist()}")
         assert d.check() == 0
