@@ -469,13 +469,18 @@ int plan_multi(const sgmv_problem* p, int n_segs, int n_proj, FusedArgs* f) {
   if ((p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->max_seg_len == 1 && n_proj > 1 &&
       p->workspace != nullptr && choose_fused(p, n_segs, f) && f->S * n_proj <= split_cap(p->n_tokens)) {
     f->r = p->r;
-    if ((long long)f->S * n_segs * n_proj <= lim.multi_workgroups) return SGMV_KERNEL_MULTI_SIDE;
+    // workgroups that hold segments count towards what must be resident; the grid, padded to
+    // whole rows of segments, must leave every workgroup its own generation copy
+    const long long grid = (long long)f->S * fused_grid_items(n_segs) * n_proj;
+    if ((long long)f->S * n_segs * n_proj <= lim.multi_workgroups && grid <= kGenerationCopies)
+      return SGMV_KERNEL_MULTI_SIDE;
     if (fused_multi_fits(*f)) return SGMV_KERNEL_MULTI_PIPELINED;
     // slices too deep for the pipelined kernel's register sets (h_in = 5120 at four slices):
     // three workgroups per compute unit still beat one launch per add-on (measured, three
     // projections of 64 segments at h = 5120: 22.7 us against 24.8 us)
     // (ranks up to 16 only: the kernels of the higher ranks use more registers and fit two per unit)
-    if (p->r <= 16 && (long long)f->S * n_segs * n_proj <= lim.multi_workgroups_most) return SGMV_KERNEL_MULTI_SIDE;
+    if (p->r <= 16 && (long long)f->S * n_segs * n_proj <= lim.multi_workgroups_most && grid <= kGenerationCopies)
+      return SGMV_KERNEL_MULTI_SIDE;
   }
   return SGMV_KERNEL_SEQUENCE;
 }
@@ -528,10 +533,11 @@ int sgmv_workspace_check(const void* workspace, void* stream) {
   // between launches all copies of the generation agree; anything else means the workspace was
   // never initialised, or a launch did not account for all of its workgroups and later launches
   // may disagree about their generation
-  if (head[kGenerationCopies + 1] != kWorkspaceMagic || head[0] == 0) return SGMV_ERR_STATE;
+  if (head[kGenerationCopies + 1] != kWorkspaceMagic) return SGMV_ERR_STATE;
+  if (head[kGenerationCopies] != 0) return SGMV_ERR_TIMEOUT;
+  if (head[0] == 0) return SGMV_ERR_STATE;
   for (int i = 1; i < kGenerationCopies; ++i)
     if (head[i] != head[0]) return SGMV_ERR_STATE;
-  if (head[kGenerationCopies] != 0) return SGMV_ERR_TIMEOUT;
   return SGMV_OK;
 }
 
@@ -837,7 +843,7 @@ int sgmv_plan_add_lora(const sgmv_problem* p, int32_t n_segs, int32_t n_proj, sg
       plan->kernel = kernel;
       plan->launches = 1;
       plan->slices = f.S;
-      plan->workgroups = kernel == SGMV_KERNEL_MULTI_SIDE ? f.S * n_segs * n_proj : f.S * n_segs;
+      plan->workgroups = f.S * (int)fused_grid_items(n_segs) * (kernel == SGMV_KERNEL_MULTI_SIDE ? n_proj : 1);
       return SGMV_OK;
     }
   }
@@ -861,7 +867,7 @@ int sgmv_plan_add_lora(const sgmv_problem* p, int32_t n_segs, int32_t n_proj, sg
     case SGMV_KERNEL_FUSED:
       plan->launches = 1;
       plan->slices = pl.fused.S;
-      plan->workgroups = pl.fused.S * ceil_div(n_segs, fused_grid_x(n_segs)) * fused_grid_x(n_segs);
+      plan->workgroups = pl.fused.S * (int)fused_grid_items(n_segs);
       break;
     case SGMV_KERNEL_MATRIX:
       plan->launches = 3;  // shrink, operand preparation, expand

@@ -379,14 +379,21 @@ template <class DT, int R, int G>
 __global__ __launch_bounds__(320) void add_lora_fused_side_kernel(
     const int32_t* __restrict__ seg_starts, int kslice, int cslice, int h_in, int h_out, int n_tokens,
     int S, long long offA, long long offB, unsigned long long* exch, unsigned long long* header,
-    float scale, int spin_limit, FusedTable tab) {
-  const int z = blockIdx.z;
+    float scale, int spin_limit, int n_segs, int n_proj, FusedTable tab) {
+  // grid (segments of a row, S, rows of segments x projections), as for the single add-on
+  const int row = __builtin_amdgcn_readfirstlane((int)(((float)blockIdx.z + 0.5f) / (float)n_proj));
+  const int z = (int)blockIdx.z - row * n_proj;
+  const int seg = row * gridDim.x + blockIdx.x;
+  if (seg >= n_segs) {  // the grid is padded to whole rows of segments
+    if (threadIdx.x < 64) leave_launch_idle(header, (int)(gridDim.x * gridDim.y * gridDim.z), (int)threadIdx.x);
+    return;
+  }
   add_lora_fused_body<DT, R, G, 1>(
       seg_starts, reinterpret_cast<const uint16_t* const*>(tab.A_ptrs[z]),
       reinterpret_cast<const uint16_t* const*>(tab.B_ptrs[z]),
       reinterpret_cast<const uint16_t*>(tab.x[z]), reinterpret_cast<uint16_t*>(tab.y[z]), kslice, cslice,
       h_in, h_out, n_tokens, S, offA, offB, exch + (long long)z * S * n_tokens * R, header, scale,
-      spin_limit, (int)blockIdx.y, (int)blockIdx.x);
+      spin_limit, seg, (int)blockIdx.y);
 }
 
 // Workspace initialisation: zero everything, then start the generation at one so that the
@@ -426,9 +433,10 @@ static hipError_t launch_fused_t(const FusedArgs& a, hipStream_t st) {
 template <class DT, int R, int G>
 static hipError_t launch_fused_side_t(const FusedArgs& a, hipStream_t st) {
   hipLaunchKernelGGL((add_lora_fused_side_kernel<DT, R, G>),
-                     dim3((unsigned)a.S, (unsigned)a.n_segs, (unsigned)a.n_proj), dim3(320), 0, st,
-                     a.seg_starts, a.kslice, a.cslice, a.h_in, a.h_out, a.n_tokens, a.S, a.offA, a.offB,
-                     a.exch, a.header, a.scale, a.spin_limit, a.table);
+                     dim3((unsigned)fused_grid_x(a.n_segs), (unsigned)a.S,
+                          (unsigned)(fused_grid_items(a.n_segs) / fused_grid_x(a.n_segs) * a.n_proj)),
+                     dim3(320), 0, st, a.seg_starts, a.kslice, a.cslice, a.h_in, a.h_out, a.n_tokens, a.S,
+                     a.offA, a.offB, a.exch, a.header, a.scale, a.spin_limit, a.n_segs, a.n_proj, a.table);
   return hipGetLastError();
 }
 

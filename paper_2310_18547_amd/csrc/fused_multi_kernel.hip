@@ -11,7 +11,7 @@
 // finishes the current one, so HBM stays busy through the phases in which a
 // single add-on leaves it idle.
 //
-// Work split: grid = (S, n_segs, Z).  Workgroup (s, seg, z) serves k-slice s /
+// Work split: S * n_segs * Z workgroups.  Workgroup (s, seg, z) serves k-slice s /
 // column-slice s of segment seg for the projections z, z + Z, z + 2 Z, ...
 // (the host launches Z = 1: one workgroup per (slice, segment) walks all
 // projections; launches small enough for all workgroups to be resident side by
@@ -55,7 +55,7 @@ template <class DT, int R, int G>
 __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
     const int32_t* __restrict__ seg_starts, int kslice, int cslice, int h_in, int h_out, int n_tokens,
     int S, int n_proj, long long offA, long long offB, unsigned long long* exch,
-    unsigned long long* header, float scale, int spin_limit, FusedTable tab) {
+    unsigned long long* header, float scale, int spin_limit, int n_segs, int Z, FusedTable tab) {
   constexpr int NT = 256, NW = 4, U = 8;
   constexpr int LPR = R / 8;
   constexpr int CPW = NT / G;  // 8-column chunks of the column slice
@@ -74,9 +74,20 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   SGMV_TRACE_DECL
   SGMV_TRACE_POINT(0);
-  const int seg = blockIdx.y, s = blockIdx.x, z = blockIdx.z, zstep = gridDim.z;
-  const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
+  // grid (segments of a row, S, rows of segments x Z): blockIdx.x is the fastest-varying part of
+  // the linear id by which workgroups are dealt to the XCDs, so the S workgroups that exchange
+  // partial sums run on one XCD and start together
   const int n_workgroups = (int)(gridDim.x * gridDim.y * gridDim.z);
+  const int zstep = Z, s = blockIdx.y;
+  const int row = Z == 1 ? (int)blockIdx.z
+                         : __builtin_amdgcn_readfirstlane((int)(((float)blockIdx.z + 0.5f) / (float)Z));
+  const int z = (int)blockIdx.z - row * Z;
+  const int seg = row * gridDim.x + blockIdx.x;
+  if (seg >= n_segs) {  // the grid is padded to whole rows of segments
+    if (wave == 0) leave_launch_idle(header, n_workgroups, lane);
+    return;
+  }
+  const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
   if (lo >= hi || z >= n_proj) {
     if (wave == 0) leave_launch_idle(header, n_workgroups, lane);
     return;
@@ -402,9 +413,10 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
 template <class DT, int R, int G>
 static hipError_t launch_multi_t(const FusedArgs& a, hipStream_t st) {
   hipLaunchKernelGGL((add_lora_fused_multi_kernel<DT, R, G>),
-                     dim3((unsigned)a.S, (unsigned)a.n_segs, (unsigned)a.Z), dim3(320), 0, st, a.seg_starts,
-                     a.kslice, a.cslice, a.h_in, a.h_out, a.n_tokens, a.S, a.n_proj, a.offA, a.offB, a.exch,
-                     a.header, a.scale, a.spin_limit, a.table);
+                     dim3((unsigned)fused_grid_x(a.n_segs), (unsigned)a.S,
+                          (unsigned)(fused_grid_items(a.n_segs) / fused_grid_x(a.n_segs) * a.Z)),
+                     dim3(320), 0, st, a.seg_starts, a.kslice, a.cslice, a.h_in, a.h_out, a.n_tokens, a.S,
+                     a.n_proj, a.offA, a.offB, a.exch, a.header, a.scale, a.spin_limit, a.n_segs, a.Z, a.table);
   return hipGetLastError();
 }
 

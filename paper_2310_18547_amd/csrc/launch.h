@@ -133,6 +133,12 @@ struct WholeArgs {
 // the S workgroups of a segment all run on one XCD: they start together (the XCDs of a launch
 // start up to 0.6 us apart) and none of them waits for a partial sum from a later XCD.
 inline int fused_grid_x(int n_segs) { return n_segs < 8 ? (n_segs > 0 ? n_segs : 1) : 8; }
+// Workgroups of such a grid per slice: the items (segments, or segments x row blocks) rounded
+// up to whole grid rows.
+inline long long fused_grid_items(long long items) {
+  const long long gx = items < 8 ? (items > 0 ? items : 1) : 8;
+  return (items + gx - 1) / gx * gx;
+}
 
 size_t tile_lds_bytes(int r, int kslice, int cslice);
 hipError_t launch_add_lora_whole(const WholeArgs& a, hipStream_t st);
