@@ -266,6 +266,20 @@ def run_probe(args):
     for mib in (16, 64):
         us = p.time_us(B.PROBE_COPY, mib << 20, K=200)
         out["copy"].append({"MiB_read_and_written": mib, "us": us, "GB/s": 2 * (mib << 20) / us / 1e3})
+    # one hop of the single-launch kernels' hand-off: a word there and back between two workgroups
+    words = torch.zeros(64, dtype=torch.int64, device="cuda:0")
+    res = torch.zeros(2, dtype=torch.int64, device="cuda:0")
+    out["handoff_round_trip_ns"] = {}
+    for partner, where in ((8, "same XCD"), (1, "next XCD"), (4, "XCD four on")):
+        trips = []
+        for rep in range(5):
+            res.zero_()
+            B.sgmv_probe(B.PROBE_HANDOFF, words, res, partner)
+            torch.cuda.synchronize()
+            ticks, gave_up = (int(v) for v in res.cpu())
+            assert gave_up == 0
+            trips.append(ticks * 10.0 / 200)
+        out["handoff_round_trip_ns"][where] = sorted(trips)[len(trips) // 2]
     print(json.dumps(out), flush=True)
 
 

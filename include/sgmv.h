@@ -294,7 +294,15 @@ int sgmv_plan_add_lora(const sgmv_problem* p, int32_t n_segs, int32_t n_proj, sg
  *   kind 1  streaming read of `bytes` device bytes at `src` (16-byte aligned, multiple of 16);
  *           `dst` may be NULL or point to at least 4 writable device bytes
  *   kind 2  copy of `bytes` device bytes from `src` to `dst` (reads and writes `bytes`)
- * Returns SGMV_OK, SGMV_ERR_NULL, SGMV_ERR_ALIGN, SGMV_ERR_UNSUPPORTED or SGMV_ERR_LAUNCH. */
+ *   kind 3  200 round trips of a 64-bit word between workgroup 0 and workgroup `bytes` (1..63)
+ *           of one launch, with the accesses the single-launch kernels hand partial sums over
+ *           with; workgroups are dealt to the eight XCDs round-robin, so 8 is a partner on
+ *           the same XCD and 1 one on the next.  `src`: 512 device bytes, 256-byte aligned,
+ *           zeroed once by the caller; `dst`: two 64-bit words, [0] receives the duration of
+ *           all round trips in ticks of the 100 MHz device clock, [1] is set to 1 if a wait
+ *           was given up (zero both before the call)
+ * Returns SGMV_OK, SGMV_ERR_NULL, SGMV_ERR_ALIGN, SGMV_ERR_SHAPE, SGMV_ERR_UNSUPPORTED or
+ * SGMV_ERR_LAUNCH. */
 int sgmv_probe(int kind, const void* src, void* dst, size_t bytes, void* stream);
 
 #ifdef __cplusplus

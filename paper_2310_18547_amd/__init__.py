@@ -11,7 +11,7 @@ _BINDING_NAMES = (
     "KERNEL_VECTOR", "KERNEL_MATRIX", "KERNEL_WHOLE", "KERNEL_NAMES", "sgmv_add_lora_multi", "sgmv_add_lora_static", "sgmv_plan_add_lora",
     "library_path", "make_problem", "sgmv_add_lora", "sgmv_expand", "sgmv_shrink",
     "sgmv_status_string", "sgmv_validate_segments", "sgmv_workspace_bytes", "sgmv_workspace_init",
-    "sgmv_workspace_check", "sgmv_probe", "PROBE_EMPTY", "PROBE_READ", "PROBE_COPY",
+    "sgmv_workspace_check", "sgmv_probe", "PROBE_EMPTY", "PROBE_READ", "PROBE_COPY", "PROBE_HANDOFF",
     "STATIC_SCRATCH_BYTES", "STATIC_MAX_WORKSPACE_BYTES",
 )
 __all__ = list(_BINDING_NAMES)

@@ -213,7 +213,7 @@ def sgmv_add_lora_multi(p: SgmvProblem, ys, xs, A_ptrs, B_ptrs, seg_starts, n_se
     return rc
 
 
-PROBE_EMPTY, PROBE_READ, PROBE_COPY = 0, 1, 2
+PROBE_EMPTY, PROBE_READ, PROBE_COPY, PROBE_HANDOFF = 0, 1, 2, 3
 
 
 def sgmv_probe(kind: int, src=None, dst=None, nbytes: int = 0, stream=None, check: bool = True) -> int:

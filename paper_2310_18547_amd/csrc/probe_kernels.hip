@@ -11,7 +11,9 @@
 //           access pattern of a workgroup's weight slices); the attainable read bandwidth
 //           for a launch that moves `bytes`;
 //   kind 2  copy of `bytes` from `src` to `dst` (reads `bytes`, writes `bytes`): the
-//           reference for scaling FETCH_SIZE / WRITE_SIZE.
+//           reference for scaling FETCH_SIZE / WRITE_SIZE;
+//   kind 3  round trips of a 64-bit word between two workgroups with the accesses of the
+//           single-launch kernels' hand-off: what one hop of that hand-off costs at least.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -49,6 +51,40 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(const uint4* __restrict
   for (; i < n; i += stride) dst[i] = src[i];
 }
 
+// Round trips of one 64-bit word between two workgroups of a launch, written and polled with
+// the agent-scope accesses of the single-launch kernels' hand-off: workgroup 0 and workgroup
+// `partner` of a grid of 64 answer each other kProbeRounds times; the others leave at once.
+// Workgroups go to the eight XCDs round-robin, so partner 8 shares workgroup 0's XCD and
+// partner 1 sits on the next one.  out[0] = ticks of the 100 MHz device clock for all rounds,
+// out[1] = 1 if a wait was given up (every wait is bounded).
+constexpr int kProbeRounds = 200;
+__global__ __launch_bounds__(64) void probe_handoff_kernel(unsigned long long* words, int partner,
+                                                           unsigned long long* out) {
+  const int id = blockIdx.x;
+  if ((id != 0 && id != partner) || threadIdx.x != 0) return;
+  unsigned long long* mine = words + (id == 0 ? 0 : 32);  // separate cache lines
+  unsigned long long* theirs = words + (id == 0 ? 32 : 0);
+  // the words may hold an earlier call's count: start above whatever is there
+  const unsigned long long base = __hip_atomic_load(words + 16, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const unsigned long long t0 = wall_clock64();
+  for (int r = 1; r <= kProbeRounds; ++r) {
+    const unsigned long long want = base + (unsigned long long)r;
+    if (id == 0) __hip_atomic_store(mine, want, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int polls = 0;
+    while (__hip_atomic_load(theirs, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != want) {
+      if (++polls > (1 << 16)) {
+        out[1] = 1;
+        return;
+      }
+    }
+    if (id != 0) __hip_atomic_store(mine, want, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  if (id == 0) {
+    out[0] = wall_clock64() - t0;
+    __hip_atomic_store(words + 16, base + kProbeRounds, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
 }  // namespace sgmv
 
 extern "C" int sgmv_probe(int kind, const void* src, void* dst, size_t bytes, void* stream) {
@@ -81,6 +117,16 @@ extern "C" int sgmv_probe(int kind, const void* src, void* dst, size_t bytes, vo
       const size_t most = (size_t)cu * 8;
       hipLaunchKernelGGL(probe_copy_kernel, dim3((unsigned)(blocks < most ? blocks : most)), dim3(256), 0, st,
                          static_cast<const uint4*>(src), static_cast<uint4*>(dst), n);
+      break;
+    }
+    case 3: {
+      if (src == nullptr || dst == nullptr) return SGMV_ERR_NULL;
+      if ((reinterpret_cast<uintptr_t>(src) & 255) != 0 || (reinterpret_cast<uintptr_t>(dst) & 15) != 0)
+        return SGMV_ERR_ALIGN;
+      if (bytes < 1 || bytes > 63) return SGMV_ERR_SHAPE;
+      hipLaunchKernelGGL(probe_handoff_kernel, dim3(64), dim3(64), 0, st,
+                         static_cast<unsigned long long*>(const_cast<void*>(src)), (int)bytes,
+                         static_cast<unsigned long long*>(dst));
       break;
     }
     default:
