@@ -44,7 +44,14 @@ MFMA_PEAK_TFLOPS = 2500.0  # dense bf16 / fp16, MI355X
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (scaled by the copy
 # kernel of sgmv_probe), keyed by what was profiled: (workload, op, kernel, slices).  A run
 # whose plan differs from the profiled one reports null.  Source: the summaries in profiles/.
-PROFILED_TRAFFIC = {}
+PROFILED_TRAFFIC = {
+    ("distinct_b64", "add_lora", "add_lora_fused_kernel", 4):
+        (18.661e6, "profiles/add_lora_fused_distinct_b64_h4096_r16.md"),
+    ("distinct_b64_r8", "add_lora", "add_lora_whole_kernel", 4):
+        (10.092e6, "profiles/add_lora_whole_distinct_b64_h4096_r8.md"),
+    ("distinct_b256", "add_lora", "add_lora_whole_kernel", 1):
+        (73.650e6, "profiles/add_lora_whole_distinct_b256_h4096_r16.md"),
+}
 
 # the paper's own latencies for this operator (one A100 80 GB, fp16, r = 16), context only
 PAPER_A100_US = {"distinct_b64": [116.0, 75.0], "distinct_b1": [37.0, 42.0]}

@@ -27,8 +27,8 @@
  *     state it keeps between calls is per-device bookkeeping that changes no
  *     result (which kernels have had their LDS limit raised, the number of
  *     compute units, the address of sgmv_add_lora_static's array); the
- *     single-launch path keeps an epoch in the caller's workspace, see
- *     sgmv_workspace_init.
+ *     single-launch path keeps a generation count in the caller's workspace,
+ *     see sgmv_workspace_init.
  *   - x is [n_tokens][h_in], y is [n_tokens][h_out], row-major, 16-bit floats
  *     of type `dtype` (IEEE binary16 or bfloat16), 16-byte aligned.
  *   - A_ptrs[i] points to segment i's shrink weights stacked over layers,
@@ -166,14 +166,15 @@ const char* sgmv_status_string(int status);
  * function.  Returns 0 for n_tokens <= 0. */
 size_t sgmv_workspace_bytes(int32_t n_tokens, int32_t r);
 
-/* Prepare a workspace for the single-launch path of sgmv_add_lora: clears it
- * and sets its epoch word with a small kernel on `stream` (so the call may be
- * recorded into a HIP graph).  The single-launch path exchanges partial sums
- * between workgroups through the workspace and tells one call's words from
- * the previous call's by an epoch that every such call advances; run this once
- * after allocating the workspace, and again if a call using it was ever
- * aborted.  `workspace` is device memory, 256-byte aligned, of at least 1024
- * bytes. */
+/* Prepare a workspace for the single-launch paths of sgmv_add_lora: clears it
+ * and sets its generation count with a small kernel on `stream` (so the call
+ * may be recorded into a HIP graph).  Those paths exchange partial sums
+ * between workgroups through the workspace and tell one call's words from an
+ * earlier call's by the generation, which every such call advances; run this
+ * once after allocating the workspace, and again if a call using it was ever
+ * aborted or sgmv_workspace_check reported an error.  `workspace` is device
+ * memory, 256-byte aligned, of at least sgmv_workspace_bytes() bytes (never
+ * less than 4352). */
 int sgmv_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 
 /* Synchronous health check of a workspace used by the single-launch path:
@@ -183,8 +184,8 @@ int sgmv_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
  * and columns of y such a workgroup was responsible for were left as they
  * were (nothing is ever stored from an incomplete sum), the others hold the
  * finished result -- and
- * SGMV_ERR_STATE if the workspace was never initialised or the launch counter
- * is not at a launch boundary (no call may be running on another stream).  In
+ * SGMV_ERR_STATE if the workspace was never initialised or the copies of its
+ * generation count disagree (no call may be running on another stream).  In
  * both cases the workspace must be re-initialised.  Returns SGMV_OK otherwise.
  * Not meant for the hot path. */
 int sgmv_workspace_check(const void* workspace, void* stream);

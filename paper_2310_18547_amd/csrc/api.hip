@@ -11,8 +11,8 @@
 #include "launch.h"
 
 // Scratch of sgmv_add_lora_static, one copy per GPU, held until the process ends:
-//   [0, 1 KiB)       header (epoch counters, error word)
-//   [1 KiB, 6 MiB)   exchange words of the single-launch kernels -- at a fixed place whatever
+//   [0, 4.25 KiB)    header (generation copies, error word)
+//   [4.25 KiB, 6 MiB) exchange words of the single-launch kernels -- at a fixed place whatever
 //                    the batch, so that a word found there was always written as an exchange
 //                    word, with the generation tag of an earlier call
 //   [6 MiB, 9 MiB)   split-K partial sums and the MFMA expand's operands of v
@@ -183,7 +183,7 @@ size_t partial_bytes(int n_tokens, int r) {
 
 // Where a call keeps its intermediate results.
 struct Scratch {
-  unsigned long long* header;  // epoch counters, error word
+  unsigned long long* header;  // generation copies, error word
   float* partials;             // split-K partial sums of the launch-per-step kernels
   unsigned long long* exch;    // exchange words of the single-launch kernels
   char* operands;              // 16-bit operand pairs of v and a range factor per row (MFMA expand)
@@ -700,7 +700,7 @@ int add_lora_launch(const sgmv_problem* p, const Scratch& sc, void* y, const voi
 
 // The device address of this GPU's copy of `scratch`, prepared for the single-launch kernels
 // the first time the GPU is seen: asked of the runtime once per device (every GPU holds its
-// own copy at its own address), then header and exchange words are cleared and the epoch set
+// own copy at its own address), then header and exchange words are cleared and the generation set
 // by a small kernel on `st`.  Calls no allocator.
 int static_scratch(hipStream_t st, char** base) {
   static std::mutex mutex;

@@ -19,7 +19,7 @@
 // Should a device deal workgroups differently the results are the same and only
 // the L2 sharing is lost.
 //
-// No workspace, no epoch, no polling, nothing to time out: the workgroups of a
+// No workspace, no generation count, no polling, nothing to time out: the workgroups of a
 // launch never wait for each other, so the launch may be of any size.
 #include <type_traits>
 

@@ -309,7 +309,7 @@ def test_fused_every_slice_count(ksplit):
 
 def test_workspace_check_sees_launch_accounting():
     # a workspace that was never initialised is reported; after any mix of single-launch kernels
-    # the epoch sits on a launch boundary again (every workgroup accounted for exactly once)
+    # all copies of the generation agree again (every workgroup accounted for exactly once)
     from paper_2310_18547_amd import binding as B
     w = wl.custom([1, 1, 1, 1, 1], 512, 512, 16, "f16", seed=41, num_layers=2)
     raw = _dev(w, init_workspace=False)
