@@ -291,7 +291,9 @@ def run_probe(args):
 
 
 def run_timeline(args):
-    """One traced call of the single-launch kernel: when its workgroups pass the marked points."""
+    """One traced call: when the workgroups of the kernel pass the marked points.  Covers the
+    single-launch add-on kernels (--op add_lora) and, for long segments, the MFMA shrink
+    (--op shrink) and expand (--op expand) kernels of the launch-per-step path."""
     import numpy as np
     import torch
     from paper_2310_18547_amd import binding as B
@@ -299,12 +301,23 @@ def run_timeline(args):
     assert "trace" in os.path.basename(B.library_path()), "the timeline needs the trace build"
     w = make_workload(args.workload, args.seed, args.layers)
     d = DeviceWorkload(w, "cuda:0", n_sets=args.sets, path=args.path, ksplit=args.ksplit)
-    plan = B.sgmv_plan_add_lora(d.problem, w.n_segs, 1)
-    assert plan.launches == 1, "the timeline covers the single-launch kernels"
-    n_wg = plan.workgroups
+    op = "add_lora" if args.op == "all" else args.op
+    if op == "add_lora":
+        plan = B.sgmv_plan_add_lora(d.problem, w.n_segs, 1)
+        assert plan.launches == 1, "the add_lora timeline covers the single-launch kernels (try --op shrink / expand)"
+        n_wg, kernel, slices = plan.workgroups, KERNEL_NAMES[plan.kernel], plan.slices
+        call = lambda layer, k: d.add_lora(layer, k)
+    else:
+        assert w.max_seg_len >= 4, "the shrink / expand timelines cover the MFMA kernels (long segments)"
+        n_wg, slices = 1 << 16, None          # an upper bound; workgroups that record nothing are left out
+        v = torch.zeros(w.n_tokens, w.r, dtype=torch.float32, device="cuda:0")
+        if op == "shrink":
+            kernel, call = "shrink_stream_kernel", lambda layer, k: d.shrink(v, layer, k)
+        else:
+            kernel, call = "expand_matrix_kernel", lambda layer, k: d.expand(v, layer, k)
     trace = torch.zeros(n_wg * 10, dtype=torch.int64, device="cuda:0")
     for i in range(64):                       # warm, untraced
-        d.add_lora(i % w.num_layers, i % args.sets)
+        call(i % w.num_layers, i % args.sets)
     torch.cuda.synchronize()
     header = d.workspace[:4352].view(torch.int64)  # generation copies (4 KiB), error word, trace word
     rows = []
@@ -312,32 +325,39 @@ def run_timeline(args):
         trace.zero_()
         header[513] = trace.data_ptr()        # eight bytes behind the error word: trace on
         torch.cuda.synchronize()
-        d.add_lora((7 + rep) % w.num_layers, rep % args.sets)
+        call((7 + rep) % w.num_layers, rep % args.sets)
         torch.cuda.synchronize()
         header[513] = 0
         rows.append(trace.cpu().numpy().reshape(n_wg, 10).astype(np.float64) * 0.01)  # 100 MHz -> us
     assert d.check() == 0
     names = {0: "workgroup started", 8: "segment bounds and pointers known",
-             9: "first load about to issue" if plan.kernel == B.KERNEL_TILE else "generation tag known (exchange wave)",
+             9: "first load about to issue" if kernel == "add_lora_tile_kernel" else "generation tag known (exchange wave)",
              1: "all loads issued",
              2: "x staged in LDS (first data)", 3: "shrink of the slice done", 4: "partial sums published",
              5: "all slices collected", 6: "y stored", 7: "exchange wave leaves"}
-    order = [0, 8, 9, 1, 2, 3, 4, 5, 6, 7] if plan.kernel == B.KERNEL_TILE else [0, 8, 1, 9, 2, 3, 4, 5, 6, 7]
-    if plan.kernel == B.KERNEL_WHOLE:          # no hand-off: the workgroup has v once its own waves are summed
+    order = [0, 8, 9, 1, 2, 3, 4, 5, 6, 7] if kernel == "add_lora_tile_kernel" else [0, 8, 1, 9, 2, 3, 4, 5, 6, 7]
+    if kernel == "add_lora_whole_kernel":      # no hand-off: the workgroup has v once its own waves are summed
         order = [0, 8, 1, 2, 3, 5, 6]
         names[3], names[5] = "shrink done (all of A_i consumed)", "v summed over the waves"
+    if op != "add_lora":
+        order = [0, 8, 1, 2, 6]
+        names[1] = "first tiles and weight loads issued"
+        names[2] = "weight slice transposed into LDS"
+        names[6] = "last tile done (results stored)"
     points = []
+    live_counts = []
     for p_ in order:
         per_rep = []
         for t in rows:
             live = t[:, 6] > 0
+            live_counts.append(int(live.sum()))
             t0 = t[live, 0].min()
             per_rep.append(np.percentile(t[live, p_] - t0, [0, 50, 90, 100]))
         q = np.median(np.asarray(per_rep), axis=0)
         points.append({"point": names[p_], "min_us": q[0], "median_us": q[1], "p90_us": q[2], "max_us": q[3]})
     out = {"benchmark": "in-kernel timeline (trace build), microseconds after the first workgroup started",
-           "workload": w.name, "kernel": KERNEL_NAMES[plan.kernel], "workgroups": n_wg,
-           "slices_per_segment": plan.slices, "traced_calls": len(rows), "points": points}
+           "workload": w.name, "kernel": kernel, "workgroups": live_counts[0] if op != "add_lora" else n_wg,
+           "slices_per_segment": slices, "traced_calls": len(rows), "points": points}
     print(json.dumps(out), flush=True)
 
 

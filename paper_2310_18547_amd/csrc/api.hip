@@ -203,7 +203,9 @@ Scratch caller_scratch(const sgmv_problem* p) {
 size_t operand_bytes(int n_tokens, int r) {
   return 2 * round_up((size_t)n_tokens * r * 2, 256) + round_up((size_t)n_tokens * 4, 256);
 }
-void set_operands(ExpandArgs* a, char* base, int n_tokens, int r) {
+void set_operands(ExpandArgs* a, const Scratch& sc, int n_tokens, int r) {
+  char* base = sc.operands;
+  a->header = sc.header;
   const size_t half = round_up((size_t)n_tokens * r * 2, 256);
   a->vh = reinterpret_cast<uint16_t*>(base);
   a->vl = reinterpret_cast<uint16_t*>(base + half);
@@ -382,6 +384,7 @@ ShrinkArgs make_shrink(const sgmv_problem* p, const Scratch& sc, const void* x,
   a.A_ptrs = A_ptrs;
   a.seg_starts = seg_starts;
   a.partials = sc.partials;
+  a.header = sc.header;
   return a;
 }
 
@@ -406,6 +409,7 @@ ExpandArgs make_expand(const sgmv_problem* p, void* y, const float* v_parts, int
   a.scale = scale;
   a.vh = a.vl = nullptr;
   a.undo = nullptr;
+  a.header = nullptr;
   return a;
 }
 
@@ -591,7 +595,7 @@ int sgmv_expand(const sgmv_problem* p, void* y, const float* v, const void* cons
   const bool have_ws = check_workspace(p) == SGMV_OK;
   if (p->path == SGMV_PATH_MATRIX && !have_ws) return check_workspace(p);
   if (have_ws && use_matrix(p, n_segs)) {
-    set_operands(&a, caller_scratch(p).operands, p->n_tokens, p->r);
+    set_operands(&a, caller_scratch(p), p->n_tokens, p->r);
     if (launch_expand_matrix(a, st) != hipSuccess) return SGMV_ERR_LAUNCH;
   } else {
     if (launch_expand_vector(a, st) != hipSuccess) return SGMV_ERR_LAUNCH;
@@ -683,7 +687,7 @@ int add_lora_launch(const sgmv_problem* p, const Scratch& sc, void* y, const voi
       if (launch_shrink_matrix(sa, st) != hipSuccess) return SGMV_ERR_LAUNCH;
       ExpandArgs e = make_expand(p, y, sa.partials, sa.ksplit, A_ptrs, B_ptrs, seg_starts, n_segs,
                                  layer_idx, scale);
-      set_operands(&e, sc.operands, p->n_tokens, p->r);
+      set_operands(&e, sc, p->n_tokens, p->r);
       return launch_expand_matrix(e, st) == hipSuccess ? SGMV_OK : SGMV_ERR_LAUNCH;
     }
     default: {

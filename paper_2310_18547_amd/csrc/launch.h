@@ -34,6 +34,7 @@ struct ShrinkArgs {
   const void* const* A_ptrs;
   const int32_t* seg_starts;
   float* partials;           // [ksplit][n_tokens][r]
+  unsigned long long* header;// workspace header or nullptr (only trace builds look at it)
 };
 
 struct ExpandArgs {
@@ -53,6 +54,7 @@ struct ExpandArgs {
   uint16_t* vh;
   uint16_t* vl;
   float* undo;
+  unsigned long long* header;// workspace header or nullptr (only trace builds look at it)
 };
 
 // Most add-ons one multi-projection launch takes.

@@ -42,6 +42,7 @@
 #include "device_common.h"
 #include "launch.h"
 #include "mfma.h"
+#include "trace.h"
 
 
 namespace sgmv {
@@ -256,7 +257,7 @@ template <class DT, int R>
 __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
     const uint16_t* __restrict__ x, const uint16_t* const* __restrict__ A_ptrs,
     const int32_t* __restrict__ seg_starts, float* __restrict__ partials, int h_in, int kslice,
-    int n_tokens, long long layer_off) {
+    int n_tokens, long long layer_off, unsigned long long* header) {
   constexpr int NW = stream_waves(R);
   constexpr int NT = 64 * NW;
   constexpr int ROWS = 16 * NW;  // rows per workgroup and step
@@ -270,6 +271,8 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
 
   const int seg = blockIdx.z, s = blockIdx.x, tid = threadIdx.x;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  SGMV_TRACE_DECL
+  SGMV_TRACE_POINT(0);
   const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
   if ((int)blockIdx.y * ROWS >= hi - lo) return;
   const uint16_t* A = A_ptrs[seg];
@@ -277,6 +280,7 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
   const int k0 = s * kslice;
   const int klen = min(h_in, k0 + kslice) - k0;
   if (klen <= 0) return;
+  SGMV_TRACE_POINT(8);
   const int m = lane & 15, g = lane >> 4;
 
   // this wave's tiles: rows lo + ROWS (blockIdx.y + j gridDim.y) + 16 wave .. +15, j = 0 .. my_tiles-1
@@ -352,10 +356,12 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
       }
     }
   }
+  SGMV_TRACE_POINT(1);
   // LDS-only barrier: the x loads stay in flight
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  SGMV_TRACE_POINT(2);
 
   // ---- stream
   f32x4 acc[NTILE];
@@ -412,6 +418,14 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
     consume(q1);
     refill(q1);
   }
+  SGMV_TRACE_POINT(6);
+#ifdef SGMV_TRACE
+  if (header != nullptr) {
+    SGMV_TRACE_FLUSH(tid == 0, 0, 2);
+    SGMV_TRACE_FLUSH(tid == 0, 6, 6);
+    SGMV_TRACE_FLUSH(tid == 0, 8, 8);
+  }
+#endif
 }
 
 // ---------------------------------------------------------------- expand
@@ -452,7 +466,7 @@ __global__ __launch_bounds__(256, (R <= 32 ? 4 : 3) - (std::is_same<DT, F16>::va
     uint16_t* __restrict__ y, const uint16_t* __restrict__ vh, const uint16_t* __restrict__ vl,
     const float* __restrict__ undo, const uint16_t* const* __restrict__ A_ptrs,
     const uint16_t* const* __restrict__ B_ptrs, const int32_t* __restrict__ seg_starts, int h_out,
-    int n_tokens, long long layer_off, float scale, int rows_per_wg) {
+    int n_tokens, long long layer_off, float scale, int rows_per_wg, unsigned long long* header) {
   constexpr int KPAD = R < 32 ? 32 : R;  // k padded to the MFMA depth
   constexpr int KSTEPS = KPAD / 32;
   constexpr int NC = kExpandCols;        // columns per workgroup
@@ -467,11 +481,14 @@ __global__ __launch_bounds__(256, (R <= 32 ? 4 : 3) - (std::is_same<DT, F16>::va
   __shared__ __align__(16) uint32_t bt[(KPAD / 8) * BLK * 4];
 
   const int seg = blockIdx.z, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  SGMV_TRACE_DECL
+  SGMV_TRACE_POINT(0);
   const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
   if ((long long)blockIdx.y * rows_per_wg >= hi - lo) return;
   const uint16_t* B = B_ptrs[seg];
   if (B == nullptr) return;
   if (A_ptrs != nullptr && A_ptrs[seg] == nullptr) return;
+  SGMV_TRACE_POINT(8);
   const int c0 = blockIdx.x * NC;
   const int ncols = min(NC, h_out - c0);
   const __amdgpu_buffer_rsrc_t rB = make_buffer(
@@ -558,10 +575,12 @@ __global__ __launch_bounds__(256, (R <= 32 ? 4 : 3) - (std::is_same<DT, F16>::va
       }
     }
   }
+  SGMV_TRACE_POINT(1);
   // LDS-only barrier: the tile loads stay in flight
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  SGMV_TRACE_POINT(2);
 
   // ---- second operands: tile t, lane (n, g): column 4 n + t of the wave's 64, k block 4 ks + g
   uint4 bop[KSTEPS][CT];
@@ -627,6 +646,14 @@ __global__ __launch_bounds__(256, (R <= 32 ? 4 : 3) - (std::is_same<DT, F16>::va
     rbeg = lo + (int)next;
     nrows = min(hi, rbeg + rows_per_wg) - rbeg;
   }
+  SGMV_TRACE_POINT(6);
+#ifdef SGMV_TRACE
+  if (header != nullptr) {
+    SGMV_TRACE_FLUSH(tid == 0, 0, 2);
+    SGMV_TRACE_FLUSH(tid == 0, 6, 6);
+    SGMV_TRACE_FLUSH(tid == 0, 8, 8);
+  }
+#endif
 }
 
 // ---------------------------------------------------------------- launchers
@@ -666,7 +693,7 @@ static hipError_t launch_shrink_matrix_t(const ShrinkArgs& a, hipStream_t st) {
     }
     hipLaunchKernelGGL(kernel, grid, dim3(64 * stream_waves(R)), shrink_stream_lds_bytes(R, a.kslice), st,
                        (const uint16_t*)a.x, (const uint16_t* const*)a.A_ptrs, a.seg_starts, a.partials,
-                       a.h_in, a.kslice, a.n_tokens, a.layer_off);
+                       a.h_in, a.kslice, a.n_tokens, a.layer_off, a.header);
     return hipGetLastError();
   }
   hipLaunchKernelGGL((shrink_matrix_kernel<DT, R>), grid, dim3(256), 0, st, (const uint16_t*)a.x,
@@ -715,7 +742,7 @@ static hipError_t launch_expand_matrix_t(const ExpandArgs& a, hipStream_t st) {
   hipLaunchKernelGGL((expand_matrix_kernel<DT, R>), grid, dim3(256), 0, st, (uint16_t*)a.y, a.vh,
                      a.vl, a.undo, (const uint16_t* const*)a.A_ptrs,
                      (const uint16_t* const*)a.B_ptrs, a.seg_starts, a.h_out, a.n_tokens,
-                     a.layer_off, a.scale, rows);
+                     a.layer_off, a.scale, rows, a.header);
   return hipGetLastError();
 }
 
