@@ -273,7 +273,9 @@ int sgmv_add_lora_static(const sgmv_problem* p, void* y, const void* x,
  * With workspace_ready set and max_seg_len == 1 (every request its own
  * adapter) all add-ons run in ONE kernel launch; otherwise the call is the
  * same as n_proj calls of sgmv_add_lora in order.  The result of every add-on
- * is bit-identical to a separate sgmv_add_lora call. */
+ * equals that of a separate sgmv_add_lora call up to the order in which the
+ * fp32 sums are taken (the single-launch kernels split the same sums over
+ * lanes differently). */
 int sgmv_add_lora_multi(const sgmv_problem* p, int32_t n_proj, void* const* ys,
                         const void* const* xs, const void* const* const* A_ptrs,
                         const void* const* const* B_ptrs, const int32_t* seg_starts,

@@ -213,7 +213,7 @@ void set_operands(ExpandArgs* a, const Scratch& sc, int n_tokens, int r) {
 }
 
 // Launch shape of the single-launch path; false when it does not apply.
-bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f) {
+bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f, bool single_add_on = true) {
   if (!p->workspace_ready) return false;
   const Limits lim = limits();
   if (p->max_seg_len != 1) return false;  // one row per segment; longer ones go to the tile kernel
@@ -258,8 +258,17 @@ bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f) {
   f->kslice = ceil_div(ceil_div(p->h_in, s), 8) * 8;
   f->cslice = ceil_div(ceil_div(p->h_out, s), 8) * 8;
   const int chunks = f->cslice / 8;
+  // Lane groups of the expand phase: as many as give every lane a chunk of the column slice, and
+  // enough that a lane holds at most sixteen weight rows.  A single add-on at ranks up to 16 stops
+  // at two (the pair of neighbouring lanes that needs no LDS to add up, fused_kernel.hip) even
+  // where that leaves lanes without a chunk: measured at h = 4096, r = 16, 1 / 8 / 16 / 32 segments:
+  // 4.02 / 4.42 / 4.43 / 4.83 us against 4.07 / 4.54 / 4.59 / 5.01 us; at ranks 32 and 64 and in
+  // the multi-projection launches the wider groups are faster (16 segments at rank 32: 5.02
+  // against 5.46 us).
+  const int most = single_add_on && p->r <= 16 ? 2 : 8;
   int g = 1;
-  while (g * 2 <= 8 && 256 / (g * 2) >= chunks) g *= 2;
+  while (g * 2 <= most && 256 / (g * 2) >= chunks) g *= 2;
+  if (most == 2 && g == 1 && chunks <= 128) g = 2;
   while (p->r / g > 16) g *= 2;
   f->G = g;
   f->rows_per_pass = 1;
@@ -471,7 +480,7 @@ int plan_single(const sgmv_problem* p, int n_segs, SinglePlan* pl) {
 int plan_multi(const sgmv_problem* p, int n_segs, int n_proj, FusedArgs* f) {
   const Limits lim = limits();
   if ((p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->max_seg_len == 1 && n_proj > 1 &&
-      p->workspace != nullptr && choose_fused(p, n_segs, f) && f->S * n_proj <= split_cap(p->n_tokens)) {
+      p->workspace != nullptr && choose_fused(p, n_segs, f, false) && f->S * n_proj <= split_cap(p->n_tokens)) {
     f->r = p->r;
     // workgroups that hold segments count towards what must be resident; the grid, padded to
     // whole rows of segments, must leave every workgroup its own generation copy

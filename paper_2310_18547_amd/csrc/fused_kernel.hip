@@ -68,12 +68,18 @@ __device__ __forceinline__ void add_lora_fused_body(
   constexpr int JL = R / G;    // weight rows per lane in the expand phase
   static_assert(JL >= 1 && JL <= 16, "bad lane-group count");
   static_assert(kMaxKSlice / 8 == NT, "one 128-bit x chunk per lane and row");
+  // Two lane groups sit in neighbouring lanes of a wave (lane group = lane % 2) and add their
+  // sums with cross-lane moves: no LDS, no barrier, 0.2 us less behind the hand-off (B = 64:
+  // 6.23 -> 6.02 us).  With four or eight groups a wave's loads of B_i would fall into runs of
+  // 256 or 128 bytes per weight row, which costs more than the barriers (B = 64 at rank 64:
+  // 15.4 -> 16.6 us), so those keep whole waves per group and meet in LDS.
+  constexpr bool INTRA = G == 2;
 
   __shared__ __align__(16) uint16_t xs[RB][kMaxKSlice];
   __shared__ float red[NW][RB][R];
   __shared__ float vs[RB][R];
   __shared__ int vs_complete;  // 0: a slice of this row block never arrived, its rows of y stay as they are
-  __shared__ __align__(16) float ex[(G > 1 ? (G - 1) : 1) * RB * CPW * 8];
+  __shared__ __align__(16) float ex[(G > 2 ? (G - 1) : 1) * RB * CPW * 8];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   SGMV_TRACE_DECL
@@ -132,7 +138,7 @@ __device__ __forceinline__ void add_lora_fused_body(
       if (lane == 0) vs_complete = block_timed_out ? 0 : 1;
       SGMV_TRACE_POINT(5);
       lds_barrier();  // (e) vs filled
-      if (G > 1) {
+      if (G > 1 && !INTRA) {
         for (int pass = 0; pass < npass; ++pass) {
           if (pass != 0) lds_barrier();  // (f) ex free
           lds_barrier();                 // (g) ex filled
@@ -150,7 +156,8 @@ __device__ __forceinline__ void add_lora_fused_body(
   // ================================================================ stream waves
   const int cpr = klen >> 3;  // 128-bit chunks in one x row slice
   const __amdgpu_buffer_rsrc_t rA = make_buffer(A + offA + (long long)k0 * R, (uint32_t)nchunks * 16u);
-  const int cg = tid / CPW, cc = tid - cg * CPW;  // lane group, chunk within pass
+  const int cg = INTRA ? tid % G : tid / CPW;  // lane group
+  const int cc = INTRA ? tid / G : tid - cg * CPW;  // chunk within pass
   const __amdgpu_buffer_rsrc_t rB = make_buffer(
       B + offB + col_lo, ncols > 0 ? (uint32_t)((long long)(R - 1) * h_out + ncols) * 2u : 0u);
   const uint32_t b_row0 = (uint32_t)(cg * JL) * (uint32_t)h_out * 2u;
@@ -296,7 +303,13 @@ __device__ __forceinline__ void add_lora_fused_body(
           }
         }
       }
-      if (G > 1) {
+      if (INTRA) {
+        // both lanes of a pair end with the pair's sum
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[rb][e] += __shfl_xor(acc[rb][e], 1, 64);
+      } else if (G > 1) {
         if (pass != 0) lds_barrier();  // (f) ex free
         if (cg > 0) {
 #pragma unroll

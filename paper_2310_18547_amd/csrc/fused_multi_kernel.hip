@@ -17,8 +17,9 @@
 // projections; launches small enough for all workgroups to be resident side by
 // side take the plain kernel in fused_kernel.hip with one projection each).
 // Its work items are (row of the segment, projection); an item is exactly the
-// work of one workgroup of the single add-on kernel, with the same arithmetic in
-// the same order, so every result is bit-identical to a separate call.
+// work of one workgroup of the single add-on kernel, with the same arithmetic (only the
+// number of lane groups that share the expand's weight rows may differ, so results
+// agree with a separate call up to the order of the fp32 additions).
 //
 // Software pipeline.  The shrink of item i+1 runs BEFORE the expand of item i:
 // item i+1's partial sums are published before item i's are collected, so the

@@ -651,9 +651,11 @@ def test_add_lora_multi_matches_single_calls_and_oracle(P, batch, share_x):
     assert d0.check() == 0
     for i, (w, d) in enumerate(zip(ws, ds)):
         assert_parity(got[i], oracle.run_workload(w, layer_idx=1, n_threads=8), "f16", f"multi proj {i}")
+        # against a separate call: the same slices, but the expand may add its weight rows in
+        # groups of another size, so the two agree to rounding, not bit for bit
         d.reset_y()
         d.add_lora(1)
-        assert np.array_equal(d.y_bits(), got[i]), f"projection {i} differs from a single call"
+        assert_parity(d.y_bits(), got[i], w.dtype, f"projection {i} against a single call")
 
 
 @pytest.mark.parametrize("dtype,r,h_in,h_out", [("bf16", 64, 2048, 1544), ("f16", 8, 1000, 4096)])
@@ -942,7 +944,7 @@ def test_random_shapes_two_step_and_multi(seed):
     for q in ds:
         single = _dev(q.w, max_seg_len=hint)
         single.add_lora(1)
-        assert np.array_equal(q.y_bits(), single.y_bits()), f"multi differs from single, seed {seed}"
+        assert_parity(q.y_bits(), single.y_bits(), dtype, f"multi against single, seed {seed}")
     assert d0.check() == 0
 
 
@@ -963,9 +965,11 @@ def test_add_lora_multi_three_workgroups_per_unit():
     assert d0.check() == 0
     for i, (w, d) in enumerate(zip(ws, ds)):
         assert_parity(got[i], oracle.run_workload(w, layer_idx=1, n_threads=8), "bf16", f"multi 768 proj {i}")
+        # against a separate call: the same slices, but the expand may add its weight rows in
+        # groups of another size, so the two agree to rounding, not bit for bit
         d.reset_y()
         d.add_lora(1)
-        assert np.array_equal(d.y_bits(), got[i]), f"projection {i} differs from a single call"
+        assert_parity(d.y_bits(), got[i], w.dtype, f"projection {i} against a single call")
 
 
 def test_measurement_probes_run_and_check_their_arguments():
