@@ -297,8 +297,10 @@ bool choose_whole(const sgmv_problem* p, int n_segs, WholeArgs* w) {
   w->S = s;
   w->cslice = ceil_div(ceil_div(p->h_out, s), 8) * 8;
   const int chunks = w->cslice / 8;
+  const int most = p->r <= 16 ? 2 : 8;  // lane groups: as choose_fused
   int g = 1;
-  while (g * 2 <= 8 && 256 / (g * 2) >= chunks) g *= 2;
+  while (g * 2 <= most && 256 / (g * 2) >= chunks) g *= 2;
+  if (most == 2 && g == 1 && chunks <= 128) g = 2;
   while (p->r / g > 16) g *= 2;
   w->G = g;
   return true;

@@ -115,6 +115,13 @@ __device__ __forceinline__ float reduce_lanes8(const float (&a)[8], int lane, in
   return d;
 }
 
+// The value the neighbouring lane (lane ^ 1) holds, by a data-parallel-primitive move inside
+// the vector ALU (a quad permutation): no trip through the LDS crossbar and its latency.
+__device__ __forceinline__ float neighbour_lane(float v) {
+  const int i = __float_as_int(v);
+  return __int_as_float(__builtin_amdgcn_update_dpp(i, i, 0xB1 /* quad_perm 1,0,3,2 */, 0xF, 0xF, true));
+}
+
 }  // namespace sgmv
 
 // ---------------------------------------------------------------------------

@@ -308,7 +308,7 @@ __device__ __forceinline__ void add_lora_fused_body(
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-          for (int e = 0; e < 8; ++e) acc[rb][e] += __shfl_xor(acc[rb][e], 1, 64);
+          for (int e = 0; e < 8; ++e) acc[rb][e] += neighbour_lane(acc[rb][e]);
       } else if (G > 1) {
         if (pass != 0) lds_barrier();  // (f) ex free
         if (cg > 0) {

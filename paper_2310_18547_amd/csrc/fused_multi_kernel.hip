@@ -63,12 +63,15 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
   constexpr int JL = R / G;    // weight rows per lane in the expand phase
   constexpr int P = kMaxProjections;
   static_assert(JL >= 1 && JL <= 8, "bad lane-group count");
+  // two lane groups: neighbouring lanes, summed with a cross-lane move; more: whole waves per
+  // group, summed through LDS (as in add_lora_fused_kernel, where the reasons are given)
+  constexpr bool INTRA = G == 2;
 
   __shared__ __align__(16) uint16_t xs[kMaxKSlice];
   __shared__ float red[NW][R];
   __shared__ float vs[R];
   __shared__ int vs_complete;  // 0: a slice of the item never arrived, its row of y stays as it is
-  __shared__ __align__(16) float ex[(G > 1 ? (G - 1) : 1) * CPW * 8];
+  __shared__ __align__(16) float ex[(G > 2 ? (G - 1) : 1) * CPW * 8];
   __shared__ unsigned long long ptr_x[P], ptr_y[P], ptr_a[P], ptr_b[P];
   __shared__ uint32_t mine;  // bit p: projection p is this workgroup's and has both pointers set
 
@@ -191,7 +194,7 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
       timed_out = timed_out || item_timed_out;
       if (lane == 0) vs_complete = item_timed_out ? 0 : 1;
       lds_barrier();               // (e) vs filled
-      if (G > 1) lds_barrier();    // (g) ex filled
+      if (G > 1 && !INTRA) lds_barrier();    // (g) ex filled
     };
     // the shrink runs one item ahead of the expand: item i+1 is published before item i is
     // collected, so the other workgroups' sums of item i have had a whole step to arrive
@@ -221,7 +224,8 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
 
   // ================================================================ stream waves
   const int cpr = klen >> 3;                          // 128-bit chunks in one x row slice
-  const int cg = tid / CPW, cc = tid - cg * CPW;      // lane group, chunk within the column slice
+  const int cg = INTRA ? tid % G : tid / CPW;         // lane group
+  const int cc = INTRA ? tid / G : tid - cg * CPW;    // chunk within the column slice
   const uint32_t b_row0 = (uint32_t)(cg * JL) * (uint32_t)h_out * 2u;
   const uint32_t row_bytes_out = (uint32_t)h_out * 2u;
   const bool col_active = cc * 8 < ncols;
@@ -304,7 +308,10 @@ __global__ __launch_bounds__(320) void add_lora_fused_multi_kernel(
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[e] = fmaf(vj, bf[e], acc[e]);
     }
-    if (G > 1) {
+    if (INTRA) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += neighbour_lane(acc[e]);
+    } else if (G > 1) {
       if (cg > 0) {
         float* dst = &ex[((cg - 1) * CPW + cc) * 8];
         *reinterpret_cast<float4*>(dst) = make_float4(acc[0], acc[1], acc[2], acc[3]);

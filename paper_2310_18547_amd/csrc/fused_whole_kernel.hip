@@ -46,10 +46,13 @@ __global__ __launch_bounds__(256) void add_lora_whole_kernel(
   constexpr int JL = R / G;    // weight rows per lane in the expand phase
   constexpr int XL = kWholeMaxHin / (8 * NT);  // 128-bit x loads per lane
   static_assert(JL >= 1 && JL <= 16, "bad lane-group count");
+  // two lane groups: neighbouring lanes, summed with a cross-lane move; more: whole waves per
+  // group, summed through LDS (as in add_lora_fused_kernel, where the reasons are given)
+  constexpr bool INTRA = G == 2;
 
   __shared__ __align__(16) uint16_t xs[kWholeMaxHin];
   __shared__ __align__(16) float red[NW][R];
-  __shared__ __align__(16) float ex[(G > 1 ? (G - 1) : 1) * CPW * 8];
+  __shared__ __align__(16) float ex[(G > 2 ? (G - 1) : 1) * CPW * 8];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   SGMV_TRACE_DECL
@@ -70,7 +73,8 @@ __global__ __launch_bounds__(256) void add_lora_whole_kernel(
   const int col_lo = min(h_out, s * cslice);
   const int ncols = max(0, min(h_out, col_lo + cslice) - col_lo);
   const int npass = (ncols + CPW * 8 - 1) / (CPW * 8);  // 0 when the column slice is empty
-  const int cg = tid / CPW, cc = tid - cg * CPW;        // lane group, chunk within pass
+  const int cg = INTRA ? tid % G : tid / CPW;           // lane group
+  const int cc = INTRA ? tid / G : tid - cg * CPW;      // chunk within pass
 
   const __amdgpu_buffer_rsrc_t rA = make_buffer(A + offA, (uint32_t)iters * (NT * 16u));
   const __amdgpu_buffer_rsrc_t rB = make_buffer(
@@ -167,7 +171,10 @@ __global__ __launch_bounds__(256) void add_lora_whole_kernel(
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] = fmaf(vj[j], bf[e], o[e]);
       }
-      if (G > 1) {
+      if (INTRA) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] += neighbour_lane(o[e]);
+      } else if (G > 1) {
         if (pass != 0) lds_barrier();  // ex free
         if (cg > 0) {
           float* dst = &ex[((cg - 1) * CPW + cc) * 8];
