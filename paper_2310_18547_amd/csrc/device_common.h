@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace sgmv {
 
 struct F16 {};
@@ -113,6 +115,23 @@ __device__ __forceinline__ float reduce_lanes8(const float (&a)[8], int lane, in
   for (int m = M3 * 2; m < 64; m <<= 1) d += __shfl_xor(d, m, 64);
   e_out = ((lane & M1) ? 4 : 0) | ((lane & M2) ? 2 : 0) | ((lane & M3) ? 1 : 0);
   return d;
+}
+
+// Sum of v over the lanes of the same row of sixteen lanes that have the same (lane % LPR),
+// left in every such lane: data-parallel-primitive moves inside the vector ALU only (quad
+// permutations for the strides 1 and 2, row rotations for 4 and 8), no trip through the LDS
+// crossbar.  LPR is 1, 2, 4 or 8.
+template <int LPR>
+__device__ __forceinline__ float row_sum_same_group(float v) {
+  auto moved = [](float f, auto ctrl) {
+    const int i = __float_as_int(f);
+    return __int_as_float(__builtin_amdgcn_update_dpp(i, i, decltype(ctrl)::value, 0xF, 0xF, true));
+  };
+  if (LPR <= 1) v += moved(v, std::integral_constant<int, 0xB1>{});   // quad_perm 1,0,3,2
+  if (LPR <= 2) v += moved(v, std::integral_constant<int, 0x4E>{});   // quad_perm 2,3,0,1
+  if (LPR <= 4) v += moved(v, std::integral_constant<int, 0x124>{});  // row_ror 4
+  v += moved(v, std::integral_constant<int, 0x128>{});                // row_ror 8
+  return v;
 }
 
 // The value the neighbouring lane (lane ^ 1) holds, by a data-parallel-primitive move inside

@@ -76,7 +76,7 @@ __device__ __forceinline__ void add_lora_fused_body(
   constexpr bool INTRA = G == 2;
 
   __shared__ __align__(16) uint16_t xs[RB][kMaxKSlice];
-  __shared__ float red[NW][RB][R];
+  __shared__ __align__(16) float red[NW * 4][RB][R];  // per wave and row of sixteen lanes
   __shared__ float vs[RB][R];
   __shared__ int vs_complete;  // 0: a slice of this row block never arrived, its rows of y stay as they are
   __shared__ __align__(16) float ex[(G > 2 ? (G - 1) : 1) * RB * CPW * 8];
@@ -114,7 +114,7 @@ __device__ __forceinline__ void add_lora_fused_body(
         const int rb = idx / R, j = idx - rb * R;
         float sum = red[0][rb][j];
 #pragma unroll
-        for (int w = 1; w < NW; ++w) sum += red[w][rb][j];
+        for (int w = 1; w < NW * 4; ++w) sum += red[w][rb][j];
         const unsigned long long word = ((unsigned long long)__float_as_uint(sum) << 32) | tag;
         __hip_atomic_store(exch + (long long)s * stride + (long long)(row0 + rb) * R + j, word,
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -247,12 +247,20 @@ __device__ __forceinline__ void add_lora_fused_body(
         }
       }
     }
+    // Lane l holds partial sums of the columns (l % LPR) * 8 .. + 7.  They are summed over each row
+    // of sixteen lanes inside the vector ALU; the first LPR lanes of every row leave the row's sums
+    // in LDS, and the exchange wave adds the sixteen rows of the workgroup in a fixed order.
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
       if (RB == 1 || rb < nrows) {
-        int e;
-        const float d = reduce_lanes8<LPR>(acc[rb], lane, e);
-        if (lane < R) red[wave][rb][(lane % LPR) * 8 + e] = d;
+        float d[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) d[e] = row_sum_same_group<LPR>(acc[rb][e]);
+        if ((lane & 15) < LPR) {
+          float* dst = &red[wave * 4 + (lane >> 4)][rb][(lane & 15) * 8];
+          *reinterpret_cast<float4*>(dst) = make_float4(d[0], d[1], d[2], d[3]);
+          *reinterpret_cast<float4*>(dst + 4) = make_float4(d[4], d[5], d[6], d[7]);
+        }
       }
     }
     SGMV_TRACE_POINT(3);
