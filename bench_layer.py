@@ -1,11 +1,13 @@
 #!/usr/bin/env python3
 """Transformer-layer microbenchmark: what the LoRA add-ons cost next to the dense projections.
 
-    python bench_layer.py [--model 7b|13b] [--batch 64] [--rank 16] [--steps 200]
+    python bench_layer.py [--model 7b|13b] [--batch 64] [--seq 1] [--rank 16] [--steps 200]
 
-One *step* is the seven dense projections of one decoder layer at decode shape (one token per
-request; attention itself is left out) with a Distinct batch: every request has its own LoRA
-adapter on all seven projections (the paper applies LoRA to q, k, v, o, gate, up, down).  The
+One *step* is the seven dense projections of one decoder layer (attention itself is left out) with a
+Distinct batch: every request has its own LoRA adapter on all seven projections.  ``--seq 1`` is the
+decode shape (one token per request); ``--seq 512`` / ``2048`` are the prefill shapes of the paper's
+transformer-layer benchmark: every request contributes a segment of that many rows (the paper
+applies LoRA to q, k, v, o, gate, up, down).  The
 backbone GEMMs are library calls (PyTorch matmul = rocBLAS / hipBLASLt); the add-ons are this
 library's kernels, issued three ways:
 
@@ -16,7 +18,7 @@ library's kernels, issued three ways:
 Consecutive steps cycle over ``--layers`` sets of backbone and adapter weights so that nothing
 is served from the on-die caches.  Everything is synthetic (random weights, as in the paper's
 microbenchmarks).  Prints ONE JSON line.  This follows the paper's transformer-layer
-benchmark in spirit only: no attention kernel, one GPU, decode shape.
+benchmark in spirit only: no attention kernel, one GPU.
 """
 from __future__ import annotations
 
@@ -35,7 +37,8 @@ MODELS = {"7b": (4096, 11008), "13b": (5120, 13824)}
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--model", choices=sorted(MODELS), default="7b")
-    ap.add_argument("--batch", type=int, default=64)
+    ap.add_argument("--batch", type=int, default=64, help="requests, each with its own adapter")
+    ap.add_argument("--seq", type=int, default=1, help="token rows per request (1 = decode)")
     ap.add_argument("--rank", type=int, default=16)
     ap.add_argument("--layers", type=int, default=4, help="weight sets cycled through")
     ap.add_argument("--steps", type=int, default=200)
@@ -49,7 +52,8 @@ def main():
     assert torch.cuda.is_available(), "bench_layer.py needs a GPU"
     dev = torch.device("cuda:0")
     h, ffn = MODELS[args.model]
-    T, r, L = args.batch, args.rank, args.layers
+    n_req, r, L = args.batch, args.rank, args.layers
+    T = n_req * args.seq  # token rows: request i owns rows i * seq .. (i + 1) * seq - 1
     gen = torch.Generator(device=dev).manual_seed(0)
     f16 = torch.float16
 
@@ -74,11 +78,11 @@ def main():
             v.copy_(rnd(*shape, std=std))
         return views
 
-    A = {n: pool(T, (L, i, r), i ** -0.5) for n, (i, o) in shapes.items()}
-    Bw = {n: pool(T, (L, r, o), r ** -0.5) for n, (i, o) in shapes.items()}
+    A = {n: pool(n_req, (L, i, r), i ** -0.5) for n, (i, o) in shapes.items()}
+    Bw = {n: pool(n_req, (L, r, o), r ** -0.5) for n, (i, o) in shapes.items()}
     A_ptrs = {n: torch.tensor([t.data_ptr() for t in A[n]], dtype=torch.int64, device=dev) for n in shapes}
     B_ptrs = {n: torch.tensor([t.data_ptr() for t in Bw[n]], dtype=torch.int64, device=dev) for n in shapes}
-    seg_starts = torch.arange(T + 1, dtype=torch.int32, device=dev)
+    seg_starts = torch.arange(0, T + 1, args.seq, dtype=torch.int32, device=dev)
     x = rnd(T, h)
     y = {n: torch.empty(T, o, dtype=f16, device=dev) for n, (i, o) in shapes.items()}
 
@@ -87,7 +91,7 @@ def main():
     B.sgmv_workspace_init(ws, ws_bytes)
     torch.cuda.synchronize()
     prob = {n: B.make_problem(B.F16, i, o, r, L, T, workspace=ws, workspace_bytes=ws_bytes,
-                              max_seg_len=1, workspace_ready=1) for n, (i, o) in shapes.items()}
+                              max_seg_len=args.seq, workspace_ready=1) for n, (i, o) in shapes.items()}
     stream = torch.cuda.Stream(device=dev)
     sh = stream.cuda_stream
 
@@ -101,11 +105,11 @@ def main():
             torch.matmul(inputs(n), W[n][l], out=y[n])
 
     def single(l, n):
-        B.sgmv_add_lora(prob[n], y[n], inputs(n), A_ptrs[n], B_ptrs[n], seg_starts, T, l, 1.0, sh)
+        B.sgmv_add_lora(prob[n], y[n], inputs(n), A_ptrs[n], B_ptrs[n], seg_starts, n_req, l, 1.0, sh)
 
     def multi(l, names):
         B.sgmv_add_lora_multi(prob[names[0]], [y[n] for n in names], [inputs(n) for n in names],
-                              [A_ptrs[n] for n in names], [B_ptrs[n] for n in names], seg_starts, T, l,
+                              [A_ptrs[n] for n in names], [B_ptrs[n] for n in names], seg_starts, n_req, l,
                               1.0, sh)
 
     def step_backbone(i):
@@ -159,9 +163,10 @@ def main():
            "lora_multi_us": timeit(step_multi), "lora_only_multi_us": timeit(lora_only_multi)}
     assert B.sgmv_workspace_check(ws, sh) == 0
     weights = sum(i * o for i, o in shapes.values()) * 2
-    lora = sum((i * r + r * o) for i, o in shapes.values()) * 2 * T
-    out = {"benchmark": "decoder-layer dense projections + LoRA add-ons, decode shape, Distinct adapters",
-           "model": args.model, "h": h, "ffn": ffn, "batch": T, "rank": r, "layers_cycled": L,
+    lora = sum((i * r + r * o) for i, o in shapes.values()) * 2 * n_req
+    out = {"benchmark": "decoder-layer dense projections + LoRA add-ons, Distinct adapters",
+           "model": args.model, "h": h, "ffn": ffn, "batch": n_req, "seq": args.seq, "tokens": T, "rank": r,
+           "layers_cycled": L,
            "steps": args.steps, "dtype": "f16", "data": "synthetic", "n_gpus": 1,
            "backbone_weight_bytes_per_step": weights, "adapter_weight_bytes_per_step": lora,
            **res,
