@@ -67,10 +67,11 @@ def make_workload(name: str, seed: int, layers: int = 0):
     if name == "tiny":
         return wl.tiny(seed=seed)
     if name.startswith("prefill"):
-        # prefill_r16, prefill_r64, prefill_mlp_r16, prefill_mlp_r64
-        r = int(name.rsplit("r", 1)[1])
+        # prefill_r16, prefill_r64, prefill_mlp_r16, prefill_mlp_r64; bf16 unless the name ends in _f16
+        dtype = "f16" if name.endswith("_f16") else "bf16"
+        r = int(name[:-4].rsplit("r", 1)[1] if name.endswith("_f16") else name.rsplit("r", 1)[1])
         h_out = 28672 if "mlp" in name else 8192
-        return wl.prefill(h_in=8192, h_out=h_out, r=r, dtype="bf16", num_layers=layers or 1, seed=seed)
+        return wl.prefill(h_in=8192, h_out=h_out, r=r, dtype=dtype, num_layers=layers or 1, seed=seed)
     if name.startswith("distinct_b"):
         batch, h, h_out, r, dtype = None, 4096, None, 16, "f16"
         for part in name.split("_")[1:]:

@@ -175,6 +175,17 @@ __device__ __forceinline__ uint2 buffer_load64(__amdgpu_buffer_rsrc_t rsrc, uint
   u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)byte_off, 0, 0);
   return make_uint2(v.x, v.y);
 }
+// 64-bit accesses with a wave-uniform byte offset added to the lane's
+__device__ __forceinline__ uint2 buffer_load64_at(__amdgpu_buffer_rsrc_t rsrc, uint32_t lane_byte_off,
+                                                  uint32_t uniform_byte_off) {
+  u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)lane_byte_off, (int)uniform_byte_off, 0);
+  return make_uint2(v.x, v.y);
+}
+__device__ __forceinline__ void buffer_store64_at(__amdgpu_buffer_rsrc_t rsrc, uint32_t lane_byte_off,
+                                                  uint32_t uniform_byte_off, const uint2& q) {
+  u32x2 v = {q.x, q.y};
+  __builtin_amdgcn_raw_buffer_store_b64(v, rsrc, (int)lane_byte_off, (int)uniform_byte_off, 0);
+}
 __device__ __forceinline__ void buffer_store64(__amdgpu_buffer_rsrc_t rsrc, uint32_t byte_off,
                                                const uint2& q) {
   u32x2 v = {q.x, q.y};
@@ -184,6 +195,14 @@ __device__ __forceinline__ void buffer_store128(__amdgpu_buffer_rsrc_t rsrc, uin
                                                 const uint4& q) {
   u32x4 v = {q.x, q.y, q.z, q.w};
   __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, (int)byte_off, 0, 0);
+}
+
+// Workgroup barrier that orders LDS traffic only: outstanding global loads stay
+// outstanding.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 }  // namespace sgmv

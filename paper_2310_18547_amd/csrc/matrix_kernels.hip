@@ -36,6 +36,9 @@
 //           a wave covers four rows x 128 contiguous bytes.  v stays fp32 in the
 //           workspace between the kernels; it enters the matrix cores as the two 16-bit
 //           parts (two MFMAs, 16 significant bits for bfloat16, 22 for binary16).
+//   expand_rowwise_kernel  the same product with the operands' homes exchanged, for rank 64
+//           and for binary16: a wave owns sixteen rows of the block, keeps their v in
+//           registers and reads B_i's strip from LDS as it walks the strip's columns.
 #include <atomic>
 #include <type_traits>
 
@@ -50,9 +53,7 @@ namespace sgmv {
 constexpr int kShrinkRows = 64;    // rows per shrink workgroup (four 16-row tiles)
 constexpr int kShrinkChunk = 256;  // k per LDS stage
 constexpr int kExpandCols = 256;   // columns per expand workgroup (64 per wave)
-constexpr int kExpandRows = 64;    // fewest rows per expand workgroup
-constexpr int kExpandRowsMost = 64;      // most
-constexpr int kExpandWorkgroups = 1536;  // workgroups beyond which a workgroup takes more rows
+constexpr int kExpandRows = 64;    // rows per expand workgroup and step (sixteen per wave in the row-wise kernel)
 
 // ---------------------------------------------------------------- shrink
 //
@@ -656,6 +657,207 @@ __global__ __launch_bounds__(256, (R <= 32 ? 4 : 3) - (std::is_same<DT, F16>::va
 #endif
 }
 
+// The expand for ranks above 32.  Same grid, operands, product and access pattern of y as
+// expand_matrix_kernel, with the roles of the operands' homes exchanged: there a wave owns
+// 64 columns, keeps their part of B_i in registers and reads v anew for every row tile, which
+// at rank 64 costs 32 registers for B_i and as many bytes of v as of y per tile.  Here
+// a wave owns sixteen rows of the block and walks the strip's four column groups: its v
+// operands stay in registers for the whole strip (v is read once per workgroup row, not
+// once per tile and wave), the strip of B_i, transposed through LDS once, is shared by
+// the four waves and read from there as operands, and all sixteen 64-bit loads of the
+// wave's part of y are in flight at once, requested before the strip is placed.
+// Workgroups are short-lived on purpose: a launch has about twice as many as fit the chip
+// at once, and the hardware hands the next one to whichever compute unit comes free.  (A
+// variant whose workgroups stayed resident and walked several blocks each, the next
+// block's loads requested as registers came free, measured 7-14 % slower: the blocks no
+// longer spread evenly.)
+template <class DT, int R>
+__global__ __launch_bounds__(256, 4) void expand_rowwise_kernel(
+    uint16_t* __restrict__ y, const uint16_t* __restrict__ vh, const uint16_t* __restrict__ vl,
+    const float* __restrict__ undo, const uint16_t* const* __restrict__ A_ptrs,
+    const uint16_t* const* __restrict__ B_ptrs, const int32_t* __restrict__ seg_starts, int h_out,
+    int n_tokens, long long layer_off, float scale, unsigned long long* header) {
+  constexpr int KPAD = R < 32 ? 32 : R;  // k padded to the MFMA depth
+  constexpr int KSTEPS = KPAD / 32;
+  constexpr int NC = kExpandCols;        // columns per workgroup
+  constexpr int NT = 256;
+  constexpr int CT = 4;                  // 16-column tiles (and columns per lane) of a group
+  constexpr int NG = NC / (16 * CT);     // column groups of the strip
+  constexpr int KPAIRS = R / 2;
+  constexpr int ROWS = kExpandRows;
+  // B_i strip, transposed, as 16-byte slots {8 consecutive k of one column}:
+  // bt[k / 8][slot], NC + 1 slots per k block; column c of the strip sits in slot
+  // (c % 4) * (NC / 4) + c / 4, so the sixteen lanes of an operand read (columns 4 n + t,
+  // n = 0..15) read consecutive slots.
+  constexpr int BLK = NC + 1;
+  __shared__ __align__(16) uint32_t bt[(KPAD / 8) * BLK * 4];
+
+  const int seg = blockIdx.z, tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  SGMV_TRACE_DECL
+  SGMV_TRACE_POINT(0);
+  const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
+  if ((long long)blockIdx.y * ROWS >= hi - lo) return;
+  const uint16_t* B = B_ptrs[seg];
+  if (B == nullptr) return;
+  if (A_ptrs != nullptr && A_ptrs[seg] == nullptr) return;
+  SGMV_TRACE_POINT(8);
+  const int c0 = blockIdx.x * NC;
+  const int ncols = min(NC, h_out - c0);
+  const __amdgpu_buffer_rsrc_t rB = make_buffer(
+      B + layer_off + c0, (uint32_t)((long long)(R - 1) * h_out + ncols) * 2u);
+
+  // this lane: token rows 4 g + i of the wave's tile (i = 0..3), columns c0 + 64 j + 4 n .. + 3
+  // of column group j
+  const int n = lane & 15, g = lane >> 4;
+
+  // ---- the strip's loads first (L2 hits mostly), so that placing the strip does not wait
+  // for the loads of y from HBM that follow them
+  constexpr int TOTAL = KPAIRS * (NC / 8);  // (k pair, 8 columns) items
+  constexpr int ITEMS = (TOTAL + NT - 1) / NT;
+  uint4 s0[ITEMS], s1[ITEMS];
+#pragma unroll
+  for (int b = 0; b < ITEMS; ++b) {
+    const int item = b * NT + tid;  // consecutive lanes: consecutive 16 bytes of a row
+    const int cg = item % (NC / 8), kp = item / (NC / 8);
+    const bool in = item < TOTAL && cg * 8 < ncols;
+    s0[b] = buffer_load128(rB, in ? (uint32_t)((2 * kp) * h_out + cg * 8) * 2u : kOutOfRange);
+    s1[b] = buffer_load128(rB, in ? (uint32_t)((2 * kp + 1) * h_out + cg * 8) * 2u : kOutOfRange);
+  }
+
+  // y: lane offsets of rows 4 g + i in the wave's tile at the strip's first group; group j
+  // adds 128 j bytes (a scalar operand); rows past the block and groups past h_out are
+  // switched off per access
+  uint32_t yoff[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) yoff[i] = (uint32_t)((4 * g + i) * h_out + c0 + n * CT) * 2u;
+  const int groups_ok = max(0, min(NG, (h_out - c0 - n * CT + 16 * CT - 1) / (16 * CT)));  // this lane's groups inside h_out
+
+  // everything the wave reads for its sixteen rows of one block
+  uint2 yq[NG][4];
+  uint4 vhi[KSTEPS], vlo[KSTEPS];
+  float un[4];
+  __amdgpu_buffer_rsrc_t rY;
+  int rows = 0;  // rows of the wave's tile inside the segment
+  auto fetch = [&](int rbeg) {
+    const int r0 = rbeg + wave * 16;
+    rows = max(0, min(16, min(hi, rbeg + ROWS) - r0));
+    rY = make_buffer(y + (long long)r0 * h_out, (uint32_t)(rows * h_out) * 2u);
+    const __amdgpu_buffer_rsrc_t rH = make_buffer(vh + (long long)r0 * R, (uint32_t)(rows * R) * 2u);
+    const __amdgpu_buffer_rsrc_t rL = make_buffer(vl + (long long)r0 * R, (uint32_t)(rows * R) * 2u);
+    // first operand: row n of the tile, k = 32 ks + 8 g .. + 7; rows past the segment and k
+    // past the rank read as zeros
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      const int k = ks * 32 + g * 8;
+      const uint32_t voff = n < (k < R ? rows : 0) ? (uint32_t)(n * R + k) * 2u : kOutOfRange;
+      vhi[ks] = buffer_load128(rH, voff);
+      vlo[ks] = buffer_load128(rL, voff);
+    }
+#pragma unroll
+    for (int j = 0; j < NG; ++j) {
+      const int ylim = j < groups_ok ? rows : 0;  // one compare per access
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        yq[j][i] = buffer_load64_at(rY, 4 * g + i < ylim ? yoff[i] : kOutOfRange, (uint32_t)j * (16 * CT * 2));
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      un[i] = std::is_same<DT, F16>::value && rows > 0 ? undo[r0 + min(4 * g + i, rows - 1)] : 1.f;
+  };
+  int rbeg = lo + (int)blockIdx.y * ROWS;
+  fetch(rbeg);
+
+  // ---- place the strip transposed: a thread takes pairs of k of eight columns
+  if (R < KPAD) {
+    for (int i = tid; i < (KPAD / 8) * BLK * 4; i += NT) bt[i] = 0u;
+    lds_barrier();
+  }
+#pragma unroll
+  for (int b = 0; b < ITEMS; ++b) {
+    const int item = b * NT + tid;
+    const int cg = item % (NC / 8), kp = item / (NC / 8);
+    if (item < TOTAL) {
+      const uint32_t a0[4] = {s0[b].x, s0[b].y, s0[b].z, s0[b].w};
+      const uint32_t a1[4] = {s1[b].x, s1[b].y, s1[b].z, s1[b].w};
+      uint32_t* blk = &bt[(kp >> 2) * BLK * 4 + (kp & 3)];  // k block, dword of the k pair
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {  // columns 8 cg + 2 i and + 2 i + 1, i.e. c % 4 = 2 (i % 2) (+ 1), c / 4 = 2 cg + i / 2
+        blk[((2 * (i & 1)) * (NC / 4) + 2 * cg + (i >> 1)) * 4] = (a0[i] & 0xFFFFu) | (a1[i] << 16);
+        blk[((2 * (i & 1) + 1) * (NC / 4) + 2 * cg + (i >> 1)) * 4] = (a0[i] >> 16) | (a1[i] & 0xFFFF0000u);
+      }
+    }
+  }
+  SGMV_TRACE_POINT(1);
+  lds_barrier();  // LDS only: the loads of y stay in flight
+  SGMV_TRACE_POINT(2);
+
+  for (;;) {
+    // the operands are read from LDS where they are used: hoisted out of this loop (they do
+    // not change from block to block) they would take 32 KPAD / 8 registers
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int j = 0; j < NG; ++j) {
+      // second operands: column 64 j + 4 n + t of the strip, k block 4 ks + g
+      auto operand = [&](int ks, int t) {
+        const int pos = t * (NC / 4) + j * 16 + n;
+        return *reinterpret_cast<const uint4*>(&bt[((ks * 4 + g) * BLK + pos) * 4]);
+      };
+      f32x4 acc[CT];
+#pragma unroll
+      for (int t = 0; t < CT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (KSTEPS == 1) {  // few registers: five workgroups per compute unit
+#pragma unroll
+        for (int t = 0; t < CT; ++t) {
+          const uint4 bop = operand(0, t);
+          acc[t] = mfma16x16x32<DT>(vlo[0], bop, acc[t]);
+          acc[t] = mfma16x16x32<DT>(vhi[0], bop, acc[t]);
+        }
+      } else {  // the group's operands at once, the four tiles' sums advancing side by side
+        uint4 bop[KSTEPS][CT];
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+          for (int t = 0; t < CT; ++t) bop[ks][t] = operand(ks, t);
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+#pragma unroll
+          for (int t = 0; t < CT; ++t) acc[t] = mfma16x16x32<DT>(vlo[ks], bop[ks][t], acc[t]);
+#pragma unroll
+          for (int t = 0; t < CT; ++t) acc[t] = mfma16x16x32<DT>(vhi[ks], bop[ks][t], acc[t]);
+        }
+      }
+      // acc[t][i] is column c0 + 64 j + 4 n + t of row 4 g + i
+      const int ylim = j < groups_ok ? rows : 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float yf[4];
+        unpack2<DT>(yq[j][i].x, yf[0], yf[1]);
+        unpack2<DT>(yq[j][i].y, yf[2], yf[3]);
+        const float sc = scale * un[i];
+        float o[4];
+#pragma unroll
+        for (int t = 0; t < CT; ++t) o[t] = yf[t] + sc * acc[t][i];
+        const uint2 out = make_uint2(pack2<DT>(o[0], o[1]), pack2<DT>(o[2], o[3]));
+        buffer_store64_at(rY, 4 * g + i < ylim ? yoff[i] : kOutOfRange, (uint32_t)j * (16 * CT * 2), out);
+      }
+    }
+    // next block of this workgroup (only when the grid is smaller than the longest segment needs)
+    const long long next = (long long)rbeg - lo + (long long)gridDim.y * ROWS;
+    if (next >= hi - lo) break;
+    rbeg = lo + (int)next;
+    fetch(rbeg);
+  }
+  SGMV_TRACE_POINT(6);
+#ifdef SGMV_TRACE
+  if (header != nullptr) {
+    SGMV_TRACE_FLUSH(tid == 0, 0, 2);
+    SGMV_TRACE_FLUSH(tid == 0, 6, 6);
+    SGMV_TRACE_FLUSH(tid == 0, 8, 8);
+  }
+#endif
+}
+
 // ---------------------------------------------------------------- launchers
 
 static unsigned row_blocks(int max_seg_len, int n_tokens, int rows_per_block) {
@@ -718,31 +920,28 @@ hipError_t launch_shrink_matrix(const ShrinkArgs& a, hipStream_t st) {
   return a.bf16 ? launch_shrink_matrix_r<BF16>(a, st) : launch_shrink_matrix_r<F16>(a, st);
 }
 
-// Rows per expand workgroup: 64, or more when that would launch several rounds of
-// workgroups, so that a workgroup's set-up (lookup, staging the strip of B_i) is spread
-// over more rows.  Depends only on the shape, so results do not depend on it.
-int expand_rows_per_wg(const ExpandArgs& a) {
-  const long long strips = (a.h_out + kExpandCols - 1) / kExpandCols;
-  int rows = kExpandRows;
-  while (rows < kExpandRowsMost && strips * (a.n_tokens / rows + a.n_segs) > kExpandWorkgroups) rows *= 2;
-  return rows;
-}
-
 template <class DT, int R>
 static hipError_t launch_expand_matrix_t(const ExpandArgs& a, hipStream_t st) {
-  const int rows = expand_rows_per_wg(a);
   dim3 grid((unsigned)((a.h_out + kExpandCols - 1) / kExpandCols),
-            row_blocks(a.max_seg_len, a.n_tokens, rows), (unsigned)a.n_segs);
+            row_blocks(a.max_seg_len, a.n_tokens, kExpandRows), (unsigned)a.n_segs);
   // v -> 16-bit operand pairs, then the expand proper
   const long long items = (long long)a.n_tokens * (R / 4);
   hipLaunchKernelGGL((finalize_v_kernel<DT, R>), dim3((unsigned)((items + 255) / 256)), dim3(256), 0,
                      st, a.v_parts, a.nparts, a.vh, a.vl, a.undo, a.n_tokens);
   const hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
-  hipLaunchKernelGGL((expand_matrix_kernel<DT, R>), grid, dim3(256), 0, st, (uint16_t*)a.y, a.vh,
-                     a.vl, a.undo, (const uint16_t* const*)a.A_ptrs,
-                     (const uint16_t* const*)a.B_ptrs, a.seg_starts, a.h_out, a.n_tokens,
-                     a.layer_off, a.scale, rows, a.header);
+  // measured: the row-wise kernel is ahead at rank 64 (8-15 %) and for binary16 at every rank
+  // (2-3 %; the range factors cost the other one its fourth workgroup per compute unit)
+  if constexpr (R > 32 || std::is_same<DT, F16>::value)
+    hipLaunchKernelGGL((expand_rowwise_kernel<DT, R>), grid, dim3(256), 0, st, (uint16_t*)a.y, a.vh,
+                       a.vl, a.undo, (const uint16_t* const*)a.A_ptrs,
+                       (const uint16_t* const*)a.B_ptrs, a.seg_starts, a.h_out, a.n_tokens,
+                       a.layer_off, a.scale, a.header);
+  else
+    hipLaunchKernelGGL((expand_matrix_kernel<DT, R>), grid, dim3(256), 0, st, (uint16_t*)a.y, a.vh,
+                       a.vl, a.undo, (const uint16_t* const*)a.A_ptrs,
+                       (const uint16_t* const*)a.B_ptrs, a.seg_starts, a.h_out, a.n_tokens,
+                       a.layer_off, a.scale, kExpandRows, a.header);
   return hipGetLastError();
 }
 
