@@ -230,6 +230,12 @@ bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f, bool single_a
     while (pw * 2 <= s) pw *= 2;
     s = pw;
   }
+  // 97 .. 128 segments of a single add-on: four slices, two workgroups per unit, rather than two
+  // (measured at h = 4096, 128 segments, r = 16 / 32: 9.35 / 18.0 us against 9.81 / 18.8; no
+  // difference at 96 segments or at rank 64; wider inputs are better off as they are)
+  if (p->ksplit == 0 && single_add_on && s == 2 && n_segs > 96 && 2 * n_segs <= lim.fused_workgroups &&
+      p->r <= 32 && need <= 2)
+    s = 4;
   // Small batches at high rank: where a slice of A_i at eight slices takes more than one batch
   // of loads (2048 128-bit chunks), sixteen slices are faster while they are all resident
   // (measured at r = 64, h = 4096 / 5120, 1..8 segments: 5.1 / 5.8 us against 5.4 / 6.7 us)
@@ -455,9 +461,16 @@ int plan_single(const sgmv_problem* p, int n_segs, SinglePlan* pl) {
     // beats the launch-per-step kernels up to rank 16 and several hundred segments (192 / 256 /
     // 512: 13.5 / 16.4 / 28.8 against 16.2 / 18.6 / 29.9; 1024: 53.9 against 51.2), without a
     // workspace also at rank 32 (64 segments: 13.0 against 14.2; rank 64: 23.8 against 22.5).
+    // For binary16 it is also ahead up to rank 16 where the input is so wide that the hand-off
+    // kernel must take an odd number of slices and with them more workgroups than compute
+    // units (h = 5120, three slices, 96 / 112 / 128 segments: 11.5 / 12.4 / 13.7 against 13.1 /
+    // 13.7 / 14.6; bfloat16 at 128 segments: 15.2 against 14.8, so not there; 72 / 80 segments,
+    // at most one workgroup per unit: 10.5 / 11.0 against 8.1 / 8.8, so not there either).
+    const bool odd_slices = fused && p->dtype == SGMV_F16 && (pl->fused.S & (pl->fused.S - 1)) != 0 &&
+                            pl->fused.S * n_segs > limits().fused_workgroups;
     if (p->path == SGMV_PATH_AUTO && p->ksplit == 0 && choose_whole(p, n_segs, &pl->whole) &&
         ((p->r == 8 && n_segs <= 512) ||
-         (!fused && n_segs <= 640 && p->r <= (p->workspace_ready ? 16 : 32)))) {
+         ((!fused || odd_slices) && n_segs <= 640 && p->r <= (p->workspace_ready ? 16 : 32)))) {
       pl->kernel = SGMV_KERNEL_WHOLE;
       return SGMV_OK;
     }

@@ -171,7 +171,7 @@ def test_plan_single_launch_shapes():
     assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and (pl.slices, pl.workgroups) == (2, 512)
     rc, pl = _plan(256, n_tokens=256, max_seg_len=1, h_in=2048)
     assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and (pl.slices, pl.workgroups) == (1, 256)
-    for batch, S in ((1, 8), (8, 8), (16, 8), (32, 8), (48, 4), (64, 4), (128, 2)):
+    for batch, S in ((1, 8), (8, 8), (16, 8), (32, 8), (48, 4), (64, 4), (96, 2), (128, 4)):
         rc, pl = _plan(batch, n_tokens=batch, max_seg_len=1)
         assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and pl.launches == 1
         assert (pl.slices, pl.workgroups) == (S, S * batch), (batch, pl.slices)
@@ -182,6 +182,13 @@ def test_plan_single_launch_shapes():
         rc, pl = _plan(batch, n_tokens=batch, max_seg_len=1, r=8)
         assert rc == 0 and pl.kernel == sg.KERNEL_WHOLE and (pl.launches, pl.slices) == (1, S)
         assert pl.workgroups == 8 * S * ((batch + 7) // 8)
+    # binary16 rows so wide that the hand-off kernel needs an odd number of slices: the kernel without
+    # hand-off once those slices outnumber the compute units
+    for batch, kernel in ((80, sg.KERNEL_FUSED), (96, sg.KERNEL_WHOLE), (128, sg.KERNEL_WHOLE)):
+        rc, pl = _plan(batch, n_tokens=batch, max_seg_len=1, h_in=5120, h_out=5120)
+        assert rc == 0 and pl.kernel == kernel, (batch, pl.kernel)
+    rc, pl = _plan(128, n_tokens=128, max_seg_len=1, h_in=5120, h_out=5120, dtype=sg.BF16)
+    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and pl.slices == 3
     # that kernel needs no workspace: it is what a caller without a prepared one gets, and forced
     # it runs without any
     rc, pl = _plan(64, n_tokens=64, max_seg_len=1, workspace_ready=0)
