@@ -46,17 +46,22 @@ MFMA_PEAK_TFLOPS = 2500.0  # dense bf16 / fp16, MI355X
 # whose plan differs from the profiled one reports null.  Source: the summaries in profiles/.
 PROFILED_TRAFFIC = {
     ("distinct_b64", "add_lora", "add_lora_fused_kernel", 4):
-        (18.661e6, "profiles/add_lora_fused_distinct_b64_h4096_r16.md"),
+        (18.637e6, "profiles/add_lora_fused_distinct_b64_h4096_r16.md"),
     ("distinct_b64_r8", "add_lora", "add_lora_whole_kernel", 4):
-        (10.092e6, "profiles/add_lora_whole_distinct_b64_h4096_r8.md"),
+        (10.074e6, "profiles/add_lora_whole_distinct_b64_h4096_r8.md"),
     ("distinct_b256", "add_lora", "add_lora_whole_kernel", 1):
-        (73.650e6, "profiles/add_lora_whole_distinct_b256_h4096_r16.md"),
+        (73.656e6, "profiles/add_lora_whole_distinct_b256_h4096_r16.md"),
 }
 
 # the paper's own latencies for this operator (one A100 80 GB, fp16, r = 16), context only
 PAPER_A100_US = {"distinct_b64": [116.0, 75.0], "distinct_b1": [37.0, 42.0]}
 
 KERNEL_NAMES = None  # filled after the binding is imported
+
+
+def expand_kernel_name(w) -> str:
+    """The MFMA expand kernel the library runs for this workload (rank 64 and binary16: row-wise)."""
+    return "expand_rowwise_kernel" if w.r > 32 or w.dtype == "f16" else "expand_matrix_kernel"
 
 
 def make_workload(name: str, seed: int, layers: int = 0):
@@ -315,7 +320,7 @@ def run_timeline(args):
         if op == "shrink":
             kernel, call = "shrink_stream_kernel", lambda layer, k: d.shrink(v, layer, k)
         else:
-            kernel, call = "expand_matrix_kernel", lambda layer, k: d.expand(v, layer, k)
+            kernel, call = expand_kernel_name(w), lambda layer, k: d.expand(v, layer, k)
     trace = torch.zeros(n_wg * 10, dtype=torch.int64, device="cuda:0")
     for i in range(64):                       # warm, untraced
         call(i % w.num_layers, i % args.sets)
@@ -444,12 +449,14 @@ def bench_one(args, op, d, w, probe):
     if op == "add_lora":
         plan = B.sgmv_plan_add_lora(d.problem, w.n_segs, P)
         kernel, launches, slices, workgroups = KERNEL_NAMES[plan.kernel], plan.launches, plan.slices, plan.workgroups
+        if plan.kernel == B.KERNEL_MATRIX:
+            kernel = kernel.replace("expand_matrix_kernel", expand_kernel_name(w))
     else:
         long_segments = w.max_seg_len >= 4
         kernel = {("shrink", False): "shrink_vector_kernel + shrink_reduce_kernel",
                   ("shrink", True): "shrink_stream_kernel + shrink_reduce_kernel",
                   ("expand", False): "expand_vector_kernel",
-                  ("expand", True): "finalize_v_kernel + expand_matrix_kernel"}[(op, long_segments)]
+                  ("expand", True): "finalize_v_kernel + " + expand_kernel_name(w)}[(op, long_segments)]
         launches, slices, workgroups = (1 if kernel == "expand_vector_kernel" else 2), None, None
     traffic = args.traffic_bytes
     traffic_source = "--traffic-bytes" if traffic is not None else None
