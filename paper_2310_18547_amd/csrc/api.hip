@@ -248,6 +248,13 @@ bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f, bool single_a
   if (s > kFusedMaxWorkgroups / n_segs) s = kFusedMaxWorkgroups / n_segs;
   if (s < need) s = need;
   if (s < 1) s = 1;
+  // a slice count forced by a wide input to five, six or seven: eight instead, where the launch
+  // has room (measured at 64 segments, h_in = 11008, six -> eight slices: rank 64 31.9 -> 27.5 us,
+  // rank 16 9.79 -> 9.53; h_in = 13824, seven -> eight: no difference)
+  if (p->ksplit == 0 && single_add_on && s == need && s > 4 && s < 8 &&
+      8LL * ceil_div(n_segs, fused_grid_x(n_segs)) * fused_grid_x(n_segs) <= kFusedMaxWorkgroups && 8 <= cap &&
+      8 <= wide / 64)
+    s = 8;
   // the grid is padded to whole rows of segments (launch.h, fused_grid_x)
   const int gx = fused_grid_x(n_segs);
   if ((long long)s * ceil_div(n_segs, gx) * gx > kFusedMaxWorkgroups) return false;
