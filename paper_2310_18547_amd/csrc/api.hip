@@ -239,10 +239,13 @@ bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f, bool single_a
   // Small batches at high rank: where a slice of A_i at eight slices takes more than one batch
   // of loads (2048 128-bit chunks), sixteen slices are faster while they are all resident
   // (measured at r = 64, h = 4096 / 5120, 1..8 segments: 5.1 / 5.8 us against 5.4 / 6.7 us)
-  if (p->ksplit == 0 && s == kFusedSlices && 2 * s * n_segs <= lim.fused_workgroups &&
-      (long long)ceil_div(p->h_in, s) * (p->r / 8) > 2048)
-    s = 2 * kFusedSlices;
+  // The same holds for the slice of B_i of a wide output (4096 -> 11008 at rank 32, 1 / 8 / 16
+  // segments: 5.7 / 5.9 / 7.1 us against 6.2 / 6.7 / 8.1), and it does not hold at rank 16, where
+  // the chunks are short (h_in = 11008 / 13824, 1 .. 16 segments: eight slices 3-5 % ahead).
   const int wide = p->h_in > p->h_out ? p->h_in : p->h_out;
+  if (p->ksplit == 0 && s == kFusedSlices && 2 * s * n_segs <= lim.fused_workgroups && p->r >= 32 &&
+      (long long)ceil_div(wide, s) * (p->r / 8) > 2048)
+    s = 2 * kFusedSlices;
   if (s > wide / 64) s = wide / 64;
   if (s > cap) s = cap;
   if (s > kFusedMaxWorkgroups / n_segs) s = kFusedMaxWorkgroups / n_segs;
@@ -262,6 +265,17 @@ bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f, bool single_a
   // from about two rounds of workgroups on the launch-per-step kernels are faster (measured)
   if (p->path == SGMV_PATH_AUTO && p->ksplit == 0 && (long long)s * n_segs > 2 * lim.fused_workgroups)
     return false;
+  // From rank 32 on, a launch of more workgroups than units is only worth it when the units get
+  // equal shares: 288 or 384 workgroups leave most units waiting for the ones with two (measured
+  // against the launch-per-step kernels, h = 5120, three slices, 96 / 128 segments: rank 32 22.4 /
+  // 24.3 against 19.1 / 22.1 us, rank 64 36.3 / 40.1 against 30.7 / 35.2; h = 8192, four slices,
+  // 96 segments: 27.8 against 24.7 and 45.2 against 41.5; 512 workgroups are fine: 128 segments
+  // at h = 4096, rank 32: 18.0 against 19.6)
+  if (p->path == SGMV_PATH_AUTO && p->ksplit == 0 && p->r >= 32 && (long long)s * n_segs > lim.fused_workgroups) {
+    const long long wg = (long long)s * n_segs;
+    const long long rounds = ceil_div((int)wg, lim.fused_workgroups);
+    if (rounds * lim.fused_workgroups * 5 > wg * 6) return false;  // more than 20 % of the slots idle
+  }
   // likewise batches of more than 128 segments that need two slices each (measured at
   // h = 4096, r = 16: 192 segments 17.3 us here against 15.5 us, 256 segments 20.0 against 18.3)
   if (p->path == SGMV_PATH_AUTO && p->ksplit == 0 && n_segs > lim.fused_workgroups / 2 &&
@@ -463,7 +477,9 @@ int plan_single(const sgmv_problem* p, int n_segs, SinglePlan* pl) {
     // One-row segments, measured on MI355X at h = 4096 (us per add-on, whole-shrink kernel
     // against the alternative): at rank 8, where A_i is small, it beats the kernel with the
     // hand-off at every batch (1 / 16 / 64 / 128 segments: 3.7 / 4.0 / 4.8 / 6.0 against 4.1 /
-    // 4.7 / 5.2 / 6.2) and the launch-per-step kernels beyond (256: 9.5 against 12.4); where the
+    // 4.7 / 5.2 / 6.2) and the launch-per-step kernels beyond (256: 9.5 against 12.4), but only
+    // while A_i is small: at h_in = 8192 the hand-off kernel is 15-20 % ahead at every batch (64
+    // segments: 6.2 against 7.4), at 5120 from 64 segments on (5.4 against 6.0); where the
     // hand-off kernel does not apply (no prepared workspace, or more segments than it takes) it
     // beats the launch-per-step kernels up to rank 16 and several hundred segments (192 / 256 /
     // 512: 13.5 / 16.4 / 28.8 against 16.2 / 18.6 / 29.9; 1024: 53.9 against 51.2), without a
@@ -476,7 +492,7 @@ int plan_single(const sgmv_problem* p, int n_segs, SinglePlan* pl) {
     const bool odd_slices = fused && p->dtype == SGMV_F16 && (pl->fused.S & (pl->fused.S - 1)) != 0 &&
                             pl->fused.S * n_segs > limits().fused_workgroups;
     if (p->path == SGMV_PATH_AUTO && p->ksplit == 0 && choose_whole(p, n_segs, &pl->whole) &&
-        ((p->r == 8 && n_segs <= 512) ||
+        ((p->r == 8 && n_segs <= 512 && (!fused || p->h_in <= 4096 || (p->h_in <= 5120 && n_segs <= 32))) ||
          ((!fused || odd_slices) && n_segs <= 640 && p->r <= (p->workspace_ready ? 16 : 32)))) {
       pl->kernel = SGMV_KERNEL_WHOLE;
       return SGMV_OK;

@@ -189,6 +189,23 @@ def test_plan_single_launch_shapes():
         assert rc == 0 and pl.kernel == kernel, (batch, pl.kernel)
     rc, pl = _plan(128, n_tokens=128, max_seg_len=1, h_in=5120, h_out=5120, dtype=sg.BF16)
     assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and pl.slices == 3
+    # rank 8 with a large A_i: the hand-off kernel again (the whole-shrink kernel re-reads A_i per slice)
+    for h, batch, kernel in ((4096, 64, sg.KERNEL_WHOLE), (5120, 32, sg.KERNEL_WHOLE), (5120, 64, sg.KERNEL_FUSED),
+                             (8192, 1, sg.KERNEL_FUSED), (8192, 64, sg.KERNEL_FUSED)):
+        rc, pl = _plan(batch, n_tokens=batch, max_seg_len=1, r=8, h_in=h, h_out=h)
+        assert rc == 0 and pl.kernel == kernel, (h, batch, pl.kernel)
+    # from rank 32 on no single launch whose workgroups would fill the units unevenly (288, 384 of 256)
+    rc, pl = _plan(96, n_tokens=96, max_seg_len=1, r=32, h_in=5120, h_out=5120)
+    assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR
+    rc, pl = _plan(96, n_tokens=96, max_seg_len=1, r=64, h_in=8192, h_out=8192)
+    assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR
+    rc, pl = _plan(128, n_tokens=128, max_seg_len=1, r=32)
+    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and pl.workgroups == 512
+    # sixteen slices for small batches from rank 32 on, by the wider of input and output
+    rc, pl = _plan(8, n_tokens=8, max_seg_len=1, r=32, h_in=4096, h_out=11008)
+    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and pl.slices == 16
+    rc, pl = _plan(8, n_tokens=8, max_seg_len=1, r=16, h_in=11008, h_out=4096)
+    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and pl.slices == 8
     # that kernel needs no workspace: it is what a caller without a prepared one gets, and forced
     # it runs without any
     rc, pl = _plan(64, n_tokens=64, max_seg_len=1, workspace_ready=0)
