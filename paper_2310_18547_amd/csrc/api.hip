@@ -78,7 +78,16 @@ Limits limits() {
 }
 
 int spin_limit_of(const sgmv_problem* p) { return p->spin_limit > 0 ? p->spin_limit : kFusedSpinLimit; }
-constexpr int kMatrixMinSegLen = 4;    // AUTO uses the MFMA kernels from this segment length on (measured crossover)
+// AUTO uses the MFMA kernels from this segment length on.  Their work goes with the number of
+// segments (every segment occupies at least one block of 64 rows), that of the vector kernels
+// with the rows: measured at h = 4096, 128 segments of 4 rows, ranks 8 / 16 / 32 / 64: vector
+// kernels 14.4 / 18.2 / 28.9 / 45.1 us against 23.9 / 26.3 / 31.3 / 47.7; 64 segments of 8 rows,
+// ranks 16 / 64: MFMA 19.1 / 37.6 against 25.1 / 60.6.
+constexpr int kMatrixMinSegLen = 6;
+// At rank 64 the vector kernels are slow enough that the MFMA kernels win from two rows per
+// segment on while the segments are few (32 segments of 2 / 4 rows: 21.7 / 21.9 us against 23.1 /
+// 31.4; the Uniform mix of 39 segments: 26.3 against 34.6; 64 segments of 4 rows: 36.9 against 34.0).
+constexpr int kMatrixFewSegments = 48;
 constexpr int kMatrixWorkgroups = 448; // workgroups the MFMA shrink aims for
 
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -155,6 +164,7 @@ bool use_matrix(const sgmv_problem* p, int n_segs) {
   if (p->path != SGMV_PATH_AUTO) return false;
   if (n_segs > kMatrixMaxSegments) return false;  // the vector kernels take any number of segments
   const int len = p->max_seg_len > 0 ? p->max_seg_len : p->n_tokens / (n_segs > 0 ? n_segs : 1);
+  if (p->r >= 64 && n_segs <= kMatrixFewSegments && len >= 2) return true;
   return len >= kMatrixMinSegLen;
 }
 
@@ -339,6 +349,12 @@ bool choose_tile(const sgmv_problem* p, int n_segs, TileArgs* t) {
   const Limits lim = limits();
   if (p->max_seg_len <= 0 || p->max_seg_len > kTileMaxSegLen) return false;
   if (n_segs > kFusedMaxWorkgroups) return false;
+  // At rank 64 a full block of sixteen rows hands 8 KB of tagged words per slice from workgroup
+  // to workgroup, and the launch-per-step MFMA kernels are ahead from about ten rows per segment
+  // on (h = 4096, one segment of 16 / 64 / 256 rows: 14.8 / 16.0 / 17.8 us against 20.2 / 20.2 /
+  // 20.7 here; Skewed mix of 32 rows, longest segment 12: 15.4 against 17.0; segments of up to 8
+  // rows: 13.0-15.5 here against 14.8-17.2)
+  if (p->path == SGMV_PATH_AUTO && p->r >= 64 && p->max_seg_len > 8) return false;
   const int cap = split_cap(p->n_tokens);
   const int narrow = p->h_in < p->h_out ? p->h_in : p->h_out;
   int z = ceil_div(p->max_seg_len, 16);

@@ -227,7 +227,19 @@ def test_plan_single_launch_shapes():
     rc, pl = _plan(64, n_tokens=64, max_seg_len=1, workspace_ready=0, r=64)
     assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR and pl.launches == 2
     rc, pl = _plan(39, n_tokens=64, max_seg_len=5, workspace_ready=0)
+    assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR   # many short segments: work by rows, not by 64-row blocks
+    rc, pl = _plan(16, n_tokens=128, max_seg_len=8, workspace_ready=0)
     assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX
+    # rank 64: the tile kernel up to eight rows per segment, then the MFMA kernels, which also take
+    # few short segments there
+    rc, pl = _plan(8, n_tokens=64, max_seg_len=8, r=64)
+    assert rc == 0 and pl.kernel == sg.KERNEL_TILE
+    rc, pl = _plan(4, n_tokens=64, max_seg_len=16, r=64)
+    assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX and pl.launches == 3
+    rc, pl = _plan(39, n_tokens=64, max_seg_len=3, r=64)
+    assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX
+    rc, pl = _plan(128, n_tokens=512, max_seg_len=4, r=64)
+    assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR
     # long segments: the MFMA kernels, three launches
     rc, pl = _plan(4, n_tokens=3450, max_seg_len=891)
     assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX and pl.launches == 3
