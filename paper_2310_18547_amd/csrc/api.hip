@@ -495,7 +495,7 @@ int plan_single(const sgmv_problem* p, int n_segs, SinglePlan* pl) {
     // hand-off at every batch (1 / 16 / 64 / 128 segments: 3.7 / 4.0 / 4.8 / 6.0 against 4.1 /
     // 4.7 / 5.2 / 6.2) and the launch-per-step kernels beyond (256: 9.5 against 12.4), but only
     // while A_i is small: at h_in = 8192 the hand-off kernel is 15-20 % ahead at every batch (64
-    // segments: 6.2 against 7.4), at 5120 from 64 segments on (5.4 against 6.0); where the
+    // segments: 6.2 against 7.4), at 5120 from 64 segments on (5.4 against 6.0; bfloat16 from 32 on); where the
     // hand-off kernel does not apply (no prepared workspace, or more segments than it takes) it
     // beats the launch-per-step kernels up to rank 16 and several hundred segments (192 / 256 /
     // 512: 13.5 / 16.4 / 28.8 against 16.2 / 18.6 / 29.9; 1024: 53.9 against 51.2), without a
@@ -508,7 +508,7 @@ int plan_single(const sgmv_problem* p, int n_segs, SinglePlan* pl) {
     const bool odd_slices = fused && p->dtype == SGMV_F16 && (pl->fused.S & (pl->fused.S - 1)) != 0 &&
                             pl->fused.S * n_segs > limits().fused_workgroups;
     if (p->path == SGMV_PATH_AUTO && p->ksplit == 0 && choose_whole(p, n_segs, &pl->whole) &&
-        ((p->r == 8 && n_segs <= 512 && (!fused || p->h_in <= 4096 || (p->h_in <= 5120 && n_segs <= 32))) ||
+        ((p->r == 8 && n_segs <= 512 && (!fused || p->h_in <= 4096)) ||
          ((!fused || odd_slices) && n_segs <= 640 && p->r <= (p->workspace_ready ? 16 : 32)))) {
       pl->kernel = SGMV_KERNEL_WHOLE;
       return SGMV_OK;

@@ -190,7 +190,7 @@ def test_plan_single_launch_shapes():
     rc, pl = _plan(128, n_tokens=128, max_seg_len=1, h_in=5120, h_out=5120, dtype=sg.BF16)
     assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and pl.slices == 3
     # rank 8 with a large A_i: the hand-off kernel again (the whole-shrink kernel re-reads A_i per slice)
-    for h, batch, kernel in ((4096, 64, sg.KERNEL_WHOLE), (5120, 32, sg.KERNEL_WHOLE), (5120, 64, sg.KERNEL_FUSED),
+    for h, batch, kernel in ((4096, 64, sg.KERNEL_WHOLE), (5120, 32, sg.KERNEL_FUSED), (5120, 64, sg.KERNEL_FUSED),
                              (8192, 1, sg.KERNEL_FUSED), (8192, 64, sg.KERNEL_FUSED)):
         rc, pl = _plan(batch, n_tokens=batch, max_seg_len=1, r=8, h_in=h, h_out=h)
         assert rc == 0 and pl.kernel == kernel, (h, batch, pl.kernel)
