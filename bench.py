@@ -67,8 +67,20 @@ def expand_kernel_name(w) -> str:
 def make_workload(name: str, seed: int, layers: int = 0):
     """Named workloads.  Generic decode shapes: distinct_b{B}[_h{H}][_o{H_OUT}][_r{R}][_{dtype}]."""
     import sgmv_workloads as wl
-    if name in ("uniform", "skewed", "identical", "uniform_paper", "skewed_paper"):
-        return wl.popularity(name, batch=64, h_in=4096, r=16, dtype="f16", num_layers=layers or 32, seed=seed)
+    kinds = ("uniform_paper", "skewed_paper", "uniform", "skewed", "identical")
+    kind = next((k for k in kinds if name == k or name.startswith(k + "_")), None)
+    if kind is not None:
+        # adapter-popularity mixes: <kind>[_b<batch>][_r<rank>], defaults batch 64, rank 16
+        batch, r = 64, 16
+        for part in name[len(kind):].split("_")[1:]:
+            if part[0] == "b":
+                batch = int(part[1:])
+            elif part[0] == "r":
+                r = int(part[1:])
+            else:
+                raise SystemExit(f"unknown workload {name!r}")
+        return wl.popularity(kind, batch=batch, h_in=4096, r=r, dtype="f16",
+                             num_layers=layers or (32 if r <= 16 else 8), seed=seed)
     if name == "tiny":
         return wl.tiny(seed=seed)
     if name.startswith("prefill"):
