@@ -465,11 +465,16 @@ def bench_one(args, op, d, w, probe):
             kernel = kernel.replace("expand_matrix_kernel", expand_kernel_name(w))
     else:
         long_segments = w.max_seg_len >= 4
+        if op == "shrink":  # asked of the library
+            sp = B.sgmv_plan_shrink(d.problem, w.n_segs)
+            long_segments = sp.kernel == B.KERNEL_MATRIX
         kernel = {("shrink", False): "shrink_vector_kernel + shrink_reduce_kernel",
                   ("shrink", True): "shrink_stream_kernel + shrink_reduce_kernel",
                   ("expand", False): "expand_vector_kernel",
                   ("expand", True): "finalize_v_kernel + " + expand_kernel_name(w)}[(op, long_segments)]
         launches, slices, workgroups = (1 if kernel == "expand_vector_kernel" else 2), None, None
+        if op == "shrink" and sp.kernel == B.KERNEL_FUSED:
+            kernel, launches, slices, workgroups = "shrink_handoff_kernel", 1, sp.slices, sp.workgroups
     traffic = args.traffic_bytes
     traffic_source = "--traffic-bytes" if traffic is not None else None
     if traffic is None and P == 1 and args.path == 0 and args.ksplit == 0:

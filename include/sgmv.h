@@ -289,6 +289,13 @@ int sgmv_add_lora_multi(const sgmv_problem* p, int32_t n_proj, void* const* ys,
  * return for these arguments. */
 int sgmv_plan_add_lora(const sgmv_problem* p, int32_t n_segs, int32_t n_proj, sgmv_plan* plan);
 
+/* The same for the stand-alone sgmv_shrink (section "Segmented Gather Matrix-Vector
+ * Multiplication", the shrink launch): SGMV_KERNEL_FUSED with one launch when one-row
+ * segments are reduced inside the launch by the hand-off between workgroups (needs a
+ * prepared workspace, max_seg_len == 1 and SGMV_PATH_AUTO), else SGMV_KERNEL_MATRIX or
+ * SGMV_KERNEL_VECTOR with two launches (partial sums, then their sum).  Host-only, pure. */
+int sgmv_plan_shrink(const sgmv_problem* p, int32_t n_segs, sgmv_plan* plan);
+
 /* Measurement aid, not part of the operator: enqueue one plain kernel of known traffic on
  * `stream`, for the benchmark's attainable-bandwidth figure and for scaling a profiler's HBM
  * byte counters (the roofline analysis of the paper's microbenchmark section compares the

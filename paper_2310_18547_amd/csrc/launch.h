@@ -146,6 +146,8 @@ size_t tile_lds_bytes(int r, int kslice, int cslice);
 hipError_t launch_add_lora_whole(const WholeArgs& a, hipStream_t st);
 hipError_t launch_add_lora_tile(const TileArgs& a, hipStream_t st);
 hipError_t launch_add_lora_fused(const FusedArgs& a, hipStream_t st);
+// Stand-alone shrink of one-row segments in one launch (x, A_ptrs, S, kslice and the hand-off fields of `a`).
+hipError_t launch_shrink_handoff(const FusedArgs& a, float* v, hipStream_t st);
 bool fused_multi_fits(const FusedArgs& a);
 hipError_t launch_add_lora_fused_multi(const FusedArgs& a, hipStream_t st);
 hipError_t launch_workspace_init(void* p, size_t bytes, size_t header_offset, hipStream_t st);

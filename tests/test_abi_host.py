@@ -262,6 +262,29 @@ def test_plan_single_launch_shapes():
     assert rc == 0 and pl.kernel == sg.KERNEL_NONE and pl.launches == 0
 
 
+def test_plan_shrink():
+    """Stand-alone shrink: one launch with the hand-off for one-row segments, else two launches."""
+    p = sg.make_problem(sg.F16, 4096, 4096, 16, 1, 64, workspace=FAKE, workspace_bytes=1 << 30, max_seg_len=1,
+                        workspace_ready=1)
+    rc, pl = sg.sgmv_plan_shrink(p, 64, check=False)
+    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and (pl.launches, pl.slices, pl.workgroups) == (1, 4, 256)
+    p.h_out = 0                                       # the output width plays no part
+    rc, pl = sg.sgmv_plan_shrink(p, 64, check=False)
+    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED
+    p.workspace_ready = 0
+    rc, pl = sg.sgmv_plan_shrink(p, 64, check=False)
+    assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR and pl.launches == 2
+    p.workspace_ready, p.path = 1, sg.PATH_VECTOR
+    rc, pl = sg.sgmv_plan_shrink(p, 64, check=False)
+    assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR
+    p.path, p.max_seg_len, p.n_tokens = sg.PATH_AUTO, 300, 1200
+    rc, pl = sg.sgmv_plan_shrink(p, 4, check=False)
+    assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX and pl.launches == 2
+    p.path = sg.PATH_FUSED
+    assert sg.sgmv_plan_shrink(p, 4, check=False)[0] == 3
+    assert sg.lib.sgmv_plan_shrink(None, 4, None) == 1
+
+
 def test_plan_multi_projection_shapes():
     # few enough workgroups for all projections side by side (two workgroups per unit)
     rc, pl = _plan(64, 2, n_tokens=64, max_seg_len=1)

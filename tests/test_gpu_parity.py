@@ -71,6 +71,55 @@ def test_shrink_accumulates_into_v():
     assert np.all(np.abs(v.cpu().numpy() - ref) <= 2e-3 + 2e-2 * np.abs(ref))
 
 
+# stand-alone shrink of one-row segments: one launch, partial sums handed over inside it
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("batch,h_in,r", [(1, 4096, 16), (7, 1000, 8), (33, 4096, 64), (64, 5120, 32), (64, 4096, 16),
+                                         (100, 2048, 16)])
+def test_shrink_single_launch_matches_oracle(dtype, batch, h_in, r):
+    w = wl.decode_distinct(batch=batch, h_in=h_in, h_out=64, r=r, dtype=dtype, num_layers=2, seed=batch + r)
+    d = _dev(w)
+    v0 = np.random.Generator(np.random.PCG64(batch)).standard_normal((batch, r)).astype(np.float32)
+    v = torch.from_numpy(v0.copy()).to("cuda:0")
+    d.shrink(v, 1)
+    ref = oracle.run_workload(w, op="shrink", layer_idx=1, v=v0.copy(), n_threads=8)
+    assert np.all(np.abs(v.cpu().numpy() - ref) <= 2e-3 + 2e-2 * np.abs(ref))
+    assert d.check() == 0
+    # twice in a row on one workspace: the second call's hand-off carries the next generation
+    d.shrink(v, 1)
+    ref2 = oracle.run_workload(w, op="shrink", layer_idx=1, v=ref.copy(), n_threads=8)
+    assert np.all(np.abs(v.cpu().numpy() - ref2) <= 4e-3 + 2e-2 * np.abs(ref2))
+    assert d.check() == 0
+
+
+def test_shrink_single_launch_wrong_hint_and_missing_adapters():
+    # the caller promised one row per segment; longer and empty segments and segments without an
+    # adapter are still handled (rows of the latter keep their v)
+    lens = [1, 3, 0, 1, 2, 1]
+    w = wl.custom(lens, 768, 64, 16, "f16", seed=21, seg_adapter=[0, 1, 2, -1, 3, 4])
+    d = _dev(w, max_seg_len=1)
+    v0 = np.full((w.n_tokens, w.r), 0.25, np.float32)
+    v = torch.from_numpy(v0.copy()).to("cuda:0")
+    d.shrink(v)
+    ref = oracle.run_workload(w, op="shrink", v=v0.copy())
+    got = v.cpu().numpy()
+    assert np.all(np.abs(got - ref) <= 2e-3 + 2e-2 * np.abs(ref))
+    assert np.all(got[4] == 0.25)          # the row of the segment without an adapter
+    assert d.check() == 0
+
+
+def test_shrink_single_launch_equals_two_launch_path():
+    from paper_2310_18547_amd import binding as B
+    w = wl.decode_distinct(batch=48, h_in=4096, h_out=64, r=16, dtype="bf16", num_layers=1, seed=5)
+    out = []
+    for path in (B.PATH_AUTO, B.PATH_VECTOR):
+        d = _dev(w, path=path)
+        v = torch.zeros(w.n_tokens, w.r, dtype=torch.float32, device="cuda:0")
+        d.shrink(v)
+        out.append(v.cpu().numpy())
+    # the slices differ between the paths, so the fp32 sums agree to rounding, not bit for bit
+    assert np.all(np.abs(out[0] - out[1]) <= 1e-4 + 1e-4 * np.abs(out[1]))
+
+
 # ------------------------------------------------------- bit-exact routing
 @pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("hint", [True, False])
