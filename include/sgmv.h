@@ -201,7 +201,11 @@ int sgmv_validate_segments(const int32_t* host_seg_starts, int32_t n_segs, int32
  *   v      device fp32 [n_tokens][r], read and written (accumulated into)
  *   x      device 16-bit [n_tokens][h_in], read
  *   A_ptrs device array of n_segs device pointers
- * Uses p->workspace.  h_out of the descriptor is ignored. */
+ * Uses p->workspace.  h_out of the descriptor is ignored.  With SGMV_PATH_AUTO, a
+ * prepared workspace (workspace_ready) and max_seg_len == 1 the call is one launch whose
+ * workgroups hand their Split-K partial sums to each other (bounded wait: a time-out is
+ * reported by sgmv_workspace_check and leaves the affected rows of v as they were);
+ * otherwise two launches, partial sums and their sum. */
 int sgmv_shrink(const sgmv_problem* p, float* v, const void* x,
                 const void* const* A_ptrs, const int32_t* seg_starts,
                 int32_t n_segs, int32_t layer_idx, void* stream);
