@@ -107,6 +107,34 @@ def test_shrink_single_launch_wrong_hint_and_missing_adapters():
     assert d.check() == 0
 
 
+def test_shrink_single_launch_gives_up_without_storing():
+    # the bounded wait of the single-launch shrink, forced from the host as for the add-on kernels:
+    # workgroup 0 tags its partial sums with a generation its neighbours do not expect, the collecting
+    # workgroup of the first segment gives up, that row of v stays as it was, every other row is finished
+    w = wl.decode_distinct(batch=32, h_in=4096, h_out=64, r=16, dtype="f16", num_layers=1, seed=77)
+    d = _dev(w, spin_limit=200)
+    from paper_2310_18547_amd import binding as B
+    plan = B.sgmv_plan_shrink(d.problem, w.n_segs)
+    assert plan.kernel == B.KERNEL_FUSED and plan.launches == 1 and plan.slices > 1
+    v0 = np.full((w.n_tokens, w.r), 3.0, np.float32)
+    ref = oracle.run_workload(w, op="shrink", v=v0.copy(), n_threads=8)
+    v = torch.from_numpy(v0.copy()).to("cuda:0")
+    d.workspace[0:4].view(torch.int32).fill_(77)
+    torch.cuda.synchronize()
+    d.shrink(v)
+    assert d.check() == 8                                   # SGMV_ERR_TIMEOUT
+    got = v.cpu().numpy()
+    assert np.all(got[0] == 3.0)
+    assert np.all(np.abs(got[1:] - ref[1:]) <= 2e-3 + 2e-2 * np.abs(ref[1:]))
+    B.sgmv_workspace_init(d.workspace, d.ws_bytes)
+    torch.cuda.synchronize()
+    d.problem.spin_limit = 0
+    v = torch.from_numpy(v0.copy()).to("cuda:0")
+    d.shrink(v)
+    assert d.check() == 0
+    assert np.all(np.abs(v.cpu().numpy() - ref) <= 2e-3 + 2e-2 * np.abs(ref))
+
+
 def test_shrink_single_launch_equals_two_launch_path():
     from paper_2310_18547_amd import binding as B
     w = wl.decode_distinct(batch=48, h_in=4096, h_out=64, r=16, dtype="bf16", num_layers=1, seed=5)
