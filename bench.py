@@ -60,8 +60,8 @@ KERNEL_NAMES = None  # filled after the binding is imported
 
 
 def expand_kernel_name(w) -> str:
-    """The MFMA expand kernel the library runs for this workload (rank 64 and binary16: row-wise)."""
-    return "expand_rowwise_kernel" if w.r > 32 or w.dtype == "f16" else "expand_matrix_kernel"
+    """The MFMA expand kernel the library runs for this workload (rank 64 and binary16 with segments of at least a 64-row block: row-wise)."""
+    return "expand_rowwise_kernel" if (w.r > 32 or w.dtype == "f16") and w.max_seg_len >= 64 else "expand_matrix_kernel"
 
 
 def make_workload(name: str, seed: int, layers: int = 0):

@@ -930,9 +930,13 @@ static hipError_t launch_expand_matrix_t(const ExpandArgs& a, hipStream_t st) {
                      st, a.v_parts, a.nparts, a.vh, a.vl, a.undo, a.n_tokens);
   const hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
-  // measured: the row-wise kernel is ahead at rank 64 (8-15 %) and for binary16 at every rank
-  // (2-3 %; the range factors cost the other one its fourth workgroup per compute unit)
-  if constexpr (R > 32 || std::is_same<DT, F16>::value)
+  // measured: with long segments the row-wise kernel is ahead at rank 64 (8-15 %) and for binary16
+  // at every rank (2-3 %; the range factors cost the other one its fourth workgroup per compute
+  // unit).  With segments shorter than a block only the first of its waves would have rows, and
+  // the column-owning kernel, whose four waves share every row tile, is ahead (eight segments of
+  // eight rows, binary16, rank 16: 6.2 against 7.6 us).
+  const int longest = a.max_seg_len > 0 ? a.max_seg_len : a.n_tokens / (a.n_segs > 0 ? a.n_segs : 1);
+  if ((R > 32 || std::is_same<DT, F16>::value) && longest >= kExpandRows)
     hipLaunchKernelGGL((expand_rowwise_kernel<DT, R>), grid, dim3(256), 0, st, (uint16_t*)a.y, a.vh,
                        a.vl, a.undo, (const uint16_t* const*)a.A_ptrs,
                        (const uint16_t* const*)a.B_ptrs, a.seg_starts, a.h_out, a.n_tokens,
