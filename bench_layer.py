@@ -86,7 +86,7 @@ def main():
     x = rnd(T, h)
     y = {n: torch.empty(T, o, dtype=f16, device=dev) for n, (i, o) in shapes.items()}
 
-    ws_bytes = B.sgmv_workspace_bytes(T, r)
+    ws_bytes = B.sgmv_workspace_bytes_multi(T, r, 3)  # q / k / v in one call may share the pass over x
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     B.sgmv_workspace_init(ws, ws_bytes)
     torch.cuda.synchronize()

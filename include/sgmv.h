@@ -166,6 +166,13 @@ const char* sgmv_status_string(int status);
  * function.  Returns 0 for n_tokens <= 0. */
 size_t sgmv_workspace_bytes(int32_t n_tokens, int32_t r);
 
+/* Workspace size that also lets sgmv_add_lora_multi share one pass over x between the shrinks
+ * of up to three add-ons on long (prefill-shaped) segments that read the same x, e.g. q / k / v or
+ * gate / up (the paper applies LoRA to all dense projections of a layer): the size of
+ * sgmv_workspace_bytes plus room for the partial sums of the other add-ons.  A workspace of the
+ * plain size works everywhere; such calls then run one add-on after the other. */
+size_t sgmv_workspace_bytes_multi(int32_t n_tokens, int32_t r, int32_t n_proj);
+
 /* Prepare a workspace for the single-launch paths of sgmv_add_lora: clears it
  * and sets its generation count with a small kernel on `stream` (so the call
  * may be recorded into a HIP graph).  Those paths exchange partial sums

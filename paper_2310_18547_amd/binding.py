@@ -80,6 +80,8 @@ def _load():
     L.sgmv_status_string.restype = c.c_char_p
     L.sgmv_workspace_bytes.argtypes = [c.c_int32, c.c_int32]
     L.sgmv_workspace_bytes.restype = c.c_size_t
+    L.sgmv_workspace_bytes_multi.argtypes = [c.c_int32, c.c_int32, c.c_int32]
+    L.sgmv_workspace_bytes_multi.restype = c.c_size_t
     L.sgmv_workspace_init.argtypes = [c.c_void_p, c.c_size_t, c.c_void_p]
     L.sgmv_workspace_init.restype = c.c_int
     L.sgmv_workspace_check.argtypes = [c.c_void_p, c.c_void_p]
@@ -144,6 +146,10 @@ def sgmv_status_string(status: int) -> str:
 
 def sgmv_workspace_bytes(n_tokens: int, r: int) -> int:
     return int(lib.sgmv_workspace_bytes(n_tokens, r))
+
+
+def sgmv_workspace_bytes_multi(n_tokens: int, r: int, n_proj: int) -> int:
+    return int(lib.sgmv_workspace_bytes_multi(n_tokens, r, n_proj))
 
 
 def sgmv_workspace_init(workspace, workspace_bytes: int, stream=None, check: bool = True) -> int:

@@ -439,6 +439,7 @@ ShrinkArgs make_shrink(const sgmv_problem* p, const Scratch& sc, const void* x,
   a.seg_starts = seg_starts;
   a.partials = sc.partials;
   a.header = sc.header;
+  a.n_shared = 0;
   return a;
 }
 
@@ -603,6 +604,13 @@ size_t sgmv_workspace_bytes(int32_t n_tokens, int32_t r) {
   if (n_tokens <= 0 || r <= 0) return 0;
   // header, fp32 split-K partials, 64-bit exchange words, 16-bit operand pairs of v
   return kWorkspaceHeader + 3 * partial_bytes(n_tokens, r) + operand_bytes(n_tokens, r);
+}
+
+size_t sgmv_workspace_bytes_multi(int32_t n_tokens, int32_t r, int32_t n_proj) {
+  const size_t single = sgmv_workspace_bytes(n_tokens, r);
+  if (single == 0 || n_proj < 2) return single;
+  const int shared = n_proj < kSharedShrinkMost ? n_proj : kSharedShrinkMost;
+  return single + (size_t)(shared - 1) * partial_bytes(n_tokens, r);
 }
 
 int sgmv_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
@@ -917,6 +925,42 @@ int sgmv_add_lora_multi(const sgmv_problem* p, int32_t n_proj, void* const* ys,
     const hipError_t err = kernel == SGMV_KERNEL_MULTI_SIDE ? launch_add_lora_fused(f, st)
                                                             : launch_add_lora_fused_multi(f, st);
     return err == hipSuccess ? SGMV_OK : SGMV_ERR_LAUNCH;
+  }
+  // Long segments on the MFMA kernels, all add-ons reading the same x (q / k / v or gate / up of a
+  // prefill batch): their shrinks share one pass over x, which is most of a shrink's bytes; then
+  // every add-on's operand preparation and expand in turn.  Needs the larger workspace of
+  // sgmv_workspace_bytes_multi for the partial sums of the second and third add-on.
+  {
+    bool same_x = n_proj >= 2 && n_proj <= kSharedShrinkMost;
+    for (int i = 1; i < n_proj && same_x; ++i) same_x = xs[i] == xs[0];
+    SinglePlan pl;
+    if (same_x && plan_single(p, n_segs, &pl) == SGMV_OK && pl.kernel == SGMV_KERNEL_MATRIX) {
+      const Scratch sc = caller_scratch(p);
+      ShrinkArgs sa = make_shrink(p, sc, xs[0], A_ptrs[0], seg_starts, n_segs, layer_idx);
+      sa.ksplit = pl.ksplit;
+      sa.kslice = pl.kslice;
+      if (shrink_shared_fits(sa, n_proj) &&
+          p->workspace_bytes >= sgmv_workspace_bytes_multi(p->n_tokens, p->r, n_proj)) {
+        // the first add-on's partial sums where a single call keeps them, the others' behind the
+        // single-call workspace (the exchange words in between are left alone: the single-launch
+        // kernels rely on what their tags say)
+        const size_t parts = partial_bytes(p->n_tokens, p->r);
+        char* const extra = static_cast<char*>(p->workspace) + sgmv_workspace_bytes(p->n_tokens, p->r);
+        sa.n_shared = n_proj;
+        for (int i = 0; i < n_proj; ++i) {
+          sa.A_shared[i] = A_ptrs[i];
+          sa.partials_shared[i] = i == 0 ? sc.partials : reinterpret_cast<float*>(extra + (size_t)(i - 1) * parts);
+        }
+        if (launch_shrink_matrix_shared(sa, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+        for (int i = 0; i < n_proj; ++i) {
+          ExpandArgs e = make_expand(p, ys[i], sa.partials_shared[i], sa.ksplit, A_ptrs[i], B_ptrs[i], seg_starts,
+                                     n_segs, layer_idx, scale);
+          set_operands(&e, sc, p->n_tokens, p->r);
+          if (launch_expand_matrix(e, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+        }
+        return SGMV_OK;
+      }
+    }
   }
   // any other shape: one add-on after the other
   for (int i = 0; i < n_proj; ++i) {

@@ -24,6 +24,9 @@ constexpr size_t kWorkspaceHeader = kWorkspaceErrorOffset + 256;
 // Upper bound of the split-K factor.
 constexpr int kMaxKSplit = 64;
 
+// Most add-ons whose MFMA shrinks share one pass over a common x.
+constexpr int kSharedShrinkMost = 3;
+
 struct ShrinkArgs {
   bool bf16;
   int r, h_in, n_tokens, n_segs;
@@ -35,6 +38,11 @@ struct ShrinkArgs {
   const int32_t* seg_starts;
   float* partials;           // [ksplit][n_tokens][r]
   unsigned long long* header;// workspace header or nullptr (only trace builds look at it)
+  // launch_shrink_matrix_shared only: n_shared add-ons on the same x, each with its pointer array
+  // and its own partial sums
+  int n_shared;
+  const void* const* A_shared[kSharedShrinkMost];
+  float* partials_shared[kSharedShrinkMost];
 };
 
 struct ExpandArgs {
@@ -155,6 +163,10 @@ hipError_t launch_shrink_vector(const ShrinkArgs& a, hipStream_t st);
 hipError_t launch_shrink_reduce(float* v, const ShrinkArgs& a, hipStream_t st);
 hipError_t launch_expand_vector(const ExpandArgs& a, hipStream_t st);
 hipError_t launch_shrink_matrix(const ShrinkArgs& a, hipStream_t st);
+// True when n_shared add-ons' slices of A_i fit in LDS side by side (launch_shrink_matrix_shared applies).
+bool shrink_shared_fits(const ShrinkArgs& a, int n_shared);
+// The MFMA shrink of a.n_shared add-ons on the same x in one pass (A_shared, partials_shared).
+hipError_t launch_shrink_matrix_shared(const ShrinkArgs& a, hipStream_t st);
 hipError_t launch_expand_matrix(const ExpandArgs& a, hipStream_t st);
 
 }  // namespace sgmv

@@ -254,10 +254,12 @@ __device__ __forceinline__ void finalize_quad(const float* __restrict__ first_pa
   }
 }
 
-template <class DT, int R>
-__global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
-    const uint16_t* __restrict__ x, const uint16_t* const* __restrict__ A_ptrs,
-    const int32_t* __restrict__ seg_starts, float* __restrict__ partials, int h_in, int kslice,
+// P add-ons that read the same x share one pass over it: P slices of A_i side by side in LDS, P
+// sets of partial sums (P = 1: the plain shrink).
+template <class DT, int R, int P>
+__device__ __forceinline__ void shrink_stream_body(
+    const uint16_t* __restrict__ x, const uint16_t* const* const (&A_ptrs)[P],
+    const int32_t* __restrict__ seg_starts, float* const (&partials)[P], int h_in, int kslice,
     int n_tokens, long long layer_off, unsigned long long* header) {
   constexpr int NW = stream_waves(R);
   constexpr int NT = 64 * NW;
@@ -276,8 +278,14 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
   SGMV_TRACE_POINT(0);
   const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
   if ((int)blockIdx.y * ROWS >= hi - lo) return;
-  const uint16_t* A = A_ptrs[seg];
-  if (A == nullptr) return;
+  const uint16_t* A[P];
+  bool any = false;
+#pragma unroll
+  for (int p = 0; p < P; ++p) {
+    A[p] = A_ptrs[p][seg];
+    any = any || A[p] != nullptr;
+  }
+  if (!any) return;
   const int k0 = s * kslice;
   const int klen = min(h_in, k0 + kslice) - k0;
   if (klen <= 0) return;
@@ -315,10 +323,14 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
   // ---- stage the slice of A_i, transposed; the first two banks of x follow the first
   // batch of its loads, so they are in flight while the slice is placed
   uint4 q0[XB], q1[XB];
-  {
-    const __amdgpu_buffer_rsrc_t rA =
-        make_buffer(A + layer_off + (long long)k0 * R, (uint32_t)klen * R * 2u);
-    const int kpad = stream_kpad(kslice);
+  const int kpad = stream_kpad(kslice);
+  const int slice_words = (kpad >> 3) * BLK * 4;  // LDS dwords of one add-on's slice
+#pragma unroll
+  for (int p = 0; p < P; ++p) {
+    // an add-on without an adapter for this segment: an empty buffer, its slice reads as zeros
+    const __amdgpu_buffer_rsrc_t rA = make_buffer(
+        A[p] != nullptr ? A[p] + layer_off + (long long)k0 * R : x, A[p] != nullptr ? (uint32_t)klen * R * 2u : 0u);
+    uint32_t* const atp = at + p * slice_words;
     const int items = (kpad >> 1) * CG;  // (pair of k, eight columns); rows past klen read as zeros
     uint4 a0[AB], a1[AB];
     for (int base = 0; base < items; base += NT * AB) {
@@ -330,7 +342,7 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
         a0[u] = buffer_load128(rA, o);
         a1[u] = buffer_load128(rA, item < items ? o + (uint32_t)R * 2u : kOutOfRange);
       }
-      if (base == 0) {
+      if (p == 0 && base == 0) {
         load_bank(q0, 0, 0);  // banks past the wave's tiles load nothing
         load_bank(q1, nb > 1 ? 0 : 1, nb > 1 ? 1 : 0);
       }
@@ -341,7 +353,7 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
           const int cg = item % CG, kp = item / CG;
           const uint32_t w0[4] = {a0[u].x, a0[u].y, a0[u].z, a0[u].w};
           const uint32_t w1[4] = {a1[u].x, a1[u].y, a1[u].z, a1[u].w};
-          uint32_t* blk = &at[(kp >> 2) * BLK * 4 + (kp & 3)];  // k block, dword of the k pair
+          uint32_t* blk = &atp[(kp >> 2) * BLK * 4 + (kp & 3)];  // k block, dword of the k pair
 #pragma unroll
           for (int i = 0; i < 4; ++i) {  // columns 8 cg + 2 i and + 2 i + 1, column n in slot n
             blk[(8 * cg + 2 * i) * 4] = (w0[i] & 0xFFFFu) | (w1[i] << 16);
@@ -353,7 +365,7 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
     if (R < RPAD) {  // slots no column of A_i fills
       for (int i = tid; i < (kpad >> 3) * (RPAD - R) * 4; i += NT) {
         const int blk = i / ((RPAD - R) * 4), w = i % ((RPAD - R) * 4);
-        at[(blk * BLK + R) * 4 + w] = 0u;
+        atp[(blk * BLK + R) * 4 + w] = 0u;
       }
     }
   }
@@ -365,24 +377,28 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
   SGMV_TRACE_POINT(2);
 
   // ---- stream
-  f32x4 acc[NTILE];
+  f32x4 acc[P][NTILE];
   int cj = 0, cb = 0;                            // bank being consumed: tile, bank of the tile
   int lj = nb > 2 ? 0 : (nb == 2 ? 1 : 2);       // next bank to load
   int lb = nb > 2 ? 2 : 0;
   auto consume = [&](const uint4 (&q)[XB]) {
     if (cb == 0) {
 #pragma unroll
-      for (int t = 0; t < NTILE; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int p = 0; p < P; ++p)
+#pragma unroll
+        for (int t = 0; t < NTILE; ++t) acc[p][t] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 #pragma unroll
     for (int i = 0; i < XB; ++i) {
       const int step = cb * XB + i;  // steps past the slice multiply zeros
 #pragma unroll
-      for (int t = 0; t < NTILE; ++t) {
-        // A_i^T first: D[column 16 t + 4 g + i][token m], four consecutive columns of a row per lane
-        const uint4 bt = *reinterpret_cast<const uint4*>(&at[((step * 4 + g) * BLK + t * 16 + m) * 4]);
-        acc[t] = mfma16x16x32<DT>(bt, q[i], acc[t]);
-      }
+      for (int p = 0; p < P; ++p)
+#pragma unroll
+        for (int t = 0; t < NTILE; ++t) {
+          // A_i^T first: D[column 16 t + 4 g + i][token m], four consecutive columns of a row per lane
+          const uint4 bt = *reinterpret_cast<const uint4*>(&at[p * slice_words + ((step * 4 + g) * BLK + t * 16 + m) * 4]);
+          acc[p][t] = mfma16x16x32<DT>(bt, q[i], acc[p][t]);
+        }
     }
     if (cb == nb - 1 && cj < my_tiles) {
       // lane (m, g): row m of the tile, columns 16 t + 4 g .. + 3 of every column tile: the
@@ -390,13 +406,15 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
       // contiguous, at rank 16)
       const int row0 = lo + ((int)blockIdx.y + cj * (int)gridDim.y) * ROWS + wave * 16;
 #pragma unroll
-      for (int t = 0; t < NTILE; ++t) {
-        const int n = t * 16 + 4 * g;
-        if (n < R && row0 + m < hi) {
-          float* dst = &partials[((long long)s * n_tokens + row0 + m) * R + n];
-          *reinterpret_cast<float4*>(dst) = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
+      for (int p = 0; p < P; ++p)
+#pragma unroll
+        for (int t = 0; t < NTILE; ++t) {
+          const int n = t * 16 + 4 * g;
+          if (n < R && row0 + m < hi) {
+            float* dst = &partials[p][((long long)s * n_tokens + row0 + m) * R + n];
+            *reinterpret_cast<float4*>(dst) = make_float4(acc[p][t][0], acc[p][t][1], acc[p][t][2], acc[p][t][3]);
+          }
         }
-      }
     }
     if (++cb == nb) {
       cb = 0;
@@ -427,6 +445,38 @@ __global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
     SGMV_TRACE_FLUSH(tid == 0, 8, 8);
   }
 #endif
+}
+
+template <class DT, int R>
+__global__ __launch_bounds__(64 * stream_waves(R), 4) void shrink_stream_kernel(
+    const uint16_t* __restrict__ x, const uint16_t* const* __restrict__ A_ptrs,
+    const int32_t* __restrict__ seg_starts, float* __restrict__ partials, int h_in, int kslice,
+    int n_tokens, long long layer_off, unsigned long long* header) {
+  const uint16_t* const* const a[1] = {A_ptrs};
+  float* const part[1] = {partials};
+  shrink_stream_body<DT, R, 1>(x, a, seg_starts, part, h_in, kslice, n_tokens, layer_off, header);
+}
+
+// The shrink of up to three add-ons on the same x in one pass (q / k / v, gate / up of a prefill
+// batch): x, more than nine tenths of the shrink's bytes, is read once instead of once per add-on.
+struct ShrinkShared {
+  const uint16_t* const* A_ptrs[kSharedShrinkMost];
+  float* partials[kSharedShrinkMost];
+};
+template <class DT, int R, int P>
+__global__ __launch_bounds__(64 * stream_waves(R), 2) void shrink_stream_shared_kernel(
+    const uint16_t* __restrict__ x, const int32_t* __restrict__ seg_starts, int h_in, int kslice,
+    int n_tokens, long long layer_off, ShrinkShared tab) {
+  const uint16_t* const* a[P];
+  float* part[P];
+#pragma unroll
+  for (int p = 0; p < P; ++p) {
+    a[p] = tab.A_ptrs[p];
+    part[p] = tab.partials[p];
+  }
+  const uint16_t* const* const (&ar)[P] = reinterpret_cast<const uint16_t* const* const (&)[P]>(a);
+  float* const (&pr)[P] = reinterpret_cast<float* const (&)[P]>(part);
+  shrink_stream_body<DT, R, P>(x, ar, seg_starts, pr, h_in, kslice, n_tokens, layer_off, nullptr);
 }
 
 // ---------------------------------------------------------------- expand
@@ -873,6 +923,53 @@ constexpr size_t kStreamMaxLds = 68 * 1024;
 
 bool shrink_stream_fits(const ShrinkArgs& a) {
   return a.kslice % 32 == 0 && shrink_stream_lds_bytes(a.r, a.kslice) <= kStreamMaxLds;
+}
+
+bool shrink_shared_fits(const ShrinkArgs& a, int n_shared) {
+  return n_shared >= 2 && n_shared <= kSharedShrinkMost && a.r <= 32 && shrink_stream_fits(a) &&
+         n_shared * shrink_stream_lds_bytes(a.r, a.kslice) <= kStreamMaxLds;
+}
+
+template <class DT, int R, int P>
+static hipError_t launch_shrink_shared_t(const ShrinkArgs& a, hipStream_t st) {
+  dim3 grid((unsigned)a.ksplit, row_blocks(a.max_seg_len, a.n_tokens, 16 * stream_waves(R)), (unsigned)a.n_segs);
+  auto kernel = shrink_stream_shared_kernel<DT, R, P>;
+  static std::atomic<bool> enabled[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (!enabled[dev].load(std::memory_order_acquire)) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStreamMaxLds);
+    if (e != hipSuccess) return e;
+    enabled[dev].store(true, std::memory_order_release);
+  }
+  ShrinkShared tab;
+  for (int i = 0; i < kSharedShrinkMost; ++i) {
+    tab.A_ptrs[i] = i < P ? (const uint16_t* const*)a.A_shared[i] : nullptr;
+    tab.partials[i] = i < P ? a.partials_shared[i] : nullptr;
+  }
+  hipLaunchKernelGGL(kernel, grid, dim3(64 * stream_waves(R)), P * shrink_stream_lds_bytes(R, a.kslice), st,
+                     (const uint16_t*)a.x, a.seg_starts, a.h_in, a.kslice, a.n_tokens, a.layer_off, tab);
+  return hipGetLastError();
+}
+
+template <class DT, int R>
+static hipError_t launch_shrink_shared_p(const ShrinkArgs& a, hipStream_t st) {
+  switch (a.n_shared) {
+    case 2: return launch_shrink_shared_t<DT, R, 2>(a, st);
+    case 3: return launch_shrink_shared_t<DT, R, 3>(a, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_shrink_matrix_shared(const ShrinkArgs& a, hipStream_t st) {
+  if (a.n_segs > 65535 || !shrink_shared_fits(a, a.n_shared)) return hipErrorInvalidValue;
+  switch (a.r) {  // rank 64: eight waves per workgroup and slices of 66 KB, left to one add-on at a time
+    case 8: return a.bf16 ? launch_shrink_shared_p<BF16, 8>(a, st) : launch_shrink_shared_p<F16, 8>(a, st);
+    case 16: return a.bf16 ? launch_shrink_shared_p<BF16, 16>(a, st) : launch_shrink_shared_p<F16, 16>(a, st);
+    case 32: return a.bf16 ? launch_shrink_shared_p<BF16, 32>(a, st) : launch_shrink_shared_p<F16, 32>(a, st);
+  }
+  return hipErrorInvalidValue;
 }
 
 template <class DT, int R>

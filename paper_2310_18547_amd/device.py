@@ -55,7 +55,7 @@ class DeviceWorkload:
     def __init__(self, w, device="cuda:0", n_sets: int = 1, max_seg_len_hint: bool = True,
                  path: int = B.PATH_AUTO, ksplit: int = 0, expand_threads: int = 0,
                  init_workspace: bool = True, max_seg_len: Optional[int] = None,
-                 spin_limit: int = 0):
+                 spin_limit: int = 0, n_proj: int = 1):
         self.w = w
         self.device = torch.device(device)
         self.A: List[torch.Tensor] = _pool_to_dev(list(w.A), self.device)
@@ -68,7 +68,8 @@ class DeviceWorkload:
         self.x = [_to_dev(w.x, self.device) for _ in range(n_sets)]
         self.y0 = _to_dev(w.y0, self.device)
         self.y = [self.y0.clone() for _ in range(n_sets)]
-        self.ws_bytes = max(B.sgmv_workspace_bytes(w.n_tokens, w.r), 256)
+        # n_proj > 1: room for multi-projection calls that share the shrink's pass over x
+        self.ws_bytes = max(B.sgmv_workspace_bytes_multi(w.n_tokens, w.r, n_proj), 256)
         # deliberately not zero-filled by torch: sgmv_workspace_init does that
         self.workspace = torch.full((self.ws_bytes,), 0xA5, dtype=torch.uint8, device=self.device)
         if init_workspace:

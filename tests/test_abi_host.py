@@ -262,6 +262,14 @@ def test_plan_single_launch_shapes():
     assert rc == 0 and pl.kernel == sg.KERNEL_NONE and pl.launches == 0
 
 
+def test_workspace_bytes_multi():
+    one = sg.sgmv_workspace_bytes(3450, 16)
+    assert sg.sgmv_workspace_bytes_multi(3450, 16, 1) == one
+    two, three, four = (sg.sgmv_workspace_bytes_multi(3450, 16, n) for n in (2, 3, 4))
+    assert one < two < three == four and (two - one) == (three - two) and two % 256 == 0
+    assert sg.sgmv_workspace_bytes_multi(0, 16, 3) == 0
+
+
 def test_plan_shrink():
     """Stand-alone shrink: one launch with the hand-off for one-row segments, else two launches."""
     p = sg.make_problem(sg.F16, 4096, 4096, 16, 1, 64, workspace=FAKE, workspace_bytes=1 << 30, max_seg_len=1,

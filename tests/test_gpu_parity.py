@@ -71,6 +71,37 @@ def test_shrink_accumulates_into_v():
     assert np.all(np.abs(v.cpu().numpy() - ref) <= 2e-3 + 2e-2 * np.abs(ref))
 
 
+# several add-ons on long segments that read the same x: one shrink pass over x for all of them
+@pytest.mark.parametrize("dtype,r,P", [("bf16", 16, 3), ("f16", 16, 2), ("bf16", 8, 3), ("f16", 32, 2), ("bf16", 32, 3),
+                                       ("bf16", 64, 2)])
+def test_multi_on_long_segments_shares_the_pass_over_x(dtype, r, P):
+    from paper_2310_18547_amd import binding as B
+    lens = [150, 0, 70, 333, 17]
+    ws = [wl.custom(lens, 1024, 520, r, dtype, seed=400 + r + k, num_layers=2,
+                    seg_adapter=[0, 1, -1 if k == 1 else 2, 3, 4]) for k in range(P)]
+    ds = [_dev(w, n_proj=P) for w in ws]
+    d0 = ds[0]
+    assert d0.ws_bytes == B.sgmv_workspace_bytes_multi(ws[0].n_tokens, r, P) >= B.sgmv_workspace_bytes(ws[0].n_tokens, r)
+    x = d0.x[0]                                   # every add-on reads the first one's x
+    B.sgmv_add_lora_multi(d0.problem, [q.y[0] for q in ds], [x] * P, [q.A_ptrs for q in ds],
+                          [q.B_ptrs for q in ds], d0.seg_starts, ws[0].n_segs, 1, ws[0].scale)
+    torch.cuda.synchronize()
+    for k, (w, q) in enumerate(zip(ws, ds)):
+        w_ref = wl.custom(lens, 1024, 520, r, dtype, seed=400 + r + k, num_layers=2,
+                          seg_adapter=[0, 1, -1 if k == 1 else 2, 3, 4])
+        w_ref.x[...] = ws[0].x
+        assert_parity(q.y_bits(), oracle.run_workload(w_ref, layer_idx=1, n_threads=8), dtype,
+                      f"shared shrink, add-on {k} of {P}, r={r}")
+    # the same call on a workspace of the plain size runs the add-ons one after the other: same results
+    # up to the order of the fp32 sums (here the same kernels, so bit for bit)
+    ds2 = [_dev(w) for w in ws]
+    B.sgmv_add_lora_multi(ds2[0].problem, [q.y[0] for q in ds2], [ds2[0].x[0]] * P, [q.A_ptrs for q in ds2],
+                          [q.B_ptrs for q in ds2], ds2[0].seg_starts, ws[0].n_segs, 1, ws[0].scale)
+    torch.cuda.synchronize()
+    for q, q2 in zip(ds, ds2):
+        assert np.array_equal(q.y_bits(), q2.y_bits())
+
+
 # stand-alone shrink of one-row segments: one launch, partial sums handed over inside it
 @pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("batch,h_in,r", [(1, 4096, 16), (7, 1000, 8), (33, 4096, 64), (64, 5120, 32), (64, 4096, 16),
