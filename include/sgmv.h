@@ -282,8 +282,12 @@ int sgmv_add_lora_static(const sgmv_problem* p, void* y, const void* x,
  *   A_ptrs, B_ptrs  HOST arrays of n_proj device pointers, each to a device
  *                   array of n_segs weight pointers as in sgmv_add_lora
  * With workspace_ready set and max_seg_len == 1 (every request its own
- * adapter) all add-ons run in ONE kernel launch; otherwise the call is the
- * same as n_proj calls of sgmv_add_lora in order.  The result of every add-on
+ * adapter) all add-ons run in ONE kernel launch.  On long segments (the MFMA
+ * kernels) two or three add-ons whose x_i are the same buffer share the shrink's
+ * pass over x when the workspace has the size of sgmv_workspace_bytes_multi
+ * (ranks up to 32).  Otherwise the call is the same as n_proj calls of
+ * sgmv_add_lora in order (sgmv_plan_add_lora reports this case: it does not
+ * know whether the x_i coincide).  The result of every add-on
  * equals that of a separate sgmv_add_lora call up to the order in which the
  * fp32 sums are taken (the single-launch kernels split the same sums over
  * lanes differently). */
