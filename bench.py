@@ -614,7 +614,7 @@ def main():
 
     w = make_workload(args.workload, args.seed, args.layers)
     d = DeviceWorkload(w, "cuda:0", n_sets=args.sets, path=args.path, ksplit=args.ksplit,
-                       expand_threads=args.expand_threads)
+                       expand_threads=args.expand_threads, n_proj=args.projections)
     if args.calibrate_copy:
         src = torch.ones(64 << 20, dtype=torch.uint8, device="cuda:0")
         dst = torch.empty_like(src)
