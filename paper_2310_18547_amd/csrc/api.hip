@@ -464,6 +464,7 @@ ExpandArgs make_expand(const sgmv_problem* p, void* y, const float* v_parts, int
   a.scale = scale;
   a.vh = a.vl = nullptr;
   a.undo = nullptr;
+  a.operands_ready = false;
   a.header = nullptr;
   return a;
 }
@@ -610,7 +611,7 @@ size_t sgmv_workspace_bytes_multi(int32_t n_tokens, int32_t r, int32_t n_proj) {
   const size_t single = sgmv_workspace_bytes(n_tokens, r);
   if (single == 0 || n_proj < 2) return single;
   const int shared = n_proj < kSharedShrinkMost ? n_proj : kSharedShrinkMost;
-  return single + (size_t)(shared - 1) * partial_bytes(n_tokens, r);
+  return single + (size_t)(shared - 1) * (partial_bytes(n_tokens, r) + operand_bytes(n_tokens, r));
 }
 
 int sgmv_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
@@ -952,12 +953,21 @@ int sgmv_add_lora_multi(const sgmv_problem* p, int32_t n_proj, void* const* ys,
           sa.partials_shared[i] = i == 0 ? sc.partials : reinterpret_cast<float*>(extra + (size_t)(i - 1) * parts);
         }
         if (launch_shrink_matrix_shared(sa, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+        // operand pairs of all add-ons in one launch (the first add-on's where a single call keeps
+        // them, the others' behind the extra partial sums), then the expands
+        ExpandArgs es[kSharedShrinkMost];
+        const size_t ops = operand_bytes(p->n_tokens, p->r);
         for (int i = 0; i < n_proj; ++i) {
-          ExpandArgs e = make_expand(p, ys[i], sa.partials_shared[i], sa.ksplit, A_ptrs[i], B_ptrs[i], seg_starts,
-                                     n_segs, layer_idx, scale);
-          set_operands(&e, sc, p->n_tokens, p->r);
-          if (launch_expand_matrix(e, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+          es[i] = make_expand(p, ys[i], sa.partials_shared[i], sa.ksplit, A_ptrs[i], B_ptrs[i], seg_starts, n_segs,
+                              layer_idx, scale);
+          Scratch own = sc;
+          if (i > 0) own.operands = extra + (size_t)(n_proj - 1) * parts + (size_t)(i - 1) * ops;
+          set_operands(&es[i], own, p->n_tokens, p->r);
+          es[i].operands_ready = true;
         }
+        if (launch_finalize_shared(es, n_proj, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+        for (int i = 0; i < n_proj; ++i)
+          if (launch_expand_matrix(es[i], st) != hipSuccess) return SGMV_ERR_LAUNCH;
         return SGMV_OK;
       }
     }

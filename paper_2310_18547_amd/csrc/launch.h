@@ -62,6 +62,7 @@ struct ExpandArgs {
   uint16_t* vh;
   uint16_t* vl;
   float* undo;
+  bool operands_ready;       // vh / vl / undo are already written (launch_finalize_shared)
   unsigned long long* header;// workspace header or nullptr (only trace builds look at it)
 };
 
@@ -167,6 +168,8 @@ hipError_t launch_shrink_matrix(const ShrinkArgs& a, hipStream_t st);
 bool shrink_shared_fits(const ShrinkArgs& a, int n_shared);
 // The MFMA shrink of a.n_shared add-ons on the same x in one pass (A_shared, partials_shared).
 hipError_t launch_shrink_matrix_shared(const ShrinkArgs& a, hipStream_t st);
+// v -> operand pairs of the n add-ons of a shared shrink in one launch (each es[i] with its own vh / vl / undo).
+hipError_t launch_finalize_shared(const ExpandArgs* es, int n, hipStream_t st);
 hipError_t launch_expand_matrix(const ExpandArgs& a, hipStream_t st);
 
 }  // namespace sgmv

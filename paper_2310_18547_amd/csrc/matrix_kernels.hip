@@ -499,6 +499,26 @@ __global__ __launch_bounds__(256) void finalize_v_kernel(
                        undo + it / GPR, it % GPR == 0);
 }
 
+// The same for the add-ons of a shared shrink in one launch: blockIdx.y is the add-on.
+struct FinalizeShared {
+  const float* v_parts[kSharedShrinkMost];
+  uint16_t* vh[kSharedShrinkMost];
+  uint16_t* vl[kSharedShrinkMost];
+  float* undo[kSharedShrinkMost];
+};
+template <class DT, int R>
+__global__ __launch_bounds__(256) void finalize_v_shared_kernel(FinalizeShared tab, int nparts, int n_tokens) {
+  constexpr int GPR = R / 4;  // threads per row
+  const int z = blockIdx.y;
+  const long long item = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long total = (long long)n_tokens * GPR;
+  const bool live = item < total;
+  const long long it = live ? item : total - 1;
+  const long long e0 = it * 4;  // first element (row * R + k)
+  finalize_quad<DT, R>(tab.v_parts[z] + e0, nparts, (long long)n_tokens * R, live, tab.vh[z] + e0, tab.vl[z] + e0,
+                       tab.undo[z] + it / GPR, it % GPR == 0);
+}
+
 // grid = (column strips, row blocks of rows_per_wg rows, n_segs); the row-block dimension
 // is walked with a stride.  vh / vl / undo come from finalize_v_kernel.
 //
@@ -1021,12 +1041,14 @@ template <class DT, int R>
 static hipError_t launch_expand_matrix_t(const ExpandArgs& a, hipStream_t st) {
   dim3 grid((unsigned)((a.h_out + kExpandCols - 1) / kExpandCols),
             row_blocks(a.max_seg_len, a.n_tokens, kExpandRows), (unsigned)a.n_segs);
-  // v -> 16-bit operand pairs, then the expand proper
-  const long long items = (long long)a.n_tokens * (R / 4);
-  hipLaunchKernelGGL((finalize_v_kernel<DT, R>), dim3((unsigned)((items + 255) / 256)), dim3(256), 0,
-                     st, a.v_parts, a.nparts, a.vh, a.vl, a.undo, a.n_tokens);
-  const hipError_t err = hipGetLastError();
-  if (err != hipSuccess) return err;
+  // v -> 16-bit operand pairs (unless a shared launch has prepared them), then the expand proper
+  if (!a.operands_ready) {
+    const long long items = (long long)a.n_tokens * (R / 4);
+    hipLaunchKernelGGL((finalize_v_kernel<DT, R>), dim3((unsigned)((items + 255) / 256)), dim3(256), 0,
+                       st, a.v_parts, a.nparts, a.vh, a.vl, a.undo, a.n_tokens);
+    const hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+  }
   // measured: with long segments the row-wise kernel is ahead at rank 64 (8-15 %) and for binary16
   // at every rank (2-3 %; the range factors cost the other one its fourth workgroup per compute
   // unit).  With segments shorter than a block only the first of its waves would have rows, and
@@ -1044,6 +1066,36 @@ static hipError_t launch_expand_matrix_t(const ExpandArgs& a, hipStream_t st) {
                        (const uint16_t* const*)a.B_ptrs, a.seg_starts, a.h_out, a.n_tokens,
                        a.layer_off, a.scale, kExpandRows, a.header);
   return hipGetLastError();
+}
+
+template <class DT, int R>
+static hipError_t launch_finalize_shared_t(const ExpandArgs* es, int n, hipStream_t st) {
+  FinalizeShared tab;
+  for (int i = 0; i < kSharedShrinkMost; ++i) {
+    const ExpandArgs& e = es[i < n ? i : 0];
+    tab.v_parts[i] = e.v_parts;
+    tab.vh[i] = e.vh;
+    tab.vl[i] = e.vl;
+    tab.undo[i] = e.undo;
+  }
+  const long long items = (long long)es[0].n_tokens * (R / 4);
+  hipLaunchKernelGGL((finalize_v_shared_kernel<DT, R>), dim3((unsigned)((items + 255) / 256), (unsigned)n), dim3(256), 0,
+                     st, tab, es[0].nparts, es[0].n_tokens);
+  return hipGetLastError();
+}
+
+// v -> operand pairs for the n add-ons of a shared shrink (their ExpandArgs with vh / vl / undo of
+// their own) in one launch; their expands then run with operands_ready set.
+hipError_t launch_finalize_shared(const ExpandArgs* es, int n, hipStream_t st) {
+  if (n < 1 || n > kSharedShrinkMost) return hipErrorInvalidValue;
+  const bool bf = es[0].bf16;
+  switch (es[0].r) {
+    case 8: return bf ? launch_finalize_shared_t<BF16, 8>(es, n, st) : launch_finalize_shared_t<F16, 8>(es, n, st);
+    case 16: return bf ? launch_finalize_shared_t<BF16, 16>(es, n, st) : launch_finalize_shared_t<F16, 16>(es, n, st);
+    case 32: return bf ? launch_finalize_shared_t<BF16, 32>(es, n, st) : launch_finalize_shared_t<F16, 32>(es, n, st);
+    case 64: return bf ? launch_finalize_shared_t<BF16, 64>(es, n, st) : launch_finalize_shared_t<F16, 64>(es, n, st);
+  }
+  return hipErrorInvalidValue;
 }
 
 template <class DT>
