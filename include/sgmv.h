@@ -282,7 +282,9 @@ int sgmv_add_lora_static(const sgmv_problem* p, void* y, const void* x,
  *   A_ptrs, B_ptrs  HOST arrays of n_proj device pointers, each to a device
  *                   array of n_segs weight pointers as in sgmv_add_lora
  * With workspace_ready set and max_seg_len == 1 (every request its own
- * adapter) all add-ons run in ONE kernel launch.  On long segments (the MFMA
+ * adapter) all add-ons run in ONE kernel launch; so do segments of a few rows
+ * (max_seg_len from 2 up to what the single-launch MFMA kernel takes) while the
+ * workgroups of all add-ons fit on the chip together.  On long segments (the MFMA
  * kernels) two or three add-ons whose x_i are the same buffer share the shrink's
  * pass over x when the workspace has the size of sgmv_workspace_bytes_multi
  * (ranks up to 32).  Otherwise the call is the same as n_proj calls of

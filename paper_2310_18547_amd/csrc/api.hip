@@ -344,7 +344,11 @@ bool choose_whole(const sgmv_problem* p, int n_segs, WholeArgs* w) {
 }
 
 // Launch shape of the single-launch MFMA kernel; false when it does not apply.
-bool choose_tile(const sgmv_problem* p, int n_segs, TileArgs* t) {
+// n_proj > 1: that many add-ons of this shape side by side in one launch (each segment's row blocks
+// and slices once per add-on, all resident together).
+bool choose_tile(const sgmv_problem* p, int n_segs_one, TileArgs* t, int n_proj = 1) {
+  const int n_segs = n_segs_one * n_proj;
+  const long long n_rows = (long long)p->n_tokens * n_proj;
   if (!p->workspace_ready) return false;
   const Limits lim = limits();
   if (p->max_seg_len <= 0 || p->max_seg_len > kTileMaxSegLen) return false;
@@ -362,7 +366,7 @@ bool choose_tile(const sgmv_problem* p, int n_segs, TileArgs* t) {
   // (the others leave at once): at most n_segs + n_tokens / 16 of them.  These, times the
   // slices, must all be resident together (one workgroup per unit).
   long long blocks = (long long)n_segs * z;
-  long long live = blocks < (long long)n_segs + p->n_tokens / 16 ? blocks : (long long)n_segs + p->n_tokens / 16;
+  long long live = blocks < (long long)n_segs + n_rows / 16 ? blocks : (long long)n_segs + n_rows / 16;
   if (live > lim.fused_workgroups) {  // too many even with one slice: fewer row blocks, walked with a stride
     z = lim.fused_workgroups / n_segs > 0 ? lim.fused_workgroups / n_segs : 1;
     blocks = live = (long long)n_segs * z;
@@ -374,19 +378,21 @@ bool choose_tile(const sgmv_problem* p, int n_segs, TileArgs* t) {
   if (p->ksplit == 0 && s > kFusedSlices) s = kFusedSlices;
   if (p->ksplit == 0 && s > lim.tile_max_grid / blocks) s = (int)(lim.tile_max_grid / blocks);  // workgroups launched in all
   if (s > narrow / 64) s = narrow / 64;  // no slice thinner than 64
-  if (s > cap) s = cap;
+  if (s > cap / n_proj) s = cap / n_proj;  // every add-on its own exchange words
   if (s < 1) s = 1;
+  if (s * n_proj > cap) return false;
   if (s * live > lim.fused_workgroups || s * blocks > lim.tile_max_grid) return false;
   for (;; ++s) {  // more slices make the LDS-resident weight slices smaller
     t->kslice = ceil_div(ceil_div(p->h_in, s), 32) * 32;
     t->cslice = ceil_div(ceil_div(p->h_out, s), 64) * 64;
     t->lds_bytes = tile_lds_bytes(p->r, t->kslice, t->cslice);
     if (t->lds_bytes <= kTileMaxLds) break;
-    if (p->ksplit > 0 || s + 1 > cap || (s + 1) * live > lim.fused_workgroups || (s + 1) * blocks > lim.tile_max_grid)
+    if (p->ksplit > 0 || (s + 1) * n_proj > cap || (s + 1) * live > lim.fused_workgroups || (s + 1) * blocks > lim.tile_max_grid)
       return false;
   }
   t->S = s;
   t->Z = z;
+  t->n_proj = n_proj;
   return true;
 }
 
@@ -410,6 +416,27 @@ void fill_fused(FusedArgs* f, const sgmv_problem* p, const Scratch& sc, const in
   f->y = nullptr;
   f->x = nullptr;
   f->A_ptrs = f->B_ptrs = nullptr;
+}
+
+// Everything of a tile launch but its shape (choose_tile) and the add-on's own pointers.
+void fill_tile(TileArgs* t, const sgmv_problem* p, const Scratch& sc, const int32_t* seg_starts, int n_segs,
+               int layer_idx, float scale) {
+  t->bf16 = p->dtype == SGMV_BF16;
+  t->r = p->r;
+  t->h_in = p->h_in;
+  t->h_out = p->h_out;
+  t->n_tokens = p->n_tokens;
+  t->n_segs = n_segs;
+  t->spin_limit = spin_limit_of(p);
+  t->offA = (long long)layer_idx * p->h_in * p->r;
+  t->offB = (long long)layer_idx * p->r * p->h_out;
+  t->y = nullptr;
+  t->x = nullptr;
+  t->A_ptrs = t->B_ptrs = nullptr;
+  t->seg_starts = seg_starts;
+  t->exch = sc.exch;
+  t->header = sc.header;
+  t->scale = scale;
 }
 
 int choose_expand_threads(const sgmv_problem* p, int n_segs) {
@@ -560,8 +587,13 @@ int plan_shrink(const sgmv_problem* p, int n_segs, ShrinkPlan* pl) {
 
 // Multi-projection call: SGMV_KERNEL_MULTI_SIDE / _PIPELINED with the launch shape in *f, or
 // SGMV_KERNEL_SEQUENCE (one sgmv_add_lora after the other).
-int plan_multi(const sgmv_problem* p, int n_segs, int n_proj, FusedArgs* f) {
+int plan_multi(const sgmv_problem* p, int n_segs, int n_proj, FusedArgs* f, TileArgs* t) {
   const Limits lim = limits();
+  // segments of a few rows: the add-ons side by side in one launch of the tile kernel while all
+  // their workgroups are resident together (fewer slices each than a single add-on would get)
+  if ((p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->max_seg_len != 1 && n_proj > 1 &&
+      p->ksplit == 0 && choose_tile(p, n_segs, t, n_proj))
+    return SGMV_KERNEL_TILE;
   if ((p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->max_seg_len == 1 && n_proj > 1 &&
       p->workspace != nullptr && choose_fused(p, n_segs, f, false) && f->S * n_proj <= split_cap(p->n_tokens)) {
     f->r = p->r;
@@ -760,23 +792,11 @@ int add_lora_launch(const sgmv_problem* p, const Scratch& sc, void* y, const voi
     }
     case SGMV_KERNEL_TILE: {
       TileArgs& t = pl.tile;
-      t.bf16 = p->dtype == SGMV_BF16;
-      t.r = p->r;
-      t.h_in = p->h_in;
-      t.h_out = p->h_out;
-      t.n_tokens = p->n_tokens;
-      t.n_segs = n_segs;
-      t.spin_limit = spin_limit_of(p);
-      t.offA = (long long)layer_idx * p->h_in * p->r;
-      t.offB = (long long)layer_idx * p->r * p->h_out;
+      fill_tile(&t, p, sc, seg_starts, n_segs, layer_idx, scale);
       t.y = y;
       t.x = x;
       t.A_ptrs = A_ptrs;
       t.B_ptrs = B_ptrs;
-      t.seg_starts = seg_starts;
-      t.exch = sc.exch;
-      t.header = sc.header;
-      t.scale = scale;
       return launch_add_lora_tile(t, st) == hipSuccess ? SGMV_OK : SGMV_ERR_LAUNCH;
     }
     case SGMV_KERNEL_FUSED: {
@@ -909,7 +929,18 @@ int sgmv_add_lora_multi(const sgmv_problem* p, int32_t n_proj, void* const* ys,
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   FusedArgs f;
-  const int kernel = plan_multi(p, n_segs, n_proj, &f);
+  TileArgs tile;
+  const int kernel = plan_multi(p, n_segs, n_proj, &f, &tile);
+  if (kernel == SGMV_KERNEL_TILE) {
+    fill_tile(&tile, p, caller_scratch(p), seg_starts, n_segs, layer_idx, scale);
+    for (int i = 0; i < kMaxProjections; ++i) {
+      tile.table.x[i] = i < n_proj ? xs[i] : nullptr;
+      tile.table.y[i] = i < n_proj ? ys[i] : nullptr;
+      tile.table.A_ptrs[i] = i < n_proj ? A_ptrs[i] : nullptr;
+      tile.table.B_ptrs[i] = i < n_proj ? B_ptrs[i] : nullptr;
+    }
+    return launch_add_lora_tile(tile, st) == hipSuccess ? SGMV_OK : SGMV_ERR_LAUNCH;
+  }
   if (kernel != SGMV_KERNEL_SEQUENCE) {
     fill_fused(&f, p, caller_scratch(p), seg_starts, n_segs, layer_idx, scale);
     f.n_proj = n_proj;
@@ -1020,7 +1051,16 @@ int sgmv_plan_add_lora(const sgmv_problem* p, int32_t n_segs, int32_t n_proj, sg
   }
   if (n_proj > 1) {
     FusedArgs f;
-    const int kernel = plan_multi(p, n_segs, n_proj, &f);
+    TileArgs tile;
+    const int kernel = plan_multi(p, n_segs, n_proj, &f, &tile);
+    if (kernel == SGMV_KERNEL_TILE) {
+      plan->kernel = kernel;
+      plan->launches = 1;
+      plan->slices = tile.S;
+      plan->workgroups = tile.S * n_segs * n_proj * tile.Z;
+      plan->lds_bytes = (int32_t)tile.lds_bytes;
+      return SGMV_OK;
+    }
     if (kernel != SGMV_KERNEL_SEQUENCE) {
       plan->kernel = kernel;
       plan->launches = 1;

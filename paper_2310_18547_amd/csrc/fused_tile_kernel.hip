@@ -56,13 +56,12 @@ size_t tile_lds_bytes(int r, int kslice, int cslice) {
 //   exch   [S][n_tokens][R] 64-bit words {fp32 value (high), tag (low)}
 //   header the workspace's generation copies, then the error flag
 template <class DT, int R>
-__global__ __launch_bounds__(320) void add_lora_tile_kernel(
-    // the first sixteen dwords are preloaded into SGPRs at wave launch
+__device__ __forceinline__ void tile_body(
     const int32_t* __restrict__ seg_starts, const uint16_t* const* __restrict__ A_ptrs,
     const uint16_t* const* __restrict__ B_ptrs, const uint16_t* __restrict__ x,
     uint16_t* __restrict__ y, int kslice, int cslice, int h_in, int h_out, int n_tokens, int S,
     long long offA, long long offB, unsigned long long* exch, unsigned long long* header,
-    float scale, int spin_limit) {
+    float scale, int spin_limit, const int seg) {
   constexpr int NT = 256, NW = 4;
   constexpr int CG = R / 8;              // 128-bit chunks in a row of A_i
   constexpr int NTILE = (R + 15) / 16;   // 16-column tiles of v
@@ -96,7 +95,7 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   SGMV_TRACE_DECL
   SGMV_TRACE_POINT(0);
-  const int seg = blockIdx.y, s = blockIdx.x;
+  const int s = blockIdx.x;
   const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
   const uint16_t* A = A_ptrs[seg];
   const uint16_t* B = B_ptrs[seg];
@@ -540,26 +539,68 @@ __global__ __launch_bounds__(320) void add_lora_tile_kernel(
 }
 
 template <class DT, int R>
-static hipError_t launch_tile_t(const TileArgs& a, hipStream_t st) {
-  auto kernel = add_lora_tile_kernel<DT, R>;
-  // LDS beyond 64 KiB per workgroup has to be enabled per kernel, once per device
-  static std::atomic<bool> enabled[64];  // zero-initialised; setting the attribute twice is harmless
+__global__ __launch_bounds__(320) void add_lora_tile_kernel(
+    // the first sixteen dwords are preloaded into SGPRs at wave launch
+    const int32_t* __restrict__ seg_starts, const uint16_t* const* __restrict__ A_ptrs,
+    const uint16_t* const* __restrict__ B_ptrs, const uint16_t* __restrict__ x,
+    uint16_t* __restrict__ y, int kslice, int cslice, int h_in, int h_out, int n_tokens, int S,
+    long long offA, long long offB, unsigned long long* exch, unsigned long long* header,
+    float scale, int spin_limit) {
+  tile_body<DT, R>(seg_starts, A_ptrs, B_ptrs, x, y, kslice, cslice, h_in, h_out, n_tokens, S, offA, offB, exch,
+                   header, scale, spin_limit, (int)blockIdx.y);
+}
+
+// Several add-ons of one shape side by side: blockIdx.y = add-on * n_segs + segment.  Each add-on
+// has its own x, y and weight pointers (tab) and its own stretch of exchange words; the segments
+// and the slicing are shared.
+template <class DT, int R>
+__global__ __launch_bounds__(320) void add_lora_tile_multi_kernel(
+    const int32_t* __restrict__ seg_starts, int kslice, int cslice, int h_in, int h_out, int n_tokens,
+    int S, long long offA, long long offB, unsigned long long* exch, unsigned long long* header,
+    float scale, int spin_limit, int n_segs, FusedTable tab) {
+  const int proj = (int)blockIdx.y / n_segs;
+  tile_body<DT, R>(seg_starts, reinterpret_cast<const uint16_t* const*>(tab.A_ptrs[proj]),
+                   reinterpret_cast<const uint16_t* const*>(tab.B_ptrs[proj]),
+                   reinterpret_cast<const uint16_t*>(tab.x[proj]), reinterpret_cast<uint16_t*>(tab.y[proj]), kslice,
+                   cslice, h_in, h_out, n_tokens, S, offA, offB, exch + (long long)proj * S * n_tokens * R, header,
+                   scale, spin_limit, (int)blockIdx.y - proj * n_segs);
+}
+
+// LDS beyond 64 KiB per workgroup has to be enabled per kernel, once per device
+static hipError_t enable_tile_lds(const void* kernel, std::atomic<bool>* enabled) {
   int dev = 0;
   hipError_t err = hipGetDevice(&dev);
   if (err != hipSuccess) return err;
   if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
   if (!enabled[dev].load(std::memory_order_acquire)) {
-    err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kTileMaxLds);
+    err = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kTileMaxLds);
     if (err != hipSuccess) return err;
     enabled[dev].store(true, std::memory_order_release);
   }
+  return hipSuccess;
+}
+
+template <class DT, int R>
+static hipError_t launch_tile_t(const TileArgs& a, hipStream_t st) {
   // A workgroup asks for more than half of the unit's LDS even when it uses less, so that no
   // two of them share a compute unit: the grid has a workgroup per segment and block of the
   // LONGEST segment, and the ones without rows, although they leave at once, hold unit slots
   // at dispatch, so that live ones were doubled up on some units while others stayed empty
   // (one long and many short segments: 10.1 us, the issue phase of every workgroup twice as long)
   const size_t lds = a.lds_bytes > kTileExclusiveLds ? a.lds_bytes : kTileExclusiveLds;
+  static std::atomic<bool> enabled[2][64];  // zero-initialised; setting the attribute twice is harmless
+  if (a.n_proj > 1) {
+    auto kernel = add_lora_tile_multi_kernel<DT, R>;
+    const hipError_t err = enable_tile_lds(reinterpret_cast<const void*>(kernel), enabled[1]);
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)a.S, (unsigned)(a.n_segs * a.n_proj), (unsigned)a.Z), dim3(320), lds,
+                       st, a.seg_starts, a.kslice, a.cslice, a.h_in, a.h_out, a.n_tokens, a.S, a.offA, a.offB,
+                       a.exch, a.header, a.scale, a.spin_limit, a.n_segs, a.table);
+    return hipGetLastError();
+  }
+  auto kernel = add_lora_tile_kernel<DT, R>;
+  const hipError_t err = enable_tile_lds(reinterpret_cast<const void*>(kernel), enabled[0]);
+  if (err != hipSuccess) return err;
   hipLaunchKernelGGL(kernel, dim3((unsigned)a.S, (unsigned)a.n_segs, (unsigned)a.Z), dim3(320),
                      lds, st, a.seg_starts, (const uint16_t* const*)a.A_ptrs,
                      (const uint16_t* const*)a.B_ptrs, (const uint16_t*)a.x, (uint16_t*)a.y, a.kslice,
@@ -580,7 +621,8 @@ static hipError_t launch_tile_r(const TileArgs& a, hipStream_t st) {
 }
 
 hipError_t launch_add_lora_tile(const TileArgs& a, hipStream_t st) {
-  if (a.lds_bytes > kTileMaxLds || a.n_segs > 65535 || a.Z > 65535) return hipErrorInvalidValue;
+  if (a.lds_bytes > kTileMaxLds || (long long)a.n_segs * (a.n_proj > 1 ? a.n_proj : 1) > 65535 || a.Z > 65535)
+    return hipErrorInvalidValue;
   return a.bf16 ? launch_tile_r<BF16>(a, st) : launch_tile_r<F16>(a, st);
 }
 

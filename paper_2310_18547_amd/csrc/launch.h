@@ -118,6 +118,8 @@ struct TileArgs {
   const int32_t* seg_starts;
   unsigned long long* exch;
   unsigned long long* header;
+  int n_proj;                // 0 or 1: one add-on (x, y, A_ptrs, B_ptrs above); else `table` holds n_proj of them, side by side
+  FusedTable table;
 };
 
 // Single-launch kernel for one-row segments in which every workgroup computes the whole

@@ -304,7 +304,15 @@ def test_plan_multi_projection_shapes():
     assert pl.workgroups == 4 * 64
     rc, pl = _plan(16, 4, n_tokens=16, max_seg_len=1)
     assert rc == 0 and pl.kernel == sg.KERNEL_MULTI_SIDE and pl.workgroups == 8 * 16 * 4
-    # multi-row segments are run one add-on after the other
+    # segments of a few rows: the add-ons side by side in one launch of the tile kernel while
+    # their workgroups are all resident together, with fewer slices each if need be ...
+    rc, pl = _plan(8, 3, n_tokens=16, max_seg_len=2)
+    assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.launches == 1
+    assert pl.slices == 8 and pl.workgroups == 8 * 8 * 3
+    rc, pl = _plan(16, 3, n_tokens=64, max_seg_len=4)
+    assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.launches == 1
+    assert pl.slices == 5 and pl.workgroups == 5 * 16 * 3
+    # ... and one add-on after the other beyond that
     rc, pl = _plan(39, 3, n_tokens=64, max_seg_len=5)
     assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.launches == 3
     rc, pl = _plan(64, 9, n_tokens=64, max_seg_len=1)

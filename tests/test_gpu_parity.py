@@ -71,6 +71,34 @@ def test_shrink_accumulates_into_v():
     assert np.all(np.abs(v.cpu().numpy() - ref) <= 2e-3 + 2e-2 * np.abs(ref))
 
 
+# several add-ons on segments of a few rows: side by side in one launch of the tile kernel
+@pytest.mark.parametrize("kind,P,dtype,r", [("uniform", 3, "f16", 16), ("skewed", 2, "bf16", 16), ("identical", 4, "f16", 16),
+                                            ("uniform_paper", 3, "bf16", 32), ("skewed_paper", 2, "f16", 8)])
+def test_multi_on_popularity_mixes_is_one_tile_launch(kind, P, dtype, r):
+    from paper_2310_18547_amd import binding as B
+    ws = [wl.popularity(kind, batch=64, h_in=1024, h_out=1280, r=r, dtype=dtype, num_layers=2, seed=600 + k)
+          for k in range(P)]
+    # same segments for all add-ons (the same requests), different adapters, inputs and outputs
+    lens = np.diff(ws[0].seg_starts).tolist()
+    ws = [ws[0]] + [wl.custom(lens, 1024, 1280, r, dtype, seed=610 + k, num_layers=2, scale=ws[0].scale)
+                    for k in range(1, P)]
+    ds = [_dev(w) for w in ws]
+    d0 = ds[0]
+    plan = B.sgmv_plan_add_lora(d0.problem, ws[0].n_segs, P)
+    assert plan.kernel == B.KERNEL_TILE and plan.launches == 1
+    B.sgmv_add_lora_multi(d0.problem, [q.y[0] for q in ds], [q.x[0] for q in ds], [q.A_ptrs for q in ds],
+                          [q.B_ptrs for q in ds], d0.seg_starts, ws[0].n_segs, 1, ws[0].scale)
+    torch.cuda.synchronize()
+    assert d0.check() == 0
+    for k, (w, q) in enumerate(zip(ws, ds)):
+        assert_parity(q.y_bits(), oracle.run_workload(w, layer_idx=1, n_threads=8), dtype, f"{kind}: add-on {k} of {P}")
+    # once more on the same workspace (next generation), into the already updated outputs
+    B.sgmv_add_lora_multi(d0.problem, [q.y[0] for q in ds], [q.x[0] for q in ds], [q.A_ptrs for q in ds],
+                          [q.B_ptrs for q in ds], d0.seg_starts, ws[0].n_segs, 0, ws[0].scale)
+    torch.cuda.synchronize()
+    assert d0.check() == 0
+
+
 # several add-ons on long segments that read the same x: one shrink pass over x for all of them
 @pytest.mark.parametrize("dtype,r,P", [("bf16", 16, 3), ("f16", 16, 2), ("bf16", 8, 3), ("f16", 32, 2), ("bf16", 32, 3),
                                        ("bf16", 64, 2)])
