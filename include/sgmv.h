@@ -284,7 +284,8 @@ int sgmv_add_lora_static(const sgmv_problem* p, void* y, const void* x,
  * With workspace_ready set and max_seg_len == 1 (every request its own
  * adapter) all add-ons run in ONE kernel launch; so do segments of a few rows
  * (max_seg_len from 2 up to what the single-launch MFMA kernel takes) while the
- * workgroups of all add-ons fit on the chip together.  On long segments (the MFMA
+ * workgroups of all add-ons fit on the chip together, and in groups of as many
+ * as fit beyond that.  On long segments (the MFMA
  * kernels) two or three add-ons whose x_i are the same buffer share the shrink's
  * pass over x when the workspace has the size of sgmv_workspace_bytes_multi
  * (ranks up to 32).  Otherwise the call is the same as n_proj calls of

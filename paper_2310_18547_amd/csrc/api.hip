@@ -591,9 +591,13 @@ int plan_multi(const sgmv_problem* p, int n_segs, int n_proj, FusedArgs* f, Tile
   const Limits lim = limits();
   // segments of a few rows: the add-ons side by side in one launch of the tile kernel while all
   // their workgroups are resident together (fewer slices each than a single add-on would get)
+  // (t->n_proj: how many go into one launch; when not all of them fit, the call takes groups of
+  // that many, and what is left over at the end in a smaller launch)
   if ((p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->max_seg_len != 1 && n_proj > 1 &&
-      p->ksplit == 0 && choose_tile(p, n_segs, t, n_proj))
-    return SGMV_KERNEL_TILE;
+      p->ksplit == 0) {
+    for (int group = n_proj; group > 1; --group)
+      if (choose_tile(p, n_segs, t, group)) return SGMV_KERNEL_TILE;
+  }
   if ((p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->max_seg_len == 1 && n_proj > 1 &&
       p->workspace != nullptr && choose_fused(p, n_segs, f, false) && f->S * n_proj <= split_cap(p->n_tokens)) {
     f->r = p->r;
@@ -932,14 +936,28 @@ int sgmv_add_lora_multi(const sgmv_problem* p, int32_t n_proj, void* const* ys,
   TileArgs tile;
   const int kernel = plan_multi(p, n_segs, n_proj, &f, &tile);
   if (kernel == SGMV_KERNEL_TILE) {
-    fill_tile(&tile, p, caller_scratch(p), seg_starts, n_segs, layer_idx, scale);
-    for (int i = 0; i < kMaxProjections; ++i) {
-      tile.table.x[i] = i < n_proj ? xs[i] : nullptr;
-      tile.table.y[i] = i < n_proj ? ys[i] : nullptr;
-      tile.table.A_ptrs[i] = i < n_proj ? A_ptrs[i] : nullptr;
-      tile.table.B_ptrs[i] = i < n_proj ? B_ptrs[i] : nullptr;
+    const Scratch sc = caller_scratch(p);
+    const int group = tile.n_proj;
+    for (int first = 0; first < n_proj; first += group) {
+      const int count = n_proj - first < group ? n_proj - first : group;
+      TileArgs t = tile;
+      if (count == 1 || (count < group && !choose_tile(p, n_segs, &t, count))) {  // left over at the end
+        for (int i = first; i < first + count; ++i) {
+          rc = add_lora_launch(p, sc, ys[i], xs[i], A_ptrs[i], B_ptrs[i], seg_starts, n_segs, layer_idx, scale, st);
+          if (rc != SGMV_OK) return rc;
+        }
+        break;
+      }
+      fill_tile(&t, p, sc, seg_starts, n_segs, layer_idx, scale);
+      for (int i = 0; i < kMaxProjections; ++i) {
+        t.table.x[i] = i < count ? xs[first + i] : nullptr;
+        t.table.y[i] = i < count ? ys[first + i] : nullptr;
+        t.table.A_ptrs[i] = i < count ? A_ptrs[first + i] : nullptr;
+        t.table.B_ptrs[i] = i < count ? B_ptrs[first + i] : nullptr;
+      }
+      if (launch_add_lora_tile(t, st) != hipSuccess) return SGMV_ERR_LAUNCH;
     }
-    return launch_add_lora_tile(tile, st) == hipSuccess ? SGMV_OK : SGMV_ERR_LAUNCH;
+    return SGMV_OK;
   }
   if (kernel != SGMV_KERNEL_SEQUENCE) {
     fill_fused(&f, p, caller_scratch(p), seg_starts, n_segs, layer_idx, scale);
@@ -1053,11 +1071,11 @@ int sgmv_plan_add_lora(const sgmv_problem* p, int32_t n_segs, int32_t n_proj, sg
     FusedArgs f;
     TileArgs tile;
     const int kernel = plan_multi(p, n_segs, n_proj, &f, &tile);
-    if (kernel == SGMV_KERNEL_TILE) {
+    if (kernel == SGMV_KERNEL_TILE) {  // groups of tile.n_proj add-ons; slices and workgroups of the first launch
       plan->kernel = kernel;
-      plan->launches = 1;
+      plan->launches = (n_proj + tile.n_proj - 1) / tile.n_proj;
       plan->slices = tile.S;
-      plan->workgroups = tile.S * n_segs * n_proj * tile.Z;
+      plan->workgroups = tile.S * n_segs * tile.n_proj * tile.Z;
       plan->lds_bytes = (int32_t)tile.lds_bytes;
       return SGMV_OK;
     }

@@ -312,8 +312,12 @@ def test_plan_multi_projection_shapes():
     rc, pl = _plan(16, 3, n_tokens=64, max_seg_len=4)
     assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.launches == 1
     assert pl.slices == 5 and pl.workgroups == 5 * 16 * 3
-    # ... and one add-on after the other beyond that
+    # ... in groups where they do not all fit (here two, then the third by itself) ...
     rc, pl = _plan(39, 3, n_tokens=64, max_seg_len=5)
+    assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.launches == 2
+    assert pl.slices * 39 * 2 <= 256 and pl.workgroups == pl.slices * 39 * 2
+    # ... and one add-on after the other beyond that
+    rc, pl = _plan(64, 3, n_tokens=128, max_seg_len=2)
     assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.launches == 3
     rc, pl = _plan(64, 9, n_tokens=64, max_seg_len=1)
     assert rc == 2

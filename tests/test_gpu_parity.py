@@ -99,6 +99,30 @@ def test_multi_on_popularity_mixes_is_one_tile_launch(kind, P, dtype, r):
     assert d0.check() == 0
 
 
+# more add-ons than fit side by side: groups of as many as fit, what is left over in a smaller launch
+@pytest.mark.parametrize("n,rows,P,dtype,r,launches", [(60, 2, 5, "f16", 16, 2), (60, 2, 7, "bf16", 16, 2),
+                                                       (40, 3, 8, "f16", 32, 3)])
+def test_multi_on_segments_of_a_few_rows_in_groups(n, rows, P, dtype, r, launches):
+    from paper_2310_18547_amd import binding as B
+    lens = [rows] * n
+    lens[3] = 0
+    lens[7] = rows - 1
+    ws = [wl.custom(lens, 1024, 1280, r, dtype, seed=700 + k, num_layers=2) for k in range(P)]
+    ds = [_dev(w) for w in ws]
+    d0 = ds[0]
+    d0.problem.max_seg_len = rows
+    plan = B.sgmv_plan_add_lora(d0.problem, n, P)
+    assert plan.kernel == B.KERNEL_TILE and plan.launches == launches
+    for layer in (1, 0):    # the second call on the next generation, into the already updated outputs
+        B.sgmv_add_lora_multi(d0.problem, [q.y[0] for q in ds], [q.x[0] for q in ds], [q.A_ptrs for q in ds],
+                              [q.B_ptrs for q in ds], d0.seg_starts, n, layer, ws[0].scale)
+        torch.cuda.synchronize()
+        assert d0.check() == 0
+        if layer == 1:
+            for k, (w, q) in enumerate(zip(ws, ds)):
+                assert_parity(q.y_bits(), oracle.run_workload(w, layer_idx=1, n_threads=8), dtype, f"add-on {k} of {P}")
+
+
 # several add-ons on long segments that read the same x: one shrink pass over x for all of them
 @pytest.mark.parametrize("dtype,r,P", [("bf16", 16, 3), ("f16", 16, 2), ("bf16", 8, 3), ("f16", 32, 2), ("bf16", 32, 3),
                                        ("bf16", 64, 2)])
