@@ -100,11 +100,20 @@ typedef enum {
                              /* a launch whose workgroups (segments x sixteen-row  */
                              /* blocks x slices) are all resident with their weight*/
                              /* slices in LDS, else SGMV_ERR_UNSUPPORTED           */
-  SGMV_PATH_WHOLE = 4        /* sgmv_add_lora only: single launch for one-row      */
+  SGMV_PATH_WHOLE = 4,       /* sgmv_add_lora only: single launch for one-row      */
                              /* segments (max_seg_len == 1) in which every         */
                              /* workgroup computes its segment's whole shrink, so  */
                              /* workgroups never wait for each other and no        */
                              /* workspace is touched; h_in at most 8192, else      */
+                             /* SGMV_ERR_UNSUPPORTED                               */
+  SGMV_PATH_ROWS = 5         /* sgmv_add_lora only: the single-launch kernel of    */
+                             /* SGMV_PATH_FUSED for one-row segments, run per ROW  */
+                             /* of the batch: a row's workgroups look its segment  */
+                             /* up on the device, so segments may have any length  */
+                             /* (max_seg_len is not consulted) and rows that share */
+                             /* an adapter read it through the caches; needs       */
+                             /* workspace_ready and a batch small enough for all   */
+                             /* workgroups to be resident, else                    */
                              /* SGMV_ERR_UNSUPPORTED                               */
 } sgmv_path;
 

@@ -6,7 +6,7 @@ first use of any of its names and raises ``ImportError`` if the library has not
 been built (``python -m paper_2310_18547_amd.build``).
 """
 _BINDING_NAMES = (
-    "F16", "BF16", "PATH_AUTO", "PATH_VECTOR", "PATH_MATRIX", "PATH_FUSED", "PATH_WHOLE", "SgmvError", "SgmvProblem", "lib",
+    "F16", "BF16", "PATH_AUTO", "PATH_VECTOR", "PATH_MATRIX", "PATH_FUSED", "PATH_WHOLE", "PATH_ROWS", "SgmvError", "SgmvProblem", "lib",
     "SgmvPlan", "KERNEL_NONE", "KERNEL_FUSED", "KERNEL_TILE", "KERNEL_MULTI_SIDE", "KERNEL_MULTI_PIPELINED",
     "KERNEL_VECTOR", "KERNEL_MATRIX", "KERNEL_WHOLE", "KERNEL_NAMES", "sgmv_add_lora_multi", "sgmv_add_lora_static", "sgmv_plan_add_lora", "sgmv_plan_shrink", "sgmv_workspace_bytes_multi",
     "library_path", "make_problem", "sgmv_add_lora", "sgmv_expand", "sgmv_shrink",

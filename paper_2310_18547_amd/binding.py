@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, os.path.basename(os.environ.get("SGMV_LIBRARY", "libsgmv.so")))
 
 F16, BF16 = 0, 1
-PATH_AUTO, PATH_VECTOR, PATH_MATRIX, PATH_FUSED, PATH_WHOLE = 0, 1, 2, 3, 4
+PATH_AUTO, PATH_VECTOR, PATH_MATRIX, PATH_FUSED, PATH_WHOLE, PATH_ROWS = 0, 1, 2, 3, 4, 5
 
 
 class SgmvError(RuntimeError):

@@ -35,6 +35,7 @@ constexpr int kTargetWorkgroups = 512; // about two workgroups per compute unit
 constexpr int kTileMaxSegLen = 4096;
 constexpr int kMatrixMaxSegments = 65535;  // the MFMA kernels put the segment on a grid dimension limited to this
 constexpr int kFusedSlices = 8;        // most slices per segment the single-launch kernels pick
+constexpr int kTileMultiSlices = 4;    // fewest slices at which a joint tile launch beats add-ons run per row
 constexpr int kFusedMaxWorkgroups = kGenerationCopies;  // every workgroup of a launch has its own generation copy
 constexpr int kFusedSpinLimit = 1 << 18;
 constexpr int kMaxDevices = 64;
@@ -113,7 +114,7 @@ int check_common(const sgmv_problem* p, const int32_t* seg_starts, int32_t n_seg
   if (p->r != 8 && p->r != 16 && p->r != 32 && p->r != 64) return SGMV_ERR_UNSUPPORTED;
   if ((need_in && (p->h_in % 8) != 0) || (need_out && (p->h_out % 8) != 0))
     return SGMV_ERR_UNSUPPORTED;
-  if (p->path < SGMV_PATH_AUTO || p->path > SGMV_PATH_WHOLE) return SGMV_ERR_UNSUPPORTED;
+  if (p->path < SGMV_PATH_AUTO || p->path > SGMV_PATH_ROWS) return SGMV_ERR_UNSUPPORTED;
   if (p->spin_limit < 0) return SGMV_ERR_UNSUPPORTED;
   if (p->ksplit < 0 || p->ksplit > kMaxKSplit) return SGMV_ERR_UNSUPPORTED;
   if (p->expand_threads != 0 && p->expand_threads != 64 && p->expand_threads != 128 &&
@@ -223,10 +224,13 @@ void set_operands(ExpandArgs* a, const Scratch& sc, int n_tokens, int r) {
 }
 
 // Launch shape of the single-launch path; false when it does not apply.
-bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f, bool single_add_on = true) {
+// by_rows: the launch's items are the rows of the batch (pass n_tokens for n_segs), each looking its
+// segment up on the device, so the segments may have any length.
+bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f, bool single_add_on = true, bool by_rows = false) {
   if (!p->workspace_ready) return false;
   const Limits lim = limits();
-  if (p->max_seg_len != 1) return false;  // one row per segment; longer ones go to the tile kernel
+  f->by_rows = by_rows;
+  if (p->max_seg_len != 1 && !by_rows) return false;  // one row per segment; longer ones go to the tile kernel
   if (n_segs > kFusedMaxWorkgroups) return false;
   const int cap = split_cap(p->n_tokens);
   const int need = ceil_div(p->h_in, kMaxKSlice);
@@ -288,7 +292,8 @@ bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f, bool single_a
   }
   // likewise batches of more than 128 segments that need two slices each (measured at
   // h = 4096, r = 16: 192 segments 17.3 us here against 15.5 us, 256 segments 20.0 against 18.3)
-  if (p->path == SGMV_PATH_AUTO && p->ksplit == 0 && n_segs > lim.fused_workgroups / 2 &&
+  // (not so rows of longer segments: 129 .. 256 of them at two slices share their weights)
+  if (p->path == SGMV_PATH_AUTO && p->ksplit == 0 && !by_rows && n_segs > lim.fused_workgroups / 2 &&
       (long long)s * n_segs > lim.fused_workgroups)
     return false;
   f->S = s;
@@ -358,7 +363,11 @@ bool choose_tile(const sgmv_problem* p, int n_segs_one, TileArgs* t, int n_proj 
   // on (h = 4096, one segment of 16 / 64 / 256 rows: 14.8 / 16.0 / 17.8 us against 20.2 / 20.2 /
   // 20.7 here; Skewed mix of 32 rows, longest segment 12: 15.4 against 17.0; segments of up to 8
   // rows: 13.0-15.5 here against 14.8-17.2)
-  if (p->path == SGMV_PATH_AUTO && p->r >= 64 && p->max_seg_len > 8) return false;
+  // (a joint launch of several add-ons hands them over side by side in the same 20 us, which beats
+  // the launch-per-step kernels one add-on after the other from about 64 rows on: two segments
+  // of 32 rows, three add-ons 21.4 against 25.1 us; of 64 rows 22.4 against 48.7; one of 32 rows
+  // 20.9 against 18.4)
+  if (p->path == SGMV_PATH_AUTO && p->r >= 64 && p->max_seg_len > 8 && (n_proj < 2 || p->n_tokens < 64)) return false;
   const int cap = split_cap(p->n_tokens);
   const int narrow = p->h_in < p->h_out ? p->h_in : p->h_out;
   int z = ceil_div(p->max_seg_len, 16);
@@ -496,6 +505,33 @@ ExpandArgs make_expand(const sgmv_problem* p, void* y, const float* v_parts, int
   return a;
 }
 
+// Small batches of segments longer than a row (or of unknown length): whether AUTO runs the
+// one-row kernel with the hand-off per ROW of the batch (SGMV_PATH_ROWS), every row's workgroups
+// reading the row's adapter through the caches, rather than the tile kernel (`tile`: it applies, with
+// `tile_slices` slices) or the launch-per-step kernels.  Measured on MI355X, binary16, us per add-on,
+// per row against what AUTO took before:
+//  * up to 64 rows it wins at every rank and width measured (ranks 8 .. 64; 4096, 5120, 8192 square,
+//    4096 -> 11008, 11008 -> 4096; 31 segment mixes and five popularity mixes each: 129 of 132 cases at
+//    rank 64 faster, the rest within 2 %).  At 4096 x 4096, rank 16, 64 rows: Uniform 5.33 against
+//    7.16 (tile kernel), Skewed 4.88 against 7.58, Identical 4.88 against 7.23, 8 segments of 8 rows
+//    4.85 against 7.12; rank 64: Uniform 11.7 against 22.7 (MFMA kernels), 8 x 8 rows 9.4 against 14.2.
+//  * 65 .. 128 rows: ahead up to rank 32 (rank 16, 128 rows: Uniform 6.40 against 9.29, Skewed 6.13
+//    against 11.9, one segment 5.79 against 7.27, 16 x 8 rows 5.85 against 7.60; rank 32: 4 x 32 rows
+//    7.96 against 10.3, Uniform 9.16 against 11.4; behind by at most 12 % on 24 segments of 4 rows
+//    at rank 32 and on 32 x 4 rows at 5120), not at rank 64 (two slices per row leave each workgroup
+//    half of B_i: 4096 -> 11008, 8 x 16 rows: 27.2 against 17.3).
+//  * 129 .. 256 rows, ranks up to 16: ahead where the tile kernel does not apply or gets fewer than
+//    its eight slices (Skewed of 256 rows 9.05 against 18.9, Uniform 7.88 against 9.83, 128 x 2 rows
+//    11.7 against 14.7; behind on 40 .. 64 segments of 4 rows, by up to 17 %), 4-8 % ahead elsewhere,
+//    which is left to the tile kernel.
+bool rows_apply(const sgmv_problem* p, bool tile, int tile_slices) {
+  if (p->max_seg_len == 1 || p->ksplit != 0 || !p->workspace_ready) return false;
+  if (p->n_tokens <= 64) return true;
+  if (p->n_tokens <= 128) return p->r <= 32;
+  if (p->n_tokens <= 256) return p->r <= 16 && (!tile || tile_slices < 8);
+  return false;
+}
+
 // What sgmv_add_lora will launch for a checked problem: the single source of the path
 // choice, shared by the entry points and by sgmv_plan_add_lora.
 struct SinglePlan {
@@ -512,8 +548,19 @@ int plan_single(const sgmv_problem* p, int n_segs, SinglePlan* pl) {
     pl->kernel = SGMV_KERNEL_WHOLE;
     return SGMV_OK;
   }
-  if ((p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->max_seg_len != 1 &&
-      choose_tile(p, n_segs, &pl->tile)) {
+  if (p->path == SGMV_PATH_ROWS) {
+    if (!choose_fused(p, p->n_tokens, &pl->fused, true, true)) return SGMV_ERR_UNSUPPORTED;
+    pl->kernel = SGMV_KERNEL_FUSED;
+    return SGMV_OK;
+  }
+  const bool tile = (p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->max_seg_len != 1 &&
+                    choose_tile(p, n_segs, &pl->tile);
+  if (p->path == SGMV_PATH_AUTO && rows_apply(p, tile, tile ? pl->tile.S : 0) &&
+      choose_fused(p, p->n_tokens, &pl->fused, true, true)) {
+    pl->kernel = SGMV_KERNEL_FUSED;
+    return SGMV_OK;
+  }
+  if (tile) {
     pl->kernel = SGMV_KERNEL_TILE;
     return SGMV_OK;
   }
@@ -589,31 +636,74 @@ int plan_shrink(const sgmv_problem* p, int n_segs, ShrinkPlan* pl) {
 // SGMV_KERNEL_SEQUENCE (one sgmv_add_lora after the other).
 int plan_multi(const sgmv_problem* p, int n_segs, int n_proj, FusedArgs* f, TileArgs* t) {
   const Limits lim = limits();
-  // segments of a few rows: the add-ons side by side in one launch of the tile kernel while all
-  // their workgroups are resident together (fewer slices each than a single add-on would get)
-  // (t->n_proj: how many go into one launch; when not all of them fit, the call takes groups of
-  // that many, and what is left over at the end in a smaller launch)
-  if ((p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->max_seg_len != 1 && n_proj > 1 &&
-      p->ksplit == 0) {
-    for (int group = n_proj; group > 1; --group)
-      if (choose_tile(p, n_segs, t, group)) return SGMV_KERNEL_TILE;
+  const bool one_row = p->max_seg_len == 1;
+  if (n_proj < 2) return SGMV_KERNEL_SEQUENCE;
+  // Segments longer than a row in a small batch: where a single add-on runs the one-row kernel
+  // per row of the batch (plan_single), so may the add-ons of this call, side by side
+  bool per_row = false;
+  if (!one_row && p->ksplit == 0 && (p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_ROWS)) {
+    FusedArgs rows;
+    TileArgs one;
+    const bool tile_one = p->path == SGMV_PATH_AUTO && choose_tile(p, n_segs, &one);
+    per_row = (p->path == SGMV_PATH_ROWS || rows_apply(p, tile_one, tile_one ? one.S : 0)) &&
+              choose_fused(p, p->n_tokens, &rows, true, true);
   }
-  if ((p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->max_seg_len == 1 && n_proj > 1 &&
-      p->workspace != nullptr && choose_fused(p, n_segs, f, false) && f->S * n_proj <= split_cap(p->n_tokens)) {
+  // The add-ons in one launch of the one-row kernels: one set of S workgroups per segment (or per
+  // row of the batch) and add-on, side by side or, for one-row segments, walking the add-ons.
+  auto joint_rows = [&]() -> int {
+    if (!(p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED || per_row) || !(one_row || per_row)) return SGMV_KERNEL_SEQUENCE;
+    const int items = per_row ? p->n_tokens : n_segs;  // what a set of S workgroups serves
+    if (p->workspace == nullptr || !choose_fused(p, items, f, false, per_row) || f->S * n_proj > split_cap(p->n_tokens))
+      return SGMV_KERNEL_SEQUENCE;
     f->r = p->r;
     // workgroups that hold segments count towards what must be resident; the grid, padded to
     // whole rows of segments, must leave every workgroup its own generation copy
-    const long long grid = (long long)f->S * fused_grid_items(n_segs) * n_proj;
-    if ((long long)f->S * n_segs * n_proj <= lim.multi_workgroups && grid <= kGenerationCopies)
+    const long long grid = (long long)f->S * fused_grid_items(items) * n_proj;
+    if ((long long)f->S * items * n_proj <= lim.multi_workgroups && grid <= kGenerationCopies)
       return SGMV_KERNEL_MULTI_SIDE;
-    if (fused_multi_fits(*f)) return SGMV_KERNEL_MULTI_PIPELINED;
+    if (!per_row && fused_multi_fits(*f)) return SGMV_KERNEL_MULTI_PIPELINED;
     // slices too deep for the pipelined kernel's register sets (h_in = 5120 at four slices):
     // three workgroups per compute unit still beat one launch per add-on (measured, three
     // projections of 64 segments at h = 5120: 22.7 us against 24.8 us)
     // (ranks up to 16 only: the kernels of the higher ranks use more registers and fit two per unit)
-    if (p->r <= 16 && (long long)f->S * n_segs * n_proj <= lim.multi_workgroups_most && grid <= kGenerationCopies)
+    if (p->r <= 16 && (long long)f->S * items * n_proj <= lim.multi_workgroups_most && grid <= kGenerationCopies)
       return SGMV_KERNEL_MULTI_SIDE;
+    return SGMV_KERNEL_SEQUENCE;
+  };
+  if (one_row) return joint_rows();
+  // Measured at 4096 x 4096, binary16, us for two / three add-ons, per row side by side against
+  // the joint tile launch below: rank 16, 64 rows: Uniform 8.1 / 11.0 against 12.6 / 20.5, Skewed
+  // 7.2 / 9.1 against 10.0 / 13.7, Identical 6.2 / 7.4 against 7.7 / 8.0, 8 segments of 8 rows
+  // 6.2 / 7.4 against 8.4 / 8.8; 128 rows: 16 x 8 rows 8.0 / 11.2 against 9.3 / 10.4, one segment 8.0 /
+  // 11.2 against 8.5 / 9.0 (three add-ons of 128 rows are 768 workgroups at two slices); rank 64,
+  // 64 rows, two add-ons: 8 x 8 rows 13.1 against 15.7, Identical 11.4 against 20.8.
+  // (at rank 32, 128 rows, two add-ons, the tile launch is ahead: one segment 10.9 against 12.2,
+  // 16 x 8 rows 11.2 against 14.5)
+  const bool rows_first = per_row && (p->n_tokens <= 64 || ((long long)n_proj * p->n_tokens <= 256 && p->r <= 16));
+  if (rows_first) {
+    const int kernel = joint_rows();
+    if (kernel != SGMV_KERNEL_SEQUENCE) return kernel;
   }
+  // segments of a few rows: the add-ons side by side in one launch of the tile kernel while all
+  // their workgroups are resident together (fewer slices each than a single add-on would get)
+  // (t->n_proj: how many go into one launch; when not all of them fit, the call takes groups of
+  // that many, and what is left over at the end in a smaller launch)
+  bool tile = false;
+  if ((p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->ksplit == 0) {
+    for (int group = n_proj; group > 1 && !tile; --group) tile = choose_tile(p, n_segs, t, group);
+  }
+  // against add-ons that run per row side by side, the joint tile launch is ahead only as one
+  // launch that keeps at least kTileMultiSlices slices (Skewed of 128 rows, three add-ons: three
+  // slices 22.0 us against 11.5 per row; Uniform of 64 rows in two launches 20.5 against 11.0);
+  // against add-ons per row one after the other it is ahead also in groups and with fewer slices
+  // (four add-ons, rank 8: 32 x 2 rows in two launches 17.5 against 19.4, Skewed of 64 rows at
+  // three slices 11.8 against 18.4; rank 32: 32 x 4 rows 30.4 against 40.6)
+  if (tile && (!per_row || (t->n_proj == n_proj && t->S >= kTileMultiSlices))) return SGMV_KERNEL_TILE;
+  if (per_row && !rows_first) {
+    const int kernel = joint_rows();
+    if (kernel != SGMV_KERNEL_SEQUENCE) return kernel;
+  }
+  if (tile) return SGMV_KERNEL_TILE;
   return SGMV_KERNEL_SEQUENCE;
 }
 
@@ -699,7 +789,7 @@ int sgmv_shrink(const sgmv_problem* p, float* v, const void* x, const void* cons
   if (!aligned(v, 16) || !aligned(x, 16)) return SGMV_ERR_ALIGN;
   rc = check_workspace(p);
   if (rc != SGMV_OK) return rc;
-  if (p->path == SGMV_PATH_FUSED || p->path == SGMV_PATH_WHOLE) return SGMV_ERR_UNSUPPORTED;
+  if (p->path == SGMV_PATH_FUSED || p->path == SGMV_PATH_WHOLE || p->path == SGMV_PATH_ROWS) return SGMV_ERR_UNSUPPORTED;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   ShrinkPlan pl;
@@ -731,7 +821,7 @@ int sgmv_expand(const sgmv_problem* p, void* y, const float* v, const void* cons
   if (n_segs == 0 || p->n_tokens == 0) return SGMV_OK;
   if (y == nullptr || v == nullptr || B_ptrs == nullptr) return SGMV_ERR_NULL;
   if (!aligned(v, 16) || !aligned(y, 16)) return SGMV_ERR_ALIGN;
-  if (p->path == SGMV_PATH_FUSED || p->path == SGMV_PATH_WHOLE) return SGMV_ERR_UNSUPPORTED;
+  if (p->path == SGMV_PATH_FUSED || p->path == SGMV_PATH_WHOLE || p->path == SGMV_PATH_ROWS) return SGMV_ERR_UNSUPPORTED;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   ExpandArgs a = make_expand(p, y, v, 1, nullptr, B_ptrs, seg_starts, n_segs, layer_idx, scale);
@@ -1039,7 +1129,7 @@ int sgmv_plan_shrink(const sgmv_problem* p, int32_t n_segs, sgmv_plan* plan) {
   if (n_segs == 0 || p->n_tokens == 0) return SGMV_OK;  // nothing is launched
   rc = check_workspace(p);
   if (rc != SGMV_OK) return rc;
-  if (p->path == SGMV_PATH_FUSED || p->path == SGMV_PATH_WHOLE) return SGMV_ERR_UNSUPPORTED;
+  if (p->path == SGMV_PATH_FUSED || p->path == SGMV_PATH_WHOLE || p->path == SGMV_PATH_ROWS) return SGMV_ERR_UNSUPPORTED;
   ShrinkPlan pl;
   rc = plan_shrink(p, n_segs, &pl);
   if (rc != SGMV_OK) return rc;
@@ -1083,7 +1173,7 @@ int sgmv_plan_add_lora(const sgmv_problem* p, int32_t n_segs, int32_t n_proj, sg
       plan->kernel = kernel;
       plan->launches = 1;
       plan->slices = f.S;
-      plan->workgroups = f.S * (int)fused_grid_items(n_segs) * (kernel == SGMV_KERNEL_MULTI_SIDE ? n_proj : 1);
+      plan->workgroups = f.S * (int)fused_grid_items(f.by_rows ? p->n_tokens : n_segs) * (kernel == SGMV_KERNEL_MULTI_SIDE ? n_proj : 1);
       return SGMV_OK;
     }
   }
@@ -1107,7 +1197,7 @@ int sgmv_plan_add_lora(const sgmv_problem* p, int32_t n_segs, int32_t n_proj, sg
     case SGMV_KERNEL_FUSED:
       plan->launches = 1;
       plan->slices = pl.fused.S;
-      plan->workgroups = pl.fused.S * (int)fused_grid_items(n_segs);
+      plan->workgroups = pl.fused.S * (int)fused_grid_items(pl.fused.by_rows ? p->n_tokens : n_segs);
       break;
     case SGMV_KERNEL_MATRIX:
       plan->launches = 3;  // shrink, operand preparation, expand

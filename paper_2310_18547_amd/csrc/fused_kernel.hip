@@ -55,13 +55,15 @@ namespace sgmv {
 // G  = lane groups of the expand phase: group g multiplies weight rows
 //      g*R/G .. (g+1)*R/G-1; the groups are summed through LDS.
 // RB = rows handled per pass over the weights (1 when every segment is one row).
-template <class DT, int R, int G, int RB>
+// BY_ROW: `seg` is a row of the batch, not a segment: the workgroup serves that one row and
+//      looks its segment up in seg_starts (n_segs of them).
+template <class DT, int R, int G, int RB, bool BY_ROW = false>
 __device__ __forceinline__ void add_lora_fused_body(
     const int32_t* __restrict__ seg_starts, const uint16_t* const* __restrict__ A_ptrs,
     const uint16_t* const* __restrict__ B_ptrs, const uint16_t* __restrict__ x,
     uint16_t* __restrict__ y, int kslice, int cslice, int h_in, int h_out, int n_tokens, int S,
     long long offA, long long offB, unsigned long long* exch, unsigned long long* header,
-    float scale, int spin_limit, int seg, int s) {
+    float scale, int spin_limit, int seg, int s, int n_segs = 0) {
   constexpr int NT = 256, NW = 4, U = 8;  // stream threads / waves, A loads per lane and batch
   constexpr int LPR = R / 8;
   constexpr int CPW = NT / G;  // 8-column chunks per pass
@@ -84,9 +86,28 @@ __device__ __forceinline__ void add_lora_fused_body(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   SGMV_TRACE_DECL
   SGMV_TRACE_POINT(0);
-  const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
-  const uint16_t* A = A_ptrs[seg];
-  const uint16_t* B = B_ptrs[seg];
+  int lo, hi;
+  const uint16_t *A, *B;
+  if constexpr (BY_ROW) {
+    // The row's segment is the number of segment ends at or before the row (empty segments
+    // count themselves out): every lane looks at one end, all loads of a wave in flight together.
+    int found = 0;
+    for (int base = 0; base < n_segs; base += 64) {
+      const int i = base + lane;
+      const int end = i < n_segs ? seg_starts[i + 1] : 0x7fffffff;
+      found += __popcll(__ballot(end <= seg));
+    }
+    found = __builtin_amdgcn_readfirstlane(found);
+    lo = seg;
+    hi = found < n_segs ? seg + 1 : seg;  // a row behind the last segment end: nothing to do
+    A = found < n_segs ? A_ptrs[found] : nullptr;
+    B = found < n_segs ? B_ptrs[found] : nullptr;
+  } else {
+    lo = seg_starts[seg];
+    hi = seg_starts[seg + 1];
+    A = A_ptrs[seg];
+    B = B_ptrs[seg];
+  }
   if (lo >= hi || A == nullptr || B == nullptr) {  // same decision in all S workgroups
     if (wave == 0) leave_launch_idle(header, (int)(gridDim.x * gridDim.y * gridDim.z), lane);
     return;
@@ -371,7 +392,7 @@ __device__ __forceinline__ void add_lora_fused_body(
 }
 
 // One add-on per launch.
-template <class DT, int R, int G, int RB>
+template <class DT, int R, int G, int RB, bool BY_ROW>
 __global__ __launch_bounds__(320) void add_lora_fused_kernel(
     // the first sixteen dwords are preloaded into SGPRs at wave launch: keep what the
     // first dependent loads need at the front
@@ -382,21 +403,25 @@ __global__ __launch_bounds__(320) void add_lora_fused_kernel(
     float scale, int spin_limit, int n_segs) {
   // grid (fused_grid_x, S, rows): blockIdx.x is the fastest-varying part of the linear id by
   // which workgroups are dealt to the XCDs, so the S workgroups of a segment share an XCD
-  const int seg = blockIdx.z * gridDim.x + blockIdx.x;
-  if (seg >= n_segs) {  // the grid is padded to whole rows of segments
+  // BY_ROW: the items of the grid are the rows of the batch instead of its segments, and an XCD
+  // (blockIdx.x) takes a run of consecutive rows, so that rows of one segment find its weights
+  // in their XCD's L2 (dealt round the XCDs, eight-row segments were read by all eight of them:
+  // 16 segments of 8 rows 8.8 us)
+  const int seg = BY_ROW ? blockIdx.x * gridDim.z + blockIdx.z : blockIdx.z * gridDim.x + blockIdx.x;
+  if (seg >= (BY_ROW ? n_tokens : n_segs)) {  // the grid is padded to whole rows of segments
     if (threadIdx.x < 64) leave_launch_idle(header, (int)(gridDim.x * gridDim.y * gridDim.z), (int)threadIdx.x);
     return;
   }
-  add_lora_fused_body<DT, R, G, RB>(seg_starts, A_ptrs, B_ptrs, x, y, kslice, cslice, h_in, h_out,
-                                    n_tokens, S, offA, offB, exch, header, scale, spin_limit, seg,
-                                    (int)blockIdx.y);
+  add_lora_fused_body<DT, R, G, RB, BY_ROW>(seg_starts, A_ptrs, B_ptrs, x, y, kslice, cslice, h_in, h_out,
+                                            n_tokens, S, offA, offB, exch, header, scale, spin_limit, seg,
+                                            (int)blockIdx.y, n_segs);
 }
 
 // Several independent add-ons of one shape per launch, side by side: blockIdx.z selects
 // the projection's x, y and pointer arrays; each projection exchanges through its own
 // stretch of the workspace.  Used while all workgroups of the launch are resident together
 // (small batches); larger launches take the pipelined kernel in fused_multi_kernel.hip.
-template <class DT, int R, int G>
+template <class DT, int R, int G, bool BY_ROW>
 __global__ __launch_bounds__(320) void add_lora_fused_side_kernel(
     const int32_t* __restrict__ seg_starts, int kslice, int cslice, int h_in, int h_out, int n_tokens,
     int S, long long offA, long long offB, unsigned long long* exch, unsigned long long* header,
@@ -404,17 +429,18 @@ __global__ __launch_bounds__(320) void add_lora_fused_side_kernel(
   // grid (segments of a row, S, rows of segments x projections), as for the single add-on
   const int row = __builtin_amdgcn_readfirstlane((int)(((float)blockIdx.z + 0.5f) / (float)n_proj));
   const int z = (int)blockIdx.z - row * n_proj;
-  const int seg = row * gridDim.x + blockIdx.x;
-  if (seg >= n_segs) {  // the grid is padded to whole rows of segments
+  // BY_ROW: items are rows of the batch, an XCD (blockIdx.x) taking a run of consecutive rows
+  const int seg = BY_ROW ? blockIdx.x * ((int)gridDim.z / n_proj) + row : row * gridDim.x + blockIdx.x;
+  if (seg >= (BY_ROW ? n_tokens : n_segs)) {  // the grid is padded to whole rows of segments
     if (threadIdx.x < 64) leave_launch_idle(header, (int)(gridDim.x * gridDim.y * gridDim.z), (int)threadIdx.x);
     return;
   }
-  add_lora_fused_body<DT, R, G, 1>(
+  add_lora_fused_body<DT, R, G, 1, BY_ROW>(
       seg_starts, reinterpret_cast<const uint16_t* const*>(tab.A_ptrs[z]),
       reinterpret_cast<const uint16_t* const*>(tab.B_ptrs[z]),
       reinterpret_cast<const uint16_t*>(tab.x[z]), reinterpret_cast<uint16_t*>(tab.y[z]), kslice, cslice,
       h_in, h_out, n_tokens, S, offA, offB, exch + (long long)z * S * n_tokens * R, header, scale,
-      spin_limit, seg, (int)blockIdx.y);
+      spin_limit, seg, (int)blockIdx.y, n_segs);
 }
 
 // Workspace initialisation: zero everything, then start the generation at one so that the
@@ -439,11 +465,12 @@ hipError_t launch_workspace_init(void* p, size_t bytes, size_t header_offset, hi
   return hipGetLastError();
 }
 
-template <class DT, int R, int G, int RB>
+template <class DT, int R, int G, int RB, bool BY_ROW>
 static hipError_t launch_fused_t(const FusedArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL((add_lora_fused_kernel<DT, R, G, RB>),
-                     dim3((unsigned)fused_grid_x(a.n_segs), (unsigned)a.S,
-                          (unsigned)((a.n_segs + fused_grid_x(a.n_segs) - 1) / fused_grid_x(a.n_segs))),
+  const int items = BY_ROW ? a.n_tokens : a.n_segs;
+  hipLaunchKernelGGL((add_lora_fused_kernel<DT, R, G, RB, BY_ROW>),
+                     dim3((unsigned)fused_grid_x(items), (unsigned)a.S,
+                          (unsigned)((items + fused_grid_x(items) - 1) / fused_grid_x(items))),
                      dim3(320), 0, st, a.seg_starts, (const uint16_t* const*)a.A_ptrs,
                      (const uint16_t* const*)a.B_ptrs, (const uint16_t*)a.x, (uint16_t*)a.y,
                      a.kslice, a.cslice, a.h_in, a.h_out, a.n_tokens, a.S, a.offA, a.offB, a.exch,
@@ -451,11 +478,12 @@ static hipError_t launch_fused_t(const FusedArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <class DT, int R, int G>
+template <class DT, int R, int G, bool BY_ROW>
 static hipError_t launch_fused_side_t(const FusedArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL((add_lora_fused_side_kernel<DT, R, G>),
-                     dim3((unsigned)fused_grid_x(a.n_segs), (unsigned)a.S,
-                          (unsigned)(fused_grid_items(a.n_segs) / fused_grid_x(a.n_segs) * a.n_proj)),
+  const int items = BY_ROW ? a.n_tokens : a.n_segs;
+  hipLaunchKernelGGL((add_lora_fused_side_kernel<DT, R, G, BY_ROW>),
+                     dim3((unsigned)fused_grid_x(items), (unsigned)a.S,
+                          (unsigned)(fused_grid_items(items) / fused_grid_x(items) * a.n_proj)),
                      dim3(320), 0, st, a.seg_starts, a.kslice, a.cslice, a.h_in, a.h_out, a.n_tokens, a.S,
                      a.offA, a.offB, a.exch, a.header, a.scale, a.spin_limit, a.n_segs, a.n_proj, a.table);
   return hipGetLastError();
@@ -463,8 +491,9 @@ static hipError_t launch_fused_side_t(const FusedArgs& a, hipStream_t st) {
 
 template <class DT, int R, int G>
 static hipError_t launch_fused_rb(const FusedArgs& a, hipStream_t st) {
-  if (a.n_proj > 0) return launch_fused_side_t<DT, R, G>(a, st);
-  return launch_fused_t<DT, R, G, 1>(a, st);
+  if (a.n_proj > 0) return a.by_rows ? launch_fused_side_t<DT, R, G, true>(a, st) : launch_fused_side_t<DT, R, G, false>(a, st);
+  if (a.by_rows) return launch_fused_t<DT, R, G, 1, true>(a, st);
+  return launch_fused_t<DT, R, G, 1, false>(a, st);
 }
 
 template <class DT, int R>

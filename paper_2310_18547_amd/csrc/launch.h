@@ -83,6 +83,7 @@ struct FusedArgs {
   int kslice, cslice;        // elements per k-slice / columns per column slice
   int G;                     // lane groups of the expand phase (1, 2, 4 or 8)
   int rows_per_pass;         // 1 when every segment is a single row, else 4
+  bool by_rows;              // the grid's items are the n_tokens rows, each looking its segment up, not the segments
   int spin_limit;            // polls before a waiting workgroup gives up
   long long offA, offB;      // layer offsets in elements
   float scale;

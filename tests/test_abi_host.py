@@ -216,12 +216,24 @@ def test_plan_single_launch_shapes():
     assert rc == 3                                   # one-row segments only
     rc, pl = _plan(64, n_tokens=64, max_seg_len=1, path=sg.PATH_WHOLE, h_in=11008)
     assert rc == 3                                   # input rows wider than a workgroup stages
-    # short multi-row segments: sixteen-row tiles, every workgroup resident
-    rc, pl = _plan(39, n_tokens=64, max_seg_len=5)
-    assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.launches == 1
-    assert pl.slices * 39 <= 256 and pl.workgroups == pl.slices * 39
-    assert 0 < pl.lds_bytes <= 160 * 1024
-    rc, pl = _plan(1, n_tokens=64, max_seg_len=64)
+    # short multi-row segments in a small batch (or segments of unknown length): the one-row kernel
+    # run per ROW of the batch, every row looking its segment up
+    for kw in (dict(n_tokens=64, max_seg_len=5), dict(n_tokens=64, max_seg_len=0), dict(n_tokens=64, max_seg_len=64)):
+        rc, pl = _plan(39, **kw)
+        assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and (pl.launches, pl.slices, pl.workgroups) == (1, 4, 256)
+    rc, pl = _plan(64, n_tokens=200, max_seg_len=0)          # ranks up to 16: up to 256 rows where the tile kernel is out
+    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and (pl.slices, pl.workgroups) == (2, 400)
+    rc, pl = _plan(39, n_tokens=64, max_seg_len=5, path=sg.PATH_ROWS)
+    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and pl.workgroups == 256
+    rc, pl = _plan(39, n_tokens=2000, max_seg_len=60, path=sg.PATH_ROWS)
+    assert rc == 3                                   # more rows than the launch takes workgroups
+    # in larger batches (or when asked for): sixteen-row tiles, every workgroup resident
+    for kw in (dict(n_tokens=64, max_seg_len=5, path=sg.PATH_FUSED), dict(n_tokens=300, max_seg_len=12)):
+        rc, pl = _plan(39, **kw)
+        assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.launches == 1
+        assert pl.slices * 39 <= 256 and pl.workgroups == pl.slices * 39
+        assert 0 < pl.lds_bytes <= 160 * 1024
+    rc, pl = _plan(1, n_tokens=64, max_seg_len=64, path=sg.PATH_FUSED)
     assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.workgroups == pl.slices * 4
     # without the prepared workspace the kernels with a hand-off are not taken
     rc, pl = _plan(64, n_tokens=64, max_seg_len=1, workspace_ready=0, r=64)
@@ -230,13 +242,15 @@ def test_plan_single_launch_shapes():
     assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR   # many short segments: work by rows, not by 64-row blocks
     rc, pl = _plan(16, n_tokens=128, max_seg_len=8, workspace_ready=0)
     assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX
-    # rank 64: the tile kernel up to eight rows per segment, then the MFMA kernels, which also take
-    # few short segments there
+    # rank 64: per row up to 64 rows; beyond, the tile kernel up to eight rows per segment, then the
+    # MFMA kernels, which also take few short segments there
     rc, pl = _plan(8, n_tokens=64, max_seg_len=8, r=64)
+    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and pl.workgroups == 256
+    rc, pl = _plan(12, n_tokens=96, max_seg_len=8, r=64)
     assert rc == 0 and pl.kernel == sg.KERNEL_TILE
-    rc, pl = _plan(4, n_tokens=64, max_seg_len=16, r=64)
+    rc, pl = _plan(6, n_tokens=96, max_seg_len=16, r=64)
     assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX and pl.launches == 3
-    rc, pl = _plan(39, n_tokens=64, max_seg_len=3, r=64)
+    rc, pl = _plan(39, n_tokens=96, max_seg_len=3, r=64)
     assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX
     rc, pl = _plan(128, n_tokens=512, max_seg_len=4, r=64)
     assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR
@@ -304,21 +318,36 @@ def test_plan_multi_projection_shapes():
     assert pl.workgroups == 4 * 64
     rc, pl = _plan(16, 4, n_tokens=16, max_seg_len=1)
     assert rc == 0 and pl.kernel == sg.KERNEL_MULTI_SIDE and pl.workgroups == 8 * 16 * 4
-    # segments of a few rows: the add-ons side by side in one launch of the tile kernel while
-    # their workgroups are all resident together, with fewer slices each if need be ...
+    # segments of a few rows in a small batch: per row, the add-ons side by side in one launch
     rc, pl = _plan(8, 3, n_tokens=16, max_seg_len=2)
+    assert rc == 0 and pl.kernel == sg.KERNEL_MULTI_SIDE and (pl.launches, pl.slices, pl.workgroups) == (1, 8, 8 * 16 * 3)
+    rc, pl = _plan(39, 3, n_tokens=64, max_seg_len=5)
+    assert rc == 0 and pl.kernel == sg.KERNEL_MULTI_SIDE and (pl.launches, pl.slices, pl.workgroups) == (1, 4, 4 * 64 * 3)
+    # 128 rows, three add-ons: the joint tile launch while it keeps at least four slices
+    rc, pl = _plan(16, 3, n_tokens=128, max_seg_len=8)
+    assert rc == 0 and pl.kernel == sg.KERNEL_TILE and (pl.launches, pl.slices, pl.workgroups) == (1, 5, 5 * 16 * 3)
+    rc, pl = _plan(64, 3, n_tokens=128, max_seg_len=2)
+    assert rc == 0 and pl.kernel == sg.KERNEL_MULTI_SIDE and (pl.launches, pl.slices) == (1, 2)
+    # the tile kernel when asked for: the add-ons side by side in one launch while their workgroups
+    # are all resident together, with fewer slices each if need be ...
+    rc, pl = _plan(8, 3, n_tokens=16, max_seg_len=2, path=sg.PATH_FUSED)
     assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.launches == 1
     assert pl.slices == 8 and pl.workgroups == 8 * 8 * 3
-    rc, pl = _plan(16, 3, n_tokens=64, max_seg_len=4)
+    rc, pl = _plan(16, 3, n_tokens=64, max_seg_len=4, path=sg.PATH_FUSED)
     assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.launches == 1
     assert pl.slices == 5 and pl.workgroups == 5 * 16 * 3
     # ... in groups where they do not all fit (here two, then the third by itself) ...
-    rc, pl = _plan(39, 3, n_tokens=64, max_seg_len=5)
+    rc, pl = _plan(39, 3, n_tokens=64, max_seg_len=5, path=sg.PATH_FUSED)
     assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.launches == 2
     assert pl.slices * 39 * 2 <= 256 and pl.workgroups == pl.slices * 39 * 2
     # ... and one add-on after the other beyond that
-    rc, pl = _plan(64, 3, n_tokens=128, max_seg_len=2)
+    rc, pl = _plan(64, 3, n_tokens=128, max_seg_len=2, path=sg.PATH_FUSED)
     assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.launches == 3
+    # rank 64, long segments, 64 rows or more: the joint tile launch (a single add-on takes the MFMA kernels)
+    rc, pl = _plan(8, 2, n_tokens=128, max_seg_len=16, r=64)
+    assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.launches == 1
+    rc, pl = _plan(8, 1, n_tokens=128, max_seg_len=16, r=64)
+    assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX
     rc, pl = _plan(64, 9, n_tokens=64, max_seg_len=1)
     assert rc == 2
     rc, pl = _plan(64, 0, n_tokens=64, max_seg_len=1)
@@ -347,8 +376,10 @@ def test_plan_agrees_with_the_resource_limits():
 def test_plan_tile_needs_resident_workgroups_and_lds():
     # 32 segments of up to 64 rows: four row blocks per segment leave two slices, whose weight
     # slices do not fit the LDS: the launch-per-step kernels take the call
-    rc, pl = _plan(32, n_tokens=248, max_seg_len=64)
+    rc, pl = _plan(32, n_tokens=248, max_seg_len=64, r=32)
     assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX
+    rc, pl = _plan(32, n_tokens=248, max_seg_len=64)          # up to rank 16 and 256 rows: per row
+    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and (pl.slices, pl.workgroups) == (2, 496)
     # a forced slice count that cannot be resident is not taken by the single-launch kernels
     rc, pl = _plan(64, n_tokens=640, max_seg_len=29, ksplit=8, path=sg.PATH_FUSED)
     assert rc == 3
@@ -357,7 +388,7 @@ def test_plan_tile_needs_resident_workgroups_and_lds():
 def test_plan_tile_counts_only_row_blocks_with_rows():
     # 17 segments, the longest of 29 rows (two row blocks): 34 blocks in the grid, but at most
     # 17 + 64/16 = 21 hold rows, so eight slices are resident (8 * 21 <= 256) in a grid of 272
-    rc, pl = _plan(17, n_tokens=64, max_seg_len=29)
+    rc, pl = _plan(17, n_tokens=64, max_seg_len=29, path=sg.PATH_FUSED)
     assert rc == 0 and pl.kernel == sg.KERNEL_TILE and (pl.slices, pl.workgroups) == (8, 272)
     # a grid far beyond one workgroup per compute unit is not taken
     rc, pl = _plan(8, n_tokens=1000, max_seg_len=300)

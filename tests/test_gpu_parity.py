@@ -82,7 +82,7 @@ def test_multi_on_popularity_mixes_is_one_tile_launch(kind, P, dtype, r):
     lens = np.diff(ws[0].seg_starts).tolist()
     ws = [ws[0]] + [wl.custom(lens, 1024, 1280, r, dtype, seed=610 + k, num_layers=2, scale=ws[0].scale)
                     for k in range(1, P)]
-    ds = [_dev(w) for w in ws]
+    ds = [_dev(w, path=B.PATH_FUSED) for w in ws]      # (left to itself, a batch this small runs per row)
     d0 = ds[0]
     plan = B.sgmv_plan_add_lora(d0.problem, ws[0].n_segs, P)
     assert plan.kernel == B.KERNEL_TILE and plan.launches == 1
@@ -99,6 +99,74 @@ def test_multi_on_popularity_mixes_is_one_tile_launch(kind, P, dtype, r):
     assert d0.check() == 0
 
 
+# the one-row kernel run per row of the batch, every row looking its segment up on the device
+@pytest.mark.parametrize("kind,dtype,r,h_in,h_out", [("uniform", "f16", 16, 4096, 4096), ("skewed", "bf16", 16, 4096, 4096),
+                                                     ("identical", "f16", 64, 1024, 2048), ("uniform_paper", "bf16", 32, 2048, 1032),
+                                                     ("skewed_paper", "f16", 8, 4096, 4096)])
+def test_rows_path_on_popularity_mixes(kind, dtype, r, h_in, h_out):
+    from paper_2310_18547_amd import binding as B
+    w = wl.popularity(kind, batch=64, h_in=h_in, h_out=h_out, r=r, dtype=dtype, num_layers=2, seed=77)
+    d = _dev(w, path=B.PATH_ROWS)
+    plan = B.sgmv_plan_add_lora(d.problem, w.n_segs)
+    assert plan.kernel == B.KERNEL_FUSED and plan.launches == 1 and plan.workgroups == plan.slices * 64
+    ref = oracle.run_workload(w, layer_idx=1, n_threads=8)
+    d.add_lora(1)
+    assert_parity(d.y_bits(), ref, dtype, f"{kind} per row")
+    assert d.check() == 0
+
+
+def test_rows_path_with_empty_segments_missing_adapters_and_many_segments():
+    from paper_2310_18547_amd import binding as B
+    # 150 segments (more than one wave's worth of segment ends), many of them empty, for 90 rows
+    rng = np.random.default_rng(5)
+    lens = [int(v) for v in rng.integers(0, 3, 150)]
+    lens[149] += 90 - sum(lens) if sum(lens) < 90 else 0
+    while sum(lens) > 90:
+        i = int(rng.integers(0, 150))
+        if lens[i] > 0:
+            lens[i] -= 1
+    adapters = [int(v) for v in rng.integers(-1, 6, 150)]
+    w = wl.custom(lens, 1024, 1024, 16, "bf16", seed=78, num_layers=2, seg_adapter=adapters, scale=0.5)
+    assert w.n_tokens == 90
+    ref = oracle.run_workload(w, layer_idx=0, n_threads=8)
+    for hint in (None, 0, 1):          # the hint is not consulted
+        d = _dev(w, path=B.PATH_ROWS, max_seg_len=hint)
+        d.add_lora(0)
+        assert_parity(d.y_bits(), ref, "bf16", f"per row, hint {hint}")
+        assert d.check() == 0
+    # more rows than a launch of this kernel takes workgroups: refused, not run another way
+    big = wl.custom([3] * 400, 256, 256, 16, "bf16", seed=79)
+    with pytest.raises(B.SgmvError) as e:
+        _dev(big, path=B.PATH_ROWS).add_lora(0)
+    assert e.value.status == 3
+
+
+# several add-ons per call with every row looking its segment up: side by side in one launch
+@pytest.mark.parametrize("kind,P,dtype,r,path", [("uniform", 2, "f16", 16, "rows"), ("skewed", 3, "bf16", 16, "auto"),
+                                                 ("identical", 4, "f16", 8, "auto"), ("uniform_paper", 2, "bf16", 32, "rows"),
+                                                 ("skewed_paper", 3, "f16", 64, "auto")])
+def test_multi_per_row_on_popularity_mixes(kind, P, dtype, r, path):
+    from paper_2310_18547_amd import binding as B
+    batch = 24 if r == 64 else 40
+    w0 = wl.popularity(kind, batch=batch, h_in=1024, h_out=1280, r=r, dtype=dtype, num_layers=2, seed=640)
+    lens = np.diff(w0.seg_starts).tolist()
+    ws = [w0] + [wl.custom(lens, 1024, 1280, r, dtype, seed=650 + k, num_layers=2, scale=w0.scale,
+                           seg_adapter=[-1 if (k == 1 and i == 0) else i for i in range(len(lens))]) for k in range(1, P)]
+    ds = [_dev(w, path=B.PATH_ROWS if path == "rows" else B.PATH_AUTO) for w in ws]
+    d0 = ds[0]
+    plan = B.sgmv_plan_add_lora(d0.problem, w0.n_segs, P)
+    if path == "rows":
+        assert plan.kernel == B.KERNEL_MULTI_SIDE and plan.launches == 1 and plan.workgroups == plan.slices * batch * P
+    for layer in (1, 0):
+        B.sgmv_add_lora_multi(d0.problem, [q.y[0] for q in ds], [q.x[0] for q in ds], [q.A_ptrs for q in ds],
+                              [q.B_ptrs for q in ds], d0.seg_starts, w0.n_segs, layer, w0.scale)
+        torch.cuda.synchronize()
+        assert d0.check() == 0
+        if layer == 1:
+            for k, (w, q) in enumerate(zip(ws, ds)):
+                assert_parity(q.y_bits(), oracle.run_workload(w, layer_idx=1, n_threads=8), dtype, f"{kind}: add-on {k} of {P}")
+
+
 # more add-ons than fit side by side: groups of as many as fit, what is left over in a smaller launch
 @pytest.mark.parametrize("n,rows,P,dtype,r,launches", [(60, 2, 5, "f16", 16, 2), (60, 2, 7, "bf16", 16, 2),
                                                        (40, 3, 8, "f16", 32, 3)])
@@ -107,10 +175,11 @@ def test_multi_on_segments_of_a_few_rows_in_groups(n, rows, P, dtype, r, launche
     lens = [rows] * n
     lens[3] = 0
     lens[7] = rows - 1
-    ws = [wl.custom(lens, 1024, 1280, r, dtype, seed=700 + k, num_layers=2) for k in range(P)]
-    ds = [_dev(w) for w in ws]
+    # the second add-on has no adapter for one of the segments: its rows of that y stay as they are
+    ws = [wl.custom(lens, 1024, 1280, r, dtype, seed=700 + k, num_layers=2,
+                    seg_adapter=[-1 if (k == 1 and i == 5) else i for i in range(n)]) for k in range(P)]
+    ds = [_dev(w, path=B.PATH_FUSED) for w in ws]
     d0 = ds[0]
-    d0.problem.max_seg_len = rows
     plan = B.sgmv_plan_add_lora(d0.problem, n, P)
     assert plan.kernel == B.KERNEL_TILE and plan.launches == launches
     for layer in (1, 0):    # the second call on the next generation, into the already updated outputs
@@ -1068,12 +1137,12 @@ def test_random_shapes_every_path(seed):
     from paper_2310_18547_amd import binding as B
     w, dtype, hint = _random_case(seed)
     ref = oracle.run_workload(w, layer_idx=1, n_threads=8)
-    for path in (B.PATH_AUTO, B.PATH_VECTOR, B.PATH_MATRIX, B.PATH_FUSED, B.PATH_WHOLE):
+    for path in (B.PATH_AUTO, B.PATH_VECTOR, B.PATH_MATRIX, B.PATH_FUSED, B.PATH_WHOLE, B.PATH_ROWS):
         d = _dev(w, path=path, max_seg_len=1 if path == B.PATH_WHOLE else hint)   # that kernel insists on the hint
         try:
             d.add_lora(1)
         except B.SgmvError as e:
-            assert path in (B.PATH_FUSED, B.PATH_WHOLE) and e.status == 3, (seed, path, e)   # single launch not applicable
+            assert path in (B.PATH_FUSED, B.PATH_WHOLE, B.PATH_ROWS) and e.status == 3, (seed, path, e)   # single launch not applicable
             continue
         assert_parity(d.y_bits(), ref, dtype, f"seed {seed} path {path} hint {hint} lens {w.seg_starts.tolist()}")
         assert d.check() == 0
