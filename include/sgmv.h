@@ -127,7 +127,9 @@ typedef struct sgmv_problem {
   int32_t n_tokens;          /* rows of x / y / v, = seg_starts[n_segs]             */
   int32_t max_seg_len;       /* longest segment, a hint for launch shape and path;  */
                              /* 0 = unknown.  A wrong hint costs speed, never       */
-                             /* correctness.                                        */
+                             /* correctness.  Batches of up to 64 rows (more at     */
+                             /* ranks below 64) run in one launch whatever it says, */
+                             /* unless it is 1, see SGMV_PATH_ROWS.                 */
   int32_t path;              /* sgmv_path, normally SGMV_PATH_AUTO                  */
   int32_t ksplit;            /* split-K factor of shrink; 0 = choose automatically  */
   int32_t expand_threads;    /* workgroup size of the vector expand kernel          */
@@ -146,7 +148,8 @@ typedef struct sgmv_problem {
 /* Kernel family a call resolves to (sgmv_plan_add_lora). */
 typedef enum {
   SGMV_KERNEL_NONE = 0,             /* nothing to launch (no segments or no rows)          */
-  SGMV_KERNEL_FUSED = 1,            /* single launch, one row per segment, vector ALUs     */
+  SGMV_KERNEL_FUSED = 1,            /* single launch, vector ALUs: a set of workgroups per */
+                                    /* one-row segment, or per row of a small batch        */
   SGMV_KERNEL_TILE = 2,             /* single launch, sixteen-row MFMA tiles               */
   SGMV_KERNEL_MULTI_SIDE = 3,       /* several projections side by side in one launch      */
   SGMV_KERNEL_MULTI_PIPELINED = 4,  /* several projections walked by every workgroup       */
@@ -291,7 +294,8 @@ int sgmv_add_lora_static(const sgmv_problem* p, void* y, const void* x,
  *   A_ptrs, B_ptrs  HOST arrays of n_proj device pointers, each to a device
  *                   array of n_segs weight pointers as in sgmv_add_lora
  * With workspace_ready set and max_seg_len == 1 (every request its own
- * adapter) all add-ons run in ONE kernel launch; so do segments of a few rows
+ * adapter) all add-ons run in ONE kernel launch; so do small batches of longer
+ * segments (per row, as under SGMV_PATH_ROWS) and segments of a few rows
  * (max_seg_len from 2 up to what the single-launch MFMA kernel takes) while the
  * workgroups of all add-ons fit on the chip together, and in groups of as many
  * as fit beyond that.  On long segments (the MFMA
