@@ -221,7 +221,8 @@ int sgmv_validate_segments(const int32_t* host_seg_starts, int32_t n_segs, int32
  *   x      device 16-bit [n_tokens][h_in], read
  *   A_ptrs device array of n_segs device pointers
  * Uses p->workspace.  h_out of the descriptor is ignored.  With SGMV_PATH_AUTO, a
- * prepared workspace (workspace_ready) and max_seg_len == 1 the call is one launch whose
+ * prepared workspace (workspace_ready) and max_seg_len == 1 (or a batch of at most 64
+ * rows, more at ranks below 64, whatever the segment lengths) the call is one launch whose
  * workgroups hand their Split-K partial sums to each other (bounded wait: a time-out is
  * reported by sgmv_workspace_check and leaves the affected rows of v as they were);
  * otherwise two launches, partial sums and their sum. */
@@ -322,8 +323,9 @@ int sgmv_plan_add_lora(const sgmv_problem* p, int32_t n_segs, int32_t n_proj, sg
 
 /* The same for the stand-alone sgmv_shrink (section "Segmented Gather Matrix-Vector
  * Multiplication", the shrink launch): SGMV_KERNEL_FUSED with one launch when one-row
- * segments are reduced inside the launch by the hand-off between workgroups (needs a
- * prepared workspace, max_seg_len == 1 and SGMV_PATH_AUTO), else SGMV_KERNEL_MATRIX or
+ * segments, or the rows of a small batch of longer ones, are reduced inside the launch
+ * by the hand-off between workgroups (needs a prepared workspace and SGMV_PATH_AUTO;
+ * max_seg_len == 1, or at most 64 rows, 128 up to rank 32, 256 up to rank 16), else SGMV_KERNEL_MATRIX or
  * SGMV_KERNEL_VECTOR with two launches (partial sums, then their sum).  Host-only, pure. */
 int sgmv_plan_shrink(const sgmv_problem* p, int32_t n_segs, sgmv_plan* plan);
 

@@ -622,6 +622,16 @@ int plan_shrink(const sgmv_problem* p, int n_segs, ShrinkPlan* pl) {
     pl->kernel = SGMV_KERNEL_FUSED;
     return SGMV_OK;
   }
+  // small batches of longer segments (or of unknown length): the same launch per row of the
+  // batch, as for the add-on (rows_apply; measured at h = 4096 against the better of the
+  // launch-per-step kernels: rank 16, Uniform / Skewed / Identical of 64 rows 4.6 / 4.4 / 4.1 against
+  // 7.7 / 7.3 / 6.7 us, of 256 rows 5.5 / 5.7 / 4.8 against 8.6 / 9.5 / 6.9; rank 64, 64 rows: 7.0 /
+  // 6.5 / 5.6 against 10.5 / 10.9 / 9.8)
+  if (p->path == SGMV_PATH_AUTO && rows_apply(p, false, 0) &&
+      choose_fused(&shrink_only, p->n_tokens, &pl->fused, true, true)) {
+    pl->kernel = SGMV_KERNEL_FUSED;
+    return SGMV_OK;
+  }
   if (use_matrix(p, n_segs)) {
     choose_split_matrix(p, n_segs, &pl->ksplit, &pl->kslice);
     pl->kernel = SGMV_KERNEL_MATRIX;
@@ -1137,7 +1147,7 @@ int sgmv_plan_shrink(const sgmv_problem* p, int32_t n_segs, sgmv_plan* plan) {
   if (pl.kernel == SGMV_KERNEL_FUSED) {
     plan->launches = 1;
     plan->slices = pl.fused.S;
-    plan->workgroups = pl.fused.S * (int)fused_grid_items(n_segs);
+    plan->workgroups = pl.fused.S * (int)fused_grid_items(pl.fused.by_rows ? p->n_tokens : n_segs);
   } else {
     plan->launches = 2;
     plan->slices = pl.ksplit;

@@ -17,7 +17,10 @@ namespace sgmv {
 
 // grid (fused_grid_x, S, rows of segments), 320 threads: four stream waves, one exchange wave.
 //   exch   [S][n_tokens][R] 64-bit words {fp32 value (high), tag (low)}
-template <class DT, int R>
+// BY_ROW: the grid's items are the n_tokens rows of the batch, not its segments; a row's
+// workgroups look the row's segment up in seg_starts, so segments may have any length, and an
+// XCD (blockIdx.x) takes a run of consecutive rows (as in the add-on kernel, fused_kernel.hip).
+template <class DT, int R, bool BY_ROW>
 __global__ __launch_bounds__(320) void shrink_handoff_kernel(
     const int32_t* __restrict__ seg_starts, const uint16_t* const* __restrict__ A_ptrs,
     const uint16_t* __restrict__ x, float* __restrict__ v, int kslice, int h_in, int n_tokens, int S,
@@ -32,13 +35,31 @@ __global__ __launch_bounds__(320) void shrink_handoff_kernel(
   const int n_workgroups = (int)(gridDim.x * gridDim.y * gridDim.z);
   // blockIdx.x is the fastest-varying part of the linear id by which workgroups are dealt to
   // the XCDs, so the S workgroups of a segment share an XCD
-  const int seg = blockIdx.z * gridDim.x + blockIdx.x, s = blockIdx.y;
-  if (seg >= n_segs) {  // the grid is padded to whole rows of segments
+  const int item = BY_ROW ? blockIdx.x * gridDim.z + blockIdx.z : blockIdx.z * gridDim.x + blockIdx.x;
+  const int s = blockIdx.y;
+  if (item >= (BY_ROW ? n_tokens : n_segs)) {  // the grid is padded to whole rows of items
     if (wave == 0) leave_launch_idle(header, n_workgroups, lane);
     return;
   }
-  const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
-  const uint16_t* A = A_ptrs[seg];
+  int lo, hi;
+  const uint16_t* A;
+  if constexpr (BY_ROW) {
+    // the row's segment: the number of segment ends at or before the row, one end per lane
+    int found = 0;
+    for (int base = 0; base < n_segs; base += 64) {
+      const int i = base + lane;
+      const int end = i < n_segs ? seg_starts[i + 1] : 0x7fffffff;
+      found += __popcll(__ballot(end <= item));
+    }
+    found = __builtin_amdgcn_readfirstlane(found);
+    lo = item;
+    hi = found < n_segs ? item + 1 : item;  // a row behind the last segment end: nothing to do
+    A = found < n_segs ? A_ptrs[found] : nullptr;
+  } else {
+    lo = seg_starts[item];
+    hi = seg_starts[item + 1];
+    A = A_ptrs[item];
+  }
   if (lo >= hi || A == nullptr) {  // same decision in all S workgroups
     if (wave == 0) leave_launch_idle(header, n_workgroups, lane);
     return;
@@ -128,13 +149,19 @@ __global__ __launch_bounds__(320) void shrink_handoff_kernel(
   }
 }
 
-template <class DT, int R>
-static hipError_t launch_shrink_handoff_t(const FusedArgs& a, float* v, hipStream_t st) {
-  const int gx = fused_grid_x(a.n_segs);
-  hipLaunchKernelGGL((shrink_handoff_kernel<DT, R>), dim3((unsigned)gx, (unsigned)a.S, (unsigned)((a.n_segs + gx - 1) / gx)),
+template <class DT, int R, bool BY_ROW>
+static hipError_t launch_shrink_handoff_b(const FusedArgs& a, float* v, hipStream_t st) {
+  const int items = BY_ROW ? a.n_tokens : a.n_segs;
+  const int gx = fused_grid_x(items);
+  hipLaunchKernelGGL((shrink_handoff_kernel<DT, R, BY_ROW>), dim3((unsigned)gx, (unsigned)a.S, (unsigned)((items + gx - 1) / gx)),
                      dim3(320), 0, st, a.seg_starts, (const uint16_t* const*)a.A_ptrs, (const uint16_t*)a.x, v,
                      a.kslice, a.h_in, a.n_tokens, a.S, a.offA, a.exch, a.header, a.spin_limit, a.n_segs);
   return hipGetLastError();
+}
+
+template <class DT, int R>
+static hipError_t launch_shrink_handoff_t(const FusedArgs& a, float* v, hipStream_t st) {
+  return a.by_rows ? launch_shrink_handoff_b<DT, R, true>(a, v, st) : launch_shrink_handoff_b<DT, R, false>(a, v, st);
 }
 
 template <class DT>

@@ -259,6 +259,24 @@ def test_shrink_single_launch_wrong_hint_and_missing_adapters():
     assert d.check() == 0
 
 
+@pytest.mark.parametrize("kind,dtype,r,h_in,hint", [("uniform", "f16", 16, 4096, None), ("skewed", "bf16", 64, 2048, 0),
+                                                    ("identical", "f16", 8, 1000, None), ("skewed_paper", "bf16", 32, 5120, None)])
+def test_shrink_single_launch_per_row_on_popularity_mixes(kind, dtype, r, h_in, hint):
+    # small batches of longer segments: the same single launch per row of the batch, every row
+    # looking its segment up (the hint is not needed)
+    from paper_2310_18547_amd import binding as B
+    w = wl.popularity(kind, batch=48, h_in=h_in, h_out=64, r=r, dtype=dtype, num_layers=2, seed=91)
+    d = _dev(w, max_seg_len=hint)
+    plan = B.sgmv_plan_shrink(d.problem, w.n_segs)
+    assert plan.kernel == B.KERNEL_FUSED and plan.launches == 1 and plan.workgroups == plan.slices * 48
+    v0 = np.random.Generator(np.random.PCG64(3)).standard_normal((48, r)).astype(np.float32)
+    v = torch.from_numpy(v0.copy()).to("cuda:0")
+    d.shrink(v, 1)
+    ref = oracle.run_workload(w, op="shrink", layer_idx=1, v=v0.copy(), n_threads=8)
+    assert np.all(np.abs(v.cpu().numpy() - ref) <= 2e-3 + 2e-2 * np.abs(ref))
+    assert d.check() == 0
+
+
 def test_shrink_single_launch_gives_up_without_storing():
     # the bounded wait of the single-launch shrink, forced from the host as for the add-on kernels:
     # workgroup 0 tags its partial sums with a generation its neighbours do not expect, the collecting
