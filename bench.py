@@ -464,10 +464,11 @@ def bench_one(args, op, d, w, probe):
         if plan.kernel == B.KERNEL_MATRIX:
             kernel = kernel.replace("expand_matrix_kernel", expand_kernel_name(w))
     else:
-        long_segments = w.max_seg_len >= 4
         if op == "shrink":  # asked of the library
             sp = B.sgmv_plan_shrink(d.problem, w.n_segs)
             long_segments = sp.kernel == B.KERNEL_MATRIX
+        else:
+            long_segments = B.sgmv_plan_expand(d.problem, w.n_segs).kernel == B.KERNEL_MATRIX
         kernel = {("shrink", False): "shrink_vector_kernel + shrink_reduce_kernel",
                   ("shrink", True): "shrink_stream_kernel + shrink_reduce_kernel",
                   ("expand", False): "expand_vector_kernel",

@@ -237,7 +237,9 @@ int sgmv_shrink(const sgmv_problem* p, float* v, const void* x,
  *   B_ptrs device array of n_segs device pointers
  * The vector kernels need no workspace; the MFMA kernels (SGMV_PATH_MATRIX, or
  * SGMV_PATH_AUTO with long segments and a workspace present) keep v's 16-bit
- * operand pairs in p->workspace.  h_in of the descriptor is ignored. */
+ * operand pairs in p->workspace.  h_in of the descriptor is ignored.  Small
+ * batches of segments longer than a row (sgmv_plan_expand) run a workgroup per
+ * row rather than per segment, so that few long segments still fill the chip. */
 int sgmv_expand(const sgmv_problem* p, void* y, const float* v,
                 const void* const* B_ptrs, const int32_t* seg_starts,
                 int32_t n_segs, int32_t layer_idx, float scale, void* stream);
@@ -328,6 +330,14 @@ int sgmv_plan_add_lora(const sgmv_problem* p, int32_t n_segs, int32_t n_proj, sg
  * max_seg_len == 1, or at most 64 rows, 128 up to rank 32, 256 up to rank 16), else SGMV_KERNEL_MATRIX or
  * SGMV_KERNEL_VECTOR with two launches (partial sums, then their sum).  Host-only, pure. */
 int sgmv_plan_shrink(const sgmv_problem* p, int32_t n_segs, sgmv_plan* plan);
+
+/* The same for the stand-alone sgmv_expand (same section, the expand launch):
+ * SGMV_KERNEL_VECTOR with one launch of a workgroup per segment and strip of columns
+ * (`slices` = strips) or, for a small batch of segments longer than a row (at most 64
+ * rows, 128 up to rank 32, 256 up to rank 16; SGMV_PATH_AUTO), per ROW and strip, the
+ * workgroups looking their row's segment up; SGMV_KERNEL_MATRIX with two launches
+ * (operand preparation, MFMA expand) for long segments with a workspace.  Host-only, pure. */
+int sgmv_plan_expand(const sgmv_problem* p, int32_t n_segs, sgmv_plan* plan);
 
 /* Measurement aid, not part of the operator: enqueue one plain kernel of known traffic on
  * `stream`, for the benchmark's attainable-bandwidth figure and for scaling a profiler's HBM

@@ -108,6 +108,8 @@ def _load():
     L.sgmv_plan_add_lora.restype = c.c_int
     L.sgmv_plan_shrink.argtypes = [P, c.c_int32, c.POINTER(SgmvPlan)]
     L.sgmv_plan_shrink.restype = c.c_int
+    L.sgmv_plan_expand.argtypes = [P, c.c_int32, c.POINTER(SgmvPlan)]
+    L.sgmv_plan_expand.restype = c.c_int
     return L
 
 
@@ -219,6 +221,17 @@ def sgmv_add_lora_multi(p: SgmvProblem, ys, xs, A_ptrs, B_ptrs, seg_starts, n_se
     if check and rc != 0:
         raise SgmvError(rc, "sgmv_add_lora_multi")
     return rc
+
+
+def sgmv_plan_expand(p: SgmvProblem, n_segs: int, check: bool = True):
+    """Host-only: the ``SgmvPlan`` of a stand-alone ``sgmv_expand`` (``check=False``: ``(status, plan)``)."""
+    plan = SgmvPlan()
+    rc = lib.sgmv_plan_expand(ctypes.byref(p), n_segs, ctypes.byref(plan))
+    if not check:
+        return rc, plan
+    if rc != 0:
+        raise SgmvError(rc, "sgmv_plan_expand")
+    return plan
 
 
 def sgmv_plan_shrink(p: SgmvProblem, n_segs: int, check: bool = True):

@@ -169,6 +169,17 @@ bool use_matrix(const sgmv_problem* p, int n_segs) {
   return len >= kMatrixMinSegLen;
 }
 
+// The stand-alone expand at rank 64 is ahead on the MFMA kernels for more short segments than the
+// shrink and the add-on are (h = 4096, 64 segments of 2 / 4 rows: 12.4 / 12.7 us against 16.1 / 20.4
+// on the vector kernel; Uniform mix of 128 rows, 56 segments: 11.8 against 27.3; 128 segments of 2
+// rows: 20.3 against 20.6).
+bool expand_use_matrix(const sgmv_problem* p, int n_segs) {
+  if (use_matrix(p, n_segs)) return true;
+  if (p->path != SGMV_PATH_AUTO || p->r < 64 || n_segs > 128) return false;
+  const int len = p->max_seg_len > 0 ? p->max_seg_len : p->n_tokens / (n_segs > 0 ? n_segs : 1);
+  return len >= 2;
+}
+
 // Split-K shape of the MFMA shrink: row blocks of 64 rows times ksplit slices should
 // give every compute unit a workgroup; slices are multiples of the MFMA depth (32).
 void choose_split_matrix(const sgmv_problem* p, int n_segs, int* ksplit, int* kslice) {
@@ -502,6 +513,7 @@ ExpandArgs make_expand(const sgmv_problem* p, void* y, const float* v_parts, int
   a.undo = nullptr;
   a.operands_ready = false;
   a.header = nullptr;
+  a.by_rows = false;
   return a;
 }
 
@@ -530,6 +542,16 @@ bool rows_apply(const sgmv_problem* p, bool tile, int tile_slices) {
   if (p->n_tokens <= 128) return p->r <= 32;
   if (p->n_tokens <= 256) return p->r <= 16 && (!tile || tile_slices < 8);
   return false;
+}
+
+// The stand-alone expand of a small batch of longer segments (or of unknown length): a workgroup
+// per row and column strip instead of per segment, as the add-on does (rows_apply); no workspace
+// is involved.
+bool expand_by_rows(const sgmv_problem* p) {
+  if (p->path != SGMV_PATH_AUTO || p->max_seg_len == 1) return false;
+  if (p->n_tokens <= 64) return true;
+  if (p->n_tokens <= 128) return p->r <= 32;
+  return p->n_tokens <= 256 && p->r <= 16;
 }
 
 // What sgmv_add_lora will launch for a checked problem: the single source of the path
@@ -838,7 +860,12 @@ int sgmv_expand(const sgmv_problem* p, void* y, const float* v, const void* cons
   // the MFMA kernels keep v's 16-bit operand pairs in the workspace
   const bool have_ws = check_workspace(p) == SGMV_OK;
   if (p->path == SGMV_PATH_MATRIX && !have_ws) return check_workspace(p);
-  if (have_ws && use_matrix(p, n_segs)) {
+  const int strips_threads = expand_by_rows(p) ? choose_expand_threads(p, p->n_tokens) : 0;
+  if (strips_threads != 0) {
+    a.by_rows = true;
+    a.threads = strips_threads;
+    if (launch_expand_vector(a, st) != hipSuccess) return SGMV_ERR_LAUNCH;
+  } else if (have_ws && expand_use_matrix(p, n_segs)) {
     set_operands(&a, caller_scratch(p), p->n_tokens, p->r);
     if (launch_expand_matrix(a, st) != hipSuccess) return SGMV_ERR_LAUNCH;
   } else {
@@ -1152,6 +1179,30 @@ int sgmv_plan_shrink(const sgmv_problem* p, int32_t n_segs, sgmv_plan* plan) {
     plan->launches = 2;
     plan->slices = pl.ksplit;
   }
+  return SGMV_OK;
+}
+
+int sgmv_plan_expand(const sgmv_problem* p, int32_t n_segs, sgmv_plan* plan) {
+  if (plan == nullptr) return SGMV_ERR_NULL;
+  *plan = sgmv_plan{};
+  static const int32_t no_segments[2] = {0, 0};  // only tested for being non-NULL
+  const int rc = check_common(p, no_segments, n_segs, 0, false, true);
+  if (rc != SGMV_OK) return rc;
+  if (n_segs == 0 || p->n_tokens == 0) return SGMV_OK;  // nothing is launched
+  if (p->path == SGMV_PATH_FUSED || p->path == SGMV_PATH_WHOLE || p->path == SGMV_PATH_ROWS) return SGMV_ERR_UNSUPPORTED;
+  const bool have_ws = check_workspace(p) == SGMV_OK;
+  if (p->path == SGMV_PATH_MATRIX && !have_ws) return check_workspace(p);
+  if (!expand_by_rows(p) && have_ws && expand_use_matrix(p, n_segs)) {
+    plan->kernel = SGMV_KERNEL_MATRIX;
+    plan->launches = 2;  // operand preparation, expand
+    return SGMV_OK;
+  }
+  const bool by_rows = expand_by_rows(p);
+  const int threads = choose_expand_threads(p, by_rows ? p->n_tokens : n_segs);
+  plan->kernel = SGMV_KERNEL_VECTOR;
+  plan->launches = 1;
+  plan->slices = ceil_div(p->h_out, threads * 8);  // column strips
+  plan->workgroups = plan->slices * (by_rows ? ceil_div(p->n_tokens, 8) * 8 : n_segs);
   return SGMV_OK;
 }
 

@@ -49,6 +49,7 @@ struct ExpandArgs {
   bool bf16;
   int r, h_out, n_tokens, n_segs;
   int threads;               // vector path: workgroup size
+  bool by_rows;              // vector path: a workgroup per row of the batch (it looks its segment up), not per segment
   int max_seg_len;           // hint, 0 = unknown
   long long layer_off;       // elements to add to every B pointer
   void* y;

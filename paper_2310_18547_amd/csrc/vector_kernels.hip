@@ -178,17 +178,39 @@ __global__ __launch_bounds__(256) void shrink_reduce_kernel(
 // parts in ascending order (nparts = 1 for a caller-supplied v).
 // A_ptrs may be nullptr (stand-alone expand); when given, a segment whose A
 // pointer is NULL is skipped like one whose B pointer is NULL.
-template <class DT, int R, int NT, int RB>
+// BY_ROW: grid = (rows of the batch rounded up to a multiple of eight, column strips): a
+// workgroup serves one row and looks the row's segment up (n_segs of them), so that a small
+// batch of long segments still fills the chip; blockIdx.x % 8, the XCD a workgroup lands on,
+// takes a run of consecutive rows, which then find their segment's weights in one L2.
+template <class DT, int R, int NT, int RB, bool BY_ROW>
 __global__ __launch_bounds__(NT) void expand_vector_kernel(
     uint16_t* __restrict__ y, const float* __restrict__ v_parts, int nparts,
     const uint16_t* const* __restrict__ A_ptrs, const uint16_t* const* __restrict__ B_ptrs,
     const int32_t* __restrict__ seg_starts, int h_out, int n_tokens, long long layer_off,
-    float scale) {
+    float scale, int n_segs) {
   constexpr int JC = R < 16 ? R : 16;  // weight rows held in registers at a time
   __shared__ float vs[RB][R];
 
-  const int seg = blockIdx.x, tid = threadIdx.x;
-  const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
+  const int tid = threadIdx.x;
+  int seg = blockIdx.x, lo, hi;
+  if constexpr (BY_ROW) {
+    const int row = ((int)blockIdx.x & 7) * ((int)gridDim.x >> 3) + ((int)blockIdx.x >> 3);
+    if (row >= n_tokens) return;
+    // the row's segment: the number of segment ends at or before the row, one end per lane
+    int found = 0;
+    for (int base = 0; base < n_segs; base += 64) {
+      const int i = base + (tid & 63);
+      const int end = i < n_segs ? seg_starts[i + 1] : 0x7fffffff;
+      found += __popcll(__ballot(end <= row));
+    }
+    seg = __builtin_amdgcn_readfirstlane(found);
+    if (seg >= n_segs) return;  // a row behind the last segment end
+    lo = row;
+    hi = row + 1;
+  } else {
+    lo = seg_starts[seg];
+    hi = seg_starts[seg + 1];
+  }
   if (lo >= hi) return;
   const uint16_t* B = B_ptrs[seg];
   if (B == nullptr) return;
@@ -313,11 +335,18 @@ hipError_t launch_shrink_reduce(float* v, const ShrinkArgs& a, hipStream_t st) {
 template <class DT, int R, int NT>
 static hipError_t launch_expand_t(const ExpandArgs& a, hipStream_t st) {
   constexpr int RB = 4;
-  dim3 grid((unsigned)a.n_segs, (unsigned)((a.h_out + NT * 8 - 1) / (NT * 8)));
-  hipLaunchKernelGGL((expand_vector_kernel<DT, R, NT, RB>), grid, dim3(NT), 0, st,
+  const unsigned strips = (unsigned)((a.h_out + NT * 8 - 1) / (NT * 8));
+  if (a.by_rows) {
+    hipLaunchKernelGGL((expand_vector_kernel<DT, R, NT, 1, true>), dim3((unsigned)((a.n_tokens + 7) / 8 * 8), strips),
+                       dim3(NT), 0, st, (uint16_t*)a.y, a.v_parts, a.nparts, (const uint16_t* const*)a.A_ptrs,
+                       (const uint16_t* const*)a.B_ptrs, a.seg_starts, a.h_out, a.n_tokens, a.layer_off, a.scale,
+                       a.n_segs);
+    return hipGetLastError();
+  }
+  hipLaunchKernelGGL((expand_vector_kernel<DT, R, NT, RB, false>), dim3((unsigned)a.n_segs, strips), dim3(NT), 0, st,
                      (uint16_t*)a.y, a.v_parts, a.nparts, (const uint16_t* const*)a.A_ptrs,
                      (const uint16_t* const*)a.B_ptrs, a.seg_starts, a.h_out, a.n_tokens,
-                     a.layer_off, a.scale);
+                     a.layer_off, a.scale, a.n_segs);
   return hipGetLastError();
 }
 

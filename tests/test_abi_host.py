@@ -366,6 +366,36 @@ def test_plan_multi_projection_shapes():
     assert rc == 2
 
 
+def test_plan_expand():
+    """Stand-alone expand: a workgroup per segment (or, small batches of longer segments, per row) and
+    strip of columns, or the MFMA kernels for long segments with a workspace."""
+    p = sg.make_problem(sg.F16, 4096, 4096, 16, 1, 64, workspace=FAKE, workspace_bytes=1 << 30, max_seg_len=1,
+                        workspace_ready=1)
+    rc, pl = sg.sgmv_plan_expand(p, 64, check=False)
+    assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR and pl.launches == 1 and pl.workgroups == pl.slices * 64
+    p.h_in = 0                                        # the input width plays no part
+    assert sg.sgmv_plan_expand(p, 64, check=False)[0] == 0
+    p.max_seg_len = 29                                # 17 segments, 64 rows: per row (rows padded to eight)
+    rc, pl = sg.sgmv_plan_expand(p, 17, check=False)
+    assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR and pl.launches == 1 and pl.workgroups == pl.slices * 64
+    p.n_tokens = 61
+    rc, pl = sg.sgmv_plan_expand(p, 17, check=False)
+    assert rc == 0 and pl.workgroups == pl.slices * 64
+    p.path = sg.PATH_VECTOR                           # as asked: per segment
+    rc, pl = sg.sgmv_plan_expand(p, 17, check=False)
+    assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR and pl.workgroups == pl.slices * 17
+    p.path, p.n_tokens, p.max_seg_len = sg.PATH_AUTO, 1200, 300
+    rc, pl = sg.sgmv_plan_expand(p, 4, check=False)
+    assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX and pl.launches == 2
+    p.workspace, p.workspace_bytes, p.workspace_ready = None, 0, 0   # no workspace: the vector kernel
+    rc, pl = sg.sgmv_plan_expand(p, 4, check=False)
+    assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR
+    for path in (sg.PATH_FUSED, sg.PATH_WHOLE, sg.PATH_ROWS):
+        p.path = path
+        assert sg.sgmv_plan_expand(p, 4, check=False)[0] == 3
+    assert sg.lib.sgmv_plan_expand(None, 4, None) == 1
+
+
 def test_plan_agrees_with_the_resource_limits():
     """Every single-launch plan keeps all its workgroups resident: at most 256 (one per
     compute unit), or 512 for the side-by-side kernel; LDS within 160 KiB."""

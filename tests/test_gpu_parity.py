@@ -277,6 +277,35 @@ def test_shrink_single_launch_per_row_on_popularity_mixes(kind, dtype, r, h_in, 
     assert d.check() == 0
 
 
+@pytest.mark.parametrize("kind,dtype,r,h_out,hint", [("uniform", "f16", 16, 4096, None), ("skewed", "bf16", 64, 2056, 0),
+                                                     ("identical", "f16", 8, 1000, None), ("skewed_paper", "bf16", 32, 5120, None)])
+def test_expand_per_row_on_popularity_mixes(kind, dtype, r, h_out, hint):
+    # small batches of longer segments: a workgroup per row and strip of columns, the row's segment looked up
+    from paper_2310_18547_amd import binding as B
+    w = wl.popularity(kind, batch=45, h_in=64, h_out=h_out, r=r, dtype=dtype, num_layers=2, seed=92, scale=0.5)
+    d = _dev(w, max_seg_len=hint)
+    plan = B.sgmv_plan_expand(d.problem, w.n_segs)
+    assert plan.kernel == B.KERNEL_VECTOR and plan.launches == 1 and plan.workgroups == plan.slices * 48
+    v0 = np.random.Generator(np.random.PCG64(4)).standard_normal((45, r)).astype(np.float32)
+    v = torch.from_numpy(v0.copy()).to("cuda:0")
+    d.expand(v, 1)
+    ref = oracle.run_workload(w, op="expand", layer_idx=1, v=v0.copy(), n_threads=8)
+    assert_parity(d.y_bits(), ref, dtype, f"{kind}: expand per row")
+
+
+def test_expand_per_row_with_empty_segments_and_missing_adapters():
+    lens = [0, 3, 0, 0, 5, 1, 0, 2, 7, 0]
+    w = wl.custom(lens, 64, 520, 16, "f16", seed=93, num_layers=2, seg_adapter=[0, 1, 2, 3, -1, 4, 5, 6, 7, 8])
+    d = _dev(w)
+    v0 = np.random.Generator(np.random.PCG64(5)).standard_normal((w.n_tokens, 16)).astype(np.float32)
+    y0 = d.y_bits().copy()
+    d.expand(torch.from_numpy(v0.copy()).to("cuda:0"), 1)
+    ref = oracle.run_workload(w, op="expand", layer_idx=1, v=v0.copy())
+    got = d.y_bits()
+    assert_parity(got, ref, "f16", "expand per row, ragged")
+    assert np.array_equal(got[3:8], y0[3:8])          # the rows of the segment without an adapter
+
+
 def test_shrink_single_launch_gives_up_without_storing():
     # the bounded wait of the single-launch shrink, forced from the host as for the add-on kernels:
     # workgroup 0 tags its partial sums with a generation its neighbours do not expect, the collecting
