@@ -539,7 +539,11 @@ ExpandArgs make_expand(const sgmv_problem* p, void* y, const float* v_parts, int
 bool rows_apply(const sgmv_problem* p, bool tile, int tile_slices) {
   if (p->max_seg_len == 1 || p->ksplit != 0 || !p->workspace_ready) return false;
   if (p->n_tokens <= 64) return true;
-  if (p->n_tokens <= 128) return p->r <= 32;
+  // (rank 64 at 65 .. 128 rows: only at widths up to 4096 and where the tile kernel is out: Uniform
+  // of 128 rows 15.3 against 44.5 us, one segment of 128 rows 12.8 against 17.4, 32 x 4 rows 17.6
+  // against 19.6; with the tile kernel to choose from, 16 x 8 rows 16.6 against 15.5)
+  if (p->n_tokens <= 128)
+    return p->r <= 32 || (!tile && p->h_in <= 4096 && p->h_out <= 4096);
   if (p->n_tokens <= 256) return p->r <= 16 && (!tile || tile_slices < 8);
   return false;
 }
@@ -711,7 +715,9 @@ int plan_multi(const sgmv_problem* p, int n_segs, int n_proj, FusedArgs* f, Tile
   // 64 rows, two add-ons: 8 x 8 rows 13.1 against 15.7, Identical 11.4 against 20.8.
   // (at rank 32, 128 rows, two add-ons, the tile launch is ahead: one segment 10.9 against 12.2,
   // 16 x 8 rows 11.2 against 14.5)
-  const bool rows_first = per_row && (p->n_tokens <= 64 || ((long long)n_proj * p->n_tokens <= 256 && p->r <= 16));
+  // (and at rank 64 per row again, the tile kernel's hand-off being bound by its volume there: two
+  // segments of 64 rows 16.8 against 21.2, 16 x 8 rows 23.0 against 31.1 in two tile launches)
+  const bool rows_first = per_row && (p->n_tokens <= 64 || ((long long)n_proj * p->n_tokens <= 256 && p->r != 32));
   if (rows_first) {
     const int kernel = joint_rows();
     if (kernel != SGMV_KERNEL_SEQUENCE) return kernel;

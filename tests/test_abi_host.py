@@ -248,9 +248,11 @@ def test_plan_single_launch_shapes():
     assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and pl.workgroups == 256
     rc, pl = _plan(12, n_tokens=96, max_seg_len=8, r=64)
     assert rc == 0 and pl.kernel == sg.KERNEL_TILE
-    rc, pl = _plan(6, n_tokens=96, max_seg_len=16, r=64)
+    rc, pl = _plan(6, n_tokens=96, max_seg_len=16, r=64)         # the tile kernel is out: per row up to 128 rows at 4096
+    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and (pl.slices, pl.workgroups) == (2, 192)
+    rc, pl = _plan(6, n_tokens=96, max_seg_len=16, r=64, h_out=11008)
     assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX and pl.launches == 3
-    rc, pl = _plan(39, n_tokens=96, max_seg_len=3, r=64)
+    rc, pl = _plan(39, n_tokens=96, max_seg_len=3, r=64, h_in=5120, h_out=5120)
     assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX
     rc, pl = _plan(128, n_tokens=512, max_seg_len=4, r=64)
     assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR
@@ -355,11 +357,14 @@ def test_plan_multi_projection_shapes():
     # ... and one add-on after the other beyond that
     rc, pl = _plan(64, 3, n_tokens=128, max_seg_len=2, path=sg.PATH_FUSED)
     assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.launches == 3
-    # rank 64, long segments, 64 rows or more: the joint tile launch (a single add-on takes the MFMA kernels)
-    rc, pl = _plan(8, 2, n_tokens=128, max_seg_len=16, r=64)
+    # rank 64, long segments, 64 rows or more: the joint tile launch (a single add-on takes the MFMA kernels) ...
+    rc, pl = _plan(8, 3, n_tokens=128, max_seg_len=16, r=64)
     assert rc == 0 and pl.kernel == sg.KERNEL_TILE and pl.launches == 1
-    rc, pl = _plan(8, 1, n_tokens=128, max_seg_len=16, r=64)
+    rc, pl = _plan(8, 1, n_tokens=128, max_seg_len=16, r=64, h_in=8192, h_out=8192)
     assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX
+    # ... except two add-ons at widths up to 4096, which run per row side by side
+    rc, pl = _plan(8, 2, n_tokens=128, max_seg_len=16, r=64)
+    assert rc == 0 and pl.kernel == sg.KERNEL_MULTI_SIDE and (pl.slices, pl.workgroups) == (2, 512)
     rc, pl = _plan(64, 9, n_tokens=64, max_seg_len=1)
     assert rc == 2
     rc, pl = _plan(64, 0, n_tokens=64, max_seg_len=1)
