@@ -668,8 +668,9 @@ int plan_shrink(const sgmv_problem* p, int n_segs, ShrinkPlan* pl) {
   return SGMV_OK;
 }
 
-// Multi-projection call: SGMV_KERNEL_MULTI_SIDE / _PIPELINED with the launch shape in *f, or
-// SGMV_KERNEL_SEQUENCE (one sgmv_add_lora after the other).
+// Multi-projection call: SGMV_KERNEL_MULTI_SIDE / _PIPELINED with the launch shape in *f (per
+// segment, or per row of the batch when f->by_rows), SGMV_KERNEL_TILE with the shape in *t (groups
+// of t->n_proj add-ons per launch), or SGMV_KERNEL_SEQUENCE (one sgmv_add_lora after the other).
 int plan_multi(const sgmv_problem* p, int n_segs, int n_proj, FusedArgs* f, TileArgs* t) {
   const Limits lim = limits();
   const bool one_row = p->max_seg_len == 1;
