@@ -134,6 +134,26 @@ def test_rows_path_with_empty_segments_missing_adapters_and_many_segments():
         d.add_lora(0)
         assert_parity(d.y_bits(), ref, "bf16", f"per row, hint {hint}")
         assert d.check() == 0
+    # the same look-up over several rounds of segment ends in the stand-alone steps and in a joint launch
+    d = _dev(w)
+    assert B.sgmv_plan_shrink(d.problem, w.n_segs).kernel == B.KERNEL_FUSED
+    assert B.sgmv_plan_expand(d.problem, w.n_segs).workgroups % 96 == 0          # 90 rows rounded up to eights
+    v = torch.zeros(90, 16, dtype=torch.float32, device="cuda:0")
+    d.shrink(v, 0)
+    v_ref = oracle.run_workload(w, op="shrink", layer_idx=0, n_threads=8)
+    assert np.all(np.abs(v.cpu().numpy() - v_ref) <= 2e-3 + 2e-2 * np.abs(v_ref))
+    d.expand(v, 0)
+    assert_parity(d.y_bits(), ref, "bf16", "per row, shrink then expand")
+    w2 = wl.custom(lens, 1024, 1024, 16, "bf16", seed=80, num_layers=2, seg_adapter=adapters[::-1], scale=0.5)
+    ds = [_dev(w), _dev(w2)]
+    plan = B.sgmv_plan_add_lora(ds[0].problem, w.n_segs, 2)
+    assert plan.kernel == B.KERNEL_MULTI_SIDE and plan.launches == 1
+    B.sgmv_add_lora_multi(ds[0].problem, [q.y[0] for q in ds], [q.x[0] for q in ds], [q.A_ptrs for q in ds],
+                          [q.B_ptrs for q in ds], ds[0].seg_starts, w.n_segs, 0, 0.5)
+    torch.cuda.synchronize()
+    assert ds[0].check() == 0
+    assert_parity(ds[0].y_bits(), ref, "bf16", "per row, joint launch, first add-on")
+    assert_parity(ds[1].y_bits(), oracle.run_workload(w2, layer_idx=0, n_threads=8), "bf16", "per row, joint launch, second add-on")
     # more rows than a launch of this kernel takes workgroups: refused, not run another way
     big = wl.custom([3] * 400, 256, 256, 16, "bf16", seed=79)
     with pytest.raises(B.SgmvError) as e:
