@@ -197,6 +197,20 @@ __device__ __forceinline__ void buffer_store128(__amdgpu_buffer_rsrc_t rsrc, uin
   __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, (int)byte_off, 0, 0);
 }
 
+// Per-row launches: the segment that holds row `row`, i.e. the number of segment ends at or
+// before it (empty segments count themselves out); n_segs when the row lies behind the last end.
+// Every lane of the calling wave looks at one end per round, the loads of a round in flight
+// together; the result is wave-uniform.  seg_starts has n_segs + 1 non-decreasing entries.
+__device__ __forceinline__ int segment_of_row(const int32_t* __restrict__ seg_starts, int n_segs, int row, int lane) {
+  int found = 0;
+  for (int base = 0; base < n_segs; base += 64) {
+    const int i = base + lane;
+    const int end = i < n_segs ? seg_starts[i + 1] : 0x7fffffff;
+    found += __popcll(__ballot(end <= row));
+  }
+  return __builtin_amdgcn_readfirstlane(found);
+}
+
 // Workgroup barrier that orders LDS traffic only: outstanding global loads stay
 // outstanding.
 __device__ __forceinline__ void lds_barrier() {

@@ -89,15 +89,7 @@ __device__ __forceinline__ void add_lora_fused_body(
   int lo, hi;
   const uint16_t *A, *B;
   if constexpr (BY_ROW) {
-    // The row's segment is the number of segment ends at or before the row (empty segments
-    // count themselves out): every lane looks at one end, all loads of a wave in flight together.
-    int found = 0;
-    for (int base = 0; base < n_segs; base += 64) {
-      const int i = base + lane;
-      const int end = i < n_segs ? seg_starts[i + 1] : 0x7fffffff;
-      found += __popcll(__ballot(end <= seg));
-    }
-    found = __builtin_amdgcn_readfirstlane(found);
+    const int found = segment_of_row(seg_starts, n_segs, seg, lane);
     lo = seg;
     hi = found < n_segs ? seg + 1 : seg;  // a row behind the last segment end: nothing to do
     A = found < n_segs ? A_ptrs[found] : nullptr;

@@ -44,14 +44,7 @@ __global__ __launch_bounds__(320) void shrink_handoff_kernel(
   int lo, hi;
   const uint16_t* A;
   if constexpr (BY_ROW) {
-    // the row's segment: the number of segment ends at or before the row, one end per lane
-    int found = 0;
-    for (int base = 0; base < n_segs; base += 64) {
-      const int i = base + lane;
-      const int end = i < n_segs ? seg_starts[i + 1] : 0x7fffffff;
-      found += __popcll(__ballot(end <= item));
-    }
-    found = __builtin_amdgcn_readfirstlane(found);
+    const int found = segment_of_row(seg_starts, n_segs, item, lane);
     lo = item;
     hi = found < n_segs ? item + 1 : item;  // a row behind the last segment end: nothing to do
     A = found < n_segs ? A_ptrs[found] : nullptr;

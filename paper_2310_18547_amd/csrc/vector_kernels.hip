@@ -196,14 +196,7 @@ __global__ __launch_bounds__(NT) void expand_vector_kernel(
   if constexpr (BY_ROW) {
     const int row = ((int)blockIdx.x & 7) * ((int)gridDim.x >> 3) + ((int)blockIdx.x >> 3);
     if (row >= n_tokens) return;
-    // the row's segment: the number of segment ends at or before the row, one end per lane
-    int found = 0;
-    for (int base = 0; base < n_segs; base += 64) {
-      const int i = base + (tid & 63);
-      const int end = i < n_segs ? seg_starts[i + 1] : 0x7fffffff;
-      found += __popcll(__ballot(end <= row));
-    }
-    seg = __builtin_amdgcn_readfirstlane(found);
+    seg = segment_of_row(seg_starts, n_segs, row, tid & 63);
     if (seg >= n_segs) return;  // a row behind the last segment end
     lo = row;
     hi = row + 1;
