@@ -7,7 +7,8 @@ One *step* is the seven dense projections of one decoder layer (attention itself
 Distinct batch: every request has its own LoRA adapter on all seven projections.  ``--seq 1`` is the
 decode shape (one token per request); ``--seq 512`` / ``2048`` are the prefill shapes of the paper's
 transformer-layer benchmark: every request contributes a segment of that many rows (the paper
-applies LoRA to q, k, v, o, gate, up, down).  The
+applies LoRA to q, k, v, o, gate, up, down); ``--mix uniform|skewed|identical`` makes the decode
+batch share adapters the way the operator microbenchmark's popularity mixes do.  The
 backbone GEMMs are library calls (PyTorch matmul = rocBLAS / hipBLASLt); the add-ons are this
 library's kernels, issued three ways:
 
@@ -39,6 +40,9 @@ def main():
     ap.add_argument("--model", choices=sorted(MODELS), default="7b")
     ap.add_argument("--batch", type=int, default=64, help="requests, each with its own adapter")
     ap.add_argument("--seq", type=int, default=1, help="token rows per request (1 = decode)")
+    ap.add_argument("--mix", choices=["distinct", "uniform", "skewed", "identical"], default="distinct",
+                    help="adapter popularity over the --batch decode rows (the operator microbenchmark's mixes): "
+                         "rows that share an adapter form one segment")
     ap.add_argument("--rank", type=int, default=16)
     ap.add_argument("--layers", type=int, default=4, help="weight sets cycled through")
     ap.add_argument("--steps", type=int, default=200)
@@ -54,6 +58,14 @@ def main():
     h, ffn = MODELS[args.model]
     n_req, r, L = args.batch, args.rank, args.layers
     T = n_req * args.seq  # token rows: request i owns rows i * seq .. (i + 1) * seq - 1
+    seg_lens = [args.seq] * n_req
+    if args.mix != "distinct":
+        # decode rows of requests that share adapters: segments as the seeded workload generator draws them
+        assert args.seq == 1, "--mix describes a decode batch"
+        import sgmv_workloads as wl
+        starts = wl.popularity(args.mix, batch=args.batch, h_in=64, h_out=64, r=8, num_layers=1, seed=0).seg_starts
+        seg_lens = np.diff(starts).tolist()
+        n_req = len(seg_lens)  # adapters in the batch
     gen = torch.Generator(device=dev).manual_seed(0)
     f16 = torch.float16
 
@@ -82,7 +94,7 @@ def main():
     Bw = {n: pool(n_req, (L, r, o), r ** -0.5) for n, (i, o) in shapes.items()}
     A_ptrs = {n: torch.tensor([t.data_ptr() for t in A[n]], dtype=torch.int64, device=dev) for n in shapes}
     B_ptrs = {n: torch.tensor([t.data_ptr() for t in Bw[n]], dtype=torch.int64, device=dev) for n in shapes}
-    seg_starts = torch.arange(0, T + 1, args.seq, dtype=torch.int32, device=dev)
+    seg_starts = torch.tensor(np.concatenate(([0], np.cumsum(seg_lens))), dtype=torch.int32, device=dev)
     x = rnd(T, h)
     y = {n: torch.empty(T, o, dtype=f16, device=dev) for n, (i, o) in shapes.items()}
 
@@ -91,7 +103,7 @@ def main():
     B.sgmv_workspace_init(ws, ws_bytes)
     torch.cuda.synchronize()
     prob = {n: B.make_problem(B.F16, i, o, r, L, T, workspace=ws, workspace_bytes=ws_bytes,
-                              max_seg_len=args.seq, workspace_ready=1) for n, (i, o) in shapes.items()}
+                              max_seg_len=max(seg_lens), workspace_ready=1) for n, (i, o) in shapes.items()}
     stream = torch.cuda.Stream(device=dev)
     sh = stream.cuda_stream
 
@@ -164,8 +176,9 @@ def main():
     assert B.sgmv_workspace_check(ws, sh) == 0
     weights = sum(i * o for i, o in shapes.values()) * 2
     lora = sum((i * r + r * o) for i, o in shapes.values()) * 2 * n_req
-    out = {"benchmark": "decoder-layer dense projections + LoRA add-ons, Distinct adapters",
-           "model": args.model, "h": h, "ffn": ffn, "batch": n_req, "seq": args.seq, "tokens": T, "rank": r,
+    out = {"benchmark": "decoder-layer dense projections + LoRA add-ons",
+           "model": args.model, "h": h, "ffn": ffn, "batch": args.batch, "seq": args.seq, "mix": args.mix,
+           "adapters": n_req, "tokens": T, "rank": r,
            "layers_cycled": L,
            "steps": args.steps, "dtype": "f16", "data": "synthetic", "n_gpus": 1,
            "backbone_weight_bytes_per_step": weights, "adapter_weight_bytes_per_step": lora,
