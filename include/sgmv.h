@@ -133,7 +133,10 @@ typedef struct sgmv_problem {
   int32_t path;              /* sgmv_path, normally SGMV_PATH_AUTO                  */
   int32_t ksplit;            /* split-K factor of shrink; 0 = choose automatically  */
   int32_t expand_threads;    /* workgroup size of the vector expand kernel          */
-                             /* (64, 128 or 256); 0 = choose automatically          */
+                             /* (64, 128 or 256), or 512 for the kernel whose four  */
+                             /* waves divide the weight rows of a 512-column strip  */
+                             /* among themselves (ranks 32 and 64 only, else        */
+                             /* SGMV_ERR_UNSUPPORTED); 0 = choose automatically     */
   int32_t workspace_ready;   /* nonzero: sgmv_workspace_init() has been run on this */
                              /* workspace (and no call on it was ever aborted);     */
                              /* enables the single-launch path                      */

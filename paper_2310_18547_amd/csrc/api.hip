@@ -118,7 +118,7 @@ int check_common(const sgmv_problem* p, const int32_t* seg_starts, int32_t n_seg
   if (p->spin_limit < 0) return SGMV_ERR_UNSUPPORTED;
   if (p->ksplit < 0 || p->ksplit > kMaxKSplit) return SGMV_ERR_UNSUPPORTED;
   if (p->expand_threads != 0 && p->expand_threads != 64 && p->expand_threads != 128 &&
-      p->expand_threads != 256)
+      p->expand_threads != 256 && !(p->expand_threads == kExpandSplit && p->r >= 32))
     return SGMV_ERR_UNSUPPORTED;
   if (p->path == SGMV_PATH_MATRIX && n_segs > 65535) return SGMV_ERR_UNSUPPORTED;  // grid dimension of the MFMA kernels
   if (layer_idx < 0 || layer_idx >= p->num_layers) return SGMV_ERR_RANGE;
@@ -459,8 +459,19 @@ void fill_tile(TileArgs* t, const sgmv_problem* p, const Scratch& sc, const int3
   t->scale = scale;
 }
 
+// Workgroup shape of the vector expand for `n_segs` items (segments, or rows of a per-row launch):
+// 64, 128 or 256 threads of eight columns each, or kExpandSplit.
 int choose_expand_threads(const sgmv_problem* p, int n_segs) {
   if (p->expand_threads) return p->expand_threads;
+  // From rank 32 on a lane of the plain kernel walks its R weight rows sixteen at a time, one
+  // memory round trip after the other; while the launch is small the kernel whose four waves
+  // divide the rows among themselves is ahead (measured at h = 4096, one-row segments, us per
+  // call, plain against divided: rank 64, 1 / 16 / 64 / 128 segments 8.5 / 10.2 / 12.9 / 17.2
+  // against 3.9 / 5.4 / 8.4 / 14.6; rank 32, 16 / 64 / 128: 6.0 / 7.7 / 10.2 against 3.9 / 5.5 /
+  // 8.2; 4096 -> 11008, 64 segments, rank 32 / 64: 11.7 / 19.0 against 9.9 / 17.1), up to about
+  // five and a half of its workgroups per compute unit (1408: ahead; 192 segments at rank 64,
+  // 1536: 19.2 against 20.6; 256 at rank 32, 2048: 13.3 against 14.5)
+  if (p->r >= 32 && (long long)n_segs * ceil_div(p->h_out, 512) <= 11LL * compute_units() / 2) return kExpandSplit;
   const int sizes[3] = {256, 128, 64};
   for (int i = 0; i < 3; ++i)
     if ((long long)n_segs * ceil_div(p->h_out, sizes[i] * 8) >= kTargetWorkgroups / 2 ||
@@ -1208,7 +1219,7 @@ int sgmv_plan_expand(const sgmv_problem* p, int32_t n_segs, sgmv_plan* plan) {
   const int threads = choose_expand_threads(p, by_rows ? p->n_tokens : n_segs);
   plan->kernel = SGMV_KERNEL_VECTOR;
   plan->launches = 1;
-  plan->slices = ceil_div(p->h_out, threads * 8);  // column strips
+  plan->slices = ceil_div(p->h_out, threads == kExpandSplit ? 512 : threads * 8);  // column strips
   plan->workgroups = plan->slices * (by_rows ? ceil_div(p->n_tokens, 8) * 8 : n_segs);
   return SGMV_OK;
 }

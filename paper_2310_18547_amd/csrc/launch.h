@@ -45,6 +45,9 @@ struct ShrinkArgs {
   float* partials_shared[kSharedShrinkMost];
 };
 
+// ExpandArgs::threads value that selects expand_split_kernel (256 threads whose four waves divide
+// the weight rows of a 512-column strip among themselves; ranks 32 and 64)
+constexpr int kExpandSplit = 512;
 struct ExpandArgs {
   bool bf16;
   int r, h_out, n_tokens, n_segs;

@@ -281,6 +281,120 @@ __global__ __launch_bounds__(NT) void expand_vector_kernel(
   }
 }
 
+// The same product with the weight rows of B_i divided among the four waves of a workgroup, for
+// ranks from 32 on: grid = (items, ceil(h_out / 512)), a lane owns eight consecutive columns as
+// above and wave w the weight rows w R/4 .. (w+1) R/4 - 1, so that all R rows of a strip are in
+// flight at once (one memory round trip instead of R/16); waves 1..3 hand their partial sums to
+// wave 0 through LDS, which adds them in wave order and to y.
+template <class DT, int R, int RB, bool BY_ROW>
+__global__ __launch_bounds__(256) void expand_split_kernel(
+    uint16_t* __restrict__ y, const float* __restrict__ v_parts, int nparts,
+    const uint16_t* const* __restrict__ A_ptrs, const uint16_t* const* __restrict__ B_ptrs,
+    const int32_t* __restrict__ seg_starts, int h_out, int n_tokens, long long layer_off,
+    float scale, int n_segs) {
+  constexpr int NT = 256, NW = 4, JW = R / NW;  // weight rows per wave
+  static_assert(R % NW == 0 && JW >= 2 && JW <= 16, "rank out of range for the split expand");
+  __shared__ float vs[RB][R];
+  __shared__ __align__(16) float red[NW - 1][RB][64 * 8];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int seg = blockIdx.x, lo, hi;
+  if constexpr (BY_ROW) {
+    const int row = ((int)blockIdx.x & 7) * ((int)gridDim.x >> 3) + ((int)blockIdx.x >> 3);
+    if (row >= n_tokens) return;
+    seg = segment_of_row(seg_starts, n_segs, row, lane);
+    if (seg >= n_segs) return;  // a row behind the last segment end
+    lo = row;
+    hi = row + 1;
+  } else {
+    lo = seg_starts[seg];
+    hi = seg_starts[seg + 1];
+  }
+  if (lo >= hi) return;
+  const uint16_t* B = B_ptrs[seg];
+  if (B == nullptr) return;
+  if (A_ptrs != nullptr && A_ptrs[seg] == nullptr) return;
+  const int c0 = (blockIdx.y * 64 + lane) * 8;
+  const bool active = c0 < h_out;
+  B += layer_off + (long long)wave * JW * h_out + c0;
+
+  for (int row0 = lo; row0 < hi; row0 += RB) {
+    const int nrows = min(RB, hi - row0);
+    uint4 b[JW];
+#pragma unroll
+    for (int j = 0; j < JW; ++j)
+      b[j] = active ? load128_stream(B + (long long)j * h_out) : make_uint4(0, 0, 0, 0);
+    uint4 yq[RB];
+    if (wave == 0) {
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+        if (active && rb < nrows) yq[rb] = load128(y + (long long)(row0 + rb) * h_out + c0);
+    }
+
+    if (row0 != lo) __syncthreads();  // vs and red are reused
+    for (int idx = tid; idx < nrows * R; idx += NT) {
+      const int rr = idx / R, j = idx - rr * R;
+      const float* src = v_parts + (long long)(row0 + rr) * R + j;
+      float sum = src[0];
+      for (int s = 1; s < nparts; ++s) sum += src[(long long)s * n_tokens * R];
+      vs[rr][j] = sum;
+    }
+    __syncthreads();
+
+    float acc[RB][8];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[rb][e] = 0.f;
+#pragma unroll
+    for (int j = 0; j < JW; ++j) {
+      float bf[8];
+      unpack8<DT>(b[j], bf);
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        if (rb < nrows) {
+          const float vj = vs[rb][wave * JW + j];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[rb][e] = fmaf(vj, bf[e], acc[rb][e]);
+        }
+      }
+    }
+    if (wave != 0) {
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        if (rb < nrows) {
+          float* dst = &red[wave - 1][rb][lane * 8];
+          *reinterpret_cast<float4*>(dst) = make_float4(acc[rb][0], acc[rb][1], acc[rb][2], acc[rb][3]);
+          *reinterpret_cast<float4*>(dst + 4) = make_float4(acc[rb][4], acc[rb][5], acc[rb][6], acc[rb][7]);
+        }
+      }
+    }
+    __syncthreads();
+    if (wave == 0 && active) {
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        if (rb < nrows) {
+#pragma unroll
+          for (int w = 0; w < NW - 1; ++w) {
+            const float4 p0 = *reinterpret_cast<const float4*>(&red[w][rb][lane * 8]);
+            const float4 p1 = *reinterpret_cast<const float4*>(&red[w][rb][lane * 8 + 4]);
+            acc[rb][0] += p0.x; acc[rb][1] += p0.y; acc[rb][2] += p0.z; acc[rb][3] += p0.w;
+            acc[rb][4] += p1.x; acc[rb][5] += p1.y; acc[rb][6] += p1.z; acc[rb][7] += p1.w;
+          }
+          float yf[8];
+          unpack8<DT>(yq[rb], yf);
+          uint4 out;
+          out.x = pack2<DT>(yf[0] + scale * acc[rb][0], yf[1] + scale * acc[rb][1]);
+          out.y = pack2<DT>(yf[2] + scale * acc[rb][2], yf[3] + scale * acc[rb][3]);
+          out.z = pack2<DT>(yf[4] + scale * acc[rb][4], yf[5] + scale * acc[rb][5]);
+          out.w = pack2<DT>(yf[6] + scale * acc[rb][6], yf[7] + scale * acc[rb][7]);
+          store128(y + (long long)(row0 + rb) * h_out + c0, out);
+        }
+      }
+    }
+  }
+}
+
 // ---------------------------------------------------------------- launchers
 
 template <class DT, int R>
@@ -344,8 +458,30 @@ static hipError_t launch_expand_t(const ExpandArgs& a, hipStream_t st) {
 }
 
 template <class DT, int R>
+static hipError_t launch_expand_split(const ExpandArgs& a, hipStream_t st) {
+  if constexpr (R >= 32) {
+    const unsigned strips = (unsigned)((a.h_out + 511) / 512);
+    if (a.by_rows) {
+      hipLaunchKernelGGL((expand_split_kernel<DT, R, 1, true>), dim3((unsigned)((a.n_tokens + 7) / 8 * 8), strips), dim3(256),
+                         0, st, (uint16_t*)a.y, a.v_parts, a.nparts, (const uint16_t* const*)a.A_ptrs,
+                         (const uint16_t* const*)a.B_ptrs, a.seg_starts, a.h_out, a.n_tokens, a.layer_off, a.scale,
+                         a.n_segs);
+    } else {
+      hipLaunchKernelGGL((expand_split_kernel<DT, R, 4, false>), dim3((unsigned)a.n_segs, strips), dim3(256), 0, st,
+                         (uint16_t*)a.y, a.v_parts, a.nparts, (const uint16_t* const*)a.A_ptrs,
+                         (const uint16_t* const*)a.B_ptrs, a.seg_starts, a.h_out, a.n_tokens, a.layer_off, a.scale,
+                         a.n_segs);
+    }
+    return hipGetLastError();
+  } else {
+    return hipErrorInvalidValue;
+  }
+}
+
+template <class DT, int R>
 static hipError_t launch_expand_nt(const ExpandArgs& a, hipStream_t st) {
   switch (a.threads) {
+    case kExpandSplit: return launch_expand_split<DT, R>(a, st);
     case 64: return launch_expand_t<DT, R, 64>(a, st);
     case 128: return launch_expand_t<DT, R, 128>(a, st);
     case 256: return launch_expand_t<DT, R, 256>(a, st);

@@ -399,6 +399,16 @@ def test_plan_expand():
         p.path = path
         assert sg.sgmv_plan_expand(p, 4, check=False)[0] == 3
     assert sg.lib.sgmv_plan_expand(None, 4, None) == 1
+    # ranks 32 and 64: while the launch is small, the kernel whose waves divide the weight rows (strips of 512 columns)
+    for r, n, strips in ((64, 64, 8), (32, 128, 8), (64, 192, 2), (16, 64, 4)):
+        q = sg.make_problem(sg.F16, 4096, 4096, r, 1, n, max_seg_len=1)
+        rc, pl = sg.sgmv_plan_expand(q, n, check=False)
+        assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR and pl.slices == strips, (r, n, pl.slices)
+    q = sg.make_problem(sg.F16, 4096, 4096, 16, 1, 64, max_seg_len=1, expand_threads=512)
+    assert sg.sgmv_plan_expand(q, 64, check=False)[0] == 3          # not below rank 32
+    q = sg.make_problem(sg.F16, 4096, 4096, 64, 1, 1024, max_seg_len=1, expand_threads=512)
+    rc, pl = sg.sgmv_plan_expand(q, 1024, check=False)
+    assert rc == 0 and pl.slices == 8 and pl.workgroups == 8 * 1024
 
 
 def test_plan_agrees_with_the_resource_limits():

@@ -313,6 +313,27 @@ def test_expand_per_row_on_popularity_mixes(kind, dtype, r, h_out, hint):
     assert_parity(d.y_bits(), ref, dtype, f"{kind}: expand per row")
 
 
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("r,h_out,lens", [(32, 1000, [1, 1, 1, 1, 1]), (64, 4096, [1] * 33), (64, 520, [0, 3, 9, 1, 0, 6]),
+                                          (32, 2056, [70, 5]), (64, 1288, [300, 1, 17])])
+def test_expand_with_the_weight_rows_divided_among_waves(dtype, r, h_out, lens):
+    # expand_threads = 512: the vector expand whose four waves take a quarter of B_i's rows each
+    # (what SGMV_PATH_AUTO picks at these ranks while the launch is small), per segment and per row
+    from paper_2310_18547_amd import binding as B
+    adapters = [(-1 if (i == 1 and len(lens) > 3) else i) for i in range(len(lens))]
+    w = wl.custom(lens, 64, h_out, r, dtype, seed=94 + r, num_layers=2, seg_adapter=adapters, scale=-0.5)
+    v0 = np.random.Generator(np.random.PCG64(6)).standard_normal((w.n_tokens, r)).astype(np.float32)
+    ref = oracle.run_workload(w, op="expand", layer_idx=1, v=v0.copy(), n_threads=8)
+    for path in (B.PATH_AUTO, B.PATH_VECTOR):          # per row where the batch is small, per segment
+        d = _dev(w, path=path, expand_threads=512)
+        d.expand(torch.from_numpy(v0.copy()).to("cuda:0"), 1)
+        assert_parity(d.y_bits(), ref, dtype, f"divided expand, path {path}")
+    # the add-on on the launch-per-step vector kernels (no workspace prepared) takes the same expand
+    d = _dev(w, path=B.PATH_VECTOR, expand_threads=512)
+    d.add_lora(1)
+    assert_parity(d.y_bits(), oracle.run_workload(w, layer_idx=1, n_threads=8), dtype, "divided expand in the add-on")
+
+
 def test_expand_per_row_with_empty_segments_and_missing_adapters():
     lens = [0, 3, 0, 0, 5, 1, 0, 2, 7, 0]
     w = wl.custom(lens, 64, 520, 16, "f16", seed=93, num_layers=2, seg_adapter=[0, 1, 2, 3, -1, 4, 5, 6, 7, 8])
