@@ -468,12 +468,15 @@ def bench_one(args, op, d, w, probe):
             sp = B.sgmv_plan_shrink(d.problem, w.n_segs)
             long_segments = sp.kernel == B.KERNEL_MATRIX
         else:
-            long_segments = B.sgmv_plan_expand(d.problem, w.n_segs).kernel == B.KERNEL_MATRIX
+            ep = B.sgmv_plan_expand(d.problem, w.n_segs)
+            long_segments = ep.kernel == B.KERNEL_MATRIX
         kernel = {("shrink", False): "shrink_vector_kernel + shrink_reduce_kernel",
                   ("shrink", True): "shrink_stream_kernel + shrink_reduce_kernel",
                   ("expand", False): "expand_vector_kernel",
                   ("expand", True): "finalize_v_kernel + " + expand_kernel_name(w)}[(op, long_segments)]
         launches, slices, workgroups = (1 if kernel == "expand_vector_kernel" else 2), None, None
+        if op == "expand" and not long_segments and ep.lds_bytes >= 6144:   # the partial sums of three waves are in LDS
+            kernel = "expand_split_kernel"
         if op == "shrink" and sp.kernel == B.KERNEL_FUSED:
             kernel, launches, slices, workgroups = "shrink_handoff_kernel", 1, sp.slices, sp.workgroups
     traffic = args.traffic_bytes

@@ -338,7 +338,8 @@ int sgmv_plan_shrink(const sgmv_problem* p, int32_t n_segs, sgmv_plan* plan);
  * SGMV_KERNEL_VECTOR with one launch of a workgroup per segment and strip of columns
  * (`slices` = strips) or, for a small batch of segments longer than a row (at most 64
  * rows, 128 up to rank 32, 256 up to rank 16; SGMV_PATH_AUTO), per ROW and strip, the
- * workgroups looking their row's segment up; SGMV_KERNEL_MATRIX with two launches
+ * workgroups looking their row's segment up (lds_bytes of 6 KB or more: the kernel
+ * whose four waves divide the weight rows, see expand_threads); SGMV_KERNEL_MATRIX with two launches
  * (operand preparation, MFMA expand) for long segments with a workspace.  Host-only, pure. */
 int sgmv_plan_expand(const sgmv_problem* p, int32_t n_segs, sgmv_plan* plan);
 

@@ -1220,6 +1220,9 @@ int sgmv_plan_expand(const sgmv_problem* p, int32_t n_segs, sgmv_plan* plan) {
   plan->kernel = SGMV_KERNEL_VECTOR;
   plan->launches = 1;
   plan->slices = ceil_div(p->h_out, threads == kExpandSplit ? 512 : threads * 8);  // column strips
+  // v of the rows of a pass, and in the kernel whose waves divide the weight rows the partial sums of three waves
+  const int rows_per_pass = by_rows ? 1 : 4;
+  plan->lds_bytes = rows_per_pass * p->r * 4 + (threads == kExpandSplit ? 3 * rows_per_pass * 512 * 4 : 0);
   plan->workgroups = plan->slices * (by_rows ? ceil_div(p->n_tokens, 8) * 8 : n_segs);
   return SGMV_OK;
 }
