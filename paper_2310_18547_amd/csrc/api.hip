@@ -35,6 +35,7 @@ constexpr int kTargetWorkgroups = 512; // about two workgroups per compute unit
 constexpr int kTileMaxSegLen = 4096;
 constexpr int kMatrixMaxSegments = 65535;  // the MFMA kernels put the segment on a grid dimension limited to this
 constexpr int kFusedSlices = 8;        // most slices per segment the single-launch kernels pick
+constexpr int kRowsMostSegments = 256;  // segments up to which SGMV_PATH_AUTO launches per row (four rounds of the look-up)
 constexpr int kTileMultiSlices = 4;    // fewest slices at which a joint tile launch beats add-ons run per row
 constexpr int kFusedMaxWorkgroups = kGenerationCopies;  // every workgroup of a launch has its own generation copy
 constexpr int kFusedSpinLimit = 1 << 18;
@@ -547,8 +548,10 @@ ExpandArgs make_expand(const sgmv_problem* p, void* y, const float* v_parts, int
 //    its eight slices (Skewed of 256 rows 9.05 against 18.9, Uniform 7.88 against 9.83, 128 x 2 rows
 //    11.7 against 14.7; behind on 40 .. 64 segments of 4 rows, by up to 17 %), 4-8 % ahead elsewhere,
 //    which is left to the tile kernel.
-bool rows_apply(const sgmv_problem* p, bool tile, int tile_slices) {
+bool rows_apply(const sgmv_problem* p, int n_segs, bool tile, int tile_slices) {
   if (p->max_seg_len == 1 || p->ksplit != 0 || !p->workspace_ready) return false;
+  // the look-up takes a round per 64 segments: not for batches of mostly empty segments
+  if (n_segs > kRowsMostSegments) return false;
   if (p->n_tokens <= 64) return true;
   // (rank 64 at 65 .. 128 rows: only at widths up to 4096 and where the tile kernel is out: Uniform
   // of 128 rows 15.3 against 44.5 us, one segment of 128 rows 12.8 against 17.4, 32 x 4 rows 17.6
@@ -562,8 +565,8 @@ bool rows_apply(const sgmv_problem* p, bool tile, int tile_slices) {
 // The stand-alone expand of a small batch of longer segments (or of unknown length): a workgroup
 // per row and column strip instead of per segment, as the add-on does (rows_apply); no workspace
 // is involved.
-bool expand_by_rows(const sgmv_problem* p) {
-  if (p->path != SGMV_PATH_AUTO || p->max_seg_len == 1) return false;
+bool expand_by_rows(const sgmv_problem* p, int n_segs) {
+  if (p->path != SGMV_PATH_AUTO || p->max_seg_len == 1 || n_segs > kRowsMostSegments) return false;
   if (p->n_tokens <= 64) return true;
   if (p->n_tokens <= 128) return p->r <= 32;
   return p->n_tokens <= 256 && p->r <= 16;
@@ -592,7 +595,7 @@ int plan_single(const sgmv_problem* p, int n_segs, SinglePlan* pl) {
   }
   const bool tile = (p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->max_seg_len != 1 &&
                     choose_tile(p, n_segs, &pl->tile);
-  if (p->path == SGMV_PATH_AUTO && rows_apply(p, tile, tile ? pl->tile.S : 0) &&
+  if (p->path == SGMV_PATH_AUTO && rows_apply(p, n_segs, tile, tile ? pl->tile.S : 0) &&
       choose_fused(p, p->n_tokens, &pl->fused, true, true)) {
     pl->kernel = SGMV_KERNEL_FUSED;
     return SGMV_OK;
@@ -664,7 +667,7 @@ int plan_shrink(const sgmv_problem* p, int n_segs, ShrinkPlan* pl) {
   // launch-per-step kernels: rank 16, Uniform / Skewed / Identical of 64 rows 4.6 / 4.4 / 4.1 against
   // 7.7 / 7.3 / 6.7 us, of 256 rows 5.5 / 5.7 / 4.8 against 8.6 / 9.5 / 6.9; rank 64, 64 rows: 7.0 /
   // 6.5 / 5.6 against 10.5 / 10.9 / 9.8)
-  if (p->path == SGMV_PATH_AUTO && rows_apply(p, false, 0) &&
+  if (p->path == SGMV_PATH_AUTO && rows_apply(p, n_segs, false, 0) &&
       choose_fused(&shrink_only, p->n_tokens, &pl->fused, true, true)) {
     pl->kernel = SGMV_KERNEL_FUSED;
     return SGMV_OK;
@@ -693,7 +696,7 @@ int plan_multi(const sgmv_problem* p, int n_segs, int n_proj, FusedArgs* f, Tile
     FusedArgs rows;
     TileArgs one;
     const bool tile_one = p->path == SGMV_PATH_AUTO && choose_tile(p, n_segs, &one);
-    per_row = (p->path == SGMV_PATH_ROWS || rows_apply(p, tile_one, tile_one ? one.S : 0)) &&
+    per_row = (p->path == SGMV_PATH_ROWS || rows_apply(p, n_segs, tile_one, tile_one ? one.S : 0)) &&
               choose_fused(p, p->n_tokens, &rows, true, true);
   }
   // The add-ons in one launch of the one-row kernels: one set of S workgroups per segment (or per
@@ -878,7 +881,7 @@ int sgmv_expand(const sgmv_problem* p, void* y, const float* v, const void* cons
   // the MFMA kernels keep v's 16-bit operand pairs in the workspace
   const bool have_ws = check_workspace(p) == SGMV_OK;
   if (p->path == SGMV_PATH_MATRIX && !have_ws) return check_workspace(p);
-  const int strips_threads = expand_by_rows(p) ? choose_expand_threads(p, p->n_tokens) : 0;
+  const int strips_threads = expand_by_rows(p, n_segs) ? choose_expand_threads(p, p->n_tokens) : 0;
   if (strips_threads != 0) {
     a.by_rows = true;
     a.threads = strips_threads;
@@ -1210,12 +1213,12 @@ int sgmv_plan_expand(const sgmv_problem* p, int32_t n_segs, sgmv_plan* plan) {
   if (p->path == SGMV_PATH_FUSED || p->path == SGMV_PATH_WHOLE || p->path == SGMV_PATH_ROWS) return SGMV_ERR_UNSUPPORTED;
   const bool have_ws = check_workspace(p) == SGMV_OK;
   if (p->path == SGMV_PATH_MATRIX && !have_ws) return check_workspace(p);
-  if (!expand_by_rows(p) && have_ws && expand_use_matrix(p, n_segs)) {
+  if (!expand_by_rows(p, n_segs) && have_ws && expand_use_matrix(p, n_segs)) {
     plan->kernel = SGMV_KERNEL_MATRIX;
     plan->launches = 2;  // operand preparation, expand
     return SGMV_OK;
   }
-  const bool by_rows = expand_by_rows(p);
+  const bool by_rows = expand_by_rows(p, n_segs);
   const int threads = choose_expand_threads(p, by_rows ? p->n_tokens : n_segs);
   plan->kernel = SGMV_KERNEL_VECTOR;
   plan->launches = 1;

@@ -225,6 +225,11 @@ def test_plan_single_launch_shapes():
     assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and (pl.slices, pl.workgroups) == (2, 400)
     rc, pl = _plan(39, n_tokens=64, max_seg_len=5, path=sg.PATH_ROWS)
     assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and pl.workgroups == 256
+    # a batch of mostly empty segments (the look-up takes a round per 64 of them): not by itself
+    rc, pl = _plan(300, n_tokens=64, max_seg_len=5)
+    assert rc == 0 and pl.kernel != sg.KERNEL_FUSED
+    rc, pl = _plan(300, n_tokens=64, max_seg_len=5, path=sg.PATH_ROWS)
+    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED
     rc, pl = _plan(39, n_tokens=2000, max_seg_len=60, path=sg.PATH_ROWS)
     assert rc == 3                                   # more rows than the launch takes workgroups
     # in larger batches (or when asked for): sixteen-row tiles, every workgroup resident
