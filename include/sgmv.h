@@ -330,14 +330,14 @@ int sgmv_plan_add_lora(const sgmv_problem* p, int32_t n_segs, int32_t n_proj, sg
  * Multiplication", the shrink launch): SGMV_KERNEL_FUSED with one launch when one-row
  * segments, or the rows of a small batch of longer ones, are reduced inside the launch
  * by the hand-off between workgroups (needs a prepared workspace and SGMV_PATH_AUTO;
- * max_seg_len == 1, or at most 64 rows, 128 up to rank 32, 256 up to rank 16), else SGMV_KERNEL_MATRIX or
+ * max_seg_len == 1, or at most 64 rows, 128 up to rank 32, 384 up to rank 16), else SGMV_KERNEL_MATRIX or
  * SGMV_KERNEL_VECTOR with two launches (partial sums, then their sum).  Host-only, pure. */
 int sgmv_plan_shrink(const sgmv_problem* p, int32_t n_segs, sgmv_plan* plan);
 
 /* The same for the stand-alone sgmv_expand (same section, the expand launch):
  * SGMV_KERNEL_VECTOR with one launch of a workgroup per segment and strip of columns
  * (`slices` = strips) or, for a small batch of segments longer than a row (at most 64
- * rows, 128 up to rank 32, 256 up to rank 16; SGMV_PATH_AUTO), per ROW and strip, the
+ * rows, 128 up to rank 32, 384 up to rank 16; SGMV_PATH_AUTO), per ROW and strip, the
  * workgroups looking their row's segment up (lds_bytes of 6 KB or more: the kernel
  * whose four waves divide the weight rows, see expand_threads); SGMV_KERNEL_MATRIX with two launches
  * (operand preparation, MFMA expand) for long segments with a workspace.  Host-only, pure. */

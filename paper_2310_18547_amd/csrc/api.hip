@@ -289,7 +289,8 @@ bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f, bool single_a
   if ((long long)s * ceil_div(n_segs, gx) * gx > kFusedMaxWorkgroups) return false;
   // slices forced by a very wide input can outnumber the compute units several times over;
   // from about two rounds of workgroups on the launch-per-step kernels are faster (measured)
-  if (p->path == SGMV_PATH_AUTO && p->ksplit == 0 && (long long)s * n_segs > 2 * lim.fused_workgroups)
+  // (per-row launches, sized by their own rule, rows_apply: up to three rounds, 384 rows at two slices)
+  if (p->path == SGMV_PATH_AUTO && p->ksplit == 0 && (long long)s * n_segs > (by_rows ? 3 : 2) * lim.fused_workgroups)
     return false;
   // From rank 32 on, a launch of more workgroups than units is only worth it when the units get
   // equal shares: 288 or 384 workgroups leave most units waiting for the ones with two (measured
@@ -559,6 +560,11 @@ bool rows_apply(const sgmv_problem* p, int n_segs, bool tile, int tile_slices) {
   if (p->n_tokens <= 128)
     return p->r <= 32 || (!tile && p->h_in <= 4096 && p->h_out <= 4096);
   if (p->n_tokens <= 256) return p->r <= 16 && (!tile || tile_slices < 8);
+  //  * 257 .. 384 rows, ranks up to 16, inputs up to 4096 wide (two slices): only where the tile kernel
+  //    is out or down to three slices (Skewed of 320 / 384 rows 11.0 / 11.9 against 19.8 / 18.4 us on the
+  //    MFMA kernels, 96 x 4 rows 14.0 against 17.2 on the vector kernels; the tile kernel with four
+  //    slices and more is ahead by 5-28 %, and at 512 rows, 1024 workgroups, nearly everything is)
+  if (p->n_tokens <= 384) return p->r <= 16 && p->h_in <= 4096 && (!tile || tile_slices < 4);
   return false;
 }
 
@@ -569,7 +575,7 @@ bool expand_by_rows(const sgmv_problem* p, int n_segs) {
   if (p->path != SGMV_PATH_AUTO || p->max_seg_len == 1 || n_segs > kRowsMostSegments) return false;
   if (p->n_tokens <= 64) return true;
   if (p->n_tokens <= 128) return p->r <= 32;
-  return p->n_tokens <= 256 && p->r <= 16;
+  return p->n_tokens <= 384 && p->r <= 16;
 }
 
 // What sgmv_add_lora will launch for a checked problem: the single source of the path
