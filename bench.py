@@ -479,6 +479,8 @@ def bench_one(args, op, d, w, probe):
             kernel = "expand_split_kernel"
         if op == "shrink" and sp.kernel == B.KERNEL_FUSED:
             kernel, launches, slices, workgroups = "shrink_handoff_kernel", 1, sp.slices, sp.workgroups
+        if op == "shrink" and sp.kernel == B.KERNEL_WHOLE:
+            kernel, launches, slices, workgroups = "shrink_whole_kernel", 1, sp.slices, sp.workgroups
     traffic = args.traffic_bytes
     traffic_source = "--traffic-bytes" if traffic is not None else None
     if traffic is None and P == 1 and args.path == 0 and args.ksplit == 0:

@@ -223,7 +223,11 @@ int sgmv_validate_segments(const int32_t* host_seg_starts, int32_t n_segs, int32
  *   v      device fp32 [n_tokens][r], read and written (accumulated into)
  *   x      device 16-bit [n_tokens][h_in], read
  *   A_ptrs device array of n_segs device pointers
- * Uses p->workspace.  h_out of the descriptor is ignored.  With SGMV_PATH_AUTO, a
+ * Uses p->workspace.  h_out of the descriptor is ignored.  One-row segments
+ * (max_seg_len == 1) whose A_i is small (h_in * r <= 65536), or whose batch is beyond what
+ * the launch with the hand-off takes, run in ONE launch of a workgroup per segment that needs
+ * no workspace (h_in at most 8192 and h_in * r a multiple of 8192; SGMV_PATH_WHOLE asks for
+ * it, SGMV_ERR_UNSUPPORTED where it does not apply).  With SGMV_PATH_AUTO, a
  * prepared workspace (workspace_ready) and max_seg_len == 1 (or a batch of at most 64
  * rows, more at ranks below 64, whatever the segment lengths) the call is one launch whose
  * workgroups hand their Split-K partial sums to each other (bounded wait: a time-out is
@@ -327,7 +331,8 @@ int sgmv_add_lora_multi(const sgmv_problem* p, int32_t n_proj, void* const* ys,
 int sgmv_plan_add_lora(const sgmv_problem* p, int32_t n_segs, int32_t n_proj, sgmv_plan* plan);
 
 /* The same for the stand-alone sgmv_shrink (section "Segmented Gather Matrix-Vector
- * Multiplication", the shrink launch): SGMV_KERNEL_FUSED with one launch when one-row
+ * Multiplication", the shrink launch): SGMV_KERNEL_WHOLE with one launch of a workgroup
+ * per one-row segment (no Split-K); SGMV_KERNEL_FUSED with one launch when one-row
  * segments, or the rows of a small batch of longer ones, are reduced inside the launch
  * by the hand-off between workgroups (needs a prepared workspace and SGMV_PATH_AUTO;
  * max_seg_len == 1, or at most 64 rows, 128 up to rank 32, 384 up to rank 16), else SGMV_KERNEL_MATRIX or

@@ -36,6 +36,7 @@ constexpr int kTileMaxSegLen = 4096;
 constexpr int kMatrixMaxSegments = 65535;  // the MFMA kernels put the segment on a grid dimension limited to this
 constexpr int kFusedSlices = 8;        // most slices per segment the single-launch kernels pick
 constexpr int kRowsMostSegments = 256;  // segments up to which SGMV_PATH_AUTO launches per row (four rounds of the look-up)
+constexpr long long kShrinkWholeMostElements = 48LL << 20;  // weights (96 MB) up to which the stand-alone shrink runs without Split-K
 constexpr int kTileMultiSlices = 4;    // fewest slices at which a joint tile launch beats add-ons run per row
 constexpr int kFusedMaxWorkgroups = kGenerationCopies;  // every workgroup of a launch has its own generation copy
 constexpr int kFusedSpinLimit = 1 << 18;
@@ -664,7 +665,29 @@ int plan_shrink(const sgmv_problem* p, int n_segs, ShrinkPlan* pl) {
   // 4.8 / 6.1 / 6.7 / 8.1 us for shrink + reduction; r = 64, 64 segments: 9.5 against 10.7)
   sgmv_problem shrink_only = *p;
   shrink_only.h_out = p->h_in;  // the output width plays no part here (and need not be set by the caller)
-  if (p->path == SGMV_PATH_AUTO && p->ksplit == 0 && choose_fused(&shrink_only, n_segs, &pl->fused)) {
+  // one workgroup per one-row segment computes the whole product: no Split-K, no second launch
+  const bool whole_fits = p->max_seg_len == 1 && p->ksplit == 0 && p->h_in <= kWholeMaxHin &&
+                          (long long)p->h_in * (p->r / 8) % (4 * 256) == 0;
+  if (p->path == SGMV_PATH_WHOLE) {
+    if (!whole_fits) return SGMV_ERR_UNSUPPORTED;
+    pl->kernel = SGMV_KERNEL_WHOLE;
+    return SGMV_OK;
+  }
+  // Measured on MI355X, us per call, against the launch with the hand-off (up to 128 segments) and
+  // the two launches of the vector kernels (beyond): where A_i is at most 128 KB (h_in * r <= 65536)
+  // it is ahead at every batch (h = 4096, rank 16, 1 / 32 / 64 / 128 / 256 / 512 segments: 3.4 / 3.9 /
+  // 4.8 / 5.8 / 8.6 / 15.0 against 3.65 / 4.3 / 5.0 / 6.6 / 11.4 / 16.6; rank 8, 64 segments: 3.2
+  // against 4.1); with a larger A_i only beyond the hand-off's batches (256 segments, rank 32:
+  // 14.8 against 16.0; h = 8192: 15.3 against 16.6; but 64 segments at rank 64: 16.8 against 9.5);
+  // from about 100 MB of weights on the Split-K kernels stream better (1024 segments at rank 16:
+  // 27.8 against 26.9; 512 at rank 64: 48.1 against 46.5).
+  const bool fused = p->path == SGMV_PATH_AUTO && p->ksplit == 0 && choose_fused(&shrink_only, n_segs, &pl->fused);
+  if (p->path == SGMV_PATH_AUTO && whole_fits && (long long)n_segs * p->h_in * p->r <= kShrinkWholeMostElements &&
+      ((long long)p->h_in * p->r <= 65536 || (!fused && n_segs > 128))) {
+    pl->kernel = SGMV_KERNEL_WHOLE;
+    return SGMV_OK;
+  }
+  if (fused) {
     pl->kernel = SGMV_KERNEL_FUSED;
     return SGMV_OK;
   }
@@ -848,12 +871,16 @@ int sgmv_shrink(const sgmv_problem* p, float* v, const void* x, const void* cons
   if (!aligned(v, 16) || !aligned(x, 16)) return SGMV_ERR_ALIGN;
   rc = check_workspace(p);
   if (rc != SGMV_OK) return rc;
-  if (p->path == SGMV_PATH_FUSED || p->path == SGMV_PATH_WHOLE || p->path == SGMV_PATH_ROWS) return SGMV_ERR_UNSUPPORTED;
+  if (p->path == SGMV_PATH_FUSED || p->path == SGMV_PATH_ROWS) return SGMV_ERR_UNSUPPORTED;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   ShrinkPlan pl;
   rc = plan_shrink(p, n_segs, &pl);
   if (rc != SGMV_OK) return rc;
+  if (pl.kernel == SGMV_KERNEL_WHOLE) {
+    const ShrinkArgs a = make_shrink(p, Scratch{}, x, A_ptrs, seg_starts, n_segs, layer_idx);
+    return launch_shrink_whole(a, v, st) == hipSuccess ? SGMV_OK : SGMV_ERR_LAUNCH;
+  }
   if (pl.kernel == SGMV_KERNEL_FUSED) {
     fill_fused(&pl.fused, p, caller_scratch(p), seg_starts, n_segs, layer_idx, 1.f);
     pl.fused.x = x;
@@ -1193,12 +1220,16 @@ int sgmv_plan_shrink(const sgmv_problem* p, int32_t n_segs, sgmv_plan* plan) {
   if (n_segs == 0 || p->n_tokens == 0) return SGMV_OK;  // nothing is launched
   rc = check_workspace(p);
   if (rc != SGMV_OK) return rc;
-  if (p->path == SGMV_PATH_FUSED || p->path == SGMV_PATH_WHOLE || p->path == SGMV_PATH_ROWS) return SGMV_ERR_UNSUPPORTED;
+  if (p->path == SGMV_PATH_FUSED || p->path == SGMV_PATH_ROWS) return SGMV_ERR_UNSUPPORTED;
   ShrinkPlan pl;
   rc = plan_shrink(p, n_segs, &pl);
   if (rc != SGMV_OK) return rc;
   plan->kernel = pl.kernel;
-  if (pl.kernel == SGMV_KERNEL_FUSED) {
+  if (pl.kernel == SGMV_KERNEL_WHOLE) {
+    plan->launches = 1;
+    plan->slices = 1;
+    plan->workgroups = n_segs;
+  } else if (pl.kernel == SGMV_KERNEL_FUSED) {
     plan->launches = 1;
     plan->slices = pl.fused.S;
     plan->workgroups = pl.fused.S * (int)fused_grid_items(pl.fused.by_rows ? p->n_tokens : n_segs);

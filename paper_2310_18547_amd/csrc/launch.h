@@ -164,6 +164,9 @@ hipError_t launch_add_lora_tile(const TileArgs& a, hipStream_t st);
 hipError_t launch_add_lora_fused(const FusedArgs& a, hipStream_t st);
 // Stand-alone shrink of one-row segments in one launch (x, A_ptrs, S, kslice and the hand-off fields of `a`).
 hipError_t launch_shrink_handoff(const FusedArgs& a, float* v, hipStream_t st);
+// Single-launch shrink of one-row segments without Split-K: one workgroup per segment adds x A_i to v.
+bool shrink_whole_fits(const ShrinkArgs& a);
+hipError_t launch_shrink_whole(const ShrinkArgs& a, float* v, hipStream_t st);
 bool fused_multi_fits(const FusedArgs& a);
 hipError_t launch_add_lora_fused_multi(const FusedArgs& a, hipStream_t st);
 hipError_t launch_workspace_init(void* p, size_t bytes, size_t header_offset, hipStream_t st);

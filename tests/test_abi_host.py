@@ -292,18 +292,39 @@ def test_workspace_bytes_multi():
 
 
 def test_plan_shrink():
-    """Stand-alone shrink: one launch with the hand-off for one-row segments, else two launches."""
+    """Stand-alone shrink of one-row segments: one launch, a workgroup per segment while A_i is small (or the
+    batch beyond the hand-off's), else one launch with the hand-off, else two launches."""
     p = sg.make_problem(sg.F16, 4096, 4096, 16, 1, 64, workspace=FAKE, workspace_bytes=1 << 30, max_seg_len=1,
                         workspace_ready=1)
-    rc, pl = sg.sgmv_plan_shrink(p, 64, check=False)
-    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and (pl.launches, pl.slices, pl.workgroups) == (1, 4, 256)
+    rc, pl = sg.sgmv_plan_shrink(p, 64, check=False)     # A_i of 128 KB: no Split-K
+    assert rc == 0 and pl.kernel == sg.KERNEL_WHOLE and (pl.launches, pl.slices, pl.workgroups) == (1, 1, 64)
     p.h_out = 0                                       # the output width plays no part
     rc, pl = sg.sgmv_plan_shrink(p, 64, check=False)
-    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED
-    p.workspace_ready = 0
+    assert rc == 0 and pl.kernel == sg.KERNEL_WHOLE
+    p.workspace_ready = 0                             # nor does the workspace
+    rc, pl = sg.sgmv_plan_shrink(p, 64, check=False)
+    assert rc == 0 and pl.kernel == sg.KERNEL_WHOLE
+    p.workspace_ready, p.r = 1, 64                    # A_i of 512 KB: Split-K with the hand-off ...
+    rc, pl = sg.sgmv_plan_shrink(p, 64, check=False)
+    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and (pl.launches, pl.slices, pl.workgroups) == (1, 4, 256)
+    p.workspace_ready = 0                             # ... which needs the prepared workspace
     rc, pl = sg.sgmv_plan_shrink(p, 64, check=False)
     assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR and pl.launches == 2
-    p.workspace_ready, p.path = 1, sg.PATH_VECTOR
+    p.workspace_ready, p.r, p.n_tokens = 1, 32, 256   # beyond the hand-off's batches: a workgroup per segment again ...
+    rc, pl = sg.sgmv_plan_shrink(p, 256, check=False)
+    assert rc == 0 and pl.kernel == sg.KERNEL_WHOLE and pl.workgroups == 256
+    p.n_tokens = 1024                                 # ... up to about 100 MB of weights
+    rc, pl = sg.sgmv_plan_shrink(p, 1024, check=False)
+    assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR and pl.launches == 2
+    p.r, p.n_tokens, p.h_in = 16, 64, 4104            # A_i not a whole number of the kernel's steps
+    rc, pl = sg.sgmv_plan_shrink(p, 64, check=False)
+    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED
+    p.path = sg.PATH_WHOLE
+    assert sg.sgmv_plan_shrink(p, 64, check=False)[0] == 3
+    p.h_in = 4096
+    rc, pl = sg.sgmv_plan_shrink(p, 64, check=False)
+    assert rc == 0 and pl.kernel == sg.KERNEL_WHOLE
+    p.path = sg.PATH_VECTOR
     rc, pl = sg.sgmv_plan_shrink(p, 64, check=False)
     assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR
     p.path, p.max_seg_len, p.n_tokens = sg.PATH_AUTO, 300, 1200

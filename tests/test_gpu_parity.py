@@ -263,6 +263,39 @@ def test_shrink_single_launch_matches_oracle(dtype, batch, h_in, r):
     assert d.check() == 0
 
 
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("batch,h_in,r,path", [(1, 4096, 16, "auto"), (64, 4096, 8, "auto"), (200, 4096, 16, "auto"),
+                                               (300, 2048, 32, "auto"), (40, 8192, 64, "whole"), (7, 1024, 16, "whole")])
+def test_shrink_without_split_k_matches_oracle(dtype, batch, h_in, r, path):
+    # one workgroup per one-row segment computes the whole product and adds it to v: no workspace involved
+    from paper_2310_18547_amd import binding as B
+    w = wl.decode_distinct(batch=batch, h_in=h_in, h_out=64, r=r, dtype=dtype, num_layers=2, seed=batch + r + 1)
+    d = _dev(w, path=B.PATH_WHOLE if path == "whole" else B.PATH_AUTO)
+    plan = B.sgmv_plan_shrink(d.problem, w.n_segs)
+    assert plan.kernel == B.KERNEL_WHOLE and plan.launches == 1 and plan.workgroups == batch
+    v0 = np.random.Generator(np.random.PCG64(batch)).standard_normal((batch, r)).astype(np.float32)
+    v = torch.from_numpy(v0.copy()).to("cuda:0")
+    d.shrink(v, 1)
+    ref = oracle.run_workload(w, op="shrink", layer_idx=1, v=v0.copy(), n_threads=8)
+    assert np.all(np.abs(v.cpu().numpy() - ref) <= 2e-3 + 2e-2 * np.abs(ref))
+
+
+def test_shrink_without_split_k_wrong_hint_and_missing_adapters():
+    # longer and empty segments than promised and segments without an adapter (their rows keep their v)
+    lens = [1, 3, 0, 1, 2, 1]
+    w = wl.custom(lens, 1024, 64, 16, "f16", seed=22, seg_adapter=[0, 1, 2, -1, 3, 4])
+    from paper_2310_18547_amd import binding as B
+    d = _dev(w, max_seg_len=1)
+    assert B.sgmv_plan_shrink(d.problem, w.n_segs).kernel == B.KERNEL_WHOLE
+    v0 = np.full((w.n_tokens, w.r), 0.25, np.float32)
+    v = torch.from_numpy(v0.copy()).to("cuda:0")
+    d.shrink(v)
+    ref = oracle.run_workload(w, op="shrink", v=v0.copy())
+    got = v.cpu().numpy()
+    assert np.all(np.abs(got - ref) <= 2e-3 + 2e-2 * np.abs(ref))
+    assert np.all(got[4] == 0.25)          # the row of the segment without an adapter
+
+
 def test_shrink_single_launch_wrong_hint_and_missing_adapters():
     # the caller promised one row per segment; longer and empty segments and segments without an
     # adapter are still handled (rows of the latter keep their v)
@@ -351,7 +384,7 @@ def test_shrink_single_launch_gives_up_without_storing():
     # the bounded wait of the single-launch shrink, forced from the host as for the add-on kernels:
     # workgroup 0 tags its partial sums with a generation its neighbours do not expect, the collecting
     # workgroup of the first segment gives up, that row of v stays as it was, every other row is finished
-    w = wl.decode_distinct(batch=32, h_in=4096, h_out=64, r=16, dtype="f16", num_layers=1, seed=77)
+    w = wl.decode_distinct(batch=32, h_in=4096, h_out=64, r=32, dtype="f16", num_layers=1, seed=77)
     d = _dev(w, spin_limit=200)
     from paper_2310_18547_amd import binding as B
     plan = B.sgmv_plan_shrink(d.problem, w.n_segs)
