@@ -681,9 +681,15 @@ int plan_shrink(const sgmv_problem* p, int n_segs, ShrinkPlan* pl) {
   // 14.8 against 16.0; h = 8192: 15.3 against 16.6; but 64 segments at rank 64: 16.8 against 9.5);
   // from about 100 MB of weights on the Split-K kernels stream better (1024 segments at rank 16:
   // 27.8 against 26.9; 512 at rank 64: 48.1 against 46.5).
+  // (an A_i of 64 .. 128 KB: only where all of it is in flight in at most two batches, and in bfloat16,
+  // whose conversions this kernel does not hide as well, only from 96 segments on: h = 4096, rank 16,
+  // 16 / 64 / 96 segments 4.2 / 5.3 / 6.0 against 3.8 / 4.8 / 6.7)
+  const long long a_elems = (long long)p->h_in * p->r;
+  const bool whole_small = a_elems <= 32768 || (a_elems <= 65536 && a_elems % (16 * 256 * 8) == 0 &&
+                                                (p->dtype == SGMV_F16 || n_segs >= 96));
   const bool fused = p->path == SGMV_PATH_AUTO && p->ksplit == 0 && choose_fused(&shrink_only, n_segs, &pl->fused);
   if (p->path == SGMV_PATH_AUTO && whole_fits && (long long)n_segs * p->h_in * p->r <= kShrinkWholeMostElements &&
-      ((long long)p->h_in * p->r <= 65536 || (!fused && n_segs > 128))) {
+      (whole_small || (!fused && n_segs > 128))) {
     pl->kernel = SGMV_KERNEL_WHOLE;
     return SGMV_OK;
   }
