@@ -494,6 +494,7 @@ ShrinkArgs make_shrink(const sgmv_problem* p, const Scratch& sc, const void* x,
   a.n_segs = n_segs;
   a.ksplit = a.kslice = 0;
   a.max_seg_len = p->max_seg_len;
+  a.by_rows = false;
   a.layer_off = (long long)layer_idx * p->h_in * p->r;
   a.x = x;
   a.A_ptrs = A_ptrs;
@@ -654,6 +655,7 @@ int plan_single(const sgmv_problem* p, int n_segs, SinglePlan* pl) {
 
 // What sgmv_shrink launches: shared by the entry point and sgmv_plan_shrink.
 struct ShrinkPlan {
+  bool whole_by_rows;  // SGMV_KERNEL_WHOLE: a workgroup per row of the batch, not per segment
   int kernel;          // SGMV_KERNEL_FUSED (hand-off inside one launch), _MATRIX or _VECTOR (+ reduction launch)
   FusedArgs fused;     // SGMV_KERNEL_FUSED
   int ksplit, kslice;  // the others
@@ -666,10 +668,12 @@ int plan_shrink(const sgmv_problem* p, int n_segs, ShrinkPlan* pl) {
   sgmv_problem shrink_only = *p;
   shrink_only.h_out = p->h_in;  // the output width plays no part here (and need not be set by the caller)
   // one workgroup per one-row segment computes the whole product: no Split-K, no second launch
-  const bool whole_fits = p->max_seg_len == 1 && p->ksplit == 0 && p->h_in <= kWholeMaxHin &&
-                          (long long)p->h_in * (p->r / 8) % (4 * 256) == 0;
+  const bool whole_shape = p->ksplit == 0 && p->h_in <= kWholeMaxHin && (long long)p->h_in * (p->r / 8) % (4 * 256) == 0;
+  const bool whole_fits = p->max_seg_len == 1 && whole_shape;
+  pl->whole_by_rows = false;
   if (p->path == SGMV_PATH_WHOLE) {
-    if (!whole_fits) return SGMV_ERR_UNSUPPORTED;
+    if (!whole_shape) return SGMV_ERR_UNSUPPORTED;
+    pl->whole_by_rows = p->max_seg_len != 1;  // longer segments (or unknown): per row of the batch
     pl->kernel = SGMV_KERNEL_WHOLE;
     return SGMV_OK;
   }
@@ -697,13 +701,30 @@ int plan_shrink(const sgmv_problem* p, int n_segs, ShrinkPlan* pl) {
     pl->kernel = SGMV_KERNEL_FUSED;
     return SGMV_OK;
   }
-  // small batches of longer segments (or of unknown length): the same launch per row of the
+  // Small batches of longer segments (or of unknown length), per row of the batch.  With a small A_i
+  // a workgroup per row without Split-K (measured at h = 4096, binary16, against the per-row launch
+  // with the hand-off below, from 512 rows the MFMA kernels: rank 16, Uniform of 64 / 128 / 256 /
+  // 384 / 512 rows 3.85 / 4.1 / 4.9 / 6.3 / 6.4 against 4.6 / 5.2 / 6.2 / 7.3 / 8.8 us, Identical of
+  // 1024 rows 8.2 against 7.8; rank 8, Uniform of 64 rows 2.9 against 4.0; rank 32, where A_i is
+  // 256 KB: 64 rows 6.6 against 5.5, 256 rows 7.2 against 9.3)
+  const bool fused_rows = p->path == SGMV_PATH_AUTO && rows_apply(p, n_segs, false, 0) &&
+                          choose_fused(&shrink_only, p->n_tokens, &pl->fused, true, true);
+  {
+    const bool small = a_elems <= 32768 || (a_elems <= 65536 && a_elems % (16 * 256 * 8) == 0 &&
+                                            (p->dtype == SGMV_F16 || p->n_tokens >= 96));
+    if (p->path == SGMV_PATH_AUTO && p->max_seg_len != 1 && whole_shape && n_segs <= kRowsMostSegments &&
+        p->n_tokens <= 512 && (small || (!fused_rows && p->n_tokens > 128 && a_elems <= 131072))) {
+      pl->whole_by_rows = true;
+      pl->kernel = SGMV_KERNEL_WHOLE;
+      return SGMV_OK;
+    }
+  }
+  // else the launch with the hand-off per row of the
   // batch, as for the add-on (rows_apply; measured at h = 4096 against the better of the
   // launch-per-step kernels: rank 16, Uniform / Skewed / Identical of 64 rows 4.6 / 4.4 / 4.1 against
   // 7.7 / 7.3 / 6.7 us, of 256 rows 5.5 / 5.7 / 4.8 against 8.6 / 9.5 / 6.9; rank 64, 64 rows: 7.0 /
   // 6.5 / 5.6 against 10.5 / 10.9 / 9.8)
-  if (p->path == SGMV_PATH_AUTO && rows_apply(p, n_segs, false, 0) &&
-      choose_fused(&shrink_only, p->n_tokens, &pl->fused, true, true)) {
+  if (fused_rows) {
     pl->kernel = SGMV_KERNEL_FUSED;
     return SGMV_OK;
   }
@@ -884,7 +905,8 @@ int sgmv_shrink(const sgmv_problem* p, float* v, const void* x, const void* cons
   rc = plan_shrink(p, n_segs, &pl);
   if (rc != SGMV_OK) return rc;
   if (pl.kernel == SGMV_KERNEL_WHOLE) {
-    const ShrinkArgs a = make_shrink(p, Scratch{}, x, A_ptrs, seg_starts, n_segs, layer_idx);
+    ShrinkArgs a = make_shrink(p, Scratch{}, x, A_ptrs, seg_starts, n_segs, layer_idx);
+    a.by_rows = pl.whole_by_rows;
     return launch_shrink_whole(a, v, st) == hipSuccess ? SGMV_OK : SGMV_ERR_LAUNCH;
   }
   if (pl.kernel == SGMV_KERNEL_FUSED) {
@@ -1234,7 +1256,7 @@ int sgmv_plan_shrink(const sgmv_problem* p, int32_t n_segs, sgmv_plan* plan) {
   if (pl.kernel == SGMV_KERNEL_WHOLE) {
     plan->launches = 1;
     plan->slices = 1;
-    plan->workgroups = n_segs;
+    plan->workgroups = pl.whole_by_rows ? ceil_div(p->n_tokens, 8) * 8 : n_segs;
   } else if (pl.kernel == SGMV_KERNEL_FUSED) {
     plan->launches = 1;
     plan->slices = pl.fused.S;

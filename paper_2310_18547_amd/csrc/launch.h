@@ -32,6 +32,7 @@ struct ShrinkArgs {
   int r, h_in, n_tokens, n_segs;
   int ksplit, kslice;        // ksplit slices of kslice elements cover h_in, none empty
   int max_seg_len;           // hint, 0 = unknown
+  bool by_rows;              // launch_shrink_whole only: a workgroup per row of the batch (it looks its segment up), not per segment
   long long layer_off;       // elements to add to every A pointer
   const void* x;
   const void* const* A_ptrs;

@@ -13,10 +13,13 @@ namespace sgmv {
 
 // grid = n_segs workgroups of 256 threads.  U = 128-bit loads of A_i per lane and batch, all in
 // flight together; the launch checks that h_in * R / 8 is a multiple of 256 * U.
-template <class DT, int R, int U>
+// BY_ROW: grid = the rows of the batch rounded up to a multiple of eight; a workgroup serves one row
+// and looks the row's segment up (n_segs of them), blockIdx.x % 8, the XCD it lands on, taking a run
+// of consecutive rows, which then find their segment's A_i in one L2.
+template <class DT, int R, int U, bool BY_ROW>
 __global__ __launch_bounds__(256) void shrink_whole_kernel(
     const int32_t* __restrict__ seg_starts, const uint16_t* const* __restrict__ A_ptrs,
-    const uint16_t* __restrict__ x, float* __restrict__ v, int h_in, long long offA) {
+    const uint16_t* __restrict__ x, float* __restrict__ v, int h_in, long long offA, int n_tokens, int n_segs) {
   constexpr int NT = 256, NW = 4;
   constexpr int LPR = R / 8;
   constexpr int XL = kWholeMaxHin / (8 * NT);  // 128-bit x loads per lane
@@ -24,8 +27,18 @@ __global__ __launch_bounds__(256) void shrink_whole_kernel(
   __shared__ __align__(16) float red[NW][R];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int seg = blockIdx.x;
-  const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
+  int seg = blockIdx.x, lo, hi;
+  if constexpr (BY_ROW) {
+    const int row = ((int)blockIdx.x & 7) * ((int)gridDim.x >> 3) + ((int)blockIdx.x >> 3);
+    if (row >= n_tokens) return;
+    seg = segment_of_row(seg_starts, n_segs, row, lane);
+    if (seg >= n_segs) return;  // a row behind the last segment end
+    lo = row;
+    hi = row + 1;
+  } else {
+    lo = seg_starts[seg];
+    hi = seg_starts[seg + 1];
+  }
   const uint16_t* A = A_ptrs[seg];
   if (lo >= hi || A == nullptr) return;
 
@@ -78,8 +91,14 @@ __global__ __launch_bounds__(256) void shrink_whole_kernel(
 
 template <class DT, int R, int U>
 static hipError_t launch_shrink_whole_t(const ShrinkArgs& a, hipStream_t st, float* v) {
-  hipLaunchKernelGGL((shrink_whole_kernel<DT, R, U>), dim3((unsigned)a.n_segs), dim3(256), 0, st, a.seg_starts,
-                     (const uint16_t* const*)a.A_ptrs, (const uint16_t*)a.x, v, a.h_in, a.layer_off);
+  if (a.by_rows)
+    hipLaunchKernelGGL((shrink_whole_kernel<DT, R, U, true>), dim3((unsigned)((a.n_tokens + 7) / 8 * 8)), dim3(256), 0, st,
+                       a.seg_starts, (const uint16_t* const*)a.A_ptrs, (const uint16_t*)a.x, v, a.h_in, a.layer_off,
+                       a.n_tokens, a.n_segs);
+  else
+    hipLaunchKernelGGL((shrink_whole_kernel<DT, R, U, false>), dim3((unsigned)a.n_segs), dim3(256), 0, st, a.seg_starts,
+                       (const uint16_t* const*)a.A_ptrs, (const uint16_t*)a.x, v, a.h_in, a.layer_off, a.n_tokens,
+                       a.n_segs);
   return hipGetLastError();
 }
 

@@ -330,20 +330,33 @@ def test_plan_shrink():
     p.path, p.max_seg_len, p.n_tokens = sg.PATH_AUTO, 300, 1200
     rc, pl = sg.sgmv_plan_shrink(p, 4, check=False)
     assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX and pl.launches == 2
-    # small batches of longer segments: one launch per row of the batch (64 rows at any rank, 256 up to rank 16)
+    # small batches of longer segments: one launch per ROW of the batch; with a small A_i a workgroup per row ...
     p.max_seg_len, p.n_tokens = 29, 64
     rc, pl = sg.sgmv_plan_shrink(p, 17, check=False)
-    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and (pl.launches, pl.slices, pl.workgroups) == (1, 4, 256)
-    p.max_seg_len, p.n_tokens = 0, 200
+    assert rc == 0 and pl.kernel == sg.KERNEL_WHOLE and (pl.launches, pl.slices, pl.workgroups) == (1, 1, 64)
+    p.max_seg_len, p.n_tokens = 0, 500
     rc, pl = sg.sgmv_plan_shrink(p, 30, check=False)
-    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and (pl.launches, pl.slices, pl.workgroups) == (1, 2, 400)
-    p.r = 64
+    assert rc == 0 and pl.kernel == sg.KERNEL_WHOLE and pl.workgroups == 504
+    p.n_tokens = 600
+    rc, pl = sg.sgmv_plan_shrink(p, 30, check=False)
+    assert rc == 0 and pl.kernel == sg.KERNEL_MATRIX and pl.launches == 2
+    # ... with a larger one Split-K and the hand-off (64 rows at any rank, 128 up to rank 32)
+    p.r, p.max_seg_len, p.n_tokens = 64, 29, 64
+    rc, pl = sg.sgmv_plan_shrink(p, 17, check=False)
+    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and (pl.launches, pl.slices, pl.workgroups) == (1, 4, 256)
+    p.n_tokens = 200
     rc, pl = sg.sgmv_plan_shrink(p, 30, check=False)
     assert rc == 0 and pl.kernel != sg.KERNEL_FUSED and pl.launches == 2
+    p.r = 32                                          # 256 KB: without Split-K where the hand-off's batches end
+    rc, pl = sg.sgmv_plan_shrink(p, 30, check=False)
+    assert rc == 0 and pl.kernel == sg.KERNEL_WHOLE and pl.workgroups == 200
     p.r, p.max_seg_len, p.n_tokens = 16, 300, 1200
-    for path in (sg.PATH_FUSED, sg.PATH_WHOLE, sg.PATH_ROWS):   # add-on kernels only
+    for path in (sg.PATH_FUSED, sg.PATH_ROWS):        # add-on kernels only
         p.path = path
         assert sg.sgmv_plan_shrink(p, 4, check=False)[0] == 3
+    p.path = sg.PATH_WHOLE                            # as asked: a workgroup per row
+    rc, pl = sg.sgmv_plan_shrink(p, 4, check=False)
+    assert rc == 0 and pl.kernel == sg.KERNEL_WHOLE and pl.workgroups == 1200
     assert sg.lib.sgmv_plan_shrink(None, 4, None) == 1
 
 

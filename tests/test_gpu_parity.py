@@ -136,14 +136,22 @@ def test_rows_path_with_empty_segments_missing_adapters_and_many_segments():
         assert d.check() == 0
     # the same look-up over several rounds of segment ends in the stand-alone steps and in a joint launch
     d = _dev(w)
-    assert B.sgmv_plan_shrink(d.problem, w.n_segs).kernel == B.KERNEL_FUSED
-    assert B.sgmv_plan_expand(d.problem, w.n_segs).workgroups % 96 == 0          # 90 rows rounded up to eights
+    assert B.sgmv_plan_shrink(d.problem, w.n_segs).workgroups == 96              # a workgroup per row, 90 rows rounded up to eights
+    assert B.sgmv_plan_expand(d.problem, w.n_segs).workgroups % 96 == 0
     v = torch.zeros(90, 16, dtype=torch.float32, device="cuda:0")
     d.shrink(v, 0)
     v_ref = oracle.run_workload(w, op="shrink", layer_idx=0, n_threads=8)
     assert np.all(np.abs(v.cpu().numpy() - v_ref) <= 2e-3 + 2e-2 * np.abs(v_ref))
     d.expand(v, 0)
     assert_parity(d.y_bits(), ref, "bf16", "per row, shrink then expand")
+    w64 = wl.custom(lens[:100], 2048, 64, 64, "bf16", seed=81, num_layers=1, seg_adapter=adapters[:100])
+    d64 = _dev(w64)
+    assert B.sgmv_plan_shrink(d64.problem, w64.n_segs).kernel == B.KERNEL_FUSED   # Split-K with the hand-off, per row
+    v64 = torch.zeros(w64.n_tokens, 64, dtype=torch.float32, device="cuda:0")
+    d64.shrink(v64, 0)
+    v64_ref = oracle.run_workload(w64, op="shrink", layer_idx=0, n_threads=8)
+    assert np.all(np.abs(v64.cpu().numpy() - v64_ref) <= 2e-3 + 2e-2 * np.abs(v64_ref))
+    assert d64.check() == 0
     w2 = wl.custom(lens, 1024, 1024, 16, "bf16", seed=80, num_layers=2, seg_adapter=adapters[::-1], scale=0.5)
     ds = [_dev(w), _dev(w2)]
     plan = B.sgmv_plan_add_lora(ds[0].problem, w.n_segs, 2)
@@ -321,7 +329,10 @@ def test_shrink_single_launch_per_row_on_popularity_mixes(kind, dtype, r, h_in, 
     w = wl.popularity(kind, batch=48, h_in=h_in, h_out=64, r=r, dtype=dtype, num_layers=2, seed=91)
     d = _dev(w, max_seg_len=hint)
     plan = B.sgmv_plan_shrink(d.problem, w.n_segs)
-    assert plan.kernel == B.KERNEL_FUSED and plan.launches == 1 and plan.workgroups == plan.slices * 48
+    if r == 16:      # A_i of 128 KB: a workgroup per row without Split-K; else Split-K with the hand-off, per row
+        assert plan.kernel == B.KERNEL_WHOLE and plan.launches == 1 and plan.workgroups == 48
+    else:
+        assert plan.kernel == B.KERNEL_FUSED and plan.launches == 1 and plan.workgroups == plan.slices * 48
     v0 = np.random.Generator(np.random.PCG64(3)).standard_normal((48, r)).astype(np.float32)
     v = torch.from_numpy(v0.copy()).to("cuda:0")
     d.shrink(v, 1)
