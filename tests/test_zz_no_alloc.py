@@ -43,14 +43,18 @@ def test_two_calls_in_a_row_the_second_smaller():
 
 def test_every_kernel_family_on_the_static_array():
     from paper_2310_18547_amd import binding as B
-    # single-launch MFMA tile kernel (segments of a few rows), then a smaller mix
+    # segments of a few rows: the hand-off kernel per row of the batch, then a smaller mix
     _check(wl.popularity("skewed", batch=64, h_in=4096, r=16, dtype="f16", num_layers=1, seed=5))
     _check(wl.custom([3, 1, 0, 5, 2], 1024, 1536, 32, "bf16", seed=7))
+    # the single-launch MFMA tile kernel on the same kind of batch, then on a larger one
+    _check(wl.popularity("skewed", batch=64, h_in=4096, r=16, dtype="f16", num_layers=1, seed=5), path=B.PATH_FUSED)
+    _check(wl.custom([70, 33, 1, 150, 96, 64, 12, 100], 1024, 768, 16, "bf16", seed=14))
     # launch-per-step MFMA kernels (long segments), then shorter ones
     _check(wl.custom([300, 170, 33], 1024, 768, 16, "bf16", seed=8), path=B.PATH_MATRIX)
     _check(wl.custom([40, 9], 512, 264, 64, "f16", seed=9), path=B.PATH_MATRIX)
-    # launch-per-step vector kernels (no length hint)
+    # no length hint: per row in a small batch, the launch-per-step vector kernels in a larger one
     _check(wl.custom([2, 5, 1, 1], 1000, 520, 16, "f16", seed=10), max_seg_len_hint=False)
+    _check(wl.custom([2, 5, 1, 1] * 100, 1000, 520, 16, "f16", seed=15), max_seg_len_hint=False)
     _check(wl.custom([1, 1], 256, 256, 8, "f16", seed=11), path=B.PATH_VECTOR)
 
 
