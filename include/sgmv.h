@@ -226,7 +226,7 @@ int sgmv_validate_segments(const int32_t* host_seg_starts, int32_t n_segs, int32
  * Uses p->workspace.  h_out of the descriptor is ignored.  One-row segments
  * (max_seg_len == 1) whose A_i is small (h_in * r <= 32768; up to 65536 in most cases), or whose batch is beyond what
  * the launch with the hand-off takes, run in ONE launch of a workgroup per segment that needs
- * no workspace (h_in at most 8192 and h_in * r a multiple of 8192; SGMV_PATH_WHOLE asks for
+ * no workspace (h_in at most 8192 and h_in * r a multiple of 2048; SGMV_PATH_WHOLE asks for
  * it, SGMV_ERR_UNSUPPORTED where it does not apply); batches of up to 512 rows in longer
  * segments run the same launch per row (every row's workgroup looks its segment up).
  * With SGMV_PATH_AUTO, a

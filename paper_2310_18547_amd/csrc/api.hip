@@ -274,6 +274,14 @@ bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f, bool single_a
       (long long)ceil_div(wide, s) * (p->r / 8) > 2048)
     s = 2 * kFusedSlices;
   if (s > wide / 64) s = wide / 64;
+  // Narrow shapes: no more slices than leave each a full batch of loads (2048 128-bit chunks of the
+  // wider weight); thinner ones only add the hand-off (measured at rank 16, 8 segments, one / two /
+  // four / eight slices: h = 1024 3.84 / 4.07 / 4.26 / 4.33 us, h = 2048 4.94 / 4.17 / 4.20 / 4.29; at
+  // h = 4096 four and eight are level, 4.38 / 4.37)
+  if (p->ksplit == 0 && wide <= 2048) {
+    const int full = (int)((long long)wide * (p->r / 8) / 2048);
+    if (s > (full > 1 ? full : 1)) s = full > 1 ? full : 1;
+  }
   if (s > cap) s = cap;
   if (s > kFusedMaxWorkgroups / n_segs) s = kFusedMaxWorkgroups / n_segs;
   if (s < need) s = need;
@@ -668,7 +676,7 @@ int plan_shrink(const sgmv_problem* p, int n_segs, ShrinkPlan* pl) {
   sgmv_problem shrink_only = *p;
   shrink_only.h_out = p->h_in;  // the output width plays no part here (and need not be set by the caller)
   // one workgroup per one-row segment computes the whole product: no Split-K, no second launch
-  const bool whole_shape = p->ksplit == 0 && p->h_in <= kWholeMaxHin && (long long)p->h_in * (p->r / 8) % (4 * 256) == 0;
+  const bool whole_shape = p->ksplit == 0 && p->h_in <= kWholeMaxHin && (long long)p->h_in * (p->r / 8) % 256 == 0;
   const bool whole_fits = p->max_seg_len == 1 && whole_shape;
   pl->whole_by_rows = false;
   if (p->path == SGMV_PATH_WHOLE) {

@@ -12,7 +12,7 @@
 namespace sgmv {
 
 // grid = n_segs workgroups of 256 threads.  U = 128-bit loads of A_i per lane and batch, all in
-// flight together; the launch checks that h_in * R / 8 is a multiple of 256 * U.
+// flight together; the launch picks the largest U of 32 .. 1 with h_in * R / 8 a multiple of 256 * U.
 // BY_ROW: grid = the rows of the batch rounded up to a multiple of eight; a workgroup serves one row
 // and looks the row's segment up (n_segs of them), blockIdx.x % 8, the XCD it lands on, taking a run
 // of consecutive rows, which then find their segment's A_i in one L2.
@@ -109,7 +109,9 @@ static hipError_t launch_shrink_whole_u(const ShrinkArgs& a, hipStream_t st, flo
   if (iters % 32 == 0) return launch_shrink_whole_t<DT, R, 32>(a, st, v);
   if (iters % 16 == 0) return launch_shrink_whole_t<DT, R, 16>(a, st, v);
   if (iters % 8 == 0) return launch_shrink_whole_t<DT, R, 8>(a, st, v);
-  return launch_shrink_whole_t<DT, R, 4>(a, st, v);
+  if (iters % 4 == 0) return launch_shrink_whole_t<DT, R, 4>(a, st, v);
+  if (iters % 2 == 0) return launch_shrink_whole_t<DT, R, 2>(a, st, v);
+  return launch_shrink_whole_t<DT, R, 1>(a, st, v);
 }
 
 template <class DT>
@@ -124,7 +126,7 @@ static hipError_t launch_shrink_whole_r(const ShrinkArgs& a, hipStream_t st, flo
 }
 
 bool shrink_whole_fits(const ShrinkArgs& a) {
-  return a.h_in <= kWholeMaxHin && (long long)a.h_in * (a.r / 8) % (4 * 256) == 0 && a.n_segs > 0;
+  return a.h_in <= kWholeMaxHin && (long long)a.h_in * (a.r / 8) % 256 == 0 && a.n_segs > 0;
 }
 
 hipError_t launch_shrink_whole(const ShrinkArgs& a, float* v, hipStream_t st) {

@@ -308,8 +308,10 @@ def test_shrink_single_launch_wrong_hint_and_missing_adapters():
     # the caller promised one row per segment; longer and empty segments and segments without an
     # adapter are still handled (rows of the latter keep their v)
     lens = [1, 3, 0, 1, 2, 1]
-    w = wl.custom(lens, 768, 64, 16, "f16", seed=21, seg_adapter=[0, 1, 2, -1, 3, 4])
+    w = wl.custom(lens, 768, 64, 64, "f16", seed=21, seg_adapter=[0, 1, 2, -1, 3, 4])
     d = _dev(w, max_seg_len=1)
+    from paper_2310_18547_amd import binding as B
+    assert B.sgmv_plan_shrink(d.problem, w.n_segs).kernel == B.KERNEL_FUSED     # Split-K with the hand-off
     v0 = np.full((w.n_tokens, w.r), 0.25, np.float32)
     v = torch.from_numpy(v0.copy()).to("cuda:0")
     d.shrink(v)
