@@ -637,10 +637,14 @@ int plan_single(const sgmv_problem* p, int n_segs, SinglePlan* pl) {
     // units (h = 5120, three slices, 96 / 112 / 128 segments: 11.5 / 12.4 / 13.7 against 13.1 /
     // 13.7 / 14.6; bfloat16 at 128 segments: 15.2 against 14.8, so not there; 72 / 80 segments,
     // at most one workgroup per unit: 10.5 / 11.0 against 8.1 / 8.8, so not there either).
+    // (the same wherever A_i is at most 64 KB, whatever the rank: h = 1024, rank 16, 1 / 8 / 32 / 64
+    // segments 3.1 / 3.3 / 3.6 / 3.7 against 3.7 / 3.9 / 4.4 / 4.4; h = 2048, rank 16, 8 / 64 segments 4.0 /
+    // 4.8 against 4.2 / 4.7; h = 1024, rank 32: 4.1 against 4.5; with 128 KB, h = 1024 at rank 64: 5.5 against 4.5)
+    const bool small_a = (long long)p->h_in * p->r <= 32768;
     const bool odd_slices = fused && p->dtype == SGMV_F16 && (pl->fused.S & (pl->fused.S - 1)) != 0 &&
                             pl->fused.S * n_segs > limits().fused_workgroups;
     if (p->path == SGMV_PATH_AUTO && p->ksplit == 0 && choose_whole(p, n_segs, &pl->whole) &&
-        ((p->r == 8 && n_segs <= 512 && (!fused || p->h_in <= 4096)) ||
+        (((p->r == 8 || small_a) && n_segs <= 512 && (!fused || p->h_in <= 4096 || small_a)) ||
          ((!fused || odd_slices) && n_segs <= 640 && p->r <= (p->workspace_ready ? 16 : 32)))) {
       pl->kernel = SGMV_KERNEL_WHOLE;
       return SGMV_OK;

@@ -169,8 +169,16 @@ def test_plan_single_launch_shapes():
     assert rc == 0 and pl.kernel == sg.KERNEL_VECTOR
     rc, pl = _plan(256, n_tokens=256, max_seg_len=1, path=sg.PATH_FUSED)
     assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and (pl.slices, pl.workgroups) == (2, 512)
-    rc, pl = _plan(256, n_tokens=256, max_seg_len=1, h_in=2048)
+    rc, pl = _plan(256, n_tokens=256, max_seg_len=1, h_in=2048)       # A_i of 64 KB: no hand-off
+    assert rc == 0 and pl.kernel == sg.KERNEL_WHOLE and (pl.slices, pl.workgroups) == (1, 256)
+    rc, pl = _plan(256, n_tokens=256, max_seg_len=1, h_in=2048, path=sg.PATH_FUSED)
     assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and (pl.slices, pl.workgroups) == (1, 256)
+    rc, pl = _plan(8, n_tokens=8, max_seg_len=1, h_in=1024, h_out=1024)    # narrow: one slice ...
+    assert rc == 0 and pl.kernel == sg.KERNEL_WHOLE
+    rc, pl = _plan(8, n_tokens=8, max_seg_len=1, h_in=1024, h_out=1024, path=sg.PATH_FUSED)
+    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and pl.slices == 1
+    rc, pl = _plan(8, n_tokens=8, max_seg_len=1, h_in=2048, h_out=2048, r=64, path=sg.PATH_FUSED)   # ... or what leaves a slice a full batch of loads
+    assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and pl.slices == 8
     for batch, S in ((1, 8), (8, 8), (16, 8), (32, 8), (48, 4), (64, 4), (96, 2), (128, 4)):
         rc, pl = _plan(batch, n_tokens=batch, max_seg_len=1)
         assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and pl.launches == 1
