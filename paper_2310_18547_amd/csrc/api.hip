@@ -341,11 +341,14 @@ bool choose_fused(const sgmv_problem* p, int n_segs, FusedArgs* f, bool single_a
 
 // Launch shape of the single-launch kernel without hand-off (one-row segments, every workgroup
 // computes the whole shrink); false when it does not apply.
-bool choose_whole(const sgmv_problem* p, int n_segs, WholeArgs* w) {
-  if (p->max_seg_len != 1) return false;
+// by_rows: the launch's items are the rows of the batch (pass n_tokens for n_segs), each looking its
+// segment up on the device, so the segments may have any length.
+bool choose_whole(const sgmv_problem* p, int n_segs, WholeArgs* w, bool by_rows = false) {
+  w->by_rows = by_rows;
+  if (p->max_seg_len != 1 && !by_rows) return false;
   if (p->h_in > kWholeMaxHin) return false;
-  // A_i is walked in whole steps of 256 128-bit loads, four or more to a batch
-  if ((long long)p->h_in * (p->r / 8) % (4 * 256) != 0) return false;
+  // A_i is walked in whole steps of 256 128-bit loads
+  if ((long long)p->h_in * (p->r / 8) % 256 != 0) return false;
   if (n_segs > 8 * 65535) return false;  // grid depth
   const Limits lim = limits();
   // as many column slices as keep the launch within one workgroup per compute unit
@@ -611,10 +614,16 @@ int plan_single(const sgmv_problem* p, int n_segs, SinglePlan* pl) {
   }
   const bool tile = (p->path == SGMV_PATH_AUTO || p->path == SGMV_PATH_FUSED) && p->max_seg_len != 1 &&
                     choose_tile(p, n_segs, &pl->tile);
-  if (p->path == SGMV_PATH_AUTO && rows_apply(p, n_segs, tile, tile ? pl->tile.S : 0) &&
-      choose_fused(p, p->n_tokens, &pl->fused, true, true)) {
-    pl->kernel = SGMV_KERNEL_FUSED;
-    return SGMV_OK;
+  if (p->path == SGMV_PATH_AUTO && rows_apply(p, n_segs, tile, tile ? pl->tile.S : 0)) {
+    // with an A_i of at most 64 KB the kernel without hand-off, as for one-row segments below
+    if ((long long)p->h_in * p->r <= 32768 && p->n_tokens <= 512 && choose_whole(p, p->n_tokens, &pl->whole, true)) {
+      pl->kernel = SGMV_KERNEL_WHOLE;
+      return SGMV_OK;
+    }
+    if (choose_fused(p, p->n_tokens, &pl->fused, true, true)) {
+      pl->kernel = SGMV_KERNEL_FUSED;
+      return SGMV_OK;
+    }
   }
   if (tile) {
     pl->kernel = SGMV_KERNEL_TILE;
@@ -1004,6 +1013,7 @@ int add_lora_launch(const sgmv_problem* p, const Scratch& sc, void* y, const voi
       w.h_in = p->h_in;
       w.h_out = p->h_out;
       w.n_segs = n_segs;
+      w.n_tokens = p->n_tokens;
       w.offA = (long long)layer_idx * p->h_in * p->r;
       w.offB = (long long)layer_idx * p->r * p->h_out;
       w.scale = scale;
@@ -1347,7 +1357,7 @@ int sgmv_plan_add_lora(const sgmv_problem* p, int32_t n_segs, int32_t n_proj, sg
     case SGMV_KERNEL_WHOLE:
       plan->launches = 1;
       plan->slices = pl.whole.S;
-      plan->workgroups = 8 * pl.whole.S * ceil_div(n_segs, 8);
+      plan->workgroups = 8 * pl.whole.S * ceil_div(pl.whole.by_rows ? p->n_tokens : n_segs, 8);
       plan->lds_bytes = 0;
       break;
     case SGMV_KERNEL_TILE:

@@ -30,16 +30,19 @@
 
 namespace sgmv {
 
-// grid = (8, S, ceil(n_segs / 8)) workgroups of 256 threads.
+// grid = (8, S, ceil(items / 8)) workgroups of 256 threads, items = segments (or rows, BY_ROW).
 //   G = lane groups of the expand phase (group g multiplies weight rows g*R/G .. (g+1)*R/G-1)
 //   U = 128-bit loads of A_i per lane and batch, all in flight together
-template <class DT, int R, int G, int U>
+// BY_ROW: the items of the grid are the n_tokens rows of the batch instead of its segments; a row's
+// workgroups look its segment up (segment_of_row) and an XCD (blockIdx.x) takes a run of
+// consecutive rows, so that small batches of longer segments with a small A_i run this kernel too.
+template <class DT, int R, int G, int U, bool BY_ROW>
 __global__ __launch_bounds__(256) void add_lora_whole_kernel(
     // the first sixteen dwords are preloaded into SGPRs at wave launch
     const int32_t* __restrict__ seg_starts, const uint16_t* const* __restrict__ A_ptrs,
     const uint16_t* const* __restrict__ B_ptrs, const uint16_t* __restrict__ x,
     uint16_t* __restrict__ y, int cslice, int h_in, int h_out, int n_segs, long long offA,
-    long long offB, float scale, unsigned long long* header) {
+    long long offB, float scale, unsigned long long* header, int n_tokens) {
   constexpr int NT = 256, NW = 4;
   constexpr int LPR = R / 8;
   constexpr int CPW = NT / G;  // 8-column chunks per pass
@@ -57,9 +60,21 @@ __global__ __launch_bounds__(256) void add_lora_whole_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   SGMV_TRACE_DECL
   SGMV_TRACE_POINT(0);
-  const int seg = blockIdx.z * 8 + blockIdx.x, s = blockIdx.y, S = gridDim.y;
-  if (seg >= n_segs) return;
-  const int lo = seg_starts[seg], hi = seg_starts[seg + 1];
+  const int s = blockIdx.y, S = gridDim.y;
+  int seg, lo, hi;
+  if constexpr (BY_ROW) {
+    const int row = blockIdx.x * gridDim.z + blockIdx.z;
+    if (row >= n_tokens) return;
+    seg = segment_of_row(seg_starts, n_segs, row, lane);
+    if (seg >= n_segs) return;  // a row behind the last segment end
+    lo = row;
+    hi = row + 1;
+  } else {
+    seg = blockIdx.z * 8 + blockIdx.x;
+    if (seg >= n_segs) return;
+    lo = seg_starts[seg];
+    hi = seg_starts[seg + 1];
+  }
   const uint16_t* A = A_ptrs[seg];
   const uint16_t* B = B_ptrs[seg];
   if (lo >= hi || A == nullptr || B == nullptr) return;
@@ -217,10 +232,18 @@ __global__ __launch_bounds__(256) void add_lora_whole_kernel(
 
 template <class DT, int R, int G, int U>
 static hipError_t launch_whole_t(const WholeArgs& a, hipStream_t st) {
-  hipLaunchKernelGGL((add_lora_whole_kernel<DT, R, G, U>),
-                     dim3(8u, (unsigned)a.S, (unsigned)((a.n_segs + 7) / 8)), dim3(256), 0, st, a.seg_starts,
-                     (const uint16_t* const*)a.A_ptrs, (const uint16_t* const*)a.B_ptrs, (const uint16_t*)a.x,
-                     (uint16_t*)a.y, a.cslice, a.h_in, a.h_out, a.n_segs, a.offA, a.offB, a.scale, a.header);
+  if (a.by_rows)
+    hipLaunchKernelGGL((add_lora_whole_kernel<DT, R, G, U, true>),
+                       dim3(8u, (unsigned)a.S, (unsigned)((a.n_tokens + 7) / 8)), dim3(256), 0, st, a.seg_starts,
+                       (const uint16_t* const*)a.A_ptrs, (const uint16_t* const*)a.B_ptrs, (const uint16_t*)a.x,
+                       (uint16_t*)a.y, a.cslice, a.h_in, a.h_out, a.n_segs, a.offA, a.offB, a.scale, a.header,
+                       a.n_tokens);
+  else
+    hipLaunchKernelGGL((add_lora_whole_kernel<DT, R, G, U, false>),
+                       dim3(8u, (unsigned)a.S, (unsigned)((a.n_segs + 7) / 8)), dim3(256), 0, st, a.seg_starts,
+                       (const uint16_t* const*)a.A_ptrs, (const uint16_t* const*)a.B_ptrs, (const uint16_t*)a.x,
+                       (uint16_t*)a.y, a.cslice, a.h_in, a.h_out, a.n_segs, a.offA, a.offB, a.scale, a.header,
+                       a.n_tokens);
   return hipGetLastError();
 }
 
@@ -231,7 +254,9 @@ static hipError_t launch_whole_u(const WholeArgs& a, hipStream_t st) {
   if (iters % 32 == 0) return launch_whole_t<DT, R, G, 32>(a, st);
   if (iters % 16 == 0) return launch_whole_t<DT, R, G, 16>(a, st);
   if (iters % 8 == 0) return launch_whole_t<DT, R, G, 8>(a, st);
-  return launch_whole_t<DT, R, G, 4>(a, st);
+  if (iters % 4 == 0) return launch_whole_t<DT, R, G, 4>(a, st);
+  if (iters % 2 == 0) return launch_whole_t<DT, R, G, 2>(a, st);
+  return launch_whole_t<DT, R, G, 1>(a, st);
 }
 
 template <class DT, int R>

@@ -133,7 +133,8 @@ struct TileArgs {
 constexpr int kWholeMaxHin = 8192;  // widest input row a workgroup stages in LDS
 struct WholeArgs {
   bool bf16;
-  int r, h_in, h_out, n_segs;
+  bool by_rows;               // a set of S workgroups per row of the batch (it looks its segment up), not per segment
+  int r, h_in, h_out, n_segs, n_tokens;
   int S;                     // workgroups per segment = column slices of the expand
   int cslice;                // columns per slice
   int G;                     // lane groups of the expand phase (1, 2, 4 or 8)

@@ -173,6 +173,8 @@ def test_plan_single_launch_shapes():
     assert rc == 0 and pl.kernel == sg.KERNEL_WHOLE and (pl.slices, pl.workgroups) == (1, 256)
     rc, pl = _plan(256, n_tokens=256, max_seg_len=1, h_in=2048, path=sg.PATH_FUSED)
     assert rc == 0 and pl.kernel == sg.KERNEL_FUSED and (pl.slices, pl.workgroups) == (1, 256)
+    rc, pl = _plan(4, n_tokens=8, max_seg_len=3, h_in=256, h_out=256, r=8)   # longer segments, small A_i: the same per row
+    assert rc == 0 and pl.kernel == sg.KERNEL_WHOLE and pl.workgroups == 8 * pl.slices
     rc, pl = _plan(8, n_tokens=8, max_seg_len=1, h_in=1024, h_out=1024)    # narrow: one slice ...
     assert rc == 0 and pl.kernel == sg.KERNEL_WHOLE
     rc, pl = _plan(8, n_tokens=8, max_seg_len=1, h_in=1024, h_out=1024, path=sg.PATH_FUSED)
@@ -474,7 +476,7 @@ def test_plan_agrees_with_the_resource_limits():
                     if pl.kernel == sg.KERNEL_TILE:
                         assert pl.workgroups <= 256 and pl.lds_bytes <= 160 * 1024
                 elif pl.kernel == sg.KERNEL_WHOLE:   # its workgroups never wait for each other: any grid
-                    assert pl.launches == 1 and m == 1 and pl.lds_bytes == 0
+                    assert pl.launches == 1 and pl.lds_bytes == 0 and (m == 1 or h_in * r <= 32768)   # longer segments: per row, small A_i
                 else:
                     assert pl.kernel in (sg.KERNEL_VECTOR, sg.KERNEL_MATRIX)
 

@@ -195,6 +195,35 @@ def test_multi_per_row_on_popularity_mixes(kind, P, dtype, r, path):
                 assert_parity(q.y_bits(), oracle.run_workload(w, layer_idx=1, n_threads=8), dtype, f"{kind}: add-on {k} of {P}")
 
 
+# small batches of longer segments with a small A_i: the kernel without hand-off per row of the batch
+@pytest.mark.parametrize("kind,dtype,r,h_in,h_out,batch", [("uniform", "f16", 16, 1024, 1024, 64), ("skewed", "bf16", 8, 2048, 4096, 40),
+                                                           ("identical", "f16", 8, 256, 256, 8), ("skewed_paper", "bf16", 32, 768, 1032, 100),
+                                                           ("uniform_paper", "f16", 64, 512, 2048, 33)])
+def test_whole_kernel_per_row_on_popularity_mixes(kind, dtype, r, h_in, h_out, batch):
+    from paper_2310_18547_amd import binding as B
+    w = wl.popularity(kind, batch=batch, h_in=h_in, h_out=h_out, r=r, dtype=dtype, num_layers=2, seed=95, scale=0.5)
+    d = _dev(w)
+    plan = B.sgmv_plan_add_lora(d.problem, w.n_segs)
+    assert plan.kernel == B.KERNEL_WHOLE and plan.launches == 1 and plan.workgroups == plan.slices * ((batch + 7) // 8 * 8)
+    ref = oracle.run_workload(w, layer_idx=1, n_threads=8)
+    d.add_lora(1)
+    assert_parity(d.y_bits(), ref, dtype, f"{kind}: whole kernel per row")
+
+
+def test_whole_kernel_per_row_with_empty_segments_and_missing_adapters():
+    lens = [0, 3, 0, 0, 5, 1, 0, 2, 7, 0] * 8          # 80 segments for 144 rows: two rounds of the look-up
+    adapters = [0, 1, 2, 3, -1, 4, 5, 6, 7, 8] * 8
+    w = wl.custom(lens, 512, 520, 16, "f16", seed=96, num_layers=2, seg_adapter=adapters)
+    d = _dev(w)
+    from paper_2310_18547_amd import binding as B
+    assert B.sgmv_plan_add_lora(d.problem, w.n_segs).kernel == B.KERNEL_WHOLE
+    y0 = d.y_bits().copy()
+    d.add_lora(1)
+    got = d.y_bits()
+    assert_parity(got, oracle.run_workload(w, layer_idx=1, n_threads=8), "f16", "whole kernel per row, ragged")
+    assert np.array_equal(got[3:8], y0[3:8])          # the rows of the first segment without an adapter
+
+
 # more add-ons than fit side by side: groups of as many as fit, what is left over in a smaller launch
 @pytest.mark.parametrize("n,rows,P,dtype,r,launches", [(60, 2, 5, "f16", 16, 2), (60, 2, 7, "bf16", 16, 2),
                                                        (40, 3, 8, "f16", 32, 3)])
@@ -1222,7 +1251,7 @@ def test_tile_kernel_takes_a_few_long_segments(lens, r, dtype):
 
 
 @pytest.mark.parametrize("n_segs,seg_len,expect", [(2500, 1, "vector"), (1100, 2, "vector"), (300, 5, "vector"), (300, 8, "matrix"),
-                                                   (256, 1, "fused"), (512, 1, "vector"), (256, 3, "tile"), (70000, 1, "vector"), (66000, 4, "vector")])
+                                                   (256, 1, "whole"), (512, 1, "whole"), (256, 3, "tile"), (70000, 1, "vector"), (66000, 4, "vector")])
 def test_many_segments_take_a_path_that_fits(n_segs, seg_len, expect):
     # more segments than the single-launch kernels can keep resident: the call still resolves
     # to a kernel family that covers it (seven adapters shared by all segments)
