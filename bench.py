@@ -46,11 +46,11 @@ MFMA_PEAK_TFLOPS = 2500.0  # dense bf16 / fp16, MI355X
 # whose plan differs from the profiled one reports null.  Source: the summaries in profiles/.
 PROFILED_TRAFFIC = {
     ("distinct_b64", "add_lora", "add_lora_fused_kernel", 4):
-        (18.637e6, "profiles/add_lora_fused_distinct_b64_h4096_r16.md"),
+        (18.620e6, "profiles/add_lora_fused_distinct_b64_h4096_r16.md"),
     ("distinct_b64_r8", "add_lora", "add_lora_whole_kernel", 4):
-        (10.074e6, "profiles/add_lora_whole_distinct_b64_h4096_r8.md"),
+        (10.086e6, "profiles/add_lora_whole_distinct_b64_h4096_r8.md"),
     ("distinct_b256", "add_lora", "add_lora_whole_kernel", 1):
-        (73.656e6, "profiles/add_lora_whole_distinct_b256_h4096_r16.md"),
+        (73.658e6, "profiles/add_lora_whole_distinct_b256_h4096_r16.md"),
 }
 
 # the paper's own latencies for this operator (one A100 80 GB, fp16, r = 16), context only
